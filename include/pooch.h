@@ -1,0 +1,187 @@
+/*
+ * pooch.h -- C ABI of the MI355X out-of-core CNN training step.
+ *
+ * One training step (forward + backward propagation, paper section 2.1) of a CNN is run
+ * inside a caller-supplied device arena whose size IS the memory budget.  Every feature
+ * map that some backward computation needs is handled in one of three ways (section
+ * 4.1.1): kept resident, swapped to pinned host memory after its last forward use and
+ * brought back before backward needs it (section 3.1), or discarded and recomputed from
+ * its producer's inputs, recursively (section 3.2).  The per-map class ("plan") comes from
+ * the paper's three phases (section 4.1.2): profile -> classify -> execute.
+ *
+ * Conventions
+ *   - plain C, no exceptions cross the boundary; every call returns a status (or an id >= 0
+ *     / a negative status).  pooch_last_error() gives the text of the last failure.
+ *   - HOST pointers unless a parameter is marked DEVICE.  Host tensors are fp32 in the
+ *     logical layout NC(D)HW / KC(kd)(kh)(kw), row-major; the library converts to its own
+ *     device layout (channels-last) on the way in and back on the way out.
+ *   - The caller owns the arena, the pinned buffer and the three streams (typically a
+ *     torch uint8 CUDA tensor, a pinned torch tensor, torch streams).  The library never
+ *     allocates device memory for tensors: parameters, gradients, batch statistics,
+ *     workspaces, the input batch, every activation and every gradient map live at
+ *     offsets inside the arena, so exceeding the budget is impossible by construction.
+ *     Running out of room is a PLANNING-time error (POOCH_E_BUDGET), never a mid-step one:
+ *     this is the paper's "excluding out-of-memory errors" (section 4.1.1).
+ *   - A context is not thread-safe; use one per thread.  All streams must have default
+ *     priority.
+ *   - A context created with arena == NULL is "planning only": graph, profile injection,
+ *     planning and simulation work (no GPU needed), compute calls return POOCH_E_STATE.
+ */
+#ifndef POOCH_H
+#define POOCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pooch_ctx pooch_ctx;
+typedef int32_t pooch_status;
+
+enum {
+    POOCH_OK = 0,
+    POOCH_E_INVALID = -1,   /* bad argument / malformed graph */
+    POOCH_E_STATE = -2,     /* call out of order (e.g. step before a plan exists) */
+    POOCH_E_BUDGET = -3,    /* the plan (or any plan) does not fit the arena / pinned buffer */
+    POOCH_E_HIP = -4,       /* a HIP runtime call failed */
+    POOCH_E_NOPROFILE = -5  /* planning needs a profile and none was measured or injected */
+};
+
+/* classes of a feature map, section 4.1.1 */
+enum { POOCH_KEEP = 0, POOCH_SWAP = 1, POOCH_RECOMPUTE = 2 };
+
+/* planning modes: in-core (everything kept) plus the four methods compared in section 5.1 */
+enum {
+    POOCH_MODE_INCORE = 0,
+    POOCH_MODE_SWAPALL_NOSCHED = 1, /* all swap; each swap-in starts with the previous backward computation */
+    POOCH_MODE_SWAPALL = 2,         /* all swap; swap-ins moved up as far as memory allows (section 4.3) */
+    POOCH_MODE_SWAPOPT = 3,         /* keep/swap search only (section 4.4.2) */
+    POOCH_MODE_POOCH = 4            /* keep/swap search, then swap/recompute classification (section 4.4.3) */
+};
+
+/* ---- context ------------------------------------------------------------------------
+ * arena        DEVICE pointer, 256-byte aligned, arena_bytes long (== the budget); may be
+ *              NULL for a planning-only context (arena_bytes still sets the budget).
+ * pinned_host  pinned HOST buffer that receives swapped-out maps; may be NULL/0 when no
+ *              plan ever swaps.
+ * stream_*     hipStream_t handles passed as void*: compute, device-to-host, host-to-device.
+ *              Three distinct streams give overlap; passing the same stream is legal.
+ * The context borrows all five; they must outlive it.  */
+pooch_status pooch_create(void *arena, size_t arena_bytes, void *pinned_host, size_t pinned_bytes,
+                          void *stream_compute, void *stream_d2h, void *stream_h2d, pooch_ctx **out);
+void pooch_destroy(pooch_ctx *);
+const char *pooch_last_error(pooch_ctx *);
+
+/* ---- graph (section 4.2: "computation graph and dependency of the NN") ----------------
+ * Insertion order is execution order.  Each call returns the id (>= 0) of the tensor the
+ * layer produces, or a negative status.  nspatial is 2 or 3; k/stride/pad have nspatial
+ * entries ordered (d,)h,w.  dims of the input are N,C,(D,)H,W.
+ * conv: cross-correlation, zero padding, no bias.  bn: training-mode batch normalisation
+ * over batch x space with learnable gamma/beta.  maxpool pads with -inf and sends the
+ * gradient to the first maximal element in scan order.  fc has a bias.  softmax_ce is the
+ * terminal node: mean over the batch of the softmax cross-entropy against int32 labels. */
+int32_t pooch_input(pooch_ctx *, const int64_t *dims, int ndim);
+int32_t pooch_conv(pooch_ctx *, int32_t x, int cout, const int *k, const int *stride, const int *pad, int nspatial);
+int32_t pooch_bn(pooch_ctx *, int32_t x, float eps);
+int32_t pooch_relu(pooch_ctx *, int32_t x);
+int32_t pooch_add(pooch_ctx *, int32_t a, int32_t b);
+int32_t pooch_maxpool(pooch_ctx *, int32_t x, const int *k, const int *stride, const int *pad, int nspatial);
+int32_t pooch_gavgpool(pooch_ctx *, int32_t x);
+int32_t pooch_fc(pooch_ctx *, int32_t x, int nout);
+int32_t pooch_softmax_ce(pooch_ctx *, int32_t logits);
+/* Freezes the graph: shapes, liveness, the feature-map list (every tensor some backward
+ * reads, except the network input, which is caller data and stays resident), the parameter
+ * list and the layout of the resident region at the bottom of the arena.
+ * POOCH_E_BUDGET if the resident region alone exceeds the arena. */
+pooch_status pooch_finalize(pooch_ctx *);
+
+/* ---- parameters and data -------------------------------------------------------------
+ * Parameters in layer order: conv -> W[K,C,k...]; bn -> gamma[C], beta[C]; fc -> W[O,I], b[O]
+ * (I flattened in logical C,(D,)H,W order).  set_* copy from host synchronously; get_grad
+ * copies the gradient of parameter i (same shape) back after a step. */
+int32_t pooch_num_params(pooch_ctx *);
+pooch_status pooch_param_info(pooch_ctx *, int32_t i, int64_t *numel, int32_t *node);
+pooch_status pooch_set_param(pooch_ctx *, int32_t i, const float *host);
+pooch_status pooch_get_grad(pooch_ctx *, int32_t i, float *host);
+pooch_status pooch_set_batch(pooch_ctx *, const float *x_host, const int32_t *labels_host);
+/* debugging / parity aid: copies the CURRENT device contents of tensor id's forward value
+ * to host in logical layout; valid only for tensors resident after the last step. */
+pooch_status pooch_get_tensor(pooch_ctx *, int32_t id, float *host);
+/* gradient of the loss w.r.t. saved BN statistics is internal; the per-channel batch mean
+ * and 1/sqrt(var+eps) of BN node `node` (C floats each) can be read back for tests. */
+pooch_status pooch_get_bn_stats(pooch_ctx *, int32_t node, float *mean, float *istd);
+
+/* ---- feature maps: the units being classified (section 4.1.1) --------------------------*/
+int32_t pooch_num_nodes(pooch_ctx *);
+int32_t pooch_num_fmaps(pooch_ctx *);
+/* bytes = size inside the arena (256-byte rounded); producer = node id */
+pooch_status pooch_fmap_info(pooch_ctx *, int32_t i, size_t *bytes, int32_t *producer);
+/* bytes of the resident region (parameters, gradients, statistics, workspaces, input) */
+size_t pooch_resident_bytes(pooch_ctx *);
+
+/* ---- phase 1: runtime profiling (section 4.2) -------------------------------------------
+ * Runs `warmup` untimed and `iters` timed steps with every map classified swap, timing each
+ * layer's forward, backward and re-forward (the forward as a recomputation would run it)
+ * and each map's swap-out / swap-in with HIP events; keeps the per-item median, in ms.
+ * Array lengths: t_fwd, t_bwd, t_refwd -> num_nodes; t_out, t_in -> num_fmaps.
+ * set_profile injects a profile (tests, CPU-only planning). */
+pooch_status pooch_profile(pooch_ctx *, int warmup, int iters);
+pooch_status pooch_get_profile(pooch_ctx *, double *t_fwd, double *t_bwd, double *t_refwd, double *t_out, double *t_in);
+pooch_status pooch_set_profile(pooch_ctx *, const double *t_fwd, const double *t_bwd, const double *t_refwd,
+                               const double *t_out, const double *t_in);
+
+/* ---- phase 2: classification (section 4.4) -----------------------------------------------
+ * pooch_plan searches a classification for `mode` by simulating the step's timeline and
+ * memory for each candidate (section 4.1.2) and installs the best one; predicted_ms (may be
+ * NULL) receives its simulated step time.  max_bruteforce_bits caps the exponential part
+ * of the keep/swap search (the binary tree over the maps whose swap-in is not hidden);
+ * <= 0 selects the default.  POOCH_E_BUDGET when not even the all-swap plan fits.
+ * pooch_set_plan installs an explicit classification (num_fmaps bytes, POOCH_KEEP/SWAP/
+ * RECOMPUTE) after validating it the same way; `sched` != 0 enables moved-up swap-ins. */
+pooch_status pooch_plan(pooch_ctx *, int mode, int max_bruteforce_bits, double *predicted_ms);
+pooch_status pooch_get_plan(pooch_ctx *, uint8_t *cls);
+pooch_status pooch_set_plan(pooch_ctx *, const uint8_t *cls, int sched);
+/* simulate without installing: step time (ms) and peak bytes of the dynamic region for an
+ * explicit classification; POOCH_E_BUDGET if it does not fit. */
+pooch_status pooch_simulate(pooch_ctx *, const uint8_t *cls, int sched, double *step_ms, size_t *peak_bytes);
+/* number of timeline simulations the last pooch_plan ran (the paper's search-space sizes) */
+int64_t pooch_plan_evaluations(pooch_ctx *);
+/* the sets found on the all-swap timeline (section 4.4.2): in_LO[i], in_LI[i] are 0/1 per map */
+pooch_status pooch_get_overhead_sets(pooch_ctx *, uint8_t *in_LO, uint8_t *in_LI);
+
+/* ---- phase 3: execution -------------------------------------------------------------------
+ * One forward + backward under the installed plan.  Enqueues everything, then synchronises
+ * all three streams before returning; *loss_out (may be NULL) receives the mean loss. */
+pooch_status pooch_step(pooch_ctx *, float *loss_out);
+
+typedef struct pooch_stats {
+    double step_ms;            /* wall time of the last step (host clock, enqueue to sync) */
+    double predicted_ms;       /* simulated step time of the installed plan (0 without profile) */
+    uint64_t swap_out_bytes;   /* bytes copied device -> host per step under the plan */
+    uint64_t swap_in_bytes;    /* bytes copied host -> device per step */
+    uint64_t peak_bytes;       /* high-water mark of the dynamic region (allocated bytes) */
+    uint64_t extent_bytes;     /* highest arena offset ever touched + 1 minus lowest, dynamic region */
+    uint64_t resident_bytes;
+    uint64_t arena_bytes;
+    int32_t n_keep, n_swap, n_recompute;
+    int32_t n_commands;        /* length of the replayed command list */
+    int32_t n_refwd;           /* forward re-executions per step */
+    int32_t reserved;
+} pooch_stats;
+pooch_status pooch_get_stats(pooch_ctx *, pooch_stats *);
+
+/* Times one step with HIP events around every command and returns per-node milliseconds of
+ * the installed plan's forward, backward and re-forward work (arrays of num_nodes doubles,
+ * any may be NULL) -- the source of per-kernel rates in the benchmark. */
+pooch_status pooch_step_timed(pooch_ctx *, float *loss_out, double *ms_fwd, double *ms_bwd, double *ms_refwd);
+
+/* measured pinned-copy rate of the host link: copies `bytes` each way `iters` times through
+ * the context's copy streams and pinned buffer; GB/s (1e9) each way. */
+pooch_status pooch_measure_link(pooch_ctx *, size_t bytes, int iters, double *d2h_gbs, double *h2d_gbs);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POOCH_H */

@@ -1,0 +1,362 @@
+// HBM-bound layers for gfx950: batch normalisation (training mode) forward / backward and
+// the element-wise layers (ReLU, residual add, gradient accumulate, copy).
+//
+// The paper (section 3.3) singles these out as layers of "small computation complexity":
+// their time is memory traffic, so every kernel moves 16 bytes per lane per access over
+// channels-last rows and touches each tensor the minimum number of times
+// (BN forward: x twice + y once; BN backward: x, dy twice + dx once).
+// Reductions are two-stage and fixed-order (per-thread strided partial sums -> in-block
+// combine -> per-channel wavefront shuffle tree in double), so results are bit-identical
+// from run to run and independent of where the tensor sits in the arena.
+#include "kernels.h"
+
+namespace pk {
+namespace {
+
+constexpr int BNT = 256;        // threads per block in the 2-d (row, channel-vector) kernels
+constexpr int MAX_RBLK = 2048;  // cap on row blocks of a reduction
+
+struct Lay2D {
+    int V;          // floats per lane access (4 when C % 4 == 0, else 1)
+    int CV;         // channel vectors per row
+    int TX, TY;     // threads across channel vectors / rows
+    int gy;         // blocks across channel vectors
+    int nblk;       // row blocks
+    int64_t rows_per_blk;
+};
+
+Lay2D layout2d(int64_t M, int C, bool vec_ok, int target_blocks)
+{
+    Lay2D L;
+    L.V = (vec_ok && C % 4 == 0) ? 4 : 1;
+    L.CV = C / L.V;
+    L.TX = L.CV < BNT ? L.CV : BNT;
+    L.TY = BNT / L.TX;
+    L.gy = (L.CV + L.TX - 1) / L.TX;
+    int64_t nb = (M + (int64_t)L.TY * 32 - 1) / ((int64_t)L.TY * 32);
+    int64_t cap = target_blocks / L.gy;
+    if (cap < 1) cap = 1;
+    if (nb > cap) nb = cap;
+    if (nb < 1) nb = 1;
+    L.rows_per_blk = (M + nb - 1) / nb;
+    L.nblk = (int)((M + L.rows_per_blk - 1) / L.rows_per_blk);
+    return L;
+}
+
+template <int V> __device__ __forceinline__ void ldv(const float *p, float (&o)[V])
+{
+    if constexpr (V == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        o[0] = t.x; o[1 % V] = t.y; o[2 % V] = t.z; o[3 % V] = t.w;
+    } else {
+        o[0] = *p;
+    }
+}
+template <int V> __device__ __forceinline__ void stv(float *p, const float (&o)[V])
+{
+    if constexpr (V == 4) *reinterpret_cast<float4 *>(p) = make_float4(o[0], o[1 % V], o[2 % V], o[3 % V]);
+    else *p = o[0];
+}
+
+// Stage 1 of both BN reductions.  part[blk][0][c] / part[blk][1][c]:
+//   forward  (dy == nullptr): sum (x - x0_c), sum (x - x0_c)^2, x0_c = first row (a shift that
+//                             keeps the variance formula from cancelling)
+//   backward:                 sum dy, sum dy * (x - mean_c)
+template <int V>
+__global__ __launch_bounds__(BNT) void bn_partial_kernel(const float *__restrict__ x, const float *__restrict__ dy,
+                                                          const float *__restrict__ mean, float *__restrict__ part,
+                                                          int64_t M, int C, int TX, int TY, int64_t rows_per_blk)
+{
+    __shared__ float red[2][BNT][V];
+    const int tid = threadIdx.x;
+    const int tx = tid % TX, ty = tid / TX;
+    const int col = blockIdx.y * TX + tx;  // channel-vector index
+    const bool active = ty < TY && col * V < C;
+    float s1[V], s2[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) s1[i] = s2[i] = 0.f;
+    if (active) {
+        float sh[V];
+        ldv<V>((dy ? mean : x) + (int64_t)col * V, sh);
+        const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
+        const int64_t r1 = r0 + rows_per_blk < M ? r0 + rows_per_blk : M;
+        for (int64_t r = r0 + ty; r < r1; r += TY) {
+            float xv[V];
+            ldv<V>(x + r * C + (int64_t)col * V, xv);
+            if (dy) {
+                float dv[V];
+                ldv<V>(dy + r * C + (int64_t)col * V, dv);
+#pragma unroll
+                for (int i = 0; i < V; ++i) { s1[i] += dv[i]; s2[i] += dv[i] * (xv[i] - sh[i]); }
+            } else {
+#pragma unroll
+                for (int i = 0; i < V; ++i) { const float d = xv[i] - sh[i]; s1[i] += d; s2[i] += d * d; }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < V; ++i) { red[0][tid][i] = s1[i]; red[1][tid][i] = s2[i]; }
+    __syncthreads();
+    if (active && ty == 0) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            float a = red[0][tx][i], b = red[1][tx][i];
+            for (int y = 1; y < TY; ++y) { a += red[0][y * TX + tx][i]; b += red[1][y * TX + tx][i]; }
+            s1[i] = a; s2[i] = b;
+        }
+        stv<V>(part + ((int64_t)blockIdx.x * 2 + 0) * C + (int64_t)col * V, s1);
+        stv<V>(part + ((int64_t)blockIdx.x * 2 + 1) * C + (int64_t)col * V, s2);
+    }
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;  // lane 0 holds the total
+}
+
+// Stage 2: one wavefront per channel sums the row-block partials in double.
+__global__ __launch_bounds__(64) void bn_stats_final_kernel(const float *__restrict__ part, const float *__restrict__ x,
+                                                             float *__restrict__ mean, float *__restrict__ istd,
+                                                             int nblk, int C, double m, double eps)
+{
+    const int c = blockIdx.x, lane = threadIdx.x;
+    double a = 0.0, b = 0.0;
+    for (int k = lane; k < nblk; k += 64) {
+        a += (double)part[((int64_t)k * 2 + 0) * C + c];
+        b += (double)part[((int64_t)k * 2 + 1) * C + c];
+    }
+    a = wave_sum(a);
+    b = wave_sum(b);
+    if (lane == 0) {
+        const double d1 = a / m;
+        double var = b / m - d1 * d1;
+        if (var < 0.0) var = 0.0;
+        mean[c] = (float)((double)x[c] + d1);
+        istd[c] = (float)(1.0 / sqrt(var + eps));
+    }
+}
+
+__global__ __launch_bounds__(64) void bn_grad_final_kernel(const float *__restrict__ part, const float *__restrict__ istd,
+                                                            float *__restrict__ dgamma, float *__restrict__ dbeta,
+                                                            int nblk, int C)
+{
+    const int c = blockIdx.x, lane = threadIdx.x;
+    double a = 0.0, b = 0.0;
+    for (int k = lane; k < nblk; k += 64) {
+        a += (double)part[((int64_t)k * 2 + 0) * C + c];
+        b += (double)part[((int64_t)k * 2 + 1) * C + c];
+    }
+    a = wave_sum(a);
+    b = wave_sum(b);
+    if (lane == 0) {
+        dbeta[c] = (float)a;
+        dgamma[c] = (float)(b * (double)istd[c]);
+    }
+}
+
+// y = gamma * (x - mean) * istd + beta
+template <int V>
+__global__ __launch_bounds__(BNT) void bn_apply_kernel(const float *__restrict__ x, const float *__restrict__ gamma,
+                                                        const float *__restrict__ beta, const float *__restrict__ mean,
+                                                        const float *__restrict__ istd, float *__restrict__ y,
+                                                        int64_t M, int C, int TX, int TY, int64_t rows_per_blk)
+{
+    const int tid = threadIdx.x;
+    const int tx = tid % TX, ty = tid / TX;
+    const int col = blockIdx.y * TX + tx;
+    if (ty >= TY || col * V >= C) return;
+    float g[V], b[V], mu[V], is[V];
+    ldv<V>(gamma + (int64_t)col * V, g);
+    ldv<V>(beta + (int64_t)col * V, b);
+    ldv<V>(mean + (int64_t)col * V, mu);
+    ldv<V>(istd + (int64_t)col * V, is);
+#pragma unroll
+    for (int i = 0; i < V; ++i) g[i] *= is[i];
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
+    const int64_t r1 = r0 + rows_per_blk < M ? r0 + rows_per_blk : M;
+    for (int64_t r = r0 + ty; r < r1; r += TY) {
+        float xv[V];
+        ldv<V>(x + r * C + (int64_t)col * V, xv);
+#pragma unroll
+        for (int i = 0; i < V; ++i) xv[i] = (xv[i] - mu[i]) * g[i] + b[i];
+        stv<V>(y + r * C + (int64_t)col * V, xv);
+    }
+}
+
+// dx (+)= gamma*istd*(dy - dbeta/m - (x-mean)*istd*dgamma/m)
+template <int V, bool ACCUM>
+__global__ __launch_bounds__(BNT) void bn_bwd_apply_kernel(const float *__restrict__ x, const float *dy,
+                                                            const float *__restrict__ gamma, const float *__restrict__ mean,
+                                                            const float *__restrict__ istd, const float *__restrict__ dgamma,
+                                                            const float *__restrict__ dbeta, float *dx,
+                                                            int64_t M, int C, int TX, int TY, int64_t rows_per_blk, float inv_m)
+{
+    const int tid = threadIdx.x;
+    const int tx = tid % TX, ty = tid / TX;
+    const int col = blockIdx.y * TX + tx;
+    if (ty >= TY || col * V >= C) return;
+    float a[V], b[V], cc[V], mu[V];
+    {
+        float g[V], is[V], dg[V], db[V];
+        ldv<V>(gamma + (int64_t)col * V, g);
+        ldv<V>(istd + (int64_t)col * V, is);
+        ldv<V>(dgamma + (int64_t)col * V, dg);
+        ldv<V>(dbeta + (int64_t)col * V, db);
+        ldv<V>(mean + (int64_t)col * V, mu);
+#pragma unroll
+        for (int i = 0; i < V; ++i) { a[i] = g[i] * is[i]; b[i] = db[i] * inv_m; cc[i] = is[i] * dg[i] * inv_m; }
+    }
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
+    const int64_t r1 = r0 + rows_per_blk < M ? r0 + rows_per_blk : M;
+    for (int64_t r = r0 + ty; r < r1; r += TY) {
+        float xv[V], dv[V];
+        ldv<V>(x + r * C + (int64_t)col * V, xv);
+        ldv<V>(dy + r * C + (int64_t)col * V, dv);
+#pragma unroll
+        for (int i = 0; i < V; ++i) dv[i] = a[i] * (dv[i] - b[i] - (xv[i] - mu[i]) * cc[i]);
+        if (ACCUM) {
+            float ov[V];
+            ldv<V>(dx + r * C + (int64_t)col * V, ov);
+#pragma unroll
+            for (int i = 0; i < V; ++i) dv[i] = ov[i] + dv[i];
+        }
+        stv<V>(dx + r * C + (int64_t)col * V, dv);
+    }
+}
+
+// ---- flat element-wise kernels: n4 float4 items then a scalar tail ----
+enum { EW_RELU_F, EW_RELU_B, EW_RELU_B_ACC, EW_ADD, EW_ACC, EW_COPY };
+
+template <int OP> __device__ __forceinline__ float ew(float a, float b, float d)
+{
+    switch (OP) {
+    case EW_RELU_F: return a > 0.f ? a : 0.f;            // a = x
+    case EW_RELU_B: return a > 0.f ? b : 0.f;            // a = y, b = dy
+    case EW_RELU_B_ACC: return d + (a > 0.f ? b : 0.f);  // d = existing dx
+    case EW_ADD: return a + b;
+    case EW_ACC: return d + a;                           // a = src
+    default: return a;
+    }
+}
+
+template <int OP>
+__global__ __launch_bounds__(256) void ew_kernel(const float *a, const float *b, float *d, int64_t n)
+{
+    constexpr bool USE_B = OP == EW_RELU_B || OP == EW_RELU_B_ACC || OP == EW_ADD;
+    constexpr bool USE_D = OP == EW_RELU_B_ACC || OP == EW_ACC;
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        const float4 av = reinterpret_cast<const float4 *>(a)[i];
+        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f), dv = bv;
+        if (USE_B) bv = reinterpret_cast<const float4 *>(b)[i];
+        if (USE_D) dv = reinterpret_cast<const float4 *>(d)[i];
+        float4 o;
+        o.x = ew<OP>(av.x, bv.x, dv.x);
+        o.y = ew<OP>(av.y, bv.y, dv.y);
+        o.z = ew<OP>(av.z, bv.z, dv.z);
+        o.w = ew<OP>(av.w, bv.w, dv.w);
+        reinterpret_cast<float4 *>(d)[i] = o;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) {
+        const int64_t i = n4 * 4 + threadIdx.x;
+        d[i] = ew<OP>(a[i], USE_B ? b[i] : 0.f, USE_D ? d[i] : 0.f);
+    }
+}
+
+template <int OP> hipError_t launch_ew(const float *a, const float *b, float *d, int64_t n, hipStream_t s)
+{
+    if (n < 0 || !a || !d) return hipErrorInvalidValue;
+    if (n == 0) return hipSuccess;
+    if (((uintptr_t)a | (uintptr_t)b | (uintptr_t)d) % 16 != 0) return hipErrorInvalidValue;
+    int64_t blocks = (n / 4 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    ew_kernel<OP><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a, b, d, n);
+    return hipGetLastError();
+}
+
+bool bn_args_ok(int64_t M, int C) { return M > 0 && C > 0 && M * (int64_t)C < ((int64_t)1 << 40); }
+
+}  // namespace
+
+size_t bn_workspace_floats(int64_t M, int C)
+{
+    if (!bn_args_ok(M, C)) return 0;
+    const Lay2D a = layout2d(M, C, true, MAX_RBLK), b = layout2d(M, C, false, MAX_RBLK);
+    return (size_t)(a.nblk > b.nblk ? a.nblk : b.nblk) * 2 * C;
+}
+
+hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const float *mean, const float *istd,
+                    float *y, int64_t M, int C, hipStream_t s)
+{
+    if (!x || !gamma || !beta || !mean || !istd || !y || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    const bool al = ((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma | (uintptr_t)beta | (uintptr_t)mean | (uintptr_t)istd) % 16 == 0;
+    const Lay2D L = layout2d(M, C, al, 8192);
+    const dim3 grid(L.nblk, L.gy), block(BNT);
+    if (L.V == 4) bn_apply_kernel<4><<<grid, block, 0, s>>>(x, gamma, beta, mean, istd, y, M, C, L.TX, L.TY, L.rows_per_blk);
+    else bn_apply_kernel<1><<<grid, block, 0, s>>>(x, gamma, beta, mean, istd, y, M, C, L.TX, L.TY, L.rows_per_blk);
+    return hipGetLastError();
+}
+
+hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
+                  float *ws, int64_t M, int C, float eps, hipStream_t s)
+{
+    if (!x || !gamma || !beta || !y || !mean || !istd || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    const bool al = ((uintptr_t)x | (uintptr_t)ws | (uintptr_t)mean) % 16 == 0;
+    Lay2D L = layout2d(M, C, al, MAX_RBLK);
+    const dim3 grid(L.nblk, L.gy), block(BNT);
+    if (L.V == 4) bn_partial_kernel<4><<<grid, block, 0, s>>>(x, nullptr, nullptr, ws, M, C, L.TX, L.TY, L.rows_per_blk);
+    else bn_partial_kernel<1><<<grid, block, 0, s>>>(x, nullptr, nullptr, ws, M, C, L.TX, L.TY, L.rows_per_blk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    bn_stats_final_kernel<<<dim3(C), dim3(64), 0, s>>>(ws, x, mean, istd, L.nblk, C, (double)M, (double)eps);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return bn_apply(x, gamma, beta, mean, istd, y, M, C, s);
+}
+
+hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const float *mean, const float *istd,
+                  float *dx, float *dgamma, float *dbeta, float *ws, int64_t M, int C, bool accumulate, hipStream_t s)
+{
+    if (!x || !dy || !gamma || !mean || !istd || !dx || !dgamma || !dbeta || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    const bool al = ((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx | (uintptr_t)ws | (uintptr_t)mean | (uintptr_t)istd |
+                     (uintptr_t)gamma | (uintptr_t)dgamma | (uintptr_t)dbeta) % 16 == 0;
+    Lay2D L = layout2d(M, C, al, MAX_RBLK);
+    {
+        const dim3 grid(L.nblk, L.gy), block(BNT);
+        if (L.V == 4) bn_partial_kernel<4><<<grid, block, 0, s>>>(x, dy, mean, ws, M, C, L.TX, L.TY, L.rows_per_blk);
+        else bn_partial_kernel<1><<<grid, block, 0, s>>>(x, dy, mean, ws, M, C, L.TX, L.TY, L.rows_per_blk);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        bn_grad_final_kernel<<<dim3(C), dim3(64), 0, s>>>(ws, istd, dgamma, dbeta, L.nblk, C);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    L = layout2d(M, C, al, 8192);
+    const dim3 grid(L.nblk, L.gy), block(BNT);
+    const float inv_m = (float)(1.0 / (double)M);
+#define BWD_APPLY(V, A) bn_bwd_apply_kernel<V, A><<<grid, block, 0, s>>>(x, dy, gamma, mean, istd, dgamma, dbeta, dx, M, C, L.TX, L.TY, L.rows_per_blk, inv_m)
+    if (L.V == 4) { if (accumulate) BWD_APPLY(4, true); else BWD_APPLY(4, false); }
+    else { if (accumulate) BWD_APPLY(1, true); else BWD_APPLY(1, false); }
+#undef BWD_APPLY
+    return hipGetLastError();
+}
+
+hipError_t relu_fwd(const float *x, float *y, int64_t n, hipStream_t s) { return launch_ew<EW_RELU_F>(x, nullptr, y, n, s); }
+hipError_t relu_bwd(const float *y, const float *dy, float *dx, int64_t n, bool accumulate, hipStream_t s)
+{
+    if (!dy) return hipErrorInvalidValue;
+    return accumulate ? launch_ew<EW_RELU_B_ACC>(y, dy, dx, n, s) : launch_ew<EW_RELU_B>(y, dy, dx, n, s);
+}
+hipError_t add_fwd(const float *a, const float *b, float *z, int64_t n, hipStream_t s)
+{
+    if (!b) return hipErrorInvalidValue;
+    return launch_ew<EW_ADD>(a, b, z, n, s);
+}
+hipError_t accumulate(float *dst, const float *src, int64_t n, hipStream_t s) { return launch_ew<EW_ACC>(src, nullptr, dst, n, s); }
+hipError_t copy(float *dst, const float *src, int64_t n, hipStream_t s) { return launch_ew<EW_COPY>(src, nullptr, dst, n, s); }
+
+}  // namespace pk

@@ -1,0 +1,585 @@
+// fp32 MFMA implicit-GEMM convolution for gfx950: forward, data gradient, filter gradient.
+//
+// The paper (section 3.3) only says that convolution layers carry "large computation
+// complexity" and are what hides swap traffic; it uses a vendor library for them.  Here
+// they are written for CDNA4: channels-last tensors make every GEMM operand row a run of
+// contiguous channels, tiles are staged through LDS with 16-byte loads/stores, and each
+// 64-lane wavefront owns a TM x TN grid of 32x32 accumulators fed by
+// v_mfma_f32_32x32x2_f32.  No atomics: the filter gradient's long reduction is split over
+// workgroups into a workspace and summed in a fixed order.
+#include "kernels.h"
+
+namespace pk {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int BK = 16;   // reduction slice per main-loop iteration
+constexpr int LDK = 20;  // LDS row stride (floats) of [row][k] tiles: 16-byte rows, conflict-free b128 reads
+constexpr int NXCD = 8;
+
+struct IGemmP {
+    const float *src;  // forward: x; data gradient: dy (channels-last)
+    const float *wgt;  // [Nout][Kred]
+    float *dst;        // [M][Nout]
+    int M, Nout, Kred, Cs;
+    int Dr, Hr, Wr;  // spatial dims the GEMM rows enumerate
+    int Ds, Hs, Ws;  // spatial dims of src
+    int kd, kh, kw, sd, sh, sw, pd, ph, pw;
+    int tiles_n, total_tiles, chunk;
+};
+
+// coordinate in the source tensor touched by filter tap `a` for a row whose base is `base`
+template <bool DGRAD>
+__device__ __forceinline__ bool src_coord(int base, int a, int s, int S, int &q)
+{
+    if (!DGRAD) {
+        q = base + a;
+        return (unsigned)q < (unsigned)S;
+    } else {
+        const int t = base - a;
+        if (t < 0) return false;
+        if (s == 1) {
+            q = t;
+        } else {
+            q = t / s;
+            if (q * s != t) return false;
+        }
+        return q < S;
+    }
+}
+
+// XCD-aware tile order: hardware deals consecutive workgroup ids round-robin to the 8
+// XCDs; give each XCD a contiguous range of tiles so that neighbours share its L2.
+__device__ __forceinline__ int remap_tile(int wg, int chunk) { return (wg % NXCD) * chunk + wg / NXCD; }
+
+template <int WGM, int WGN, int TM, int TN, bool VEC, bool DGRAD, bool ACCUM>
+__global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
+{
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    constexpr int A_V = (BM * 4 + NT - 1) / NT, B_V = (BN * 4 + NT - 1) / NT;  // float4 loads per thread (VEC)
+    constexpr int A_S = BM * 16 / NT, B_S = BN * 16 / NT;                      // scalar loads per thread
+    static_assert(BM * 16 % NT == 0 && BN * 16 % NT == 0, "tile/threads mismatch");
+
+    __shared__ __attribute__((aligned(16))) float As[BM * LDK];
+    __shared__ __attribute__((aligned(16))) float Bs[BN * LDK];
+    __shared__ int4 rowinfo[BM];
+
+    const int tid = threadIdx.x;
+    const int logical = remap_tile(blockIdx.x, p.chunk);
+    if (logical >= p.total_tiles) return;
+    const int m0 = (logical / p.tiles_n) * BM, n0 = (logical % p.tiles_n) * BN;
+
+    for (int r = tid; r < BM; r += NT) {
+        const int m = m0 + r;
+        int4 ri = make_int4(-1, 0, 0, 0);
+        if (m < p.M) {
+            const int w_ = m % p.Wr;
+            int t = m / p.Wr;
+            const int h_ = t % p.Hr;
+            t /= p.Hr;
+            const int d_ = t % p.Dr;
+            const int n = t / p.Dr;
+            ri = DGRAD ? make_int4(n, d_ + p.pd, h_ + p.ph, w_ + p.pw)
+                       : make_int4(n, d_ * p.sd - p.pd, h_ * p.sh - p.ph, w_ * p.sw - p.pw);
+        }
+        rowinfo[r] = ri;
+    }
+    __syncthreads();
+
+    float4 av[VEC ? A_V : 1], bv[VEC ? B_V : 1];
+    float as[VEC ? 1 : A_S], bs[VEC ? 1 : B_S];
+    int4 ri_reg[VEC ? A_V : 1];
+    if (VEC) {
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) ri_reg[i] = rowinfo[(tid / 4 + i * (NT / 4)) % BM];
+    }
+
+    auto load_tiles = [&](int k0) {
+        if (VEC) {
+            const int k = k0 + 4 * (tid % 4);
+            const bool kok = k < p.Kred;
+            int a = 0, b = 0, e = 0, c = 0;
+            if (kok) {
+                const int tap = k / p.Cs;
+                c = k - tap * p.Cs;
+                e = tap % p.kw;
+                const int t2 = tap / p.kw;
+                b = t2 % p.kh;
+                a = t2 / p.kh;
+            }
+#pragma unroll
+            for (int i = 0; i < A_V; ++i) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                const int4 ri = ri_reg[i];
+                int qd, qh, qw;
+                if (kok && tid / 4 + i * (NT / 4) < BM && ri.x >= 0 && src_coord<DGRAD>(ri.y, a, p.sd, p.Ds, qd) &&
+                    src_coord<DGRAD>(ri.z, b, p.sh, p.Hs, qh) && src_coord<DGRAD>(ri.w, e, p.sw, p.Ws, qw)) {
+                    const int64_t off = ((((int64_t)ri.x * p.Ds + qd) * p.Hs + qh) * p.Ws + qw) * p.Cs + c;
+                    v = *reinterpret_cast<const float4 *>(p.src + off);
+                }
+                av[i] = v;
+            }
+#pragma unroll
+            for (int i = 0; i < B_V; ++i) {
+                const int n = n0 + tid / 4 + i * (NT / 4);
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (kok && tid / 4 + i * (NT / 4) < BN && n < p.Nout) v = *reinterpret_cast<const float4 *>(p.wgt + (int64_t)n * p.Kred + k);
+                bv[i] = v;
+            }
+        } else {
+            const int k = k0 + (tid % 16);
+            const bool kok = k < p.Kred;
+            int a = 0, b = 0, e = 0, c = 0;
+            if (kok) {
+                const int tap = k / p.Cs;
+                c = k - tap * p.Cs;
+                e = tap % p.kw;
+                const int t2 = tap / p.kw;
+                b = t2 % p.kh;
+                a = t2 / p.kh;
+            }
+#pragma unroll
+            for (int i = 0; i < A_S; ++i) {
+                float v = 0.f;
+                const int4 ri = rowinfo[tid / 16 + i * (NT / 16)];
+                int qd, qh, qw;
+                if (kok && ri.x >= 0 && src_coord<DGRAD>(ri.y, a, p.sd, p.Ds, qd) &&
+                    src_coord<DGRAD>(ri.z, b, p.sh, p.Hs, qh) && src_coord<DGRAD>(ri.w, e, p.sw, p.Ws, qw)) {
+                    const int64_t off = ((((int64_t)ri.x * p.Ds + qd) * p.Hs + qh) * p.Ws + qw) * p.Cs + c;
+                    v = p.src[off];
+                }
+                as[i] = v;
+            }
+#pragma unroll
+            for (int i = 0; i < B_S; ++i) {
+                const int n = n0 + tid / 16 + i * (NT / 16);
+                bs[i] = (kok && n < p.Nout) ? p.wgt[(int64_t)n * p.Kred + k] : 0.f;
+            }
+        }
+    };
+
+    auto store_tiles = [&]() {
+        if (VEC) {
+#pragma unroll
+            for (int i = 0; i < A_V; ++i)
+                if (tid / 4 + i * (NT / 4) < BM)
+                    *reinterpret_cast<float4 *>(&As[(tid / 4 + i * (NT / 4)) * LDK + 4 * (tid % 4)]) = av[i];
+#pragma unroll
+            for (int i = 0; i < B_V; ++i)
+                if (tid / 4 + i * (NT / 4) < BN)
+                    *reinterpret_cast<float4 *>(&Bs[(tid / 4 + i * (NT / 4)) * LDK + 4 * (tid % 4)]) = bv[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_S; ++i) As[(tid / 16 + i * (NT / 16)) * LDK + (tid % 16)] = as[i];
+#pragma unroll
+            for (int i = 0; i < B_S; ++i) Bs[(tid / 16 + i * (NT / 16)) * LDK + (tid % 16)] = bs[i];
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int lane = tid % 64, wave = tid / 64;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int r = lane % 32, h = lane / 32;
+
+    const int nk = (p.Kred + BK - 1) / BK;
+    load_tiles(0);
+    for (int it = 0; it < nk; ++it) {
+        store_tiles();
+        __syncthreads();
+        if (it + 1 < nk) load_tiles((it + 1) * BK);
+
+        // lane half h covers k = 8h .. 8h+7 of the slice; MFMA step t multiplies k = 8h + t
+        float af[TM][8], bf[TN][8];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const float *ap = &As[(wm * TM * 32 + i * 32 + r) * LDK + h * 8];
+            const float4 lo = *reinterpret_cast<const float4 *>(ap);
+            const float4 hi = *reinterpret_cast<const float4 *>(ap + 4);
+            af[i][0] = lo.x; af[i][1] = lo.y; af[i][2] = lo.z; af[i][3] = lo.w;
+            af[i][4] = hi.x; af[i][5] = hi.y; af[i][6] = hi.z; af[i][7] = hi.w;
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const float *bp = &Bs[(wn * TN * 32 + j * 32 + r) * LDK + h * 8];
+            const float4 lo = *reinterpret_cast<const float4 *>(bp);
+            const float4 hi = *reinterpret_cast<const float4 *>(bp + 4);
+            bf[j][0] = lo.x; bf[j][1] = lo.y; bf[j][2] = lo.z; bf[j][3] = lo.w;
+            bf[j][4] = hi.x; bf[j][5] = hi.y; bf[j][6] = hi.z; bf[j][7] = hi.w;
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
+        __syncthreads();
+    }
+
+    // accumulator element v of a lane is row 8*(v/4) + 4*h + v%4, column r of the 32x32 tile
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * TN * 32 + j * 32 + r;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * TM * 32 + i * 32 + (v / 4) * 8 + h * 4 + (v % 4);
+                if (m < p.M && col < p.Nout) {
+                    const int64_t idx = (int64_t)m * p.Nout + col;
+                    float val = acc[i][j][v];
+                    if (ACCUM) val = p.dst[idx] + val;
+                    p.dst[idx] = val;
+                }
+            }
+        }
+}
+
+template <int WGM, int WGN, int TM, int TN, bool DGRAD>
+hipError_t launch_igemm(IGemmP p, bool vec, bool accum, hipStream_t s)
+{
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    const int tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.Nout + BN - 1) / BN;
+    p.total_tiles = tiles_m * p.tiles_n;
+    p.chunk = (p.total_tiles + NXCD - 1) / NXCD;
+    const dim3 grid(p.chunk * NXCD), block(64 * WGM * WGN);
+    if (vec) {
+        if (accum) igemm_kernel<WGM, WGN, TM, TN, true, DGRAD, true><<<grid, block, 0, s>>>(p);
+        else igemm_kernel<WGM, WGN, TM, TN, true, DGRAD, false><<<grid, block, 0, s>>>(p);
+    } else {
+        if (accum) igemm_kernel<WGM, WGN, TM, TN, false, DGRAD, true><<<grid, block, 0, s>>>(p);
+        else igemm_kernel<WGM, WGN, TM, TN, false, DGRAD, false><<<grid, block, 0, s>>>(p);
+    }
+    return hipGetLastError();
+}
+
+template <bool DGRAD>
+hipError_t dispatch_igemm(const IGemmP &p, bool accum, hipStream_t s)
+{
+    const bool vec = (p.Cs % 4 == 0) && ((uintptr_t)p.src % 16 == 0) && ((uintptr_t)p.wgt % 16 == 0);
+    if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, DGRAD>(p, vec, accum, s);
+    if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, DGRAD>(p, vec, accum, s);
+    return launch_igemm<2, 2, 2, 2, DGRAD>(p, vec, accum, s);
+}
+
+bool geom_ok(const ConvGeom &g)
+{
+    if (g.N <= 0 || g.C <= 0 || g.K <= 0 || g.D <= 0 || g.H <= 0 || g.W <= 0) return false;
+    if (g.kd <= 0 || g.kh <= 0 || g.kw <= 0 || g.sd <= 0 || g.sh <= 0 || g.sw <= 0) return false;
+    if (g.pd < 0 || g.ph < 0 || g.pw < 0) return false;
+    if (g.Do != (g.D + 2 * g.pd - g.kd) / g.sd + 1 || g.Ho != (g.H + 2 * g.ph - g.kh) / g.sh + 1 ||
+        g.Wo != (g.W + 2 * g.pw - g.kw) / g.sw + 1)
+        return false;
+    if (g.Do <= 0 || g.Ho <= 0 || g.Wo <= 0) return false;
+    // row indices and reduction lengths are 32-bit inside the kernels
+    const int64_t lim = (int64_t)1 << 31;
+    if (g.rows_out() >= lim - 4096 || g.rows_in() >= lim - 4096) return false;
+    if (g.taps() * g.C >= lim || g.taps() * g.K >= lim) return false;
+    return true;
+}
+
+// ------------------------------------------------------------------ filter gradient
+
+struct WGradP {
+    const float *dy;  // [M][K]
+    const float *x;   // channels-last input
+    float *out;       // nsplit == 1: dw [K][Kred]; else partials [nsplit][K][Kred]
+    int M, K, Kred, C;
+    int Do, Ho, Wo, D, H, W;
+    int kd, kh, kw, sd, sh, sw, pd, ph, pw;
+    int tiles_n, chunk_rows, nsplit;
+};
+
+template <int WGM, int WGN, int TM, int TN, bool VECA, bool VECB>
+__global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
+{
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;  // BM over output channels, BN over taps*C
+    constexpr int LDA = (BM + 63) / 64 * 64 + 32, LDB = (BN + 63) / 64 * 64 + 32;
+    constexpr int A_V = 4 * BM / NT, B_V = 4 * BN / NT, A_S = 16 * BM / NT, B_S = 16 * BN / NT;
+    static_assert(4 * BM % NT == 0 && 4 * BN % NT == 0, "tile/threads mismatch");
+
+    __shared__ __attribute__((aligned(16))) float As[BK * LDA];
+    __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
+
+    const int tid = threadIdx.x;
+    const int k0 = (blockIdx.x / p.tiles_n) * BM;  // first output channel of the tile
+    const int j0 = (blockIdx.x % p.tiles_n) * BN;  // first (tap, c) column of the tile
+    const int split = blockIdx.y;
+    const int mbeg = split * p.chunk_rows;
+    const int mend = min(p.M, mbeg + p.chunk_rows);
+
+    float4 av[VECA ? A_V : 1], bv[VECB ? B_V : 1];
+    float as[VECA ? 1 : A_S], bs[VECB ? 1 : B_S];
+
+    // column of x-patches this thread gathers (fixed for the whole kernel in the VECB path)
+    int vb_a = 0, vb_b = 0, vb_e = 0, vb_c = 0;
+    bool vb_ok = false;
+    if (VECB) {
+        const int col = j0 + 4 * (tid % (BN / 4));
+        vb_ok = col < p.Kred;
+        if (vb_ok) {
+            const int tap = col / p.C;
+            vb_c = col - tap * p.C;
+            vb_e = tap % p.kw;
+            const int t2 = tap / p.kw;
+            vb_b = t2 % p.kh;
+            vb_a = t2 / p.kh;
+        }
+    }
+
+    auto x_offset = [&](int m, int a, int b, int e, int c, int64_t &off) -> bool {
+        const int ow = m % p.Wo;
+        int t = m / p.Wo;
+        const int oh = t % p.Ho;
+        t /= p.Ho;
+        const int od = t % p.Do;
+        const int n = t / p.Do;
+        const int id = od * p.sd - p.pd + a, ih = oh * p.sh - p.ph + b, iw = ow * p.sw - p.pw + e;
+        if ((unsigned)id >= (unsigned)p.D || (unsigned)ih >= (unsigned)p.H || (unsigned)iw >= (unsigned)p.W) return false;
+        off = ((((int64_t)n * p.D + id) * p.H + ih) * p.W + iw) * p.C + c;
+        return true;
+    };
+
+    auto load_tiles = [&](int mb) {
+        if (VECA) {
+#pragma unroll
+            for (int i = 0; i < A_V; ++i) {
+                const int f = tid + i * NT;
+                const int m = mb + f / (BM / 4), col = k0 + 4 * (f % (BM / 4));
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (m < mend && col < p.K) v = *reinterpret_cast<const float4 *>(p.dy + (int64_t)m * p.K + col);
+                av[i] = v;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_S; ++i) {
+                const int f = tid + i * NT;
+                const int m = mb + f / BM, col = k0 + f % BM;
+                as[i] = (m < mend && col < p.K) ? p.dy[(int64_t)m * p.K + col] : 0.f;
+            }
+        }
+        if (VECB) {
+#pragma unroll
+            for (int i = 0; i < B_V; ++i) {
+                const int m = mb + (tid + i * NT) / (BN / 4);
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                int64_t off;
+                if (vb_ok && m < mend && x_offset(m, vb_a, vb_b, vb_e, vb_c, off))
+                    v = *reinterpret_cast<const float4 *>(p.x + off);
+                bv[i] = v;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < B_S; ++i) {
+                const int f = tid + i * NT;
+                const int m = mb + f / BN, col = j0 + f % BN;
+                float v = 0.f;
+                if (m < mend && col < p.Kred) {
+                    const int tap = col / p.C;
+                    const int c = col - tap * p.C;
+                    const int e = tap % p.kw;
+                    const int t2 = tap / p.kw;
+                    int64_t off;
+                    if (x_offset(m, t2 / p.kh, t2 % p.kh, e, c, off)) v = p.x[off];
+                }
+                bs[i] = v;
+            }
+        }
+    };
+
+    auto store_tiles = [&]() {
+        if (VECA) {
+#pragma unroll
+            for (int i = 0; i < A_V; ++i) {
+                const int f = tid + i * NT;
+                *reinterpret_cast<float4 *>(&As[(f / (BM / 4)) * LDA + 4 * (f % (BM / 4))]) = av[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_S; ++i) {
+                const int f = tid + i * NT;
+                As[(f / BM) * LDA + f % BM] = as[i];
+            }
+        }
+        if (VECB) {
+#pragma unroll
+            for (int i = 0; i < B_V; ++i) {
+                const int f = tid + i * NT;
+                *reinterpret_cast<float4 *>(&Bs[(f / (BN / 4)) * LDB + 4 * (f % (BN / 4))]) = bv[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < B_S; ++i) {
+                const int f = tid + i * NT;
+                Bs[(f / BN) * LDB + f % BN] = bs[i];
+            }
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int lane = tid % 64, wave = tid / 64;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int r = lane % 32, h = lane / 32;
+
+    if (mbeg < mend) load_tiles(mbeg);
+    for (int mb = mbeg; mb < mend; mb += BK) {
+        store_tiles();
+        __syncthreads();
+        if (mb + BK < mend) load_tiles(mb + BK);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            float af[TM], bf[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = As[(2 * t + h) * LDA + wm * TM * 32 + i * 32 + r];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bf[j] = Bs[(2 * t + h) * LDB + wn * TN * 32 + j * 32 + r];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    float *out = p.out + (int64_t)split * p.K * p.Kred;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = j0 + wn * TN * 32 + j * 32 + r;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = k0 + wm * TM * 32 + i * 32 + (v / 4) * 8 + h * 4 + (v % 4);
+                if (k < p.K && col < p.Kred) out[(int64_t)k * p.Kred + col] = acc[i][j][v];
+            }
+        }
+}
+
+// dw[i] = partial[0][i] + partial[1][i] + ... in split order
+__global__ void reduce_splits_kernel(const float *__restrict__ part, float *__restrict__ dw, int64_t n, int nsplit)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = part[i];
+    for (int k = 1; k < nsplit; ++k) s += part[(int64_t)k * n + i];
+    dw[i] = s;
+}
+
+struct WGradCfg {
+    int bm, bn, nsplit, chunk_rows;
+};
+
+constexpr size_t WGRAD_WS_CAP = (size_t)64 << 20;
+
+WGradCfg wgrad_cfg(const ConvGeom &g)
+{
+    WGradCfg c;
+    const int64_t M = g.rows_out(), Kred = g.taps() * g.C;
+    c.bm = g.K <= 32 ? 32 : (g.K <= 64 ? 64 : 128);
+    c.bn = 128;
+    const int64_t tiles = ((g.K + c.bm - 1) / c.bm) * ((Kred + c.bn - 1) / c.bn);
+    int64_t ns = (2048 + tiles - 1) / tiles;
+    const int64_t max_by_rows = (M + 63) / 64;
+    if (ns > max_by_rows) ns = max_by_rows;
+    const int64_t max_by_ws = (int64_t)(WGRAD_WS_CAP / ((size_t)g.K * Kred * sizeof(float)));
+    if (ns > max_by_ws) ns = max_by_ws;
+    if (ns < 1) ns = 1;
+    int64_t chunk = (M + ns - 1) / ns;
+    chunk = (chunk + BK - 1) / BK * BK;
+    c.chunk_rows = (int)chunk;
+    c.nsplit = (int)((M + chunk - 1) / chunk);
+    return c;
+}
+
+template <int WGM, int WGN, int TM, int TN>
+hipError_t launch_wgrad(WGradP p, bool veca, bool vecb, hipStream_t s)
+{
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    const int tiles_m = (p.K + BM - 1) / BM;
+    p.tiles_n = (p.Kred + BN - 1) / BN;
+    const dim3 grid(tiles_m * p.tiles_n, p.nsplit), block(64 * WGM * WGN);
+    if (veca && vecb) wgrad_kernel<WGM, WGN, TM, TN, true, true><<<grid, block, 0, s>>>(p);
+    else if (veca) wgrad_kernel<WGM, WGN, TM, TN, true, false><<<grid, block, 0, s>>>(p);
+    else if (vecb) wgrad_kernel<WGM, WGN, TM, TN, false, true><<<grid, block, 0, s>>>(p);
+    else wgrad_kernel<WGM, WGN, TM, TN, false, false><<<grid, block, 0, s>>>(p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s)
+{
+    if (!x || !w_krsc || !y || !geom_ok(g)) return hipErrorInvalidValue;
+    IGemmP p;
+    p.src = x; p.wgt = w_krsc; p.dst = y;
+    p.M = (int)g.rows_out(); p.Nout = g.K; p.Kred = (int)(g.taps() * g.C); p.Cs = g.C;
+    p.Dr = g.Do; p.Hr = g.Ho; p.Wr = g.Wo; p.Ds = g.D; p.Hs = g.H; p.Ws = g.W;
+    p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
+    return dispatch_igemm<false>(p, false, s);
+}
+
+hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g, bool accumulate, hipStream_t s)
+{
+    if (!dy || !w_crsk || !dx || !geom_ok(g)) return hipErrorInvalidValue;
+    IGemmP p;
+    p.src = dy; p.wgt = w_crsk; p.dst = dx;
+    p.M = (int)g.rows_in(); p.Nout = g.C; p.Kred = (int)(g.taps() * g.K); p.Cs = g.K;
+    p.Dr = g.D; p.Hr = g.H; p.Wr = g.W; p.Ds = g.Do; p.Hs = g.Ho; p.Ws = g.Wo;
+    p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
+    return dispatch_igemm<true>(p, accumulate, s);
+}
+
+size_t conv_wgrad_workspace(const ConvGeom &g)
+{
+    if (!geom_ok(g)) return 0;
+    const WGradCfg c = wgrad_cfg(g);
+    return c.nsplit > 1 ? (size_t)c.nsplit * g.K * g.taps() * g.C * sizeof(float) : 0;
+}
+
+hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *workspace, const ConvGeom &g, hipStream_t s)
+{
+    if (!dy || !x || !dw_krsc || !geom_ok(g)) return hipErrorInvalidValue;
+    const WGradCfg c = wgrad_cfg(g);
+    if (c.nsplit > 1 && !workspace) return hipErrorInvalidValue;
+    WGradP p;
+    p.dy = dy; p.x = x; p.out = c.nsplit > 1 ? workspace : dw_krsc;
+    p.M = (int)g.rows_out(); p.K = g.K; p.Kred = (int)(g.taps() * g.C); p.C = g.C;
+    p.Do = g.Do; p.Ho = g.Ho; p.Wo = g.Wo; p.D = g.D; p.H = g.H; p.W = g.W;
+    p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
+    p.chunk_rows = c.chunk_rows; p.nsplit = c.nsplit; p.tiles_n = 0;
+    const bool veca = (g.K % 4 == 0) && ((uintptr_t)dy % 16 == 0);
+    const bool vecb = (g.C % 4 == 0) && ((uintptr_t)x % 16 == 0);
+    hipError_t e;
+    if (c.bm == 32) e = launch_wgrad<1, 2, 1, 2>(p, veca, vecb, s);
+    else if (c.bm == 64) e = launch_wgrad<1, 2, 2, 2>(p, veca, vecb, s);
+    else e = launch_wgrad<2, 2, 2, 2>(p, veca, vecb, s);
+    if (e != hipSuccess) return e;
+    if (c.nsplit > 1) {
+        const int64_t n = (int64_t)g.K * p.Kred;
+        reduce_splits_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(workspace, dw_krsc, n, c.nsplit);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+}  // namespace pk

@@ -1,0 +1,71 @@
+// Host-side launchers of the gfx950 kernels.  All tensors are fp32, channels-last on the
+// device: activations N,(D,)H,W,C; filters K,(kd,)kh,kw,C ("KRSC") plus a transposed copy
+// C,(kd,)kh,kw,K ("CRSK") for the data gradient.  Every launcher checks its operands on
+// the host and returns hipErrorInvalidValue instead of launching on a mismatch.
+// All kernels are deterministic (fixed-order reductions, no atomics) and do not depend on
+// where in memory a tensor sits beyond 256-byte alignment.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace pk {
+
+struct ConvGeom {
+    int N, C, D, H, W;     // input, channels-last N,D,H,W,C (D == 1 for 2-d)
+    int K;                 // output channels
+    int Do, Ho, Wo;        // output spatial size
+    int kd, kh, kw, sd, sh, sw, pd, ph, pw;
+    int64_t rows_out() const { return (int64_t)N * Do * Ho * Wo; }
+    int64_t rows_in() const { return (int64_t)N * D * H * W; }
+    int64_t taps() const { return (int64_t)kd * kh * kw; }
+};
+
+// y[N,Do,Ho,Wo,K] = cross-correlation of x with w_krsc (implicit GEMM M=rows_out, N=K, K=taps*C)
+hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s);
+// dx[N,D,H,W,C] (+)= data gradient; w_crsk is the transposed filter copy
+hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g, bool accumulate, hipStream_t s);
+// bytes of split-K workspace conv_wgrad needs for this geometry (0 if none)
+size_t conv_wgrad_workspace(const ConvGeom &g);
+// dw_krsc[K,taps,C] = filter gradient, deterministic split-K through `workspace`
+hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *workspace, const ConvGeom &g, hipStream_t s);
+
+// number of floats of scratch the BN reductions need for an [M][C] tensor
+size_t bn_workspace_floats(int64_t M, int C);
+// batch statistics (mean, 1/sqrt(var+eps)) then y = gamma*(x-mean)*istd + beta
+hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
+                  float *ws, int64_t M, int C, float eps, hipStream_t s);
+// apply only, with saved statistics (used when a BN output is recomputed)
+hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const float *mean, const float *istd,
+                    float *y, int64_t M, int C, hipStream_t s);
+// dgamma, dbeta and dx (dx may alias dy); accumulate adds into dx instead of overwriting
+hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const float *mean, const float *istd,
+                  float *dx, float *dgamma, float *dbeta, float *ws, int64_t M, int C, bool accumulate, hipStream_t s);
+
+hipError_t relu_fwd(const float *x, float *y, int64_t n, hipStream_t s);
+// dx (+)= dy where y > 0 (dx may alias dy when not accumulating)
+hipError_t relu_bwd(const float *y, const float *dy, float *dx, int64_t n, bool accumulate, hipStream_t s);
+hipError_t add_fwd(const float *a, const float *b, float *z, int64_t n, hipStream_t s);
+// dst += src
+hipError_t accumulate(float *dst, const float *src, int64_t n, hipStream_t s);
+hipError_t copy(float *dst, const float *src, int64_t n, hipStream_t s);
+
+struct PoolGeom {
+    int N, C, D, H, W, Do, Ho, Wo, kd, kh, kw, sd, sh, sw, pd, ph, pw;
+};
+hipError_t maxpool_fwd(const float *x, float *y, const PoolGeom &g, hipStream_t s);
+hipError_t maxpool_bwd(const float *x, const float *dy, float *dx, const PoolGeom &g, bool accumulate, hipStream_t s);
+// x[N][S][C] -> y[N][C]
+hipError_t gavgpool_fwd(const float *x, float *y, int N, int64_t S, int C, hipStream_t s);
+hipError_t gavgpool_bwd(const float *dy, float *dx, int N, int64_t S, int C, bool accumulate, hipStream_t s);
+
+// y[n][o] += b[o];  db[o] = sum_n dy[n][o]
+hipError_t bias_add(float *y, const float *b, int N, int O, hipStream_t s);
+hipError_t bias_grad(const float *dy, float *db, int N, int O, hipStream_t s);
+
+// loss[0] = mean_n (logsumexp(z_n) - z_n[t_n]); per_sample is N floats of scratch
+hipError_t softmax_ce_fwd(const float *z, const int32_t *labels, float *per_sample, float *loss, int N, int K, hipStream_t s);
+// dz (+)= (softmax(z) - onehot)/N
+hipError_t softmax_ce_bwd(const float *z, const int32_t *labels, float *dz, int N, int K, bool accumulate, hipStream_t s);
+
+}  // namespace pk

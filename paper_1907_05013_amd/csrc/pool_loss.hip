@@ -1,0 +1,265 @@
+// Pooling, global average pooling, FC bias and softmax cross-entropy kernels for gfx950.
+// Channels-last tensors: consecutive lanes take consecutive channels, so every access of a
+// wavefront is one contiguous run.  No atomics anywhere: the max-pool gradient is a gather
+// (each input element visits the windows that contain it in scan order), which makes it
+// deterministic and gives the same summation order as scattering window by window.
+#include "kernels.h"
+
+namespace pk {
+namespace {
+
+// first maximal in-bounds element (scan order d,h,w) of window (od,oh,ow) for channel c of image n
+__device__ __forceinline__ void window_argmax(const float *__restrict__ x, const PoolGeom &g, int n, int od, int oh, int ow, int c,
+                                              float &best, int &bd, int &bh, int &bw)
+{
+    bd = -1; bh = -1; bw = -1;
+    best = -INFINITY;
+    for (int a = 0; a < g.kd; ++a) {
+        const int id = od * g.sd - g.pd + a;
+        if ((unsigned)id >= (unsigned)g.D) continue;
+        for (int b = 0; b < g.kh; ++b) {
+            const int ih = oh * g.sh - g.ph + b;
+            if ((unsigned)ih >= (unsigned)g.H) continue;
+            for (int e = 0; e < g.kw; ++e) {
+                const int iw = ow * g.sw - g.pw + e;
+                if ((unsigned)iw >= (unsigned)g.W) continue;
+                const float v = x[((((int64_t)n * g.D + id) * g.H + ih) * g.W + iw) * g.C + c];
+                if (bd < 0 || v > best) { best = v; bd = id; bh = ih; bw = iw; }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, PoolGeom g, int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % g.C);
+    int64_t t = i / g.C;
+    const int ow = (int)(t % g.Wo); t /= g.Wo;
+    const int oh = (int)(t % g.Ho); t /= g.Ho;
+    const int od = (int)(t % g.Do);
+    const int n = (int)(t / g.Do);
+    float best; int bd, bh, bw;
+    window_argmax(x, g, n, od, oh, ow, c, best, bd, bh, bw);
+    y[i] = best;
+}
+
+__device__ __forceinline__ int ceil_div_pos(int a, int b) { return a <= 0 ? 0 : (a + b - 1) / b; }
+
+template <bool ACCUM>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy, float *dx, PoolGeom g, int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % g.C);
+    int64_t t = i / g.C;
+    const int iw = (int)(t % g.W); t /= g.W;
+    const int ih = (int)(t % g.H); t /= g.H;
+    const int id = (int)(t % g.D);
+    const int n = (int)(t / g.D);
+    // windows o with o*s - p <= i <= o*s - p + k - 1
+    const int od0 = ceil_div_pos(id + g.pd - g.kd + 1, g.sd), od1 = min(g.Do - 1, (id + g.pd) / g.sd);
+    const int oh0 = ceil_div_pos(ih + g.ph - g.kh + 1, g.sh), oh1 = min(g.Ho - 1, (ih + g.ph) / g.sh);
+    const int ow0 = ceil_div_pos(iw + g.pw - g.kw + 1, g.sw), ow1 = min(g.Wo - 1, (iw + g.pw) / g.sw);
+    float acc = 0.f;
+    for (int od = od0; od <= od1; ++od)
+        for (int oh = oh0; oh <= oh1; ++oh)
+            for (int ow = ow0; ow <= ow1; ++ow) {
+                float best; int bd, bh, bw;
+                window_argmax(x, g, n, od, oh, ow, c, best, bd, bh, bw);
+                if (bd == id && bh == ih && bw == iw)
+                    acc += dy[((((int64_t)n * g.Do + od) * g.Ho + oh) * g.Wo + ow) * g.C + c];
+            }
+    dx[i] = ACCUM ? dx[i] + acc : acc;
+}
+
+// y[n][c] = (1/S) sum_s x[n][s][c], s ascending
+__global__ __launch_bounds__(256) void gavgpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int N, int64_t S, int C)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)N * C) return;
+    const int c = (int)(i % C);
+    const int64_t n = i / C;
+    const float *p = x + n * S * C + c;
+    float s = 0.f;
+    for (int64_t k = 0; k < S; ++k) s += p[k * C];
+    y[i] = s / (float)S;
+}
+
+template <bool ACCUM>
+__global__ __launch_bounds__(256) void gavgpool_bwd_kernel(const float *__restrict__ dy, float *dx, int N, int64_t S, int C, int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % C);
+    const int64_t n = i / ((int64_t)S * C);
+    const float v = dy[n * C + c] / (float)S;
+    dx[i] = ACCUM ? dx[i] + v : v;
+}
+
+__global__ __launch_bounds__(256) void bias_add_kernel(float *y, const float *__restrict__ b, int64_t total, int O)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < total) y[i] += b[i % O];
+}
+
+// db[o] = sum_n dy[n][o], n ascending
+__global__ __launch_bounds__(256) void bias_grad_kernel(const float *__restrict__ dy, float *__restrict__ db, int N, int O)
+{
+    const int o = blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= O) return;
+    float s = 0.f;
+    for (int n = 0; n < N; ++n) s += dy[(int64_t)n * O + o];
+    db[o] = s;
+}
+
+__device__ __forceinline__ float block_reduce(float v, float *sh, bool is_max)
+{
+    // 256 threads: wavefront shuffle tree, then the 4 wave results combined in order
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float o = __shfl_down(v, off, 64);
+        v = is_max ? fmaxf(v, o) : v + o;
+    }
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+    __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    float r = sh[0];
+    for (int w = 1; w < (int)(blockDim.x / 64); ++w) r = is_max ? fmaxf(r, sh[w]) : r + sh[w];
+    return r;
+}
+
+// one block per sample: lse = max + log sum exp(z - max)
+__device__ __forceinline__ float row_lse(const float *__restrict__ zr, int K, float *sh)
+{
+    float mx = -INFINITY;
+    for (int j = threadIdx.x; j < K; j += blockDim.x) mx = fmaxf(mx, zr[j]);
+    mx = block_reduce(mx, sh, true);
+    float se = 0.f;
+    for (int j = threadIdx.x; j < K; j += blockDim.x) se += expf(zr[j] - mx);
+    se = block_reduce(se, sh, false);
+    return mx + logf(se);
+}
+
+__global__ __launch_bounds__(256) void softmax_ce_row_kernel(const float *__restrict__ z, const int32_t *__restrict__ labels,
+                                                              float *__restrict__ per_sample, int K)
+{
+    __shared__ float sh[4];
+    const int n = blockIdx.x;
+    const float *zr = z + (int64_t)n * K;
+    const float lse = row_lse(zr, K, sh);
+    if (threadIdx.x == 0) {
+        const int t = labels[n];
+        per_sample[n] = (t >= 0 && t < K) ? lse - zr[t] : 0.f;
+    }
+}
+
+__global__ __launch_bounds__(64) void loss_mean_kernel(const float *__restrict__ per_sample, float *__restrict__ loss, int N)
+{
+    double s = 0.0;
+    for (int n = threadIdx.x; n < N; n += 64) s += (double)per_sample[n];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+    if (threadIdx.x == 0) loss[0] = (float)(s / (double)N);
+}
+
+template <bool ACCUM>
+__global__ __launch_bounds__(256) void softmax_ce_bwd_kernel(const float *__restrict__ z, const int32_t *__restrict__ labels,
+                                                              float *dz, int K, float inv_n)
+{
+    __shared__ float sh[4];
+    const int n = blockIdx.x;
+    const float *zr = z + (int64_t)n * K;
+    const float lse = row_lse(zr, K, sh);
+    const int t = labels[n];
+    for (int j = threadIdx.x; j < K; j += blockDim.x) {
+        const float v = (expf(zr[j] - lse) - (j == t ? 1.f : 0.f)) * inv_n;
+        float *o = dz + (int64_t)n * K + j;
+        *o = ACCUM ? *o + v : v;
+    }
+}
+
+bool pool_ok(const PoolGeom &g)
+{
+    if (g.N <= 0 || g.C <= 0 || g.D <= 0 || g.H <= 0 || g.W <= 0) return false;
+    if (g.kd <= 0 || g.kh <= 0 || g.kw <= 0 || g.sd <= 0 || g.sh <= 0 || g.sw <= 0 || g.pd < 0 || g.ph < 0 || g.pw < 0) return false;
+    if (g.Do != (g.D + 2 * g.pd - g.kd) / g.sd + 1 || g.Ho != (g.H + 2 * g.ph - g.kh) / g.sh + 1 ||
+        g.Wo != (g.W + 2 * g.pw - g.kw) / g.sw + 1)
+        return false;
+    return g.Do > 0 && g.Ho > 0 && g.Wo > 0;
+}
+
+inline dim3 blocks_for(int64_t total) { return dim3((unsigned)((total + 255) / 256)); }
+
+}  // namespace
+
+hipError_t maxpool_fwd(const float *x, float *y, const PoolGeom &g, hipStream_t s)
+{
+    if (!x || !y || !pool_ok(g)) return hipErrorInvalidValue;
+    const int64_t total = (int64_t)g.N * g.Do * g.Ho * g.Wo * g.C;
+    maxpool_fwd_kernel<<<blocks_for(total), dim3(256), 0, s>>>(x, y, g, total);
+    return hipGetLastError();
+}
+
+hipError_t maxpool_bwd(const float *x, const float *dy, float *dx, const PoolGeom &g, bool accumulate, hipStream_t s)
+{
+    if (!x || !dy || !dx || !pool_ok(g)) return hipErrorInvalidValue;
+    const int64_t total = (int64_t)g.N * g.D * g.H * g.W * g.C;
+    if (accumulate) maxpool_bwd_kernel<true><<<blocks_for(total), dim3(256), 0, s>>>(x, dy, dx, g, total);
+    else maxpool_bwd_kernel<false><<<blocks_for(total), dim3(256), 0, s>>>(x, dy, dx, g, total);
+    return hipGetLastError();
+}
+
+hipError_t gavgpool_fwd(const float *x, float *y, int N, int64_t S, int C, hipStream_t s)
+{
+    if (!x || !y || N <= 0 || S <= 0 || C <= 0) return hipErrorInvalidValue;
+    gavgpool_fwd_kernel<<<blocks_for((int64_t)N * C), dim3(256), 0, s>>>(x, y, N, S, C);
+    return hipGetLastError();
+}
+
+hipError_t gavgpool_bwd(const float *dy, float *dx, int N, int64_t S, int C, bool accumulate, hipStream_t s)
+{
+    if (!dy || !dx || N <= 0 || S <= 0 || C <= 0) return hipErrorInvalidValue;
+    const int64_t total = (int64_t)N * S * C;
+    if (accumulate) gavgpool_bwd_kernel<true><<<blocks_for(total), dim3(256), 0, s>>>(dy, dx, N, S, C, total);
+    else gavgpool_bwd_kernel<false><<<blocks_for(total), dim3(256), 0, s>>>(dy, dx, N, S, C, total);
+    return hipGetLastError();
+}
+
+hipError_t bias_add(float *y, const float *b, int N, int O, hipStream_t s)
+{
+    if (!y || !b || N <= 0 || O <= 0) return hipErrorInvalidValue;
+    const int64_t total = (int64_t)N * O;
+    bias_add_kernel<<<blocks_for(total), dim3(256), 0, s>>>(y, b, total, O);
+    return hipGetLastError();
+}
+
+hipError_t bias_grad(const float *dy, float *db, int N, int O, hipStream_t s)
+{
+    if (!dy || !db || N <= 0 || O <= 0) return hipErrorInvalidValue;
+    bias_grad_kernel<<<blocks_for(O), dim3(256), 0, s>>>(dy, db, N, O);
+    return hipGetLastError();
+}
+
+hipError_t softmax_ce_fwd(const float *z, const int32_t *labels, float *per_sample, float *loss, int N, int K, hipStream_t s)
+{
+    if (!z || !labels || !per_sample || !loss || N <= 0 || K <= 0) return hipErrorInvalidValue;
+    softmax_ce_row_kernel<<<dim3(N), dim3(256), 0, s>>>(z, labels, per_sample, K);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    loss_mean_kernel<<<dim3(1), dim3(64), 0, s>>>(per_sample, loss, N);
+    return hipGetLastError();
+}
+
+hipError_t softmax_ce_bwd(const float *z, const int32_t *labels, float *dz, int N, int K, bool accumulate, hipStream_t s)
+{
+    if (!z || !labels || !dz || N <= 0 || K <= 0) return hipErrorInvalidValue;
+    const float inv_n = 1.f / (float)N;
+    if (accumulate) softmax_ce_bwd_kernel<true><<<dim3(N), dim3(256), 0, s>>>(z, labels, dz, K, inv_n);
+    else softmax_ce_bwd_kernel<false><<<dim3(N), dim3(256), 0, s>>>(z, labels, dz, K, inv_n);
+    return hipGetLastError();
+}
+
+}  // namespace pk

@@ -1,0 +1,306 @@
+"""Pins for the plan oracle (oracle/plan.py): the feature-map arithmetic the paper prints,
+closed forms of the timeline, the paper's 8-layer worked example, brute force over all
+classifications of tiny nets, an allocator cross-check and an independent schedule
+validator."""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import plan as P
+import schedule_check
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+BIG = 1 << 44
+
+
+def uniform_profile(G, fwd=1.0, bwd=2.0, out=0.5, inn=0.5):
+    nf = len(G.fmaps)
+    return P.Profile([fwd] * G.n, [bwd] * G.n, [fwd] * G.n, [out] * nf, [inn] * nf)
+
+
+def random_profile(G, rng, link=1.0):
+    nf = len(G.fmaps)
+    tf = list(rng.uniform(0.2, 3.0, G.n))
+    return P.Profile(tf, list(rng.uniform(0.2, 5.0, G.n)), list(np.array(tf) * rng.uniform(0.3, 1.0, G.n)),
+                     list(rng.uniform(0.1, 4.0, nf) * link), list(rng.uniform(0.1, 4.0, nf) * link))
+
+
+def relu_chain(nlayers=8, shape=(4, 8, 16, 16)):
+    net = workloads.Net()
+    t = net.input(shape)
+    for _ in range(nlayers):
+        t = net.relu(t)
+    t = net.gavgpool(t)
+    net.softmax_ce(t)
+    return net
+
+
+# ---- what the paper prints about ResNet-50 (section 1, section 5.2, table 3) -------------
+
+def test_resnet50_feature_map_arithmetic():
+    with open(os.path.join(GOLD, "resnet50_memory.json")) as f:
+        gold = json.load(f)
+    G = P.Graph(workloads.resnet50(batch=640))
+    assert len(G.fmaps) == gold["table3_total_maps"] == 105
+    gb640 = sum(G.fmap_bytes()) / 1e9
+    assert gb640 > gold["b640_more_than_gb"] and gb640 < 52.0          # "more than 50 GB"
+    ops = [G.ops[t] for t in G.fmaps]
+    assert ops.count("conv") == 53 and ops.count("relu") == 49
+    assert ops.count("maxpool") == ops.count("gavgpool") == ops.count("fc") == 1
+    cap = gold["device_gb"] * 2 ** 30
+    g255 = P.Graph(workloads.resnet50(batch=gold["first_failing_batch"]))
+    assert sum(g255.fmap_bytes()) > cap          # in-core fails from batch 256 on 16 GB
+    g128 = P.Graph(workloads.resnet50(batch=128))
+    assert sum(g128.fmap_bytes()) < cap
+    # table 3 keeps 66 maps at batch 512: the last 66 maps fit 16 GB, 67 + the rest's traffic do too,
+    # but the sum grows monotonically from the output end
+    g512 = P.Graph(workloads.resnet50(batch=512))
+    b = g512.fmap_bytes()
+    assert sum(b[-gold["table3_keep"]:]) < cap
+
+
+# ---- allocator ---------------------------------------------------------------------------
+
+def test_arena_random_against_bitmap():
+    rng = np.random.default_rng(3)
+    cap_units = 200
+    A = P.Arena(cap_units * 256)
+    owner = np.zeros(cap_units, np.int32)
+    tagmap = np.full(cap_units, -1, np.int64)
+    live = {}
+    seen = -1
+    nid = 0
+    for it in range(3000):
+        if live and rng.random() < 0.45:
+            k = list(live)[rng.integers(len(live))]
+            off, size = live.pop(k)
+            tag = int(rng.integers(-1, 6)) if rng.random() < 0.3 else -1
+            A.free(off, size, tag)
+            owner[off // 256:(off + size) // 256] = 0
+            tagmap[off // 256:(off + size) // 256] = tag
+        else:
+            units = int(rng.integers(1, 30))
+            top = bool(rng.random() < 0.4)
+            if rng.random() < 0.1:
+                seen = max(seen, int(rng.integers(-1, 6)))
+            r = A.alloc(units * 256, top, seen)
+            eff = np.where(tagmap <= seen, -1, tagmap)
+            # brute force: best achievable (max tag) over all free windows
+            best = None
+            for u in range(cap_units - units + 1):
+                if (owner[u:u + units] == 0).all():
+                    cost = eff[u:u + units].max()
+                    if best is None or cost < best:
+                        best = cost
+            if best is None:
+                assert r is None
+                continue
+            assert r is not None
+            off, tag = r
+            u = off // 256
+            assert (owner[u:u + units] == 0).all()
+            assert eff[u:u + units].max() == tag == best
+            nid += 1
+            owner[u:u + units] = nid
+            live[nid] = (off, units * 256)
+        assert A.used == int((owner != 0).sum()) * 256
+    assert A.peak <= cap_units * 256
+
+
+# ---- timeline closed forms -----------------------------------------------------------------
+
+def test_all_keep_time_is_sum_of_layers():
+    for net in (workloads.tiny_cnn(), workloads.resnet50(batch=2, size=32, blocks=(1, 1), width=4)):
+        G = P.Graph(net)
+        rng = np.random.default_rng(1)
+        prof = random_profile(G, rng)
+        S = P.build_schedule(G, [P.KEEP] * len(G.fmaps), BIG)
+        T, LO, LI = P.simulate(G, S, prof)
+        expect = sum(prof.t_fwd[i] for i in range(1, G.n)) + sum(prof.t_bwd[i] for i in range(1, G.n))
+        assert abs(T - expect) < 1e-9 and not LO and not LI
+        assert all(c[0] in (P.KF, P.KB) for c in S.cmds)
+        # in-core peak: every feature map plus at least the loss gradient is live at the turn
+        assert S.peak >= sum(G.fmap_bytes())
+
+
+def test_chain_swap_all_hidden_swapouts():
+    """chain with every swap-out shorter than the next forward: forward time is unchanged and
+    the last swap-out trails it by exactly its own duration"""
+    G = P.Graph(relu_chain(8))
+    nf = len(G.fmaps)
+    prof = P.Profile([2.0] * G.n, [2.0] * G.n, [2.0] * G.n, [1.5] * nf, [0.1] * nf)
+    S = P.build_schedule(G, [P.SWAP] * nf, BIG)
+    t = [0.0, 0.0, 0.0]
+    # recompute by hand: forward end = sum t_fwd; last D2H ends at fwd_end + t_out
+    T, LO, LI = P.simulate(G, S, prof)
+    fwd_end = 2.0 * (G.n - 1)
+    last = G.fmaps[-1]
+    assert LO == {last}            # only the last map's swap-out sticks out past the forward pass
+    # backward cannot start its first layer before that map came back: fwd_end + t_out + t_in
+    bwd = sum(prof.t_bwd[i] for i in range(1, G.n))
+    assert abs(T - (fwd_end + 1.5 + 0.1 + bwd)) < 1e-9
+    assert LI == {last}
+
+
+def test_paper_eight_layer_example_sets():
+    """section 4.4.2's example: 8 layers, all swapped; swap-outs of layers 5,6,7 are not hidden
+    (they pile up at the end of forward), swap-ins of layers 4,6,7 stall backward; layers
+    0..3 are hidden both ways.  Durations are chosen to produce that timeline."""
+    with open(os.path.join(GOLD, "eight_layer_example.json")) as f:
+        gold = json.load(f)
+    G = P.Graph(relu_chain(8))
+    layer_map = G.fmaps[:8]          # map k = output of layer k (node k+1)
+    nf = len(G.fmaps)
+    assert nf == 9                   # 8 layers + the pooled vector the loss reads
+    t_fwd = [0.0] + gold["t_fwd"] + [0.0, 0.0]
+    t_bwd = [0.0] + gold["t_bwd"] + [0.0, 0.0]
+    prof = P.Profile(t_fwd, t_bwd, t_fwd, gold["t_out"] + [0.0], gold["t_in"] + [0.0])
+    S = P.build_schedule(G, [P.SWAP] * nf, BIG)
+    T, LO, LI = P.simulate(G, S, prof)
+    lo = sorted(layer_map.index(t) for t in LO if t in layer_map)
+    li = sorted(layer_map.index(t) for t in LI if t in layer_map)
+    assert lo == gold["L_O"] == [5, 6, 7]
+    assert li == gold["L_I"] == [4, 6, 7]
+    pl = P.Planner(G, prof, BIG, max_bits=16)
+    cls, Tbest = pl.plan("swapopt")
+    # undecided = L_O u L_I = {4..7}; layers 0..3 stay swap; search tree = 2^|L_I| leaves,
+    # one greedy candidate (L_O \ L_I = {5}) per leaf
+    assert [cls[G.fidx[layer_map[k]]] for k in range(4)] == [P.SWAP] * 4
+    n_li = len(pl.LI)
+    n_g = len(pl.LO - pl.LI)
+    assert pl.evals <= 2 + (1 << n_li) * (1 + n_g)
+    assert Tbest <= T
+
+
+# ---- schedules are memory-safe whatever the timings ---------------------------------------------
+
+def small_nets():
+    return {
+        "tiny": workloads.tiny_cnn(),
+        "res": workloads.resnet50(batch=2, size=32, nclasses=5, blocks=(2, 1), width=4),
+        "c3d": workloads.cnn3d(size=8, channels=(2, 3, 4), nclasses=2, batch=2),
+        "chain": relu_chain(6),
+    }
+
+
+@pytest.mark.parametrize("name", ["tiny", "res", "c3d", "chain"])
+def test_random_plans_schedule_valid(name):
+    net = small_nets()[name]
+    G = P.Graph(net)
+    nf = len(G.fmaps)
+    rng = np.random.default_rng(11)
+    incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
+    schedule_check.check(G, incore.cmds, BIG)
+    nvalid = 0
+    for trial in range(60):
+        cls = [int(v) for v in rng.integers(0, 3, nf)]
+        frac = rng.uniform(0.35, 1.2)
+        cap = int(incore.peak * frac) // 256 * 256
+        for ahead in (True, False):
+            try:
+                S = P.build_schedule(G, cls, cap, ahead)
+            except P.Budget:
+                continue
+            nvalid += 1
+            assert S.peak <= cap and S.extent <= cap
+            schedule_check.check(G, S.cmds, cap)
+            # every swap map goes out exactly once and comes back at most once
+            outs = [c[1] for c in S.cmds if c[0] == P.KO]
+            ins = [c[1] for c in S.cmds if c[0] == P.KI]
+            assert sorted(outs) == sorted(G.fmaps[k] for k in range(nf) if cls[k] == P.SWAP)
+            assert len(set(ins)) == len(ins) and set(ins) <= set(outs)
+    assert nvalid > 20
+
+
+def test_infeasible_budget_is_an_error_not_a_crash():
+    G = P.Graph(workloads.tiny_cnn())
+    nf = len(G.fmaps)
+    with pytest.raises(P.Budget):
+        P.build_schedule(G, [P.KEEP] * nf, 256 * 8)
+    with pytest.raises(P.Budget):
+        P.build_schedule(G, [P.SWAP] * nf, BIG, pinned_cap=256)
+
+
+# ---- the search ---------------------------------------------------------------------------------
+
+def brute_force_best(G, prof, cap):
+    nf = len(G.fmaps)
+    best = None
+    for cls in itertools.product((P.KEEP, P.SWAP, P.RECOMPUTE), repeat=nf):
+        try:
+            S = P.build_schedule(G, list(cls), cap)
+        except P.Budget:
+            continue
+        T = P.simulate(G, S, prof)[0]
+        if best is None or T < best:
+            best = T
+    return best
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_modes_monotone_and_feasible_vs_brute_force(seed):
+    rng = np.random.default_rng(seed)
+    G = P.Graph(relu_chain(5, shape=(2, 4, 8, 8)))   # 6 maps -> 729 classifications
+    nf = len(G.fmaps)
+    prof = random_profile(G, rng, link=rng.choice([0.3, 1.0, 3.0]))
+    incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
+    cap = int(incore.peak * rng.uniform(0.5, 0.9)) // 256 * 256
+    pl = P.Planner(G, prof, cap)
+    try:
+        T_ns = pl.plan("swapall_nosched")[1]
+    except P.Budget:
+        pytest.skip("all-swap does not fit this draw")
+    T_all = pl.plan("swapall")[1]
+    cls_opt, T_opt = pl.plan("swapopt")
+    cls_p, T_p = pl.plan("pooch")
+    assert T_p <= T_opt + 1e-12 <= T_all + 2e-12
+    assert T_all <= T_ns + 1e-9
+    # feasible and no better than the true optimum
+    S = P.build_schedule(G, cls_p, cap)
+    assert abs(P.simulate(G, S, prof)[0] - T_p) < 1e-12
+    schedule_check.check(G, S.cmds, cap)
+    T_star = brute_force_best(G, prof, cap)
+    assert T_star <= T_p + 1e-12
+    assert P.RECOMPUTE not in cls_opt
+
+
+def test_fast_link_means_fewer_recomputes():
+    """table 3: the machine with the faster host link recomputes fewer maps"""
+    net = workloads.resnet50(batch=4, size=64, nclasses=10, blocks=(1, 1, 1, 1), width=8)
+    G = P.Graph(net)
+    nf = len(G.fmaps)
+    rng = np.random.default_rng(5)
+    base = random_profile(G, rng)
+    incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
+    cap = int(incore.peak * 0.5) // 256 * 256
+    counts = []
+    for link in (4.0, 0.05):
+        prof = P.Profile(base.t_fwd, base.t_bwd, base.t_refwd, [v * link for v in base.t_out], [v * link for v in base.t_in])
+        cls, _ = P.Planner(G, prof, cap, max_bits=4).plan("pooch")
+        counts.append(cls.count(P.RECOMPUTE))
+    assert counts[1] <= counts[0]
+
+
+def test_recompute_ratio_rule_and_tie():
+    """r >= 1 stays swap (tie included); r < 1 becomes recompute; O(|L|^2) simulations"""
+    G = P.Graph(relu_chain(4, shape=(2, 4, 8, 8)))
+    nf = len(G.fmaps)
+    incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
+    cap = BIG
+    # swap is free (zero-length copies): swap_overhead = 0 -> r = inf -> nothing is recomputed
+    prof = P.Profile([1.0] * G.n, [1.0] * G.n, [1.0] * G.n, [0.0] * nf, [0.0] * nf)
+    pl = P.Planner(G, prof, cap)
+    cls, T = pl.step2([P.SWAP] * nf, pl.evaluate([P.SWAP] * nf))
+    assert cls == [P.SWAP] * nf
+    # recomputation is free and copies are slow: every map that can be recomputed is
+    prof = P.Profile([1.0] * G.n, [1.0] * G.n, [0.0] * G.n, [5.0] * nf, [5.0] * nf)
+    pl = P.Planner(G, prof, cap)
+    T0 = pl.evaluate([P.SWAP] * nf)
+    pl.evals = 0
+    cls, T = pl.step2([P.SWAP] * nf, T0)
+    assert cls.count(P.RECOMPUTE) >= nf - 1 and T < T0
+    assert pl.evals <= 2 * nf * nf + nf
