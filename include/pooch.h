@@ -106,9 +106,11 @@ pooch_status pooch_param_info(pooch_ctx *, int32_t i, int64_t *numel, int32_t *n
 pooch_status pooch_set_param(pooch_ctx *, int32_t i, const float *host);
 pooch_status pooch_get_grad(pooch_ctx *, int32_t i, float *host);
 pooch_status pooch_set_batch(pooch_ctx *, const float *x_host, const int32_t *labels_host);
-/* debugging / parity aid: copies the CURRENT device contents of tensor id's forward value
- * to host in logical layout; valid only for tensors resident after the last step. */
-pooch_status pooch_get_tensor(pooch_ctx *, int32_t id, float *host);
+/* parity aid: during every following step, right after the forward of layer `id` has run,
+ * its output is copied to `host` in logical layout (the step synchronises there, so this is
+ * for tests, not for timed runs).  host == NULL cancels the capture of that layer.  The
+ * buffer must stay valid until cancelled or the context is destroyed. */
+pooch_status pooch_capture_tensor(pooch_ctx *, int32_t id, float *host);
 /* gradient of the loss w.r.t. saved BN statistics is internal; the per-channel batch mean
  * and 1/sqrt(var+eps) of BN node `node` (C floats each) can be read back for tests. */
 pooch_status pooch_get_bn_stats(pooch_ctx *, int32_t node, float *mean, float *istd);
@@ -150,6 +152,16 @@ pooch_status pooch_simulate(pooch_ctx *, const uint8_t *cls, int sched, double *
 int64_t pooch_plan_evaluations(pooch_ctx *);
 /* the sets found on the all-swap timeline (section 4.4.2): in_LO[i], in_LI[i] are 0/1 per map */
 pooch_status pooch_get_overhead_sets(pooch_ctx *, uint8_t *in_LO, uint8_t *in_LI);
+
+/* test aid: the installed plan's command list, one row of 8 int64 per command:
+ * kind, id, a0..a5 with kind 0 forward, 1 re-forward, 2 backward (id = layer; forward rows:
+ * out, in0, in1 offsets; backward rows: dy, saved-tensor offset, then (offset, mode) of each
+ * input's gradient, mode 0 none / 1 write / 2 accumulate / 3 reuse dy's buffer), 3 swap-out,
+ * 4 swap-in (id = tensor; device offset, pinned offset), 5 record, 6 wait (id = stream 0
+ * compute / 1 device-to-host / 2 host-to-device; a0 = event).  Offsets are relative to the
+ * dynamic region (arena + resident bytes); -1 = none, -2 = the resident network input.
+ * *nrows receives the number of commands; rows may be NULL to query it. */
+pooch_status pooch_get_commands(pooch_ctx *, int64_t *rows, int64_t max_rows, int64_t *nrows);
 
 /* ---- phase 3: execution -------------------------------------------------------------------
  * One forward + backward under the installed plan.  Enqueues everything, then synchronises

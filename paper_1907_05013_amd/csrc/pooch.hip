@@ -1,0 +1,1056 @@
+// C ABI of the out-of-core training step: context, layer graph, resident-region layout,
+// parameter / batch marshalling, the command-list executor with its swap engine (paper
+// section 3.1) and recompute executor (section 3.2), the runtime profiler (section 4.2)
+// and the entry points of the classification (section 4.4).
+//
+// Execution model: a plan is a static command list (plan.cpp).  pooch_step() replays it on
+// three caller-owned HIP streams -- compute, device-to-host, host-to-device -- with every
+// cross-stream dependency expressed as an event record / wait pair, so the host enqueues a
+// whole step without blocking and synchronises once at the end.
+#include "../../include/pooch.h"
+#include "core.hpp"
+#include "kernels.h"
+
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <new>
+
+using namespace pooch;
+
+namespace {
+
+struct ParamInfo {
+    int node;
+    int which;            // 0: filter / gamma / fc weight, 1: beta / fc bias
+    int64_t numel;
+    int64_t off_val;      // resident offsets (bytes from the arena base)
+    int64_t off_val_t;    // transposed filter copy for the data gradient, or -1
+    int64_t off_grad;
+};
+
+struct Timing {
+    std::vector<int> start, stop;      // per command: indices into the timing-event pool, -1 = untimed
+    std::vector<int> rstart, rstop;    // profile mode: the re-forward run right after a forward
+};
+
+}  // namespace
+
+struct pooch_ctx {
+    char *arena = nullptr;
+    size_t arena_bytes = 0;
+    char *pinned = nullptr;
+    size_t pinned_bytes = 0;
+    hipStream_t st[3] = {nullptr, nullptr, nullptr};
+
+    Graph G;
+    bool finalized = false;
+    std::vector<ParamInfo> params;
+    std::vector<int64_t> off_mean, off_istd;  // per node (BN only), resident offsets
+    int64_t off_input = 0, off_labels = 0, off_ws_wgrad = 0, off_ws_bn = 0, off_loss_ps = 0, off_loss = 0;
+    int64_t resident_bytes = 0;
+    int nclasses = 0;
+
+    Profile prof;
+    bool has_plan = false;
+    std::vector<uint8_t> cls;
+    bool ahead = true;
+    Schedule sched;
+    double predicted_ms = 0.0;
+    int64_t evals = 0;
+    double last_step_ms = 0.0;
+
+    std::vector<hipEvent_t> sync_events;    // no timing
+    std::vector<hipEvent_t> timing_events;  // with timing
+    std::vector<float *> capture;           // per node host destination or nullptr
+    std::vector<float> host_tmp;
+    std::string err;
+};
+
+namespace {
+
+int64_t round_up(int64_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
+
+pooch_status fail(pooch_ctx *c, pooch_status s, const std::string &msg)
+{
+    if (c) c->err = msg;
+    return s;
+}
+
+#define HIPCHK(expr)                                                                                       \
+    do {                                                                                                   \
+        hipError_t e_ = (expr);                                                                            \
+        if (e_ != hipSuccess) return fail(c, POOCH_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+pk::ConvGeom conv_geom(const Graph &G, int i)
+{
+    const Node &nd = G.nodes[i];
+    const Node &x = G.nodes[nd.in[0]];
+    pk::ConvGeom g;
+    g.N = (int)x.N; g.C = (int)x.C; g.D = (int)x.sp[0]; g.H = (int)x.sp[1]; g.W = (int)x.sp[2];
+    g.K = (int)nd.C;
+    g.Do = (int)nd.sp[0]; g.Ho = (int)nd.sp[1]; g.Wo = (int)nd.sp[2];
+    if (nd.op == OP_FC) {
+        // a fully-connected layer is a convolution whose filter covers the whole input
+        g.kd = g.D; g.kh = g.H; g.kw = g.W; g.sd = g.sh = g.sw = 1; g.pd = g.ph = g.pw = 0;
+    } else {
+        g.kd = nd.k[0]; g.kh = nd.k[1]; g.kw = nd.k[2];
+        g.sd = nd.st[0]; g.sh = nd.st[1]; g.sw = nd.st[2];
+        g.pd = nd.pd[0]; g.ph = nd.pd[1]; g.pw = nd.pd[2];
+    }
+    return g;
+}
+
+pk::PoolGeom pool_geom(const Graph &G, int i)
+{
+    const Node &nd = G.nodes[i];
+    const Node &x = G.nodes[nd.in[0]];
+    pk::PoolGeom g;
+    g.N = (int)x.N; g.C = (int)x.C; g.D = (int)x.sp[0]; g.H = (int)x.sp[1]; g.W = (int)x.sp[2];
+    g.Do = (int)nd.sp[0]; g.Ho = (int)nd.sp[1]; g.Wo = (int)nd.sp[2];
+    g.kd = nd.k[0]; g.kh = nd.k[1]; g.kw = nd.k[2];
+    g.sd = nd.st[0]; g.sh = nd.st[1]; g.sw = nd.st[2];
+    g.pd = nd.pd[0]; g.ph = nd.pd[1]; g.pw = nd.pd[2];
+    return g;
+}
+
+// logical K,C,taps  <->  device K,taps,C and C,taps,K
+void filter_to_device_layouts(const float *kcr, int64_t K, int64_t C, int64_t T, float *krc, float *crk)
+{
+    for (int64_t k = 0; k < K; ++k)
+        for (int64_t c = 0; c < C; ++c)
+            for (int64_t t = 0; t < T; ++t) {
+                const float v = kcr[(k * C + c) * T + t];
+                krc[(k * T + t) * C + c] = v;
+                crk[(c * T + t) * K + k] = v;
+            }
+}
+
+void filter_from_device_layout(const float *krc, int64_t K, int64_t C, int64_t T, float *kcr)
+{
+    for (int64_t k = 0; k < K; ++k)
+        for (int64_t c = 0; c < C; ++c)
+            for (int64_t t = 0; t < T; ++t) kcr[(k * C + c) * T + t] = krc[(k * T + t) * C + c];
+}
+
+// logical N,C,S <-> device N,S,C
+void act_to_device_layout(const float *ncs, int64_t N, int64_t C, int64_t S, float *nsc)
+{
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t c = 0; c < C; ++c) {
+            const float *src = ncs + (n * C + c) * S;
+            float *dst = nsc + n * S * C + c;
+            for (int64_t s = 0; s < S; ++s) dst[s * C] = src[s];
+        }
+}
+
+void act_from_device_layout(const float *nsc, int64_t N, int64_t C, int64_t S, float *ncs)
+{
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t c = 0; c < C; ++c) {
+            float *dst = ncs + (n * C + c) * S;
+            const float *src = nsc + n * S * C + c;
+            for (int64_t s = 0; s < S; ++s) dst[s] = src[s * C];
+        }
+}
+
+struct Exec {
+    pooch_ctx *c;
+    const Schedule &S;
+    explicit Exec(pooch_ctx *ctx, const Schedule &s) : c(ctx), S(s) {}
+
+    float *R(int64_t off) const { return reinterpret_cast<float *>(c->arena + off); }  // resident
+    float *D(int64_t off) const
+    {
+        if (off == OFF_INPUT) return R(c->off_input);
+        if (off < 0) return nullptr;
+        return reinterpret_cast<float *>(c->arena + c->resident_bytes + off);
+    }
+    const ParamInfo &P(int node, int which) const { return c->params[c->G.nodes[node].param[which]]; }
+
+    hipError_t forward(int i, int64_t out, int64_t in0, int64_t in1, bool refwd)
+    {
+        const Graph &G = c->G;
+        const Node &nd = G.nodes[i];
+        hipStream_t s = c->st[S_COMPUTE];
+        switch (nd.op) {
+        case OP_CONV: return pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i), s);
+        case OP_BN: {
+            const int64_t M = nd.numel() / nd.C;
+            if (refwd)
+                return pk::bn_apply(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), R(c->off_mean[i]), R(c->off_istd[i]),
+                                    D(out), M, (int)nd.C, s);
+            return pk::bn_fwd(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), D(out), R(c->off_mean[i]), R(c->off_istd[i]),
+                              R(c->off_ws_bn), M, (int)nd.C, nd.eps, s);
+        }
+        case OP_RELU: return pk::relu_fwd(D(in0), D(out), nd.numel(), s);
+        case OP_ADD: return pk::add_fwd(D(in0), D(in1), D(out), nd.numel(), s);
+        case OP_MAXPOOL: return pk::maxpool_fwd(D(in0), D(out), pool_geom(G, i), s);
+        case OP_GAVGPOOL: {
+            const Node &x = G.nodes[nd.in[0]];
+            return pk::gavgpool_fwd(D(in0), D(out), (int)x.N, x.sp[0] * x.sp[1] * x.sp[2], (int)x.C, s);
+        }
+        case OP_FC: {
+            hipError_t e = pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i), s);
+            if (e != hipSuccess) return e;
+            return pk::bias_add(D(out), R(P(i, 1).off_val), (int)nd.N, (int)nd.C, s);
+        }
+        case OP_LOSS: {
+            const Node &z = G.nodes[nd.in[0]];
+            return pk::softmax_ce_fwd(D(in0), reinterpret_cast<const int32_t *>(c->arena + c->off_labels), R(c->off_loss_ps),
+                                      R(c->off_loss), (int)z.N, (int)z.C, s);
+        }
+        default: return hipErrorInvalidValue;
+        }
+    }
+
+    // one gradient output of an element-wise "pass dy on" (residual add)
+    hipError_t pass_on(int64_t dy, int64_t off, int mode, int64_t n)
+    {
+        hipStream_t s = c->st[S_COMPUTE];
+        if (mode == M_WRITE) return pk::copy(D(off), D(dy), n, s);
+        if (mode == M_ACC) return pk::accumulate(D(off), D(dy), n, s);
+        return hipSuccess;  // none / transferred: the buffer itself changes owner
+    }
+
+    hipError_t backward(int i, const int64_t *a)
+    {
+        const Graph &G = c->G;
+        const Node &nd = G.nodes[i];
+        hipStream_t s = c->st[S_COMPUTE];
+        const int64_t dy = a[0], need = a[1], o0 = a[2], o1 = a[4];
+        const int m0 = (int)a[3], m1 = (int)a[5];
+        switch (nd.op) {
+        case OP_CONV: case OP_FC: {
+            const pk::ConvGeom g = conv_geom(G, i);
+            hipError_t e = pk::conv_wgrad(D(dy), D(need), R(P(i, 0).off_grad), R(c->off_ws_wgrad), g, s);
+            if (e != hipSuccess) return e;
+            if (nd.op == OP_FC) {
+                e = pk::bias_grad(D(dy), R(P(i, 1).off_grad), (int)nd.N, (int)nd.C, s);
+                if (e != hipSuccess) return e;
+            }
+            if (m0 == M_NONE) return hipSuccess;
+            return pk::conv_dgrad(D(dy), R(P(i, 0).off_val_t), D(o0), g, m0 == M_ACC, s);
+        }
+        case OP_BN: {
+            const int64_t M = nd.numel() / nd.C;
+            float *dx = m0 == M_NONE ? D(dy) : D(o0);
+            return pk::bn_bwd(D(need), D(dy), R(P(i, 0).off_val), R(c->off_mean[i]), R(c->off_istd[i]), dx,
+                              R(P(i, 0).off_grad), R(P(i, 1).off_grad), R(c->off_ws_bn), M, (int)nd.C, m0 == M_ACC, s);
+        }
+        case OP_RELU:
+            if (m0 == M_NONE) return hipSuccess;
+            return pk::relu_bwd(D(need), D(dy), D(o0), nd.numel(), m0 == M_ACC, s);
+        case OP_ADD: {
+            hipError_t e = pass_on(dy, o0, m0, nd.numel());
+            if (e != hipSuccess) return e;
+            return pass_on(dy, o1, m1, nd.numel());
+        }
+        case OP_MAXPOOL:
+            if (m0 == M_NONE) return hipSuccess;
+            return pk::maxpool_bwd(D(need), D(dy), D(o0), pool_geom(G, i), m0 == M_ACC, s);
+        case OP_GAVGPOOL: {
+            if (m0 == M_NONE) return hipSuccess;
+            const Node &x = G.nodes[nd.in[0]];
+            return pk::gavgpool_bwd(D(dy), D(o0), (int)x.N, x.sp[0] * x.sp[1] * x.sp[2], (int)x.C, m0 == M_ACC, s);
+        }
+        case OP_LOSS: {
+            if (m0 == M_NONE) return hipSuccess;
+            const Node &z = G.nodes[nd.in[0]];
+            return pk::softmax_ce_bwd(D(need), reinterpret_cast<const int32_t *>(c->arena + c->off_labels), D(o0), (int)z.N,
+                                      (int)z.C, m0 == M_ACC, s);
+        }
+        default: return hipErrorInvalidValue;
+        }
+    }
+};
+
+pooch_status ensure_events(pooch_ctx *c, std::vector<hipEvent_t> &pool, size_t n, unsigned flags)
+{
+    while (pool.size() < n) {
+        hipEvent_t e;
+        HIPCHK(hipEventCreateWithFlags(&e, flags));
+        pool.push_back(e);
+    }
+    return POOCH_OK;
+}
+
+pooch_status copy_out_capture(pooch_ctx *c, int i, const float *dev)
+{
+    const Node &nd = c->G.nodes[i];
+    const int64_t n = nd.numel();
+    c->host_tmp.resize((size_t)n);
+    HIPCHK(hipStreamSynchronize(c->st[S_COMPUTE]));
+    HIPCHK(hipMemcpy(c->host_tmp.data(), dev, (size_t)n * 4, hipMemcpyDeviceToHost));
+    act_from_device_layout(c->host_tmp.data(), nd.N, nd.C, nd.sp[0] * nd.sp[1] * nd.sp[2], c->capture[i]);
+    return POOCH_OK;
+}
+
+// Replays a command list.  tm != nullptr: every forward / re-forward / backward / copy command
+// is bracketed by timing events on its own stream; profile_refwd additionally runs (and
+// times) each layer's re-forward variant right after its forward, on the same buffers.
+pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd, float *loss_out)
+{
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    const size_t swap_bytes = (size_t)S.swap_bytes;
+    if (swap_bytes > 0 && (!c->pinned || swap_bytes > c->pinned_bytes)) return fail(c, POOCH_E_BUDGET, "pinned buffer too small");
+    pooch_status ps = ensure_events(c, c->sync_events, (size_t)S.n_events, hipEventDisableTiming);
+    if (ps != POOCH_OK) return ps;
+    const int64_t cap = (int64_t)c->arena_bytes - c->resident_bytes;
+    size_t n_te = 0;
+    if (tm) {
+        const size_t nc = S.cmds.size();
+        tm->start.assign(nc, -1); tm->stop.assign(nc, -1); tm->rstart.assign(nc, -1); tm->rstop.assign(nc, -1);
+        for (size_t k = 0; k < nc; ++k) {
+            const int kind = S.cmds[k].kind;
+            if (kind == K_REC || kind == K_WAIT) continue;
+            tm->start[k] = (int)n_te++; tm->stop[k] = (int)n_te++;
+            if (profile_refwd && kind == K_FWD && c->G.nodes[S.cmds[k].id].op != OP_LOSS) {
+                tm->rstart[k] = (int)n_te++; tm->rstop[k] = (int)n_te++;
+            }
+        }
+        ps = ensure_events(c, c->timing_events, n_te, hipEventDefault);
+        if (ps != POOCH_OK) return ps;
+    }
+    Exec X(c, S);
+    const Graph &G = c->G;
+    auto in_arena = [&](int64_t off, int64_t bytes) { return off == OFF_INPUT || off == OFF_NONE || (off >= 0 && off + bytes <= cap); };
+    for (size_t k = 0; k < S.cmds.size(); ++k) {
+        const Cmd &cm = S.cmds[k];
+        const int stream = cm.kind <= K_BWD ? S_COMPUTE : (cm.kind == K_OUT ? S_D2H : (cm.kind == K_IN ? S_H2D : cm.id));
+        if (tm && tm->start[k] >= 0) HIPCHK(hipEventRecord(c->timing_events[tm->start[k]], c->st[stream]));
+        switch (cm.kind) {
+        case K_FWD: case K_REFWD: {
+            const int i = cm.id;
+            if (!in_arena(cm.a[0], G.bytes[i])) return fail(c, POOCH_E_INVALID, "command outside the arena");
+            HIPCHK(X.forward(i, cm.a[0], cm.a[1], cm.a[2], cm.kind == K_REFWD));
+            if (tm && tm->start[k] >= 0) HIPCHK(hipEventRecord(c->timing_events[tm->stop[k]], c->st[stream]));
+            if (tm && tm->rstart[k] >= 0) {
+                HIPCHK(hipEventRecord(c->timing_events[tm->rstart[k]], c->st[stream]));
+                HIPCHK(X.forward(i, cm.a[0], cm.a[1], cm.a[2], true));
+                HIPCHK(hipEventRecord(c->timing_events[tm->rstop[k]], c->st[stream]));
+            }
+            if (cm.kind == K_FWD && c->capture[i] && G.nodes[i].op != OP_LOSS) {
+                ps = copy_out_capture(c, i, X.D(cm.a[0]));
+                if (ps != POOCH_OK) return ps;
+            }
+            break;
+        }
+        case K_BWD: {
+            const int i = cm.id;
+            for (int j = 0; j < 2; ++j)
+                if (cm.a[3 + 2 * j] != M_NONE && !in_arena(cm.a[2 + 2 * j], G.bytes[G.nodes[i].in[j]]))
+                    return fail(c, POOCH_E_INVALID, "command outside the arena");
+            HIPCHK(X.backward(i, cm.a));
+            if (tm && tm->start[k] >= 0) HIPCHK(hipEventRecord(c->timing_events[tm->stop[k]], c->st[stream]));
+            break;
+        }
+        case K_OUT: {
+            const int64_t bytes = G.nodes[cm.id].numel() * 4;
+            if (!in_arena(cm.a[0], bytes) || (size_t)(cm.a[1] + bytes) > c->pinned_bytes) return fail(c, POOCH_E_INVALID, "swap-out outside its buffers");
+            HIPCHK(hipMemcpyAsync(c->pinned + cm.a[1], X.D(cm.a[0]), (size_t)bytes, hipMemcpyDeviceToHost, c->st[S_D2H]));
+            if (tm) HIPCHK(hipEventRecord(c->timing_events[tm->stop[k]], c->st[stream]));
+            break;
+        }
+        case K_IN: {
+            const int64_t bytes = G.nodes[cm.id].numel() * 4;
+            if (!in_arena(cm.a[0], bytes) || (size_t)(cm.a[1] + bytes) > c->pinned_bytes) return fail(c, POOCH_E_INVALID, "swap-in outside its buffers");
+            HIPCHK(hipMemcpyAsync(X.D(cm.a[0]), c->pinned + cm.a[1], (size_t)bytes, hipMemcpyHostToDevice, c->st[S_H2D]));
+            if (tm) HIPCHK(hipEventRecord(c->timing_events[tm->stop[k]], c->st[stream]));
+            break;
+        }
+        case K_REC: HIPCHK(hipEventRecord(c->sync_events[cm.a[0]], c->st[cm.id])); break;
+        case K_WAIT: HIPCHK(hipStreamWaitEvent(c->st[cm.id], c->sync_events[cm.a[0]], 0)); break;
+        default: return fail(c, POOCH_E_INVALID, "unknown command");
+        }
+    }
+    for (int s = 0; s < 3; ++s) HIPCHK(hipStreamSynchronize(c->st[s]));
+    if (loss_out) HIPCHK(hipMemcpy(loss_out, c->arena + c->off_loss, 4, hipMemcpyDeviceToHost));
+    return POOCH_OK;
+}
+
+pooch_status elapsed(pooch_ctx *c, int a, int b, double &ms)
+{
+    float f = 0.f;
+    HIPCHK(hipEventElapsedTime(&f, c->timing_events[a], c->timing_events[b]));
+    ms = (double)f;
+    return POOCH_OK;
+}
+
+double median(std::vector<double> &v)
+{
+    if (v.empty()) return 0.0;
+    std::sort(v.begin(), v.end());
+    const size_t n = v.size();
+    return n % 2 ? v[n / 2] : 0.5 * (v[n / 2 - 1] + v[n / 2]);
+}
+
+int32_t add_node(pooch_ctx *c, const Node &nd)
+{
+    c->G.nodes.push_back(nd);
+    return (int32_t)c->G.nodes.size() - 1;
+}
+
+bool valid_tensor(const pooch_ctx *c, int32_t x)
+{
+    return x >= 0 && x < (int32_t)c->G.nodes.size() && c->G.nodes[x].op != OP_LOSS;
+}
+
+#define GRAPH_OPEN(c)                                                           \
+    do {                                                                        \
+        if (!(c)) return POOCH_E_INVALID;                                       \
+        if ((c)->finalized) return fail((c), POOCH_E_STATE, "graph is frozen"); \
+    } while (0)
+
+bool window_out(const Node &x, int nspatial, const int *k, const int *stride, const int *pad, Node &nd)
+{
+    if (nspatial != x.nsp || (nspatial != 2 && nspatial != 3)) return false;
+    nd.nsp = nspatial;
+    nd.N = x.N;
+    for (int d = 0; d < 3; ++d) { nd.k[d] = 1; nd.st[d] = 1; nd.pd[d] = 0; nd.sp[d] = 1; }
+    const int o = 3 - nspatial;
+    for (int d = 0; d < nspatial; ++d) {
+        if (k[d] <= 0 || stride[d] <= 0 || pad[d] < 0) return false;
+        nd.k[o + d] = k[d]; nd.st[o + d] = stride[d]; nd.pd[o + d] = pad[d];
+        const int64_t in = x.sp[o + d];
+        if (in + 2 * pad[d] < k[d]) return false;
+        nd.sp[o + d] = (in + 2 * pad[d] - k[d]) / stride[d] + 1;
+    }
+    return true;
+}
+
+pooch_status install(pooch_ctx *c, const std::vector<uint8_t> &cls, bool ahead, double predicted)
+{
+    Schedule S;
+    std::string why;
+    const int64_t cap = (int64_t)c->arena_bytes - c->resident_bytes;
+    const int64_t pinned_cap = c->arena ? (int64_t)c->pinned_bytes : -1;
+    if (!build_schedule(c->G, cls, cap, ahead, pinned_cap, S, &why)) return fail(c, POOCH_E_BUDGET, why);
+    c->sched = std::move(S);
+    c->cls = cls;
+    c->ahead = ahead;
+    c->has_plan = true;
+    c->predicted_ms = predicted;
+    return POOCH_OK;
+}
+
+Profile zero_profile(const Graph &G)
+{
+    Profile P;
+    P.t_fwd.assign(G.n(), 0.0); P.t_bwd.assign(G.n(), 0.0); P.t_refwd.assign(G.n(), 0.0);
+    P.t_out.assign(G.fmaps.size(), 0.0); P.t_in.assign(G.fmaps.size(), 0.0);
+    P.valid = true;
+    return P;
+}
+
+bool valid_classes(const pooch_ctx *c, const uint8_t *cls)
+{
+    for (size_t k = 0; k < c->G.fmaps.size(); ++k)
+        if (cls[k] > CLS_RECOMPUTE) return false;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+pooch_status pooch_create(void *arena, size_t arena_bytes, void *pinned_host, size_t pinned_bytes, void *stream_compute,
+                          void *stream_d2h, void *stream_h2d, pooch_ctx **out)
+{
+    if (!out) return POOCH_E_INVALID;
+    *out = nullptr;
+    if (arena && ((uintptr_t)arena % ALIGN != 0)) return POOCH_E_INVALID;
+    if (!pinned_host && pinned_bytes != 0) return POOCH_E_INVALID;
+    pooch_ctx *c = new (std::nothrow) pooch_ctx();
+    if (!c) return POOCH_E_INVALID;
+    c->arena = static_cast<char *>(arena);
+    c->arena_bytes = arena_bytes;
+    c->pinned = static_cast<char *>(pinned_host);
+    c->pinned_bytes = pinned_bytes;
+    c->st[0] = static_cast<hipStream_t>(stream_compute);
+    c->st[1] = static_cast<hipStream_t>(stream_d2h);
+    c->st[2] = static_cast<hipStream_t>(stream_h2d);
+    *out = c;
+    return POOCH_OK;
+}
+
+void pooch_destroy(pooch_ctx *c)
+{
+    if (!c) return;
+    for (hipEvent_t e : c->sync_events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->timing_events) (void)hipEventDestroy(e);
+    delete c;
+}
+
+const char *pooch_last_error(pooch_ctx *c) { return c ? c->err.c_str() : "null context"; }
+
+int32_t pooch_input(pooch_ctx *c, const int64_t *dims, int ndim)
+{
+    GRAPH_OPEN(c);
+    if (!dims || (ndim != 4 && ndim != 5) || !c->G.nodes.empty()) return fail(c, POOCH_E_INVALID, "input: bad dims or not the first node");
+    Node nd;
+    nd.op = OP_INPUT;
+    nd.nsp = ndim - 2;
+    nd.N = dims[0];
+    nd.C = dims[1];
+    for (int d = 0; d < nd.nsp; ++d) nd.sp[3 - nd.nsp + d] = dims[2 + d];
+    if (nd.N <= 0 || nd.C <= 0 || nd.sp[0] <= 0 || nd.sp[1] <= 0 || nd.sp[2] <= 0) return fail(c, POOCH_E_INVALID, "input: non-positive size");
+    return add_node(c, nd);
+}
+
+int32_t pooch_conv(pooch_ctx *c, int32_t x, int cout, const int *k, const int *stride, const int *pad, int nspatial)
+{
+    GRAPH_OPEN(c);
+    if (!valid_tensor(c, x) || cout <= 0 || !k || !stride || !pad) return fail(c, POOCH_E_INVALID, "conv: bad argument");
+    Node nd;
+    nd.op = OP_CONV;
+    if (!window_out(c->G.nodes[x], nspatial, k, stride, pad, nd)) return fail(c, POOCH_E_INVALID, "conv: bad geometry");
+    nd.C = cout;
+    nd.in[0] = x;
+    nd.nin = 1;
+    return add_node(c, nd);
+}
+
+int32_t pooch_bn(pooch_ctx *c, int32_t x, float eps)
+{
+    GRAPH_OPEN(c);
+    if (!valid_tensor(c, x) || !(eps >= 0.f)) return fail(c, POOCH_E_INVALID, "bn: bad argument");
+    Node nd = c->G.nodes[x];
+    nd.op = OP_BN;
+    nd.in[0] = x; nd.in[1] = -1;
+    nd.nin = 1;
+    nd.eps = eps;
+    nd.param[0] = nd.param[1] = -1;
+    return add_node(c, nd);
+}
+
+int32_t pooch_relu(pooch_ctx *c, int32_t x)
+{
+    GRAPH_OPEN(c);
+    if (!valid_tensor(c, x)) return fail(c, POOCH_E_INVALID, "relu: bad argument");
+    Node nd = c->G.nodes[x];
+    nd.op = OP_RELU;
+    nd.in[0] = x; nd.in[1] = -1;
+    nd.nin = 1;
+    nd.param[0] = nd.param[1] = -1;
+    return add_node(c, nd);
+}
+
+int32_t pooch_add(pooch_ctx *c, int32_t a, int32_t b)
+{
+    GRAPH_OPEN(c);
+    if (!valid_tensor(c, a) || !valid_tensor(c, b)) return fail(c, POOCH_E_INVALID, "add: bad argument");
+    const Node &A = c->G.nodes[a], &B = c->G.nodes[b];
+    if (A.N != B.N || A.C != B.C || A.sp[0] != B.sp[0] || A.sp[1] != B.sp[1] || A.sp[2] != B.sp[2] || A.nsp != B.nsp)
+        return fail(c, POOCH_E_INVALID, "add: shapes differ");
+    Node nd = A;
+    nd.op = OP_ADD;
+    nd.in[0] = a; nd.in[1] = b;
+    nd.nin = 2;
+    nd.param[0] = nd.param[1] = -1;
+    return add_node(c, nd);
+}
+
+int32_t pooch_maxpool(pooch_ctx *c, int32_t x, const int *k, const int *stride, const int *pad, int nspatial)
+{
+    GRAPH_OPEN(c);
+    if (!valid_tensor(c, x) || !k || !stride || !pad) return fail(c, POOCH_E_INVALID, "maxpool: bad argument");
+    Node nd;
+    nd.op = OP_MAXPOOL;
+    if (!window_out(c->G.nodes[x], nspatial, k, stride, pad, nd)) return fail(c, POOCH_E_INVALID, "maxpool: bad geometry");
+    for (int d = 0; d < nspatial; ++d)
+        if (pad[d] >= k[d]) return fail(c, POOCH_E_INVALID, "maxpool: padding must be smaller than the window");
+    nd.C = c->G.nodes[x].C;
+    nd.in[0] = x;
+    nd.nin = 1;
+    return add_node(c, nd);
+}
+
+int32_t pooch_gavgpool(pooch_ctx *c, int32_t x)
+{
+    GRAPH_OPEN(c);
+    if (!valid_tensor(c, x)) return fail(c, POOCH_E_INVALID, "gavgpool: bad argument");
+    Node nd;
+    nd.op = OP_GAVGPOOL;
+    nd.nsp = c->G.nodes[x].nsp;
+    nd.N = c->G.nodes[x].N;
+    nd.C = c->G.nodes[x].C;
+    nd.in[0] = x;
+    nd.nin = 1;
+    return add_node(c, nd);
+}
+
+int32_t pooch_fc(pooch_ctx *c, int32_t x, int nout)
+{
+    GRAPH_OPEN(c);
+    if (!valid_tensor(c, x) || nout <= 0) return fail(c, POOCH_E_INVALID, "fc: bad argument");
+    Node nd;
+    nd.op = OP_FC;
+    nd.nsp = c->G.nodes[x].nsp;
+    nd.N = c->G.nodes[x].N;
+    nd.C = nout;
+    nd.in[0] = x;
+    nd.nin = 1;
+    return add_node(c, nd);
+}
+
+int32_t pooch_softmax_ce(pooch_ctx *c, int32_t logits)
+{
+    GRAPH_OPEN(c);
+    if (!valid_tensor(c, logits)) return fail(c, POOCH_E_INVALID, "softmax_ce: bad argument");
+    const Node &z = c->G.nodes[logits];
+    if (z.sp[0] * z.sp[1] * z.sp[2] != 1) return fail(c, POOCH_E_INVALID, "softmax_ce: logits must be N x classes");
+    Node nd;
+    nd.op = OP_LOSS;
+    nd.N = 1; nd.C = 1;
+    nd.in[0] = logits;
+    nd.nin = 1;
+    return add_node(c, nd);
+}
+
+pooch_status pooch_finalize(pooch_ctx *c)
+{
+    GRAPH_OPEN(c);
+    Graph &G = c->G;
+    const std::string bad = G.analyze();
+    if (!bad.empty()) return fail(c, POOCH_E_INVALID, bad);
+    const int n = G.n();
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) { const int64_t o = off; off += round_up(bytes); return o; };
+    c->off_input = take(G.nodes[0].numel() * 4);
+    c->off_labels = take(G.nodes[0].N * 4);
+    c->off_mean.assign(n, -1);
+    c->off_istd.assign(n, -1);
+    c->params.clear();
+    size_t ws_wgrad = 0, ws_bn = 0;
+    for (int i = 0; i < n; ++i) {
+        Node &nd = G.nodes[i];
+        if (nd.op == OP_CONV || nd.op == OP_FC) {
+            const pk::ConvGeom g = conv_geom(G, i);
+            // the conv kernels index rows and reduction lengths with 32 bits
+            const int64_t lim = ((int64_t)1 << 31) - 4096;
+            if (g.rows_in() >= lim || g.rows_out() >= lim || g.taps() * std::max(g.C, g.K) >= lim)
+                return fail(c, POOCH_E_INVALID, "conv/fc: tensor too large for the kernels' 32-bit row index");
+            const int64_t numel = (int64_t)g.K * g.C * g.taps();
+            ParamInfo p{i, 0, numel, take(numel * 4), take(numel * 4), take(numel * 4)};
+            nd.param[0] = (int)c->params.size();
+            c->params.push_back(p);
+            ws_wgrad = std::max(ws_wgrad, pk::conv_wgrad_workspace(g));
+            if (nd.op == OP_FC) {
+                ParamInfo b{i, 1, nd.C, take(nd.C * 4), -1, take(nd.C * 4)};
+                nd.param[1] = (int)c->params.size();
+                c->params.push_back(b);
+            }
+        } else if (nd.op == OP_BN) {
+            for (int w = 0; w < 2; ++w) {
+                ParamInfo p{i, w, nd.C, take(nd.C * 4), -1, take(nd.C * 4)};
+                nd.param[w] = (int)c->params.size();
+                c->params.push_back(p);
+            }
+            c->off_mean[i] = take(nd.C * 4);
+            c->off_istd[i] = take(nd.C * 4);
+            ws_bn = std::max(ws_bn, pk::bn_workspace_floats(nd.numel() / nd.C, (int)nd.C) * 4);
+        } else if (nd.op == OP_LOSS) {
+            c->nclasses = (int)G.nodes[nd.in[0]].C;
+        }
+    }
+    c->off_ws_wgrad = take((int64_t)ws_wgrad);
+    c->off_ws_bn = take((int64_t)ws_bn);
+    c->off_loss_ps = take(G.nodes[0].N * 4);
+    c->off_loss = take(4);
+    c->resident_bytes = off;
+    if ((size_t)off > c->arena_bytes) return fail(c, POOCH_E_BUDGET, "the resident region alone exceeds the arena");
+    c->capture.assign(n, nullptr);
+    c->finalized = true;
+    return POOCH_OK;
+}
+
+#define NEED_FINAL(c)                                                                     \
+    do {                                                                                  \
+        if (!(c)) return POOCH_E_INVALID;                                                 \
+        if (!(c)->finalized) return fail((c), POOCH_E_STATE, "graph is not finalized");  \
+    } while (0)
+
+int32_t pooch_num_params(pooch_ctx *c)
+{
+    NEED_FINAL(c);
+    return (int32_t)c->params.size();
+}
+
+pooch_status pooch_param_info(pooch_ctx *c, int32_t i, int64_t *numel, int32_t *node)
+{
+    NEED_FINAL(c);
+    if (i < 0 || i >= (int32_t)c->params.size()) return fail(c, POOCH_E_INVALID, "parameter index out of range");
+    if (numel) *numel = c->params[i].numel;
+    if (node) *node = c->params[i].node;
+    return POOCH_OK;
+}
+
+pooch_status pooch_set_param(pooch_ctx *c, int32_t i, const float *host)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (i < 0 || i >= (int32_t)c->params.size() || !host) return fail(c, POOCH_E_INVALID, "set_param: bad argument");
+    const ParamInfo &p = c->params[i];
+    if (p.off_val_t < 0) {
+        HIPCHK(hipMemcpy(c->arena + p.off_val, host, (size_t)p.numel * 4, hipMemcpyHostToDevice));
+        return POOCH_OK;
+    }
+    const pk::ConvGeom g = conv_geom(c->G, p.node);
+    std::vector<float> krc((size_t)p.numel), crk((size_t)p.numel);
+    filter_to_device_layouts(host, g.K, g.C, g.taps(), krc.data(), crk.data());
+    HIPCHK(hipMemcpy(c->arena + p.off_val, krc.data(), (size_t)p.numel * 4, hipMemcpyHostToDevice));
+    HIPCHK(hipMemcpy(c->arena + p.off_val_t, crk.data(), (size_t)p.numel * 4, hipMemcpyHostToDevice));
+    return POOCH_OK;
+}
+
+pooch_status pooch_get_grad(pooch_ctx *c, int32_t i, float *host)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (i < 0 || i >= (int32_t)c->params.size() || !host) return fail(c, POOCH_E_INVALID, "get_grad: bad argument");
+    const ParamInfo &p = c->params[i];
+    if (p.off_val_t < 0) {
+        HIPCHK(hipMemcpy(host, c->arena + p.off_grad, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
+        return POOCH_OK;
+    }
+    const pk::ConvGeom g = conv_geom(c->G, p.node);
+    std::vector<float> krc((size_t)p.numel);
+    HIPCHK(hipMemcpy(krc.data(), c->arena + p.off_grad, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
+    filter_from_device_layout(krc.data(), g.K, g.C, g.taps(), host);
+    return POOCH_OK;
+}
+
+pooch_status pooch_set_batch(pooch_ctx *c, const float *x_host, const int32_t *labels_host)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (!x_host || !labels_host) return fail(c, POOCH_E_INVALID, "set_batch: null pointer");
+    const Node &in = c->G.nodes[0];
+    for (int64_t n = 0; n < in.N; ++n)
+        if (labels_host[n] < 0 || labels_host[n] >= c->nclasses) return fail(c, POOCH_E_INVALID, "set_batch: label out of range");
+    std::vector<float> tmp((size_t)in.numel());
+    act_to_device_layout(x_host, in.N, in.C, in.sp[0] * in.sp[1] * in.sp[2], tmp.data());
+    HIPCHK(hipMemcpy(c->arena + c->off_input, tmp.data(), tmp.size() * 4, hipMemcpyHostToDevice));
+    HIPCHK(hipMemcpy(c->arena + c->off_labels, labels_host, (size_t)in.N * 4, hipMemcpyHostToDevice));
+    return POOCH_OK;
+}
+
+pooch_status pooch_capture_tensor(pooch_ctx *c, int32_t id, float *host)
+{
+    NEED_FINAL(c);
+    if (id <= 0 || id >= c->G.n() || c->G.nodes[id].op == OP_LOSS) return fail(c, POOCH_E_INVALID, "capture: not a layer output");
+    c->capture[id] = host;
+    return POOCH_OK;
+}
+
+pooch_status pooch_get_bn_stats(pooch_ctx *c, int32_t node, float *mean, float *istd)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (node < 0 || node >= c->G.n() || c->G.nodes[node].op != OP_BN) return fail(c, POOCH_E_INVALID, "not a bn node");
+    const size_t bytes = (size_t)c->G.nodes[node].C * 4;
+    if (mean) HIPCHK(hipMemcpy(mean, c->arena + c->off_mean[node], bytes, hipMemcpyDeviceToHost));
+    if (istd) HIPCHK(hipMemcpy(istd, c->arena + c->off_istd[node], bytes, hipMemcpyDeviceToHost));
+    return POOCH_OK;
+}
+
+int32_t pooch_num_nodes(pooch_ctx *c)
+{
+    if (!c) return POOCH_E_INVALID;
+    return (int32_t)c->G.nodes.size();
+}
+
+int32_t pooch_num_fmaps(pooch_ctx *c)
+{
+    NEED_FINAL(c);
+    return (int32_t)c->G.fmaps.size();
+}
+
+pooch_status pooch_fmap_info(pooch_ctx *c, int32_t i, size_t *bytes, int32_t *producer)
+{
+    NEED_FINAL(c);
+    if (i < 0 || i >= (int32_t)c->G.fmaps.size()) return fail(c, POOCH_E_INVALID, "feature-map index out of range");
+    if (bytes) *bytes = (size_t)c->G.bytes[c->G.fmaps[i]];
+    if (producer) *producer = c->G.fmaps[i];
+    return POOCH_OK;
+}
+
+size_t pooch_resident_bytes(pooch_ctx *c) { return (c && c->finalized) ? (size_t)c->resident_bytes : 0; }
+
+pooch_status pooch_profile(pooch_ctx *c, int warmup, int iters)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (warmup < 0 || iters <= 0) return fail(c, POOCH_E_INVALID, "profile: bad iteration counts");
+    const Graph &G = c->G;
+    const std::vector<uint8_t> allswap(G.fmaps.size(), CLS_SWAP);
+    Schedule S;
+    std::string why;
+    if (!build_schedule(G, allswap, (int64_t)c->arena_bytes - c->resident_bytes, true, (int64_t)c->pinned_bytes, S, &why))
+        return fail(c, POOCH_E_BUDGET, "profiling runs every map as swap and that does not fit: " + why);
+    const int n = G.n();
+    const size_t nf = G.fmaps.size();
+    std::vector<std::vector<double>> f(n), b(n), r(n), o(nf), in(nf);
+    Timing tm;
+    for (int it = 0; it < warmup + iters; ++it) {
+        const bool timed = it >= warmup;
+        pooch_status ps = run_schedule(c, S, timed ? &tm : nullptr, timed, nullptr);
+        if (ps != POOCH_OK) return ps;
+        if (!timed) continue;
+        for (size_t k = 0; k < S.cmds.size(); ++k) {
+            if (tm.start[k] < 0) continue;
+            const Cmd &cm = S.cmds[k];
+            double ms;
+            ps = elapsed(c, tm.start[k], tm.stop[k], ms);
+            if (ps != POOCH_OK) return ps;
+            switch (cm.kind) {
+            case K_FWD: f[cm.id].push_back(ms); break;
+            case K_REFWD: r[cm.id].push_back(ms); break;
+            case K_BWD: b[cm.id].push_back(ms); break;
+            case K_OUT: o[G.fidx[cm.id]].push_back(ms); break;
+            case K_IN: in[G.fidx[cm.id]].push_back(ms); break;
+            default: break;
+            }
+            if (tm.rstart[k] >= 0) {
+                ps = elapsed(c, tm.rstart[k], tm.rstop[k], ms);
+                if (ps != POOCH_OK) return ps;
+                r[cm.id].push_back(ms);
+            }
+        }
+    }
+    Profile P;
+    P.t_fwd.resize(n); P.t_bwd.resize(n); P.t_refwd.resize(n); P.t_out.resize(nf); P.t_in.resize(nf);
+    for (int i = 0; i < n; ++i) { P.t_fwd[i] = median(f[i]); P.t_bwd[i] = median(b[i]); P.t_refwd[i] = median(r[i]); }
+    for (size_t k = 0; k < nf; ++k) { P.t_out[k] = median(o[k]); P.t_in[k] = median(in[k]); }
+    P.valid = true;
+    c->prof = P;
+    return POOCH_OK;
+}
+
+pooch_status pooch_get_profile(pooch_ctx *c, double *t_fwd, double *t_bwd, double *t_refwd, double *t_out, double *t_in)
+{
+    NEED_FINAL(c);
+    if (!c->prof.valid) return fail(c, POOCH_E_NOPROFILE, "no profile");
+    const Profile &P = c->prof;
+    if (t_fwd) std::copy(P.t_fwd.begin(), P.t_fwd.end(), t_fwd);
+    if (t_bwd) std::copy(P.t_bwd.begin(), P.t_bwd.end(), t_bwd);
+    if (t_refwd) std::copy(P.t_refwd.begin(), P.t_refwd.end(), t_refwd);
+    if (t_out) std::copy(P.t_out.begin(), P.t_out.end(), t_out);
+    if (t_in) std::copy(P.t_in.begin(), P.t_in.end(), t_in);
+    return POOCH_OK;
+}
+
+pooch_status pooch_set_profile(pooch_ctx *c, const double *t_fwd, const double *t_bwd, const double *t_refwd, const double *t_out,
+                               const double *t_in)
+{
+    NEED_FINAL(c);
+    if (!t_fwd || !t_bwd || !t_refwd || !t_out || !t_in) return fail(c, POOCH_E_INVALID, "set_profile: null pointer");
+    const int n = c->G.n();
+    const size_t nf = c->G.fmaps.size();
+    for (int i = 0; i < n; ++i)
+        if (!(t_fwd[i] >= 0.0) || !(t_bwd[i] >= 0.0) || !(t_refwd[i] >= 0.0)) return fail(c, POOCH_E_INVALID, "set_profile: negative or NaN duration");
+    for (size_t k = 0; k < nf; ++k)
+        if (!(t_out[k] >= 0.0) || !(t_in[k] >= 0.0)) return fail(c, POOCH_E_INVALID, "set_profile: negative or NaN duration");
+    Profile P;
+    P.t_fwd.assign(t_fwd, t_fwd + n); P.t_bwd.assign(t_bwd, t_bwd + n); P.t_refwd.assign(t_refwd, t_refwd + n);
+    P.t_out.assign(t_out, t_out + nf); P.t_in.assign(t_in, t_in + nf);
+    P.valid = true;
+    c->prof = P;
+    return POOCH_OK;
+}
+
+pooch_status pooch_plan(pooch_ctx *c, int mode, int max_bruteforce_bits, double *predicted_ms)
+{
+    NEED_FINAL(c);
+    if (mode < POOCH_MODE_INCORE || mode > POOCH_MODE_POOCH) return fail(c, POOCH_E_INVALID, "plan: unknown mode");
+    if (!c->prof.valid && mode >= POOCH_MODE_SWAPOPT) return fail(c, POOCH_E_NOPROFILE, "plan: the search needs a profile");
+    const Profile zero = c->prof.valid ? Profile() : zero_profile(c->G);
+    const Profile &P = c->prof.valid ? c->prof : zero;
+    int bits = max_bruteforce_bits <= 0 ? 10 : max_bruteforce_bits;
+    if (bits > 20) bits = 20;
+    const int64_t cap = (int64_t)c->arena_bytes - c->resident_bytes;
+    Planner pl(c->G, P, cap, c->arena ? (int64_t)c->pinned_bytes : -1, bits);
+    std::vector<uint8_t> cls;
+    double T = 0.0;
+    bool ahead = true;
+    const bool ok = pl.plan(mode, cls, T, ahead);
+    c->evals = pl.evals;
+    if (!ok) return fail(c, POOCH_E_BUDGET, "plan: not even the safest plan of this mode fits the budget");
+    const pooch_status ps = install(c, cls, ahead, T);
+    if (ps != POOCH_OK) return ps;
+    if (predicted_ms) *predicted_ms = T;
+    return POOCH_OK;
+}
+
+pooch_status pooch_get_plan(pooch_ctx *c, uint8_t *cls)
+{
+    NEED_FINAL(c);
+    if (!c->has_plan) return fail(c, POOCH_E_STATE, "no plan installed");
+    if (!cls) return fail(c, POOCH_E_INVALID, "get_plan: null pointer");
+    std::copy(c->cls.begin(), c->cls.end(), cls);
+    return POOCH_OK;
+}
+
+pooch_status pooch_set_plan(pooch_ctx *c, const uint8_t *cls, int sched)
+{
+    NEED_FINAL(c);
+    if (!cls || !valid_classes(c, cls)) return fail(c, POOCH_E_INVALID, "set_plan: bad classification");
+    const std::vector<uint8_t> v(cls, cls + c->G.fmaps.size());
+    double T = 0.0;
+    if (c->prof.valid) {
+        Schedule S;
+        if (build_schedule(c->G, v, (int64_t)c->arena_bytes - c->resident_bytes, sched != 0,
+                           c->arena ? (int64_t)c->pinned_bytes : -1, S))
+            T = simulate(c->G, S, c->prof).T;
+    }
+    return install(c, v, sched != 0, T);
+}
+
+pooch_status pooch_simulate(pooch_ctx *c, const uint8_t *cls, int sched, double *step_ms, size_t *peak_bytes)
+{
+    NEED_FINAL(c);
+    if (!cls || !valid_classes(c, cls)) return fail(c, POOCH_E_INVALID, "simulate: bad classification");
+    const std::vector<uint8_t> v(cls, cls + c->G.fmaps.size());
+    Schedule S;
+    std::string why;
+    if (!build_schedule(c->G, v, (int64_t)c->arena_bytes - c->resident_bytes, sched != 0, c->arena ? (int64_t)c->pinned_bytes : -1, S, &why))
+        return fail(c, POOCH_E_BUDGET, why);
+    if (peak_bytes) *peak_bytes = (size_t)S.peak;
+    if (step_ms) {
+        if (!c->prof.valid) return fail(c, POOCH_E_NOPROFILE, "simulate: no profile");
+        *step_ms = simulate(c->G, S, c->prof).T;
+    }
+    return POOCH_OK;
+}
+
+int64_t pooch_plan_evaluations(pooch_ctx *c) { return c ? c->evals : 0; }
+
+pooch_status pooch_get_overhead_sets(pooch_ctx *c, uint8_t *in_LO, uint8_t *in_LI)
+{
+    NEED_FINAL(c);
+    if (!c->prof.valid) return fail(c, POOCH_E_NOPROFILE, "overhead sets: no profile");
+    const std::vector<uint8_t> allswap(c->G.fmaps.size(), CLS_SWAP);
+    Schedule S;
+    std::string why;
+    if (!build_schedule(c->G, allswap, (int64_t)c->arena_bytes - c->resident_bytes, true, c->arena ? (int64_t)c->pinned_bytes : -1, S, &why))
+        return fail(c, POOCH_E_BUDGET, why);
+    const SimResult sr = simulate(c->G, S, c->prof);
+    const size_t nf = c->G.fmaps.size();
+    if (in_LO) { std::fill(in_LO, in_LO + nf, 0); for (int t : sr.LO) in_LO[c->G.fidx[t]] = 1; }
+    if (in_LI) { std::fill(in_LI, in_LI + nf, 0); for (int t : sr.LI) in_LI[c->G.fidx[t]] = 1; }
+    return POOCH_OK;
+}
+
+pooch_status pooch_get_commands(pooch_ctx *c, int64_t *rows, int64_t max_rows, int64_t *nrows)
+{
+    NEED_FINAL(c);
+    if (!c->has_plan) return fail(c, POOCH_E_STATE, "no plan installed");
+    const int64_t n = (int64_t)c->sched.cmds.size();
+    if (nrows) *nrows = n;
+    if (!rows) return POOCH_OK;
+    if (max_rows < n) return fail(c, POOCH_E_INVALID, "get_commands: buffer too small");
+    for (int64_t k = 0; k < n; ++k) {
+        const Cmd &cm = c->sched.cmds[k];
+        int64_t *r = rows + 8 * k;
+        r[0] = cm.kind; r[1] = cm.id;
+        for (int j = 0; j < 6; ++j) r[2 + j] = cm.a[j];
+    }
+    return POOCH_OK;
+}
+
+pooch_status pooch_step(pooch_ctx *c, float *loss_out)
+{
+    NEED_FINAL(c);
+    if (!c->has_plan) return fail(c, POOCH_E_STATE, "step: no plan installed");
+    const auto t0 = std::chrono::steady_clock::now();
+    const pooch_status ps = run_schedule(c, c->sched, nullptr, false, loss_out);
+    c->last_step_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    return ps;
+}
+
+pooch_status pooch_get_stats(pooch_ctx *c, pooch_stats *st)
+{
+    NEED_FINAL(c);
+    if (!st) return fail(c, POOCH_E_INVALID, "get_stats: null pointer");
+    std::memset(st, 0, sizeof(*st));
+    st->resident_bytes = (uint64_t)c->resident_bytes;
+    st->arena_bytes = (uint64_t)c->arena_bytes;
+    if (!c->has_plan) return POOCH_OK;
+    st->step_ms = c->last_step_ms;
+    st->predicted_ms = c->predicted_ms;
+    uint64_t out_b = 0, in_b = 0;
+    for (const Cmd &cm : c->sched.cmds) {
+        if (cm.kind == K_OUT) out_b += (uint64_t)c->G.nodes[cm.id].numel() * 4;
+        if (cm.kind == K_IN) in_b += (uint64_t)c->G.nodes[cm.id].numel() * 4;
+    }
+    st->swap_out_bytes = out_b;
+    st->swap_in_bytes = in_b;
+    st->peak_bytes = (uint64_t)c->sched.peak;
+    st->extent_bytes = (uint64_t)c->sched.extent;
+    for (uint8_t k : c->cls) {
+        if (k == CLS_KEEP) st->n_keep++;
+        else if (k == CLS_SWAP) st->n_swap++;
+        else st->n_recompute++;
+    }
+    st->n_commands = (int32_t)c->sched.cmds.size();
+    st->n_refwd = c->sched.n_refwd;
+    return POOCH_OK;
+}
+
+pooch_status pooch_step_timed(pooch_ctx *c, float *loss_out, double *ms_fwd, double *ms_bwd, double *ms_refwd)
+{
+    NEED_FINAL(c);
+    if (!c->has_plan) return fail(c, POOCH_E_STATE, "step: no plan installed");
+    Timing tm;
+    pooch_status ps = run_schedule(c, c->sched, &tm, false, loss_out);
+    if (ps != POOCH_OK) return ps;
+    const int n = c->G.n();
+    if (ms_fwd) std::fill(ms_fwd, ms_fwd + n, 0.0);
+    if (ms_bwd) std::fill(ms_bwd, ms_bwd + n, 0.0);
+    if (ms_refwd) std::fill(ms_refwd, ms_refwd + n, 0.0);
+    for (size_t k = 0; k < c->sched.cmds.size(); ++k) {
+        const Cmd &cm = c->sched.cmds[k];
+        if (cm.kind > K_BWD) continue;
+        double ms;
+        ps = elapsed(c, tm.start[k], tm.stop[k], ms);
+        if (ps != POOCH_OK) return ps;
+        double *dst = cm.kind == K_FWD ? ms_fwd : (cm.kind == K_BWD ? ms_bwd : ms_refwd);
+        if (dst) dst[cm.id] += ms;
+    }
+    return POOCH_OK;
+}
+
+pooch_status pooch_measure_link(pooch_ctx *c, size_t bytes, int iters, double *d2h_gbs, double *h2d_gbs)
+{
+    NEED_FINAL(c);
+    if (!c->arena || !c->pinned) return fail(c, POOCH_E_STATE, "measure_link needs an arena and a pinned buffer");
+    const size_t dyn = c->arena_bytes - (size_t)c->resident_bytes;
+    if (bytes == 0 || iters <= 0 || bytes > c->pinned_bytes || bytes > dyn) return fail(c, POOCH_E_INVALID, "measure_link: bad size");
+    pooch_status ps = ensure_events(c, c->timing_events, 2, hipEventDefault);
+    if (ps != POOCH_OK) return ps;
+    char *dev = c->arena + c->resident_bytes;
+    for (int dir = 0; dir < 2; ++dir) {
+        hipStream_t s = c->st[dir == 0 ? S_D2H : S_H2D];
+        // one untimed copy first
+        if (dir == 0) HIPCHK(hipMemcpyAsync(c->pinned, dev, bytes, hipMemcpyDeviceToHost, s));
+        else HIPCHK(hipMemcpyAsync(dev, c->pinned, bytes, hipMemcpyHostToDevice, s));
+        HIPCHK(hipEventRecord(c->timing_events[0], s));
+        for (int it = 0; it < iters; ++it) {
+            if (dir == 0) HIPCHK(hipMemcpyAsync(c->pinned, dev, bytes, hipMemcpyDeviceToHost, s));
+            else HIPCHK(hipMemcpyAsync(dev, c->pinned, bytes, hipMemcpyHostToDevice, s));
+        }
+        HIPCHK(hipEventRecord(c->timing_events[1], s));
+        HIPCHK(hipStreamSynchronize(s));
+        double ms;
+        ps = elapsed(c, 0, 1, ms);
+        if (ps != POOCH_OK) return ps;
+        const double gbs = (double)bytes * iters / (ms * 1e-3) / 1e9;
+        if (dir == 0 && d2h_gbs) *d2h_gbs = gbs;
+        if (dir == 1 && h2d_gbs) *h2d_gbs = gbs;
+    }
+    return POOCH_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every symbol the
+header declares, rejects malformed graphs and out-of-order calls with a status (never a
+crash), and its planning-only context reports the feature-map set the paper's ResNet-50
+numbers pin down."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads
+from paper_1907_05013_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "pooch.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pooch_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = header_symbols()
+    assert len(names) >= 35
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.SYMBOLS) == names          # the binding covers exactly the header
+
+
+def test_stats_struct_matches_header_size():
+    # 2 doubles + 6 uint64 + 6 int32
+    assert C.sizeof(B.Stats) == 2 * 8 + 6 * 8 + 6 * 4
+
+
+def test_planning_only_context_resnet50_feature_maps():
+    c = B.Context(workloads.resnet50(batch=640), 16 << 30, device=None)
+    fm = c.fmaps()
+    assert len(fm) == 105                                     # table 3's total
+    assert 50e9 < sum(b for b, _ in fm) < 52e9                # "more than 50 GB" (section 5.2)
+    assert c.resident_bytes() < 1 << 30
+    with pytest.raises(B.PoochError) as e:                    # compute calls need an arena
+        c.step()
+    assert e.value.status == B.E_STATE
+
+
+def _raw():
+    L = B.lib()
+    h = C.c_void_p()
+    assert L.pooch_create(None, 1 << 30, None, 0, None, None, None, C.byref(h)) == 0
+    return L, h
+
+
+def test_malformed_graphs_are_rejected():
+    L, h = _raw()
+    dims = (C.c_int64 * 4)(2, 3, 8, 8)
+    assert L.pooch_relu(h, 0) == B.E_INVALID                    # no input yet
+    assert L.pooch_input(h, dims, 3) == B.E_INVALID             # rank
+    assert L.pooch_input(h, dims, 4) == 0
+    assert L.pooch_input(h, dims, 4) == B.E_INVALID             # second input
+    k3 = (C.c_int * 2)(3, 3)
+    one = (C.c_int * 2)(1, 1)
+    big = (C.c_int * 2)(20, 20)
+    zero = (C.c_int * 2)(0, 0)
+    assert L.pooch_conv(h, 0, 4, big, one, zero, 2) == B.E_INVALID      # window larger than the padded input
+    assert L.pooch_conv(h, 0, 4, k3, zero, one, 2) == B.E_INVALID       # stride 0
+    assert L.pooch_conv(h, 0, 4, k3, one, one, 3) == B.E_INVALID        # spatial rank mismatch
+    assert L.pooch_conv(h, 7, 4, k3, one, one, 2) == B.E_INVALID        # unknown tensor
+    t = L.pooch_conv(h, 0, 4, k3, one, one, 2)
+    assert t == 1
+    u = L.pooch_conv(h, 0, 5, k3, one, one, 2)
+    assert L.pooch_add(h, t, u) == B.E_INVALID                          # shapes differ
+    assert L.pooch_softmax_ce(h, t) == B.E_INVALID                      # logits must be N x classes
+    assert L.pooch_finalize(h) == B.E_INVALID                           # no loss node
+    assert b"softmax_ce" in L.pooch_last_error(h)
+    assert L.pooch_num_fmaps(h) == B.E_STATE
+    L.pooch_destroy(h)
+
+
+def test_dangling_output_and_state_errors():
+    L, h = _raw()
+    dims = (C.c_int64 * 4)(2, 3, 8, 8)
+    L.pooch_input(h, dims, 4)
+    a = L.pooch_relu(h, 0)
+    L.pooch_relu(h, 0)                         # never consumed
+    g = L.pooch_gavgpool(h, a)
+    L.pooch_softmax_ce(h, g)
+    assert L.pooch_finalize(h) == B.E_INVALID
+    L.pooch_destroy(h)
+
+    c = B.Context(workloads.tiny_cnn(), 1 << 30, device=None)
+    with pytest.raises(B.PoochError) as e:
+        c.get_plan()
+    assert e.value.status == B.E_STATE
+    with pytest.raises(B.PoochError) as e:
+        c.plan("pooch")
+    assert e.value.status == B.E_NOPROFILE
+    assert B.lib().pooch_relu(c.h, 1) == B.E_STATE              # graph is frozen
+    with pytest.raises(B.PoochError) as e:
+        c.set_plan([7] * c.n_fmaps)
+    assert e.value.status == B.E_INVALID
+    with pytest.raises(B.PoochError):
+        c.set_profile(*([[-1.0] * c.n_nodes] * 3 + [[1.0] * c.n_fmaps] * 2))
+
+
+def test_budget_errors_at_planning_time():
+    net = workloads.tiny_cnn()
+    big = B.Context(net, 1 << 30, device=None)
+    res = big.resident_bytes()
+    with pytest.raises(B.BudgetError):
+        B.Context(net, res - 256, device=None)                     # resident region alone does not fit
+    c = B.Context(net, res + 4 * 256, device=None)
+    with pytest.raises(B.BudgetError):
+        c.plan("incore")
+    with pytest.raises(B.BudgetError):
+        c.set_plan([B.KEEP] * c.n_fmaps)
+    with pytest.raises(B.BudgetError):
+        c.simulate([B.SWAP] * c.n_fmaps, want_time=False)

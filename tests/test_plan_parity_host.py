@@ -1,0 +1,159 @@
+"""The library's planner (C++) against the plan oracle (oracle/plan.py), on the CPU.
+
+Integer work must agree exactly: feature-map set, command lists (kinds, ids, arena and
+pinned offsets, events), peak bytes, L_O / L_I, the classification every mode picks, the
+number of simulations.  Simulated times are sums of the same doubles in the same order, so
+they agree to the last bit as well.  The library's command lists also go through the
+independent schedule validator."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import schedule_check
+import workloads
+from oracle import plan as P
+from paper_1907_05013_amd import binding as B
+
+BIG = 1 << 44
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def nets():
+    return {
+        "tiny": workloads.tiny_cnn(),
+        "res": workloads.resnet50(batch=2, size=32, nclasses=5, blocks=(2, 1), width=4),
+        "c3d": workloads.cnn3d(size=8, channels=(2, 3, 4), nclasses=2, batch=2),
+        "bott": workloads.bottleneck_stage(batch=2, ch=16, size=8, blocks=2),
+    }
+
+
+def lib_ctx(net, dyn_cap):
+    probe = B.Context(net, 1 << 40, device=None)
+    res = probe.resident_bytes()
+    return B.Context(net, res + dyn_cap, device=None), res
+
+
+def rand_profile(G, rng, link=1.0):
+    nf = len(G.fmaps)
+    tf = rng.uniform(0.2, 3.0, G.n)
+    return [tf, rng.uniform(0.2, 5.0, G.n), tf * rng.uniform(0.3, 1.0, G.n),
+            rng.uniform(0.1, 4.0, nf) * link, rng.uniform(0.1, 4.0, nf) * link]
+
+
+def as_rows(S):
+    rows = []
+    for c in S.cmds:
+        r = list(c) + [0] * (8 - len(c))
+        rows.append(r)
+    return np.array(rows, np.int64).reshape(-1, 8)
+
+
+@pytest.mark.parametrize("name", ["tiny", "res", "c3d", "bott"])
+def test_feature_maps_and_command_lists_identical(name):
+    net = nets()[name]
+    G = P.Graph(net)
+    nf = len(G.fmaps)
+    incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
+    c, _ = lib_ctx(net, BIG)
+    assert [(G.bytes[t], t) for t in G.fmaps] == c.fmaps()
+    rng = np.random.default_rng(21)
+    prof = rand_profile(G, rng)
+    oprof = P.Profile(*[list(v) for v in prof])
+    ncmp = 0
+    for trial in range(40):
+        cls = [int(v) for v in rng.integers(0, 3, nf)] if trial else [P.KEEP] * nf
+        cap = BIG if trial == 0 else int(incore.peak * rng.uniform(0.35, 1.2)) // 256 * 256
+        c, _ = lib_ctx(net, cap)
+        c.set_profile(*prof)
+        for ahead in (True, False):
+            try:
+                S = P.build_schedule(G, cls, cap, ahead)
+            except P.Budget:
+                with pytest.raises(B.BudgetError):
+                    c.set_plan(cls, ahead)
+                continue
+            c.set_plan(cls, ahead)
+            rows = c.commands()
+            assert np.array_equal(rows, as_rows(S))
+            st = c.stats()
+            assert (st.peak_bytes, st.extent_bytes, st.n_refwd) == (S.peak, S.extent, S.n_refwd)
+            T, peak = c.simulate(cls, ahead)
+            assert T == P.simulate(G, S, oprof)[0] and peak == S.peak
+            schedule_check.check(G, [tuple(int(v) for v in r) for r in rows], cap)
+            ncmp += 1
+    assert ncmp > 20
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_every_mode_picks_the_oracles_plan(seed):
+    rng = np.random.default_rng(100 + seed)
+    net = list(nets().values())[seed % 4]
+    G = P.Graph(net)
+    nf = len(G.fmaps)
+    incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
+    cap = int(incore.peak * rng.uniform(0.45, 0.95)) // 256 * 256
+    prof = rand_profile(G, rng, link=float(rng.choice([0.2, 1.0, 4.0])))
+    oprof = P.Profile(*[list(v) for v in prof])
+    c, _ = lib_ctx(net, cap)
+    c.set_profile(*prof)
+    bits = 5
+    for mode in ("swapall_nosched", "swapall", "swapopt", "pooch"):
+        pl = P.Planner(G, oprof, cap, max_bits=bits)
+        try:
+            ocls, oT = pl.plan(mode)
+        except P.Budget:
+            with pytest.raises(B.BudgetError):
+                c.plan(mode, bits)
+            continue
+        cls, T = c.plan(mode, bits)
+        assert list(cls) == list(ocls)
+        assert T == oT
+        assert c.plan_evaluations() == pl.evals
+        if mode == "swapopt":
+            lo, li = c.overhead_sets()
+            assert {G.fmaps[k] for k in range(nf) if lo[k]} == pl.LO
+            assert {G.fmaps[k] for k in range(nf) if li[k]} == pl.LI
+
+
+def test_paper_eight_layer_example_through_the_library():
+    """section 4.4.2's worked example: L_O = {5,6,7}, L_I = {4,6,7} on the all-swap timeline"""
+    with open(os.path.join(GOLD, "eight_layer_example.json")) as f:
+        gold = json.load(f)
+    net = workloads.Net()
+    t = net.input((4, 8, 16, 16))
+    for _ in range(8):
+        t = net.relu(t)
+    net.softmax_ce(net.gavgpool(t))
+    c, _ = lib_ctx(net, BIG)
+    assert c.n_fmaps == 9
+    t_fwd = [0.0] + gold["t_fwd"] + [0.0, 0.0]
+    t_bwd = [0.0] + gold["t_bwd"] + [0.0, 0.0]
+    c.set_profile(t_fwd, t_bwd, t_fwd, gold["t_out"] + [0.0], gold["t_in"] + [0.0])
+    lo, li = c.overhead_sets()
+    assert [k for k in range(8) if lo[k]] == gold["L_O"]
+    assert [k for k in range(8) if li[k]] == gold["L_I"]
+    cls, T = c.plan("swapopt", 16)
+    assert list(cls[:4]) == [B.SWAP] * 4                       # hidden both ways: swap at once
+    n_li = int(li.sum())                                       # the pooled vector may join the sets
+    n_g = int((lo & ~li & 1).sum())
+    assert c.plan_evaluations() <= 2 + (1 << n_li) * (1 + n_g)  # 2^|L_I| leaves x |L_O \ L_I| greedy
+
+
+def test_resnet50_b640_plan_fits_16gib():
+    """the paper's headline case as a planning problem: 105 maps, > 50 GB, 16 GiB arena"""
+    net = workloads.resnet50(batch=640)
+    c = B.Context(net, 16 << 30, device=None)
+    G = P.Graph(net)
+    rng = np.random.default_rng(9)
+    prof = rand_profile(G, rng)
+    c.set_profile(*prof)
+    cls, T = c.plan("pooch", 4)
+    st = c.stats()
+    assert st.resident_bytes + st.extent_bytes <= 16 << 30
+    assert st.n_keep + st.n_swap + st.n_recompute == 105
+    rows = c.commands()
+    schedule_check.check(G, [tuple(int(v) for v in r) for r in rows], (16 << 30) - st.resident_bytes)
+    with pytest.raises(B.BudgetError):
+        c.plan("incore")                                        # in-core fails (section 5.2)
