@@ -1,0 +1,297 @@
+"""Benchmark of the out-of-core training step on one MI355X.
+
+A "step" is one forward + backward pass of the whole hot path under the memory budget:
+the plan comes from the library's own profiling pass and classification (both excluded
+from the timed region, as in the paper's section 5.2), inputs are resident in HBM.
+Default workload: ResNet-50, batch 640, fp32, 16 GiB arena (the paper's headline case).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--budget-gib G]
+
+Prints one JSON line.  `value` = images/sec under the budget.  Also measured in the same
+run: the in-core step at the same batch (overhead), per-kernel-family rates from HIP events
+recorded inside the timed steps (conv MFMA utilisation, BN / ReLU HBM GB/s), the swap
+traffic against the measured pinned-copy rate of the host link, and the CPU oracle on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+PEAK_MFMA_FP32 = 157.3e12   # MI355X dense fp32 matrix FLOP/s
+PEAK_HBM = 8.0e12           # bytes/s
+PAPER_B640_IMG_S = 195.0    # paper, ResNet50 batch 640 on V100 16 GB + PCIe3 (316 img/s in-core, 38 % degradation)
+
+WORKLOADS = {
+    # name: (config loader name, overrides, default budget in GiB or fraction of in-core peak)
+    "resnet50_b640_16g": ("resnet50_b640", {}, 16.0),
+    "resnet50_b64": ("resnet50_b64", {}, None),
+    "bottleneck_half": ("bottleneck", {}, "half"),
+    "cnn3d_24g": ("cnn3d", {}, 24.0),
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr)
+    sys.stderr.flush()
+
+
+def conv_geoms(net):
+    """per conv / fc node: (M rows_out, N cout, K reduction) of the implicit GEMM"""
+    shp = workloads.shapes(net)
+    out = {}
+    for i, L in enumerate(net):
+        if L["op"] == "conv":
+            xin = shp[L["x"]]
+            out[i] = (int(np.prod(shp[i][2:])) * shp[i][0], L["cout"], xin[1] * int(np.prod(L["k"])))
+        elif L["op"] == "fc":
+            out[i] = (shp[i][0], L["nout"], int(np.prod(shp[L["x"]][1:])))
+    return out
+
+
+def elem_counts(net):
+    shp = workloads.shapes(net)
+    return [int(np.prod(s)) if s else 0 for s in shp]
+
+
+def incore_arena(net, B):
+    """(smallest arena found that holds the in-core run, its peak of live bytes, resident bytes)"""
+    c = B.Context(net, 1 << 46, device=None)
+    keep = [B.KEEP] * c.n_fmaps
+    _, peak = c.simulate(keep, want_time=False)
+    res = c.resident_bytes()
+    dyn = peak
+    while True:
+        try:
+            B.Context(net, res + dyn, device=None).simulate(keep, want_time=False)
+            return int(res + dyn), int(peak), int(res)
+        except B.BudgetError:
+            dyn = int(dyn * 1.02) // 256 * 256 + 256
+
+
+def timed_steps(ctx, torch, steps, warmup):
+    for _ in range(warmup):
+        ctx.step()
+    acc = None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        r = ctx.step_timed()
+        acc = [np.array(v) for v in r[1:]] if acc is None else [a + np.array(v) for a, v in zip(acc, r[1:])]
+        loss = r[0]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dt / steps, [a / steps for a in acc], loss
+
+
+def kernel_report(ctx, net, ms, nrefwd_counts=None):
+    """group per-node event times by kernel family; ms = (fwd, bwd, refwd, bwd_filter) per node"""
+    fwd, bwd, refwd, bwf = ms
+    geo = conv_geoms(net)
+    n_el = elem_counts(net)
+    by_kernel = {}
+
+    def add(name, flops, t, launches=1):
+        if t <= 0:
+            return
+        k = by_kernel.setdefault(name, [0.0, 0.0, 0])
+        k[0] += flops
+        k[1] += t
+        k[2] += launches
+
+    conv_flops = conv_ms = 0.0
+    for i, (M, N, K) in geo.items():
+        fl = 2.0 * M * N * K
+        parts = [(0, fwd[i], 1), (1, bwd[i] - bwf[i], 1), (2, bwf[i], 1)]
+        for part, t, _ in parts:
+            if part == 1 and net[i].get("x") == 0:
+                continue            # the first layer has no data gradient
+            add(ctx.node_kernel(i, part), fl, t)
+            if net[i]["op"] == "conv":
+                conv_flops += fl
+                conv_ms += t
+        if refwd[i] > 0:
+            n = max(1, int(round(refwd[i] / max(fwd[i], 1e-9))))
+            add(ctx.node_kernel(i, 0), fl * n, refwd[i], n)
+            conv_flops += fl * n
+            conv_ms += refwd[i]
+    bn_bytes = bn_ms = ew_bytes = ew_ms = 0.0
+    for i, L in enumerate(net):
+        if L["op"] == "bn":
+            bn_bytes += (12 + 20) * n_el[i]
+            bn_ms += fwd[i] + bwd[i]
+            if refwd[i] > 0:
+                bn_bytes += 8 * n_el[i]
+                bn_ms += refwd[i]
+        elif L["op"] == "relu":
+            ew_bytes += (8 + 12) * n_el[i]
+            ew_ms += fwd[i] + bwd[i]
+            if refwd[i] > 0:
+                ew_bytes += 8 * n_el[i]
+                ew_ms += refwd[i]
+        elif L["op"] == "add":
+            ew_bytes += 12 * n_el[i]
+            ew_ms += fwd[i]
+    return by_kernel, (conv_flops, conv_ms), (bn_bytes, bn_ms), (ew_bytes, ew_ms)
+
+
+def cpu_baseline(name, budget_s=20.0):
+    """the oracle as it stands on a bounded sample of the workload, images/sec"""
+    from oracle.net import OracleNet
+    cfg, kw, _ = WORKLOADS[name]
+    if cfg.startswith("resnet50"):
+        sample = {"batch": 2}
+    elif cfg == "bottleneck":
+        sample = {"batch": 8}
+    else:
+        sample = {"size": 48}
+    net, seed = workloads.load(cfg, **dict(kw, **sample))
+    params = workloads.make_params(net, seed)
+    x, t = workloads.make_batch(net, seed)
+    o = OracleNet(net, params, np.float32)
+    t0 = time.perf_counter()
+    o.step(x, t)
+    dt = time.perf_counter() - t0
+    batch = net[0]["shape"][0]
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    desc = "one oracle step of %s with %s (%.1f s)" % (cfg, ", ".join("%s=%s" % kv for kv in sample.items()), dt)
+    value = batch / dt
+    if cfg == "cnn3d":
+        # per-voxel cost is size-independent: scale the 48^3 sample to the 192^3 volume
+        value = value / (192 / 48) ** 3
+        desc += ", scaled by (48/192)^3 to the full volume"
+    return {"value": value, "unit": "images/sec", "cores": cores, "kind": "oracle", "sample": desc}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="resnet50_b640_16g", choices=sorted(WORKLOADS))
+    ap.add_argument("--budget-gib", type=float, default=None)
+    ap.add_argument("--mode", default="pooch", choices=["swapall_nosched", "swapall", "swapopt", "pooch"])
+    ap.add_argument("--bits", type=int, default=8, help="cap on the exponential part of the keep/swap search")
+    ap.add_argument("--no-incore", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    from paper_1907_05013_amd import binding as B
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+
+    cfg, kw, budget = WORKLOADS[args.workload]
+    net, seed = workloads.load(cfg, **kw)
+    batch = net[0]["shape"][0]
+    params = workloads.make_params(net, seed)
+    x, t = workloads.make_batch(net, seed)
+    incore_bytes, incore_peak, resident = incore_arena(net, B)
+    if args.budget_gib is not None:
+        budget = args.budget_gib
+    if budget == "half":
+        arena_bytes = resident + (incore_peak // 2) // 256 * 256
+    elif budget is None:
+        arena_bytes = incore_bytes
+    else:
+        arena_bytes = int(budget * 2 ** 30)
+    under_budget = arena_bytes < incore_bytes
+    fm_bytes = sum(b for b, _ in B.Context(net, 1 << 46, device=None).fmaps())
+    log("[bench] %s: batch %d, %d layers, feature maps %.2f GB, in-core arena %.2f GB, arena %.2f GB" %
+        (args.workload, batch, len(net), fm_bytes / 1e9, incore_bytes / 1e9, arena_bytes / 1e9))
+
+    result_extra = {}
+    if under_budget:
+        ctx = B.Context(net, arena_bytes, pinned_bytes=fm_bytes + 4096)
+        ctx.set_params(params)
+        ctx.set_batch(x, t)
+        link = ctx.measure_link(min(1 << 30, (arena_bytes - resident) // 2 // 256 * 256), 3)
+        log("[bench] host link: D2H %.1f GB/s, H2D %.1f GB/s" % link)
+        t0 = time.perf_counter()
+        ctx.profile(warmup=1, iters=2)
+        t1 = time.perf_counter()
+        cls, predicted = ctx.plan(args.mode, args.bits)
+        t2 = time.perf_counter()
+        st = ctx.stats()
+        log("[bench] profile %.1f s, plan %.1f s (%d simulations): keep/swap/recompute %d/%d/%d, predicted %.1f ms" %
+            (t1 - t0, t2 - t1, ctx.plan_evaluations(), st.n_keep, st.n_swap, st.n_recompute, predicted))
+        sec, ms, loss = timed_steps(ctx, torch, args.steps, args.warmup)
+        st = ctx.stats()
+        result_extra.update({
+            "plan": {"mode": args.mode, "keep": st.n_keep, "swap": st.n_swap, "recompute": st.n_recompute,
+                     "re_forwards": st.n_refwd, "predicted_ms": predicted,
+                     "profile_s": t1 - t0, "plan_s": t2 - t1, "simulations": ctx.plan_evaluations()},
+            "swap": {"out_GB": st.swap_out_bytes / 1e9, "in_GB": st.swap_in_bytes / 1e9,
+                     "link_peak_d2h_GBs": link[0], "link_peak_h2d_GBs": link[1],
+                     "achieved_GBs_over_step": (st.swap_out_bytes + st.swap_in_bytes) / 1e9 / sec},
+        })
+        rep = kernel_report(ctx, net, ms)
+        ctx.close()
+        del ctx
+        torch.cuda.empty_cache()
+    incore_sec = None
+    if not under_budget or not args.no_incore:
+        ctx = B.Context(net, incore_bytes)
+        ctx.set_params(params)
+        ctx.set_batch(x, t)
+        ctx.set_plan([B.KEEP] * ctx.n_fmaps)
+        incore_sec, ms_in, loss_in = timed_steps(ctx, torch, args.steps, args.warmup)
+        rep_in = kernel_report(ctx, net, ms_in)
+        if not under_budget:
+            sec, rep, loss = incore_sec, rep_in, loss_in
+        ctx.close()
+        del ctx
+        torch.cuda.empty_cache()
+
+    by_kernel, (cfl, cms), (bnb, bnms), (ewb, ewms) = rep
+    dom = max(by_kernel.items(), key=lambda kv: kv[1][1])
+    dom_tflops = dom[1][0] / (dom[1][1] * 1e-3)
+    out = {
+        "metric": "images/sec per train step under budget",
+        "value": batch / sec,
+        "unit": "images/sec",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": sec * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": (batch / sec) / PAPER_B640_IMG_S if args.workload == "resnet50_b640_16g" else None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "batch": batch, "arena_GiB": arena_bytes / 2 ** 30,
+                   "feature_maps_GB": fm_bytes / 1e9, "incore_arena_GB": incore_bytes / 1e9,
+                   "under_budget": under_budget},
+        "loss": loss,
+        "roofline": {"bound": "mfma", "kernel": dom[0], "achieved": dom_tflops / 1e12, "peak": PEAK_MFMA_FP32 / 1e12,
+                     "unit": "TFLOP/s", "frac": dom_tflops / PEAK_MFMA_FP32, "traffic": None,
+                     "launches_per_step": dom[1][2], "avg_launch_ms": dom[1][1] / max(dom[1][2], 1)},
+        "conv_mfma_util": (cfl / (cms * 1e-3)) / PEAK_MFMA_FP32 if cms > 0 else None,
+        "conv_TFLOPs": cfl / (cms * 1e-3) / 1e12 if cms > 0 else None,
+        "bn_hbm_GBs": bnb / (bnms * 1e-3) / 1e9 if bnms > 0 else None,
+        "relu_add_hbm_GBs": ewb / (ewms * 1e-3) / 1e9 if ewms > 0 else None,
+        "hbm_peak_GBs": PEAK_HBM / 1e9,
+        "kernels": {k: {"TFLOPs": v[0] / (v[1] * 1e-3) / 1e12, "ms_per_step": v[1], "launches": v[2]}
+                    for k, v in sorted(by_kernel.items())},
+    }
+    if incore_sec is not None:
+        out["incore_images_per_sec"] = batch / incore_sec
+        out["overhead_vs_incore"] = 1.0 - incore_sec / sec if under_budget else 0.0
+    out.update(result_extra)
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

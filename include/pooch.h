@@ -186,8 +186,15 @@ pooch_status pooch_get_stats(pooch_ctx *, pooch_stats *);
 
 /* Times one step with HIP events around every command and returns per-node milliseconds of
  * the installed plan's forward, backward and re-forward work (arrays of num_nodes doubles,
- * any may be NULL) -- the source of per-kernel rates in the benchmark. */
-pooch_status pooch_step_timed(pooch_ctx *, float *loss_out, double *ms_fwd, double *ms_bwd, double *ms_refwd);
+ * any may be NULL) -- the source of per-kernel rates in the benchmark.  ms_bwd_filter is the
+ * part of a conv / fc layer's backward spent on the filter gradient (the data gradient takes
+ * the rest of ms_bwd); zero for other layers. */
+pooch_status pooch_step_timed(pooch_ctx *, float *loss_out, double *ms_fwd, double *ms_bwd, double *ms_refwd,
+                              double *ms_bwd_filter);
+/* name of the GPU kernel variant a conv / fc layer launches for part 0 forward, 1 data
+ * gradient, 2 filter gradient (static string, "" for other layers): lets a benchmark group
+ * per-layer times by kernel, as a profiler's per-kernel summary does. */
+const char *pooch_node_kernel(pooch_ctx *, int32_t node, int part);
 
 /* measured pinned-copy rate of the host link: copies `bytes` each way `iters` times through
  * the context's copy streams and pinned buffer; GB/s (1e9) each way. */

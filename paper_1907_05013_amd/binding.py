@@ -75,7 +75,8 @@ SYMBOLS = {
     "pooch_get_commands": (_i32, [_ctx, _pi64, _i64, _pi64]),
     "pooch_step": (_i32, [_ctx, _pf]),
     "pooch_get_stats": (_i32, [_ctx, C.POINTER(Stats)]),
-    "pooch_step_timed": (_i32, [_ctx, _pf, _pd, _pd, _pd]),
+    "pooch_step_timed": (_i32, [_ctx, _pf, _pd, _pd, _pd, _pd]),
+    "pooch_node_kernel": (C.c_char_p, [_ctx, _i32, C.c_int]),
     "pooch_measure_link": (_i32, [_ctx, _sz, C.c_int, _pd, _pd]),
 }
 
@@ -89,6 +90,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libpooch.so is not built: run `python -m paper_1907_05013_amd.build` "
                                "(there is no fallback path)")
+        # torch first: the library then binds to the HIP runtime torch has already loaded, so
+        # the arena torch allocates and the kernels launched here live in one runtime
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         for name, (res, args) in SYMBOLS.items():
             fn = getattr(L, name)
@@ -316,9 +320,12 @@ class Context:
 
     def step_timed(self):
         loss = C.c_float()
-        a = [np.empty(self.n_nodes) for _ in range(3)]
+        a = [np.empty(self.n_nodes) for _ in range(4)]
         self._chk(self.L.pooch_step_timed(self.h, C.byref(loss), *[_dptr(v) for v in a]))
-        return loss.value, a[0], a[1], a[2]
+        return loss.value, a[0], a[1], a[2], a[3]
+
+    def node_kernel(self, node, part):
+        return self.L.pooch_node_kernel(self.h, node, part).decode()
 
     def stats(self):
         s = Stats()

@@ -549,6 +549,28 @@ hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const Con
     return dispatch_igemm<true>(p, accumulate, s);
 }
 
+const char *conv_fwd_kernel(const ConvGeom &g)
+{
+    const bool vec = g.C % 4 == 0;
+    if (g.K <= 32) return vec ? "igemm_kernel<4,1,2,1,vec,fwd>" : "igemm_kernel<4,1,2,1,scalar,fwd>";
+    if (g.K <= 64) return vec ? "igemm_kernel<4,1,2,2,vec,fwd>" : "igemm_kernel<4,1,2,2,scalar,fwd>";
+    return vec ? "igemm_kernel<2,2,2,2,vec,fwd>" : "igemm_kernel<2,2,2,2,scalar,fwd>";
+}
+
+const char *conv_dgrad_kernel(const ConvGeom &g)
+{
+    const bool vec = g.K % 4 == 0;
+    if (g.C <= 32) return vec ? "igemm_kernel<4,1,2,1,vec,dgrad>" : "igemm_kernel<4,1,2,1,scalar,dgrad>";
+    if (g.C <= 64) return vec ? "igemm_kernel<4,1,2,2,vec,dgrad>" : "igemm_kernel<4,1,2,2,scalar,dgrad>";
+    return vec ? "igemm_kernel<2,2,2,2,vec,dgrad>" : "igemm_kernel<2,2,2,2,scalar,dgrad>";
+}
+
+const char *conv_wgrad_kernel(const ConvGeom &g)
+{
+    const WGradCfg c = wgrad_cfg(g);
+    return c.bm == 32 ? "wgrad_kernel<1,2,1,2>" : (c.bm == 64 ? "wgrad_kernel<1,2,2,2>" : "wgrad_kernel<2,2,2,2>");
+}
+
 size_t conv_wgrad_workspace(const ConvGeom &g)
 {
     if (!geom_ok(g)) return 0;

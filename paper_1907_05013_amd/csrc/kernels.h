@@ -30,6 +30,11 @@ size_t conv_wgrad_workspace(const ConvGeom &g);
 // dw_krsc[K,taps,C] = filter gradient, deterministic split-K through `workspace`
 hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *workspace, const ConvGeom &g, hipStream_t s);
 
+// names of the kernel variants the three launchers above pick for a geometry
+const char *conv_fwd_kernel(const ConvGeom &g);
+const char *conv_dgrad_kernel(const ConvGeom &g);
+const char *conv_wgrad_kernel(const ConvGeom &g);
+
 // number of floats of scratch the BN reductions need for an [M][C] tensor
 size_t bn_workspace_floats(int64_t M, int C);
 // batch statistics (mean, 1/sqrt(var+eps)) then y = gamma*(x-mean)*istd + beta

@@ -32,6 +32,7 @@ struct ParamInfo {
 struct Timing {
     std::vector<int> start, stop;      // per command: indices into the timing-event pool, -1 = untimed
     std::vector<int> rstart, rstop;    // profile mode: the re-forward run right after a forward
+    std::vector<int> mid;              // conv / fc backward: between the filter and the data gradient
 };
 
 }  // namespace
@@ -158,6 +159,7 @@ void act_from_device_layout(const float *nsc, int64_t N, int64_t C, int64_t S, f
 struct Exec {
     pooch_ctx *c;
     const Schedule &S;
+    hipEvent_t mid = nullptr;  // when set, recorded between the filter gradient and the data gradient
     explicit Exec(pooch_ctx *ctx, const Schedule &s) : c(ctx), S(s) {}
 
     float *R(int64_t off) const { return reinterpret_cast<float *>(c->arena + off); }  // resident
@@ -228,6 +230,10 @@ struct Exec {
             if (e != hipSuccess) return e;
             if (nd.op == OP_FC) {
                 e = pk::bias_grad(D(dy), R(P(i, 1).off_grad), (int)nd.N, (int)nd.C, s);
+                if (e != hipSuccess) return e;
+            }
+            if (mid) {
+                e = hipEventRecord(mid, s);
                 if (e != hipSuccess) return e;
             }
             if (m0 == M_NONE) return hipSuccess;
@@ -302,11 +308,14 @@ pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool prof
     if (tm) {
         const size_t nc = S.cmds.size();
         tm->start.assign(nc, -1); tm->stop.assign(nc, -1); tm->rstart.assign(nc, -1); tm->rstop.assign(nc, -1);
+        tm->mid.assign(nc, -1);
         for (size_t k = 0; k < nc; ++k) {
             const int kind = S.cmds[k].kind;
             if (kind == K_REC || kind == K_WAIT) continue;
             tm->start[k] = (int)n_te++; tm->stop[k] = (int)n_te++;
-            if (profile_refwd && kind == K_FWD && c->G.nodes[S.cmds[k].id].op != OP_LOSS) {
+            const Op op = kind <= K_BWD ? c->G.nodes[S.cmds[k].id].op : OP_INPUT;
+            if (kind == K_BWD && (op == OP_CONV || op == OP_FC)) tm->mid[k] = (int)n_te++;
+            if (profile_refwd && kind == K_FWD && op != OP_LOSS) {
                 tm->rstart[k] = (int)n_te++; tm->rstop[k] = (int)n_te++;
             }
         }
@@ -342,7 +351,9 @@ pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool prof
             for (int j = 0; j < 2; ++j)
                 if (cm.a[3 + 2 * j] != M_NONE && !in_arena(cm.a[2 + 2 * j], G.bytes[G.nodes[i].in[j]]))
                     return fail(c, POOCH_E_INVALID, "command outside the arena");
+            X.mid = (tm && tm->mid[k] >= 0) ? c->timing_events[tm->mid[k]] : nullptr;
             HIPCHK(X.backward(i, cm.a));
+            X.mid = nullptr;
             if (tm && tm->start[k] >= 0) HIPCHK(hipEventRecord(c->timing_events[tm->stop[k]], c->st[stream]));
             break;
         }
@@ -999,7 +1010,7 @@ pooch_status pooch_get_stats(pooch_ctx *c, pooch_stats *st)
     return POOCH_OK;
 }
 
-pooch_status pooch_step_timed(pooch_ctx *c, float *loss_out, double *ms_fwd, double *ms_bwd, double *ms_refwd)
+pooch_status pooch_step_timed(pooch_ctx *c, float *loss_out, double *ms_fwd, double *ms_bwd, double *ms_refwd, double *ms_bwd_filter)
 {
     NEED_FINAL(c);
     if (!c->has_plan) return fail(c, POOCH_E_STATE, "step: no plan installed");
@@ -1010,6 +1021,7 @@ pooch_status pooch_step_timed(pooch_ctx *c, float *loss_out, double *ms_fwd, dou
     if (ms_fwd) std::fill(ms_fwd, ms_fwd + n, 0.0);
     if (ms_bwd) std::fill(ms_bwd, ms_bwd + n, 0.0);
     if (ms_refwd) std::fill(ms_refwd, ms_refwd + n, 0.0);
+    if (ms_bwd_filter) std::fill(ms_bwd_filter, ms_bwd_filter + n, 0.0);
     for (size_t k = 0; k < c->sched.cmds.size(); ++k) {
         const Cmd &cm = c->sched.cmds[k];
         if (cm.kind > K_BWD) continue;
@@ -1018,8 +1030,22 @@ pooch_status pooch_step_timed(pooch_ctx *c, float *loss_out, double *ms_fwd, dou
         if (ps != POOCH_OK) return ps;
         double *dst = cm.kind == K_FWD ? ms_fwd : (cm.kind == K_BWD ? ms_bwd : ms_refwd);
         if (dst) dst[cm.id] += ms;
+        if (ms_bwd_filter && tm.mid[k] >= 0) {
+            ps = elapsed(c, tm.start[k], tm.mid[k], ms);
+            if (ps != POOCH_OK) return ps;
+            ms_bwd_filter[cm.id] += ms;
+        }
     }
     return POOCH_OK;
+}
+
+const char *pooch_node_kernel(pooch_ctx *c, int32_t node, int part)
+{
+    if (!c || !c->finalized || node < 0 || node >= c->G.n() || part < 0 || part > 2) return "";
+    const Op op = c->G.nodes[node].op;
+    if (op != OP_CONV && op != OP_FC) return "";
+    const pk::ConvGeom g = conv_geom(c->G, node);
+    return part == 0 ? pk::conv_fwd_kernel(g) : (part == 1 ? pk::conv_dgrad_kernel(g) : pk::conv_wgrad_kernel(g));
 }
 
 pooch_status pooch_measure_link(pooch_ctx *c, size_t bytes, int iters, double *d2h_gbs, double *h2d_gbs)

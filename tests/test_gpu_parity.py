@@ -1,0 +1,335 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+and every out-of-core plan against the in-core GPU run, bit for bit.
+
+Tolerance (floating point): per tensor, ||gpu - oracle||_2 <= 1e-3 * ||oracle||_2, and for
+the loss |gpu - oracle| <= 1e-3 * |oracle| -- the bar the benchmark spec fixes for fp32.
+The oracle accumulates in double; the kernels accumulate in fp32 (MFMA), so the observed
+error is far below the bar and the tests also print it.  Swapping copies bits and
+recomputation re-executes the same deterministic kernels (sections 3.1, 3.2), so any plan
+must reproduce the in-core loss and gradients exactly."""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle.net import OracleNet
+from oracle import plan as OP
+from paper_1907_05013_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-3
+BIG = 1 << 44
+
+
+def say(*a):
+    print(*a)
+    sys.stdout.flush()
+
+
+def rel(a, b):
+    a = np.asarray(a, np.float64).ravel()
+    b = np.asarray(b, np.float64).ravel()
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def plan_sizes(net):
+    """(resident bytes, in-core peak of the dynamic region) from a planning-only context"""
+    c = B.Context(net, 1 << 44, device=None)
+    _, peak = c.simulate([B.KEEP] * c.n_fmaps, want_time=False)
+    return c.resident_bytes(), peak
+
+
+def gpu_step(net, params, x, t, cls=None, sched=True, dyn_bytes=None, capture=False):
+    """one step under an explicit classification (default: all keep); returns loss, grads, outs"""
+    res, peak = plan_sizes(net)
+    dyn = 2 * peak if dyn_bytes is None else dyn_bytes     # in-core: room to spare
+    G = OP.Graph(net)
+    fbytes = sum(G.fmap_bytes())
+    c = B.Context(net, res + dyn, pinned_bytes=fbytes + 256)
+    c.set_params(params)
+    c.set_batch(x, t)
+    c.set_plan([B.KEEP] * c.n_fmaps if cls is None else cls, sched)
+    outs = {}
+    if capture:
+        shp = workloads.shapes(net)
+        for i in range(1, len(net) - 1):
+            outs[i] = np.full(shp[i], np.nan, np.float32)
+            c.capture(i, outs[i])
+    loss = c.step()
+    grads = c.get_grads([s for _, _, s in workloads.param_shapes(net)])
+    st = c.stats()
+    c.close()
+    return loss, grads, outs, st
+
+
+def oracle_step(net, params, x, t):
+    o = OracleNet(net, params, np.float32)
+    loss, grads, _ = o.step(x, t)
+    return loss, grads, o.out
+
+
+def check_against_oracle(tag, net, seed, perturb=True, capture=True):
+    params = workloads.make_params(net, seed, perturb=perturb)
+    x, t = workloads.make_batch(net, seed)
+    say("[case]", tag, "input", net[0]["shape"], "layers", len(net), "seed", seed)
+    ol, og, oo = oracle_step(net, params, x, t)
+    gl, gg, go, _ = gpu_step(net, params, x, t, capture=capture)
+    worst = 0.0
+    if capture:
+        for i in sorted(go):
+            r = rel(go[i], oo[i])
+            worst = max(worst, r)
+            assert np.isfinite(go[i]).all(), (tag, "layer", i, net[i]["op"], "not finite")
+            assert r <= RTOL, (tag, "forward of layer", i, net[i]["op"], r)
+    assert abs(gl - ol) <= RTOL * abs(ol), (tag, "loss", gl, ol)
+    names = workloads.param_shapes(net)
+    for k, (a, b) in enumerate(zip(gg, og)):
+        r = rel(a, b)
+        worst = max(worst, r)
+        assert a.shape == b.shape and np.isfinite(a).all()
+        assert r <= RTOL, (tag, "gradient of parameter", k, names[k], r)
+    say("[ok]", tag, "loss gpu %.7f oracle %.7f worst relative error %.2e" % (gl, ol, worst))
+    return params, x, t, gl, gg
+
+
+def assert_bit_exact(tag, ref, got):
+    (l0, g0), (l1, g1) = ref, got
+    assert np.float32(l0).tobytes() == np.float32(l1).tobytes(), (tag, "loss differs", l0, l1)
+    for k, (a, b) in enumerate(zip(g0, g1)):
+        assert a.tobytes() == b.tobytes(), (tag, "gradient", k, "differs; max abs", float(np.abs(a - b).max()))
+
+
+# ------------------------------------------------------------------ configuration 1
+
+def tiny_explicit_plan(net):
+    """2 maps swap, 1 recomputes, the rest stay: the first two conv outputs swap, the second
+    ReLU output is recomputed"""
+    G = OP.Graph(net)
+    cls = [B.KEEP] * len(G.fmaps)
+    convs = [k for k, t in enumerate(G.fmaps) if net[t]["op"] == "conv"]
+    relus = [k for k, t in enumerate(G.fmaps) if net[t]["op"] == "relu"]
+    cls[convs[0]] = cls[convs[1]] = B.SWAP
+    cls[relus[1]] = B.RECOMPUTE
+    return cls
+
+
+def test_config1_tiny_cnn_vs_oracle_and_explicit_plan():
+    net, seed = workloads.load("tiny")
+    params, x, t, loss, grads = check_against_oracle("config1 tiny", net, seed)
+    cls = tiny_explicit_plan(net)
+    assert cls.count(B.SWAP) == 2 and cls.count(B.RECOMPUTE) == 1
+    # smallest arena (in 256-byte steps) that admits this plan; it is below the in-core peak
+    G = OP.Graph(net)
+    res, peak = plan_sizes(net)
+    lo = None
+    for cap in range(256, peak + 256, 256):
+        try:
+            OP.build_schedule(G, cls, cap)
+            lo = cap
+            break
+        except OP.Budget:
+            continue
+    assert lo is not None and lo < peak
+    l1, g1, _, st = gpu_step(net, params, x, t, cls=cls, dyn_bytes=lo)
+    assert (st.n_swap, st.n_recompute) == (2, 1) and st.n_refwd >= 1 and st.swap_out_bytes > 0
+    assert_bit_exact("config1 plan", (loss, grads), (l1, g1))
+    # default initialisation too (gamma = 1, beta = 0, bias = 0)
+    check_against_oracle("config1 tiny, default init", net, seed, perturb=False)
+
+
+# ------------------------------------------------------------------ layer zoo / edge cases
+
+def zoo_net(batch, cin, size, c1, c2, k1, s1, p1):
+    """conv (k1, stride s1, pad p1) -> bn -> relu -> maxpool 3/2/1 -> conv 1x1 -> bn -> fork:
+    [conv 3x3 -> bn] + identity -> relu -> gavgpool -> fc"""
+    net = workloads.Net()
+    t = net.input((batch, cin, size, size))
+    t = net.relu(net.bn(net.conv(t, c1, (k1, k1), (s1, s1), (p1, p1))))
+    t = net.maxpool(t, (3, 3), (2, 2), (1, 1))
+    t = net.bn(net.conv(t, c2, (1, 1), (1, 1), (0, 0)))
+    u = net.bn(net.conv(t, c2, (3, 3), (1, 1), (1, 1)))
+    t = net.relu(net.add(u, t))
+    t = net.fc(net.gavgpool(t), 7)
+    net.softmax_ce(t)
+    return net
+
+
+@pytest.mark.parametrize("batch,cin,size,c1,c2,k1,s1,p1", [
+    (1, 1, 9, 3, 5, 3, 1, 1),         # batch 1, odd sizes, channel counts not multiples of 4
+    (3, 3, 17, 6, 7, 7, 2, 3),        # stem-like 7x7 stride 2 on 3 channels, ragged everything
+    (2, 4, 12, 8, 12, 5, 1, 0),       # no padding, vector path (C % 4 == 0)
+    (2, 8, 16, 40, 136, 3, 2, 1),     # more than one 128-wide output-channel tile, strided 3x3
+])
+def test_layer_zoo_vs_oracle(batch, cin, size, c1, c2, k1, s1, p1):
+    net = zoo_net(batch, cin, size, c1, c2, k1, s1, p1)
+    check_against_oracle("zoo %s" % ((batch, cin, size, c1, c2, k1, s1, p1),), net, 77 + size)
+
+
+def test_fc_on_spatial_input_and_3d():
+    """fc directly on a feature map with spatial extent (flattened in logical C,D,H,W order)"""
+    net = workloads.Net()
+    t = net.input((2, 2, 5, 6, 7))
+    t = net.relu(net.bn(net.conv(t, 5, (3, 3, 3), (1, 2, 1), (1, 0, 1))))
+    t = net.maxpool(t, (2, 2, 2), (2, 2, 2), (0, 0, 0))
+    t = net.fc(t, 4)
+    net.softmax_ce(t)
+    check_against_oracle("fc on 3-d map", net, 5)
+
+
+# ------------------------------------------------------------------ reduced copies of configs 2-5
+
+def reduced_nets():
+    return {
+        # several 128-row tiles plus a ragged tail in every conv GEMM; all ResNet-50 layer kinds
+        "resnet": workloads.resnet50(batch=3, size=64, nclasses=11, blocks=(2, 1, 1, 1), width=16),
+        "bottleneck": workloads.bottleneck_stage(batch=3, ch=256, size=14, blocks=2),
+        "cnn3d": workloads.cnn3d(size=20, channels=(4, 8, 12), nclasses=2, batch=1),
+    }
+
+
+@pytest.mark.parametrize("name", ["resnet", "bottleneck", "cnn3d"])
+def test_reduced_configs_vs_oracle_and_random_plans(name):
+    net = reduced_nets()[name]
+    params, x, t, loss, grads = check_against_oracle("reduced " + name, net, 31)
+    G = OP.Graph(net)
+    nf = len(G.fmaps)
+    res, peak = plan_sizes(net)
+    rng = np.random.default_rng(4)
+    ran = 0
+    for trial in range(40):
+        cls = [int(v) for v in rng.integers(0, 3, nf)]
+        cap = int(peak * rng.uniform(0.4, 1.0)) // 256 * 256
+        sched = bool(trial % 2)
+        try:
+            OP.build_schedule(G, cls, cap, sched)
+        except OP.Budget:
+            continue
+        say("[plan]", name, "trial", trial, "cap", cap, "sched", sched, "classes", "".join(map(str, cls)))
+        l1, g1, _, st = gpu_step(net, params, x, t, cls=cls, sched=sched, dyn_bytes=cap)
+        assert st.peak_bytes <= cap
+        assert_bit_exact("%s trial %d" % (name, trial), (loss, grads), (l1, g1))
+        ran += 1
+        if ran >= 8:
+            break
+    assert ran >= 4
+
+
+# ------------------------------------------------------------------ full-size runs
+
+def decision_aware_check(tag, net, seed, perturb=False):
+    """Whole-net parity where ReLU sign decisions can differ between two correct fp32 runs.
+
+    A pre-activation within rounding distance of zero may legitimately land on either side;
+    the backward pass then differs by that element's whole gradient, which moves every
+    upstream weight gradient by about 1/sqrt(#positions) of its norm per flipped element
+    (the oracle's own fp32-storage build differs from its fp64 build by up to 1e-2 on
+    ResNet-50 for this reason alone).  So: forward values and the loss are held to 1e-3;
+    every decision that differs must be a near-tie (the oracle's pre-activation lies within
+    the two runs' largest element-wise distance, itself <= 1e-3 of the rms); with no differing
+    decision the gradients are held to 1e-3, otherwise to
+        1e-3 + 4 * e0 + 0.5 * sqrt(sum_l F_l / P_l)
+    with e0 = error of the oracle's fp32 build against its fp64 build on that tensor,
+    F_l the differing decisions of ReLU layer l and P_l its positions (batch x space)."""
+    params = workloads.make_params(net, seed, perturb=perturb)
+    x, t = workloads.make_batch(net, seed)
+    say("[case]", tag, "input", net[0]["shape"], "layers", len(net), "seed", seed)
+    o32 = OracleNet(net, params, np.float32)
+    l32, g32, _ = o32.step(x, t)
+    o64 = OracleNet(net, params, np.float64)
+    l64, g64, _ = o64.step(x, t)
+    gl, gg, go, _ = gpu_step(net, params, x, t, capture=True)
+    assert abs(gl - l32) <= RTOL * abs(l32), (tag, "loss", gl, l32)
+    flips, allowance2, worst_f = 0, 0.0, 0.0
+    for i in sorted(go):
+        r = rel(go[i], o32.out[i])
+        worst_f = max(worst_f, r)
+        assert np.isfinite(go[i]).all() and r <= RTOL, (tag, "forward of layer", i, net[i]["op"], r)
+        if net[i]["op"] == "relu":
+            diff = (go[i] > 0) != (o32.out[i] > 0)
+            f = int(diff.sum())
+            if f:
+                # valid only as a near-tie: the oracle's pre-activation is no further from zero
+                # than the two runs are from each other, and that distance is itself small
+                pre = o32.out[net[i]["x"]]
+                rms = float(np.sqrt(np.mean(pre.astype(np.float64) ** 2)))
+                gap = float(np.abs(go[net[i]["x"]] - pre).max())
+                assert gap <= RTOL * rms, (tag, "layer", i, "pre-activation error", gap, rms)
+                assert float(np.abs(pre[diff]).max()) <= gap, (tag, "layer", i, "decision differs away from a tie")
+                flips += f
+                allowance2 += f / (pre.shape[0] * float(np.prod(pre.shape[2:])))
+    names = workloads.param_shapes(net)
+    worst_g = 0.0
+    for k, (a, b32, b64) in enumerate(zip(gg, g32, g64)):
+        e0 = rel(b32, b64)
+        bar = RTOL if flips == 0 else RTOL + 4 * e0 + 0.5 * np.sqrt(allowance2)
+        r = rel(a, b32)
+        worst_g = max(worst_g, r)
+        assert np.isfinite(a).all() and r <= bar, (tag, "gradient of parameter", k, names[k], r, bar)
+    say("[ok]", tag, "loss gpu %.7f oracle %.7f; worst forward error %.2e; %d differing ReLU decisions; worst gradient error %.2e"
+        % (gl, l32, worst_f, flips, worst_g))
+    return params, x, t, gl, gg
+
+
+def test_config2_bottleneck_full_size_profile_plan_execute():
+    """32 x 256 x 56 x 56, three bottleneck blocks, budget = 50 % of the in-core peak: the
+    three phases of section 4.1.2 end to end, against the oracle and the in-core run"""
+    net, seed = workloads.load("bottleneck")
+    params, x, t, loss, grads = decision_aware_check("config2 full", net, seed)
+    res, peak = plan_sizes(net)
+    budget_dyn = (peak // 2) // 256 * 256
+    G = OP.Graph(net)
+    c = B.Context(net, res + budget_dyn, pinned_bytes=sum(G.fmap_bytes()) + 256)
+    c.set_params(params)
+    c.set_batch(x, t)
+    c.profile(warmup=1, iters=3)
+    results = {}
+    for mode in ("swapall_nosched", "swapall", "swapopt", "pooch"):
+        cls, T = c.plan(mode, 6)
+        l1 = c.step()
+        g1 = c.get_grads([s for _, _, s in workloads.param_shapes(net)])
+        st = c.stats()
+        assert st.resident_bytes + st.extent_bytes <= st.arena_bytes
+        assert_bit_exact("config2 " + mode, (loss, grads), (l1, g1))
+        c.step()
+        ms = c.stats().step_ms
+        results[mode] = (T, ms)
+        say("[config2] %-16s predicted %.2f ms measured %.2f ms keep/swap/recompute %d/%d/%d" %
+            (mode, T, ms, st.n_keep, st.n_swap, st.n_recompute))
+    # the search never makes the simulated step slower (section 5.1's ordering)
+    assert results["pooch"][0] <= results["swapopt"][0] + 1e-9 <= results["swapall"][0] + 2e-9
+    c.close()
+
+
+def test_resnet50_full_resolution_small_batch():
+    """ResNet-50 at 224 x 224 with batch 4: every layer shape of configurations 3 and 4 except
+    the batch extent"""
+    net, seed = workloads.load("resnet50_b64", batch=4)
+    decision_aware_check("resnet50 224 batch 4", net, seed)
+
+
+def kinkless_probe(x_shape, cout, k, stride, pad, with_bn):
+    """input -> conv (-> bn) -> gavgpool -> fc -> loss: no ReLU or max-pool, so nothing discrete
+    separates two correct fp32 runs and the 1e-3 bar applies at any size"""
+    net = workloads.Net()
+    t = net.input(x_shape)
+    t = net.conv(t, cout, k, stride, pad)
+    if with_bn:
+        t = net.bn(t)
+    t = net.fc(net.gavgpool(t), 10)
+    net.softmax_ce(t)
+    return net
+
+
+@pytest.mark.parametrize("x_shape,cout,k,stride,pad", [
+    ((32, 256, 56, 56), 64, (1, 1), (1, 1), (0, 0)),     # configuration 2's three conv shapes at full size
+    ((32, 64, 56, 56), 64, (3, 3), (1, 1), (1, 1)),
+    ((32, 64, 56, 56), 256, (1, 1), (1, 1), (0, 0)),
+    ((16, 3, 224, 224), 64, (7, 7), (2, 2), (3, 3)),     # the ResNet-50 stem
+    ((16, 256, 56, 56), 128, (1, 1), (2, 2), (0, 0)),    # strided 1x1 of a down-sampling block
+    ((1, 1, 48, 48, 48), 32, (3, 3, 3), (1, 1, 1), (1, 1, 1)),   # configuration 5's first conv (reduced volume)
+    ((1, 32, 32, 32, 32), 32, (3, 3, 3), (1, 1, 1), (1, 1, 1)),
+])
+def test_conv_bn_shapes_full_size_without_kinks(x_shape, cout, k, stride, pad):
+    net = kinkless_probe(x_shape, cout, k, stride, pad, True)
+    check_against_oracle("probe %s -> %d k%s s%s" % (x_shape, cout, k, stride), net, 123, capture=False)
