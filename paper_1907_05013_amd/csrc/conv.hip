@@ -28,6 +28,8 @@ struct IGemmP {
     int Ds, Hs, Ws;  // spatial dims of src
     int kd, kh, kw, sd, sh, sw, pd, ph, pw;
     int tiles_n, total_tiles, chunk;
+    // destination rows: identity, or (dst_strided) GEMM row (n,d,h,w) -> row ((n*DD + d*SD)*HD + h*SH)*WD + w*SW
+    int dst_strided, DD, HD, WD, SD, SH, SW;
 };
 
 // coordinate in the source tensor touched by filter tap `a` for a row whose base is `base`
@@ -66,6 +68,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     __shared__ __attribute__((aligned(16))) float As[BM * LDK];
     __shared__ __attribute__((aligned(16))) float Bs[BN * LDK];
     __shared__ int4 rowinfo[BM];
+    __shared__ int rowdst[BM];
 
     const int tid = threadIdx.x;
     const int logical = remap_tile(blockIdx.x, p.chunk);
@@ -75,6 +78,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     for (int r = tid; r < BM; r += NT) {
         const int m = m0 + r;
         int4 ri = make_int4(-1, 0, 0, 0);
+        int rd = -1;
         if (m < p.M) {
             const int w_ = m % p.Wr;
             int t = m / p.Wr;
@@ -84,8 +88,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             const int n = t / p.Dr;
             ri = DGRAD ? make_int4(n, d_ + p.pd, h_ + p.ph, w_ + p.pw)
                        : make_int4(n, d_ * p.sd - p.pd, h_ * p.sh - p.ph, w_ * p.sw - p.pw);
+            rd = p.dst_strided ? ((n * p.DD + d_ * p.SD) * p.HD + h_ * p.SH) * p.WD + w_ * p.SW : m;
         }
         rowinfo[r] = ri;
+        rowdst[r] = rd;
     }
     __syncthreads();
 
@@ -234,8 +240,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             const int col = n0 + wn * TN * 32 + j * 32 + r;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * TM * 32 + i * 32 + (v / 4) * 8 + h * 4 + (v % 4);
-                if (m < p.M && col < p.Nout) {
+                const int m = rowdst[wm * TM * 32 + i * 32 + (v / 4) * 8 + h * 4 + (v % 4)];
+                if (m >= 0 && col < p.Nout) {
                     const int64_t idx = (int64_t)m * p.Nout + col;
                     float val = acc[i][j][v];
                     if (ACCUM) val = p.dst[idx] + val;
@@ -271,6 +277,25 @@ hipError_t dispatch_igemm(const IGemmP &p, bool accum, hipStream_t s)
     if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, DGRAD>(p, vec, accum, s);
     if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, DGRAD>(p, vec, accum, s);
     return launch_igemm<2, 2, 2, 2, DGRAD>(p, vec, accum, s);
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, int64_t n)
+{
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
+        reinterpret_cast<float4 *>(p)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) p[n4 * 4 + threadIdx.x] = 0.f;
+}
+
+hipError_t fill_zero(float *p, int64_t n, hipStream_t s)
+{
+    if ((uintptr_t)p % 16 != 0) return hipErrorInvalidValue;
+    int64_t blocks = (n / 4 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    fill_zero_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(p, n);
+    return hipGetLastError();
 }
 
 bool geom_ok(const ConvGeom &g)
@@ -475,14 +500,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
         }
 }
 
-// dw[i] = partial[0][i] + partial[1][i] + ... in split order
-__global__ void reduce_splits_kernel(const float *__restrict__ part, float *__restrict__ dw, int64_t n, int nsplit)
+// dw[e] = sum over splits, in a fixed order: lane group g adds splits g, g+4, g+8, ... and the
+// four group sums are combined as ((s0 + s1) + s2) + s3
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restrict__ part, float *__restrict__ dw, int64_t n, int nsplit)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    float s = part[i];
-    for (int k = 1; k < nsplit; ++k) s += part[(int64_t)k * n + i];
-    dw[i] = s;
+    __shared__ float sh[4][64];
+    const int l = threadIdx.x % 64, g = threadIdx.x / 64;
+    const int64_t e = (int64_t)blockIdx.x * 64 + l;
+    float s = 0.f;
+    if (e < n) {
+#pragma unroll 4
+        for (int k = g; k < nsplit; k += 4) s += part[(int64_t)k * n + e];
+    }
+    sh[g][l] = s;
+    __syncthreads();
+    if (g == 0 && e < n) dw[e] = ((sh[0][l] + sh[1][l]) + sh[2][l]) + sh[3][l];
 }
 
 struct WGradCfg {
@@ -496,10 +528,12 @@ WGradCfg wgrad_cfg(const ConvGeom &g)
     WGradCfg c;
     const int64_t M = g.rows_out(), Kred = g.taps() * g.C;
     c.bm = g.K <= 32 ? 32 : (g.K <= 64 ? 64 : 128);
-    c.bn = 128;
+    c.bn = Kred <= 64 ? 64 : 128;
     const int64_t tiles = ((g.K + c.bm - 1) / c.bm) * ((Kred + c.bn - 1) / c.bn);
-    int64_t ns = (2048 + tiles - 1) / tiles;
-    const int64_t max_by_rows = (M + 63) / 64;
+    // enough workgroups to fill 256 compute units several times over, but each split keeps at
+    // least 256 rows so that its epilogue (a full tile written to the workspace) stays small
+    int64_t ns = (1024 + tiles - 1) / tiles;
+    const int64_t max_by_rows = (M + 255) / 256;
     if (ns > max_by_rows) ns = max_by_rows;
     const int64_t max_by_ws = (int64_t)(WGRAD_WS_CAP / ((size_t)g.K * Kred * sizeof(float)));
     if (ns > max_by_ws) ns = max_by_ws;
@@ -535,17 +569,40 @@ hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeo
     p.M = (int)g.rows_out(); p.Nout = g.K; p.Kred = (int)(g.taps() * g.C); p.Cs = g.C;
     p.Dr = g.Do; p.Hr = g.Ho; p.Wr = g.Wo; p.Ds = g.D; p.Hs = g.H; p.Ws = g.W;
     p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
+    p.dst_strided = 0; p.DD = p.HD = p.WD = p.SD = p.SH = p.SW = 0;
     return dispatch_igemm<false>(p, false, s);
+}
+
+// a strided 1x1 filter without padding touches only every (sd,sh,sw)-th input position: its
+// data gradient is a plain GEMM over the OUTPUT rows scattered to those positions; all other
+// positions receive zero
+bool pointwise_strided(const ConvGeom &g)
+{
+    return g.taps() == 1 && g.pd == 0 && g.ph == 0 && g.pw == 0 && (g.sd > 1 || g.sh > 1 || g.sw > 1);
 }
 
 hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g, bool accumulate, hipStream_t s)
 {
     if (!dy || !w_crsk || !dx || !geom_ok(g)) return hipErrorInvalidValue;
     IGemmP p;
+    if (pointwise_strided(g)) {
+        if (!accumulate) {
+            const hipError_t e = fill_zero(dx, g.rows_in() * g.C, s);
+            if (e != hipSuccess) return e;
+        }
+        p.src = dy; p.wgt = w_crsk; p.dst = dx;
+        p.M = (int)g.rows_out(); p.Nout = g.C; p.Kred = g.K; p.Cs = g.K;
+        p.Dr = g.Do; p.Hr = g.Ho; p.Wr = g.Wo; p.Ds = g.Do; p.Hs = g.Ho; p.Ws = g.Wo;
+        p.kd = p.kh = p.kw = 1; p.sd = p.sh = p.sw = 1; p.pd = p.ph = p.pw = 0;
+        p.dst_strided = 1; p.DD = g.D; p.HD = g.H; p.WD = g.W; p.SD = g.sd; p.SH = g.sh; p.SW = g.sw;
+        // rows that are not written keep their zeros, so the scatter always adds
+        return dispatch_igemm<false>(p, true, s);
+    }
     p.src = dy; p.wgt = w_crsk; p.dst = dx;
     p.M = (int)g.rows_in(); p.Nout = g.C; p.Kred = (int)(g.taps() * g.K); p.Cs = g.K;
     p.Dr = g.D; p.Hr = g.H; p.Wr = g.W; p.Ds = g.Do; p.Hs = g.Ho; p.Ws = g.Wo;
     p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
+    p.dst_strided = 0; p.DD = p.HD = p.WD = p.SD = p.SH = p.SW = 0;
     return dispatch_igemm<true>(p, accumulate, s);
 }
 
@@ -560,6 +617,11 @@ const char *conv_fwd_kernel(const ConvGeom &g)
 const char *conv_dgrad_kernel(const ConvGeom &g)
 {
     const bool vec = g.K % 4 == 0;
+    if (pointwise_strided(g)) {
+        if (g.C <= 32) return vec ? "igemm_kernel<4,1,2,1,vec,fwd>" : "igemm_kernel<4,1,2,1,scalar,fwd>";
+        if (g.C <= 64) return vec ? "igemm_kernel<4,1,2,2,vec,fwd>" : "igemm_kernel<4,1,2,2,scalar,fwd>";
+        return vec ? "igemm_kernel<2,2,2,2,vec,fwd>" : "igemm_kernel<2,2,2,2,scalar,fwd>";
+    }
     if (g.C <= 32) return vec ? "igemm_kernel<4,1,2,1,vec,dgrad>" : "igemm_kernel<4,1,2,1,scalar,dgrad>";
     if (g.C <= 64) return vec ? "igemm_kernel<4,1,2,2,vec,dgrad>" : "igemm_kernel<4,1,2,2,scalar,dgrad>";
     return vec ? "igemm_kernel<2,2,2,2,vec,dgrad>" : "igemm_kernel<2,2,2,2,scalar,dgrad>";
@@ -568,6 +630,7 @@ const char *conv_dgrad_kernel(const ConvGeom &g)
 const char *conv_wgrad_kernel(const ConvGeom &g)
 {
     const WGradCfg c = wgrad_cfg(g);
+    if (c.bn == 64) return c.bm == 32 ? "wgrad_kernel<1,2,1,1>" : (c.bm == 64 ? "wgrad_kernel<2,2,1,1>" : "wgrad_kernel<2,2,2,1>");
     return c.bm == 32 ? "wgrad_kernel<1,2,1,2>" : (c.bm == 64 ? "wgrad_kernel<1,2,2,2>" : "wgrad_kernel<2,2,2,2>");
 }
 
@@ -592,13 +655,19 @@ hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *wo
     const bool veca = (g.K % 4 == 0) && ((uintptr_t)dy % 16 == 0);
     const bool vecb = (g.C % 4 == 0) && ((uintptr_t)x % 16 == 0);
     hipError_t e;
-    if (c.bm == 32) e = launch_wgrad<1, 2, 1, 2>(p, veca, vecb, s);
-    else if (c.bm == 64) e = launch_wgrad<1, 2, 2, 2>(p, veca, vecb, s);
-    else e = launch_wgrad<2, 2, 2, 2>(p, veca, vecb, s);
+    if (c.bn == 64) {
+        if (c.bm == 32) e = launch_wgrad<1, 2, 1, 1>(p, veca, vecb, s);
+        else if (c.bm == 64) e = launch_wgrad<2, 2, 1, 1>(p, veca, vecb, s);
+        else e = launch_wgrad<2, 2, 2, 1>(p, veca, vecb, s);
+    } else {
+        if (c.bm == 32) e = launch_wgrad<1, 2, 1, 2>(p, veca, vecb, s);
+        else if (c.bm == 64) e = launch_wgrad<1, 2, 2, 2>(p, veca, vecb, s);
+        else e = launch_wgrad<2, 2, 2, 2>(p, veca, vecb, s);
+    }
     if (e != hipSuccess) return e;
     if (c.nsplit > 1) {
         const int64_t n = (int64_t)g.K * p.Kred;
-        reduce_splits_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(workspace, dw_krsc, n, c.nsplit);
+        reduce_splits_kernel<<<dim3((unsigned)((n + 63) / 64)), dim3(256), 0, s>>>(workspace, dw_krsc, n, c.nsplit);
         e = hipGetLastError();
     }
     return e;

@@ -74,6 +74,136 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const float *__restric
     dx[i] = ACCUM ? dx[i] + acc : acc;
 }
 
+// 2-d 3x3 window, stride 2, padding 1 (the ResNet stem pool), C % 4 == 0.  One thread owns the
+// 2x2 block of input positions (2a..2a+1, 2b..2b+1) of four channels.  Only the windows
+// (a..a+1, b..b+1) reach that block; their union is a 5x5 patch, loaded once.
+template <bool ACCUM>
+__global__ __launch_bounds__(256) void maxpool_k3s2p1_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy, float *dx,
+                                                                  PoolGeom g, int HB, int WB, int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int C4 = g.C / 4;
+    const int c = (int)(i % C4) * 4;
+    int64_t t = i / C4;
+    const int b = (int)(t % WB); t /= WB;
+    const int a = (int)(t % HB);
+    const int n = (int)(t / HB);
+    float4 patch[5][5];
+    bool rv[5], cv[5];
+#pragma unroll
+    for (int r = 0; r < 5; ++r) { rv[r] = (unsigned)(2 * a - 1 + r) < (unsigned)g.H; cv[r] = (unsigned)(2 * b - 1 + r) < (unsigned)g.W; }
+#pragma unroll
+    for (int r = 0; r < 5; ++r)
+#pragma unroll
+        for (int q = 0; q < 5; ++q) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (rv[r] && cv[q]) v = *reinterpret_cast<const float4 *>(x + (((int64_t)n * g.H + (2 * a - 1 + r)) * g.W + (2 * b - 1 + q)) * g.C + c);
+            patch[r][q] = v;
+        }
+    float acc[2][2][4];
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int ch = 0; ch < 4; ++ch) acc[r][q][ch] = 0.f;
+#pragma unroll
+    for (int wi = 0; wi < 2; ++wi)
+#pragma unroll
+        for (int wj = 0; wj < 2; ++wj) {
+            if (a + wi >= g.Ho || b + wj >= g.Wo) continue;
+            const float4 d4 = *reinterpret_cast<const float4 *>(dy + (((int64_t)n * g.Ho + (a + wi)) * g.Wo + (b + wj)) * g.C + c);
+            const float d[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+            for (int ch = 0; ch < 4; ++ch) {
+                float best = 0.f;
+                int bi = -1;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int q = 0; q < 3; ++q) {
+                        const int pr = 2 * wi + r, pq = 2 * wj + q;
+                        if (!(rv[pr] && cv[pq])) continue;
+                        const float4 v4 = patch[pr][pq];
+                        const float v = ch == 0 ? v4.x : (ch == 1 ? v4.y : (ch == 2 ? v4.z : v4.w));
+                        if (bi < 0 || v > best) { best = v; bi = pr * 5 + pq; }
+                    }
+                // the block is patch rows/cols 1..2
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        if (bi == (1 + r) * 5 + (1 + q)) acc[r][q][ch] += d[ch];
+            }
+        }
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            if (!(rv[1 + r] && cv[1 + q])) continue;
+            float4 *o = reinterpret_cast<float4 *>(dx + (((int64_t)n * g.H + (2 * a + r)) * g.W + (2 * b + q)) * g.C + c);
+            float4 v = make_float4(acc[r][q][0], acc[r][q][1], acc[r][q][2], acc[r][q][3]);
+            if (ACCUM) { const float4 e = *o; v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w; }
+            *o = v;
+        }
+}
+
+// window == stride, no padding, every extent a multiple of the stride: each input position
+// belongs to exactly one window.  One thread per window and V channels.
+template <int V, bool ACCUM>
+__global__ __launch_bounds__(256) void maxpool_tiled_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy, float *dx,
+                                                                 PoolGeom g, int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int CV = g.C / V;
+    const int c = (int)(i % CV) * V;
+    int64_t t = i / CV;
+    const int ow = (int)(t % g.Wo); t /= g.Wo;
+    const int oh = (int)(t % g.Ho); t /= g.Ho;
+    const int od = (int)(t % g.Do);
+    const int n = (int)(t / g.Do);
+    float best[V];
+    int bi[V];
+#pragma unroll
+    for (int ch = 0; ch < V; ++ch) { best[ch] = 0.f; bi[ch] = -1; }
+    int e = 0;
+    for (int p = 0; p < g.kd; ++p)
+        for (int q = 0; q < g.kh; ++q)
+            for (int r = 0; r < g.kw; ++r, ++e) {
+                const float *src = x + ((((int64_t)n * g.D + od * g.sd + p) * g.H + oh * g.sh + q) * g.W + ow * g.sw + r) * g.C + c;
+                float v[V];
+                if (V == 4) { const float4 v4 = *reinterpret_cast<const float4 *>(src); v[0] = v4.x; v[1 % V] = v4.y; v[2 % V] = v4.z; v[3 % V] = v4.w; }
+                else v[0] = *src;
+#pragma unroll
+                for (int ch = 0; ch < V; ++ch)
+                    if (bi[ch] < 0 || v[ch] > best[ch]) { best[ch] = v[ch]; bi[ch] = e; }
+            }
+    float d[V];
+    {
+        const float *src = dy + i / CV * g.C + c;
+        if (V == 4) { const float4 v4 = *reinterpret_cast<const float4 *>(src); d[0] = v4.x; d[1 % V] = v4.y; d[2 % V] = v4.z; d[3 % V] = v4.w; }
+        else d[0] = *src;
+    }
+    e = 0;
+    for (int p = 0; p < g.kd; ++p)
+        for (int q = 0; q < g.kh; ++q)
+            for (int r = 0; r < g.kw; ++r, ++e) {
+                float *dst = dx + ((((int64_t)n * g.D + od * g.sd + p) * g.H + oh * g.sh + q) * g.W + ow * g.sw + r) * g.C + c;
+                float o[V];
+#pragma unroll
+                for (int ch = 0; ch < V; ++ch) o[ch] = bi[ch] == e ? d[ch] : 0.f;
+                if (V == 4) {
+                    float4 v = make_float4(o[0], o[1 % V], o[2 % V], o[3 % V]);
+                    if (ACCUM) { const float4 old = *reinterpret_cast<float4 *>(dst); v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w; }
+                    *reinterpret_cast<float4 *>(dst) = v;
+                } else {
+                    *dst = ACCUM ? *dst + o[0] : o[0];
+                }
+            }
+}
+
 // y[n][c] = (1/S) sum_s x[n][s][c], s ascending
 __global__ __launch_bounds__(256) void gavgpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int N, int64_t S, int C)
 {
@@ -206,6 +336,25 @@ hipError_t maxpool_fwd(const float *x, float *y, const PoolGeom &g, hipStream_t 
 hipError_t maxpool_bwd(const float *x, const float *dy, float *dx, const PoolGeom &g, bool accumulate, hipStream_t s)
 {
     if (!x || !dy || !dx || !pool_ok(g)) return hipErrorInvalidValue;
+    const bool al16 = ((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx) % 16 == 0;
+    if (g.D == 1 && g.kd == 1 && g.sd == 1 && g.pd == 0 && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2 && g.ph == 1 && g.pw == 1 &&
+        g.C % 4 == 0 && al16) {
+        const int HB = (g.H + 1) / 2, WB = (g.W + 1) / 2;
+        const int64_t tot = (int64_t)g.N * HB * WB * (g.C / 4);
+        if (accumulate) maxpool_k3s2p1_bwd_kernel<true><<<blocks_for(tot), dim3(256), 0, s>>>(x, dy, dx, g, HB, WB, tot);
+        else maxpool_k3s2p1_bwd_kernel<false><<<blocks_for(tot), dim3(256), 0, s>>>(x, dy, dx, g, HB, WB, tot);
+        return hipGetLastError();
+    }
+    if (g.kd == g.sd && g.kh == g.sh && g.kw == g.sw && g.pd == 0 && g.ph == 0 && g.pw == 0 && g.D % g.sd == 0 && g.H % g.sh == 0 &&
+        g.W % g.sw == 0) {
+        const bool v4 = g.C % 4 == 0 && al16;
+        const int64_t tot = (int64_t)g.N * g.Do * g.Ho * g.Wo * (g.C / (v4 ? 4 : 1));
+#define TILED(V, A) maxpool_tiled_bwd_kernel<V, A><<<blocks_for(tot), dim3(256), 0, s>>>(x, dy, dx, g, tot)
+        if (v4) { if (accumulate) TILED(4, true); else TILED(4, false); }
+        else { if (accumulate) TILED(1, true); else TILED(1, false); }
+#undef TILED
+        return hipGetLastError();
+    }
     const int64_t total = (int64_t)g.N * g.D * g.H * g.W * g.C;
     if (accumulate) maxpool_bwd_kernel<true><<<blocks_for(total), dim3(256), 0, s>>>(x, dy, dx, g, total);
     else maxpool_bwd_kernel<false><<<blocks_for(total), dim3(256), 0, s>>>(x, dy, dx, g, total);

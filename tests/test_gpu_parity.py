@@ -160,6 +160,8 @@ def zoo_net(batch, cin, size, c1, c2, k1, s1, p1):
     (3, 3, 17, 6, 7, 7, 2, 3),        # stem-like 7x7 stride 2 on 3 channels, ragged everything
     (2, 4, 12, 8, 12, 5, 1, 0),       # no padding, vector path (C % 4 == 0)
     (2, 8, 16, 40, 136, 3, 2, 1),     # more than one 128-wide output-channel tile, strided 3x3
+    (2, 4, 13, 8, 12, 3, 1, 1),       # odd extent into the 3x3/2 max-pool with C % 4 == 0
+    (2, 8, 15, 16, 64, 1, 2, 0),      # strided 1x1 convolution (its data gradient is a scatter)
 ])
 def test_layer_zoo_vs_oracle(batch, cin, size, c1, c2, k1, s1, p1):
     net = zoo_net(batch, cin, size, c1, c2, k1, s1, p1)
@@ -327,8 +329,10 @@ def kinkless_probe(x_shape, cout, k, stride, pad, with_bn):
     ((32, 64, 56, 56), 256, (1, 1), (1, 1), (0, 0)),
     ((16, 3, 224, 224), 64, (7, 7), (2, 2), (3, 3)),     # the ResNet-50 stem
     ((16, 256, 56, 56), 128, (1, 1), (2, 2), (0, 0)),    # strided 1x1 of a down-sampling block
-    ((1, 1, 48, 48, 48), 32, (3, 3, 3), (1, 1, 1), (1, 1, 1)),   # configuration 5's first conv (reduced volume)
-    ((1, 32, 32, 32, 32), 32, (3, 3, 3), (1, 1, 1), (1, 1, 1)),
+    # configuration 5's first two convs on a reduced volume; batch 2 because with one sample the
+    # pooled BN output is exactly beta and the filter gradient is identically zero
+    ((2, 1, 48, 48, 48), 32, (3, 3, 3), (1, 1, 1), (1, 1, 1)),
+    ((2, 32, 32, 32, 32), 32, (3, 3, 3), (1, 1, 1), (1, 1, 1)),
 ])
 def test_conv_bn_shapes_full_size_without_kinks(x_shape, cout, k, stride, pad):
     net = kinkless_probe(x_shape, cout, k, stride, pad, True)
