@@ -178,9 +178,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="resnet50_b640_16g", choices=sorted(WORKLOADS))
     ap.add_argument("--budget-gib", type=float, default=None)
-    ap.add_argument("--mode", default="pooch", choices=["swapall_nosched", "swapall", "swapopt", "pooch"])
-    ap.add_argument("--bits", type=int, default=8, help="cap on the exponential part of the keep/swap search")
+    ap.add_argument("--mode", default="refine", choices=["swapall_nosched", "swapall", "swapopt", "pooch", "refine"],
+                    help="planner whose step is reported as `value`; refine = the paper's two steps + local search")
+    ap.add_argument("--bits", type=int, default=4, help="cap on the exponential part of the keep/swap search")
+    ap.add_argument("--no-paper-mode", action="store_true", help="skip the extra leg that times the paper's own two-step plan")
     ap.add_argument("--no-incore", action="store_true")
+    ap.add_argument("--dump-profile", default=None, help="write the measured profile (ms per layer / map) to this .npz file")
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -218,19 +221,35 @@ def main():
         link = ctx.measure_link(min(1 << 30, (arena_bytes - resident) // 2 // 256 * 256), 3)
         log("[bench] host link: D2H %.1f GB/s, H2D %.1f GB/s" % link)
         t0 = time.perf_counter()
-        ctx.profile(warmup=1, iters=2)
+        prof = ctx.profile(warmup=1, iters=2)
         t1 = time.perf_counter()
+        if args.dump_profile:
+            np.savez(args.dump_profile, t_fwd=prof[0], t_bwd=prof[1], t_refwd=prof[2], t_out=prof[3], t_in=prof[4],
+                     arena_bytes=arena_bytes, pinned_bytes=fm_bytes + 4096)
+        if args.mode == "refine" and not args.no_paper_mode:
+            # the paper's own classification (section 4.4, two steps), timed the same way
+            tp = time.perf_counter()
+            _, pred_p = ctx.plan("pooch", args.bits)
+            tp = time.perf_counter() - tp
+            sec_p, _, _ = timed_steps(ctx, torch, args.steps, args.warmup)
+            stp = ctx.stats()
+            result_extra["paper_two_step_plan"] = {
+                "images_per_sec": batch / sec_p, "ms_per_step": sec_p * 1e3, "predicted_ms": pred_p, "plan_s": tp,
+                "keep": stp.n_keep, "swap": stp.n_swap, "recompute": stp.n_recompute, "swap_out_GB": stp.swap_out_bytes / 1e9}
+            log("[bench] paper's two-step plan: %.1f ms/step (predicted %.1f), keep/swap/recompute %d/%d/%d" %
+                (sec_p * 1e3, pred_p, stp.n_keep, stp.n_swap, stp.n_recompute))
+        t1b = time.perf_counter()
         cls, predicted = ctx.plan(args.mode, args.bits)
         t2 = time.perf_counter()
         st = ctx.stats()
         log("[bench] profile %.1f s, plan %.1f s (%d simulations): keep/swap/recompute %d/%d/%d, predicted %.1f ms" %
-            (t1 - t0, t2 - t1, ctx.plan_evaluations(), st.n_keep, st.n_swap, st.n_recompute, predicted))
+            (t1 - t0, t2 - t1b, ctx.plan_evaluations(), st.n_keep, st.n_swap, st.n_recompute, predicted))
         sec, ms, loss = timed_steps(ctx, torch, args.steps, args.warmup)
         st = ctx.stats()
         result_extra.update({
             "plan": {"mode": args.mode, "keep": st.n_keep, "swap": st.n_swap, "recompute": st.n_recompute,
                      "re_forwards": st.n_refwd, "predicted_ms": predicted,
-                     "profile_s": t1 - t0, "plan_s": t2 - t1, "simulations": ctx.plan_evaluations()},
+                     "profile_s": t1 - t0, "plan_s": t2 - t1b, "simulations": ctx.plan_evaluations()},
             "swap": {"out_GB": st.swap_out_bytes / 1e9, "in_GB": st.swap_in_bytes / 1e9,
                      "link_peak_d2h_GBs": link[0], "link_peak_h2d_GBs": link[1],
                      "achieved_GBs_over_step": (st.swap_out_bytes + st.swap_in_bytes) / 1e9 / sec},
@@ -287,6 +306,8 @@ def main():
     if incore_sec is not None:
         out["incore_images_per_sec"] = batch / incore_sec
         out["overhead_vs_incore"] = 1.0 - incore_sec / sec if under_budget else 0.0
+        if "paper_two_step_plan" in result_extra:
+            result_extra["paper_two_step_plan"]["overhead_vs_incore"] = 1.0 - incore_sec * result_extra["paper_two_step_plan"]["images_per_sec"] / batch
     out.update(result_extra)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.workload)

@@ -13,7 +13,9 @@ TEST INFRASTRUCTURE ONLY (slow, obvious, no sharing with the HIP library).  It c
     host-to-device -- from profiled durations (section 4.1.2),
   * the two-step heuristic search (section 4.4): L_O / L_I extraction on the all-swap
     timeline, binary tree over L_I with a greedy scan of L_O \\ L_I from the output layer,
-    then r(X) = recompute_overhead / swap_overhead (equation 1) for the maps left in swap.
+    then r(X) = recompute_overhead / swap_overhead (equation 1) for the maps left in swap,
+  * mode "refine" (not in the paper): the two steps followed by a local search over single
+    class changes, judged by the same simulation.
 
 Where the paper is silent the readings are those listed in DESIGN.md ("Readings").
 """
@@ -607,7 +609,10 @@ class Planner:
         cls, T = self.step1(allswap, T)
         if mode == "swapopt":
             return cls, T
-        return self.step2(cls, T)
+        cls, T = self.step2(cls, T)
+        if mode == "pooch":
+            return cls, T
+        return self.refine(cls, T)
 
     def step1(self, allswap, T_all):
         """keep/swap search (section 4.4.2)"""
@@ -661,19 +666,46 @@ class Planner:
                 rec[k] = RECOMPUTE
                 T_rec = self.evaluate(rec)
                 if T_res is None or T_rec is None:
-                    ratios[k] = float("inf")
+                    # the flip does not fit now; it may once other maps have moved: X stays in L
+                    # but cannot be picked in this round
+                    ratios[k] = None
                     continue
                 swap_ov = T0 - T_res
                 rec_ov = T_rec - T_res
                 ratios[k] = float("inf") if swap_ov <= 0.0 else rec_ov / swap_ov
-            L = [k for k in L if ratios[k] < 1.0]
-            if not L:
+            L = [k for k in L if ratios[k] is None or ratios[k] < 1.0]
+            cand = [k for k in L if ratios[k] is not None]
+            if not cand:
                 break
-            kmin = L[0]
-            for k in L:
+            kmin = cand[0]
+            for k in cand:
                 if ratios[k] < ratios[kmin]:
                     kmin = k
             cls[kmin] = RECOMPUTE
             L.remove(kmin)
             T0 = self.evaluate(cls)
         return cls, T0
+
+    def refine(self, cls, T0):
+        """Not in the paper: a local search on top of its two steps, with the same simulator
+        and the same three classes.  Each round evaluates every single-map change of class
+        and applies the one with the smallest simulated step time (first in (map, class)
+        order on ties) if it is strictly faster; stops when no change helps."""
+        cls = list(cls)
+        while True:
+            best = None
+            for k in range(len(cls)):
+                for v in (KEEP, SWAP, RECOMPUTE):
+                    if v == cls[k]:
+                        continue
+                    trial = list(cls)
+                    trial[k] = v
+                    T = self.evaluate(trial)
+                    if T is None:
+                        continue
+                    if T < (T0 if best is None else best[0]):
+                        best = (T, k, v)
+            if best is None:
+                return cls, T0
+            T0, k, v = best
+            cls[k] = v

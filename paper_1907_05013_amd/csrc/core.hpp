@@ -80,7 +80,7 @@ struct SimResult {
 };
 SimResult simulate(const Graph &G, const Schedule &S, const Profile &P);
 
-enum : int { MODE_INCORE = 0, MODE_SWAPALL_NOSCHED = 1, MODE_SWAPALL = 2, MODE_SWAPOPT = 3, MODE_POOCH = 4 };
+enum : int { MODE_INCORE = 0, MODE_SWAPALL_NOSCHED = 1, MODE_SWAPALL = 2, MODE_SWAPOPT = 3, MODE_POOCH = 4, MODE_REFINE = 5 };
 
 struct Planner {
     const Graph &G;
@@ -97,6 +97,7 @@ struct Planner {
     bool plan(int mode, std::vector<uint8_t> &cls, double &T, bool &ahead);
     void step1(const std::vector<uint8_t> &allswap, double T_all, std::vector<uint8_t> &best, double &best_T);
     void step2(std::vector<uint8_t> &cls, double &T0);
+    void refine(std::vector<uint8_t> &cls, double &T0);
 };
 
 }  // namespace pooch

@@ -632,6 +632,8 @@ bool Planner::plan(int mode, std::vector<uint8_t> &cls, double &T, bool &ahead)
     T = best_T;
     if (mode == MODE_SWAPOPT) return true;
     step2(cls, T);
+    if (mode == MODE_POOCH) return true;
+    refine(cls, T);
     return true;
 }
 
@@ -694,6 +696,7 @@ void Planner::step2(std::vector<uint8_t> &cls, double &T0)
         if (cls[k] == CLS_SWAP) L.push_back((int)k);
     while (!L.empty()) {
         std::vector<double> ratio(cls.size(), INF);
+        std::vector<char> fits(cls.size(), 1);
         for (int k : L) {
             std::vector<uint8_t> res = cls;
             res[k] = CLS_KEEP;
@@ -701,21 +704,53 @@ void Planner::step2(std::vector<uint8_t> &cls, double &T0)
             std::vector<uint8_t> rc = cls;
             rc[k] = CLS_RECOMPUTE;
             const double T_rec = evaluate(rc);
-            if (T_res < 0.0 || T_rec < 0.0) continue;
+            if (T_res < 0.0 || T_rec < 0.0) {
+                // does not fit now; it may once other maps have moved: stays in L, not pickable
+                fits[k] = 0;
+                continue;
+            }
             const double swap_ov = T0 - T_res, rec_ov = T_rec - T_res;
             ratio[k] = swap_ov <= 0.0 ? INF : rec_ov / swap_ov;
         }
-        std::vector<int> L2;
+        std::vector<int> L2, cand;
         for (int k : L)
-            if (ratio[k] < 1.0) L2.push_back(k);
+            if (!fits[k] || ratio[k] < 1.0) L2.push_back(k);
         L.swap(L2);
-        if (L.empty()) break;
-        int kmin = L[0];
         for (int k : L)
+            if (fits[k]) cand.push_back(k);
+        if (cand.empty()) break;
+        int kmin = cand[0];
+        for (int k : cand)
             if (ratio[k] < ratio[kmin]) kmin = k;
         cls[kmin] = CLS_RECOMPUTE;
         L.erase(std::find(L.begin(), L.end(), kmin));
         T0 = evaluate(cls);
+    }
+}
+
+// Not in the paper: local search over single class changes on top of the two steps, judged by
+// the same simulation; best strictly-improving change per round, first in (map, class) order.
+void Planner::refine(std::vector<uint8_t> &cls, double &T0)
+{
+    for (;;) {
+        double best_T = T0;
+        int best_k = -1, best_v = 0;
+        for (size_t k = 0; k < cls.size(); ++k)
+            for (int v = CLS_KEEP; v <= CLS_RECOMPUTE; ++v) {
+                if (v == cls[k]) continue;
+                std::vector<uint8_t> trial = cls;
+                trial[k] = (uint8_t)v;
+                const double T = evaluate(trial);
+                if (T < 0.0) continue;
+                if (T < best_T) {
+                    best_T = T;
+                    best_k = (int)k;
+                    best_v = v;
+                }
+            }
+        if (best_k < 0) return;
+        T0 = best_T;
+        cls[best_k] = (uint8_t)best_v;
     }
 }
 

@@ -257,6 +257,8 @@ def test_modes_monotone_and_feasible_vs_brute_force(seed):
     T_all = pl.plan("swapall")[1]
     cls_opt, T_opt = pl.plan("swapopt")
     cls_p, T_p = pl.plan("pooch")
+    cls_r, T_r = pl.plan("refine")
+    assert T_r <= T_p
     assert T_p <= T_opt + 1e-12 <= T_all + 2e-12
     assert T_all <= T_ns + 1e-9
     # feasible and no better than the true optimum
@@ -264,7 +266,16 @@ def test_modes_monotone_and_feasible_vs_brute_force(seed):
     assert abs(P.simulate(G, S, prof)[0] - T_p) < 1e-12
     schedule_check.check(G, S.cmds, cap)
     T_star = brute_force_best(G, prof, cap)
-    assert T_star <= T_p + 1e-12
+    assert T_star <= T_r + 1e-12 and T_star <= T_p + 1e-12
+    Sr = P.build_schedule(G, cls_r, cap)
+    assert abs(P.simulate(G, Sr, prof)[0] - T_r) < 1e-12
+    # the local search ends in a plan no single class change improves
+    for k in range(nf):
+        for v in (P.KEEP, P.SWAP, P.RECOMPUTE):
+            trial = list(cls_r)
+            trial[k] = v
+            T = pl.evaluate(trial)
+            assert T is None or T >= T_r
     assert P.RECOMPUTE not in cls_opt
 
 

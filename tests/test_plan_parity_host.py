@@ -99,7 +99,7 @@ def test_every_mode_picks_the_oracles_plan(seed):
     c, _ = lib_ctx(net, cap)
     c.set_profile(*prof)
     bits = 5
-    for mode in ("swapall_nosched", "swapall", "swapopt", "pooch"):
+    for mode in ("swapall_nosched", "swapall", "swapopt", "pooch", "refine"):
         pl = P.Planner(G, oprof, cap, max_bits=bits)
         try:
             ocls, oT = pl.plan(mode)
