@@ -93,6 +93,13 @@ int32_t pooch_maxpool(pooch_ctx *, int32_t x, const int *k, const int *stride, c
 int32_t pooch_gavgpool(pooch_ctx *, int32_t x);
 int32_t pooch_fc(pooch_ctx *, int32_t x, int nout);
 int32_t pooch_softmax_ce(pooch_ctx *, int32_t logits);
+/* Layer fusion (default on; call before pooch_finalize): a bn or add whose only consumer is a
+ * relu is executed inside that relu, so its output is never written to memory.  Results are
+ * those of the unfused layers; the feature-map set is unchanged (backward of a fused bn+relu
+ * reads the bn's input and re-derives the relu decision from it).
+ * pooch_node_fused: id of the relu a layer was fused into, -1 if it executes on its own. */
+pooch_status pooch_set_fusion(pooch_ctx *, int enable);
+int32_t pooch_node_fused(pooch_ctx *, int32_t id);
 /* Freezes the graph: shapes, liveness, the feature-map list (every tensor some backward
  * reads, except the network input, which is caller data and stays resident), the parameter
  * list and the layout of the resident region at the bottom of the arena.

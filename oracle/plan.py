@@ -44,9 +44,15 @@ def _round(n):
 # ------------------------------------------------------------------ graph analysis
 
 class Graph:
-    """static facts about a layer list (see workloads.py for the format)"""
+    """static facts about a layer list (see workloads.py for the format).
 
-    def __init__(self, net):
+    fuse=True applies the executor's layer fusion: a BN or add whose only consumer is a ReLU
+    is executed inside that ReLU ("bnrelu", "addrelu"); the BN / add output is then never
+    materialised (op "dead", zero bytes, no commands).  The feature-map set does not change:
+    backward of a bnrelu reads the BN's input (the ReLU decision is re-derived from it),
+    backward of an addrelu reads the ReLU's output."""
+
+    def __init__(self, net, fuse=False):
         self.net = net
         n = len(net)
         self.n = n
@@ -60,12 +66,27 @@ class Graph:
             else:
                 self.inputs.append([L["x"]])
         self.shape = self._shapes()
+        self.fused_into = [-1] * n
+        if fuse:
+            raw = [[] for _ in range(n)]
+            for i in range(n):
+                for t in self.inputs[i]:
+                    if i not in raw[t]:
+                        raw[t].append(i)
+            for i in range(n):
+                if self.ops[i] in ("bn", "add") and len(raw[i]) == 1 and self.ops[raw[i][0]] == "relu":
+                    j = raw[i][0]
+                    self.ops[j] = "bnrelu" if self.ops[i] == "bn" else "addrelu"
+                    self.inputs[j] = list(self.inputs[i])
+                    self.ops[i] = "dead"
+                    self.inputs[i] = []
+                    self.fused_into[i] = j
         self.bytes = []
         for i in range(n):
             numel = 1
             for v in self.shape[i]:
                 numel *= v
-            self.bytes.append(0 if self.ops[i] == "softmax_ce" else _round(4 * numel))
+            self.bytes.append(0 if self.ops[i] in ("softmax_ce", "dead") else _round(4 * numel))
         self.consumers = [[] for _ in range(n)]
         for i in range(n):
             for t in self.inputs[i]:
@@ -75,9 +96,9 @@ class Graph:
         # tensors the backward of node i reads
         self.needs = []
         for i, op in enumerate(self.ops):
-            if op in ("conv", "bn", "maxpool", "fc", "softmax_ce"):
+            if op in ("conv", "bn", "bnrelu", "maxpool", "fc", "softmax_ce"):
                 self.needs.append([self.inputs[i][0]])
-            elif op == "relu":
+            elif op in ("relu", "addrelu"):
                 self.needs.append([i])
             else:
                 self.needs.append([])
@@ -413,6 +434,8 @@ def _walk(G, cls, cap, ahead, info):
     # ---------------- forward
     for i in range(1, n):
         ins = G.inputs[i]
+        if G.ops[i] == "dead":
+            continue
         if G.ops[i] == "softmax_ce":
             emit(KF, i, OFF_NONE, loc[ins[0]], OFF_NONE)
         else:
@@ -463,7 +486,7 @@ def _walk(G, cls, cap, ahead, info):
         dy = gloc[i] if op != "softmax_ce" else OFF_NONE
         outs = []
         transferred = False
-        if op in ("relu", "bn"):
+        if op in ("relu", "bn", "bnrelu"):
             x = ins[0]
             if x == 0:
                 outs.append((OFF_NONE, M_NONE))
@@ -473,7 +496,7 @@ def _walk(G, cls, cap, ahead, info):
                 outs.append((dy, M_TRANSFER))
             else:
                 outs.append((gloc[x], M_ACC))
-        elif op == "add":
+        elif op in ("add", "addrelu"):
             for u in ins:
                 if u == 0:
                     outs.append((OFF_NONE, M_NONE))

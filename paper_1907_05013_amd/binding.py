@@ -51,6 +51,8 @@ SYMBOLS = {
     "pooch_gavgpool": (_i32, [_ctx, _i32]),
     "pooch_fc": (_i32, [_ctx, _i32, C.c_int]),
     "pooch_softmax_ce": (_i32, [_ctx, _i32]),
+    "pooch_set_fusion": (_i32, [_ctx, C.c_int]),
+    "pooch_node_fused": (_i32, [_ctx, _i32]),
     "pooch_finalize": (_i32, [_ctx]),
     "pooch_num_params": (_i32, [_ctx]),
     "pooch_param_info": (_i32, [_ctx, _i32, _pi64, _pi32]),
@@ -124,8 +126,9 @@ class Context:
     """One pooch_ctx.  `budget_bytes` is the size of the arena.  With device=None the context
     is planning-only (no GPU touched): graph, profile injection, planning, simulation."""
 
-    def __init__(self, net, budget_bytes, pinned_bytes=0, device="cuda:0"):
+    def __init__(self, net, budget_bytes, pinned_bytes=0, device="cuda:0", fuse=True):
         self.L = lib()
+        self.fuse = bool(fuse)
         self.net = net
         self.budget_bytes = int(budget_bytes)
         self._keep = []          # python objects whose memory the library borrows
@@ -176,6 +179,7 @@ class Context:
 
     def _build(self, net):
         L, h = self.L, self.h
+        self._chk(L.pooch_set_fusion(h, 1 if self.fuse else 0))
         for i, layer in enumerate(net):
             op = layer["op"]
             if op == "input":
@@ -205,6 +209,10 @@ class Context:
         self.n_nodes = L.pooch_num_nodes(h)
         self.n_fmaps = self._chk(L.pooch_num_fmaps(h))
         self.n_params = self._chk(L.pooch_num_params(h))
+
+    def node_fused(self, node):
+        """id of the relu this layer is executed in, or -1"""
+        return self.L.pooch_node_fused(self.h, node)
 
     # ---- parameters and data
     def param_info(self, i):

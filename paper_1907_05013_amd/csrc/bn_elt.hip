@@ -58,13 +58,20 @@ template <int V> __device__ __forceinline__ void stv(float *p, const float (&o)[
     else *p = o[0];
 }
 
+// The one expression every kernel uses for a normalised value (g = gamma * istd): forward, the
+// fused ReLU decision in forward and its re-derivation in backward all round identically.
+__device__ __forceinline__ float bn_val(float x, float mu, float g, float b) { return __fmaf_rn(x - mu, g, b); }
+
 // Stage 1 of both BN reductions.  part[blk][0][c] / part[blk][1][c]:
 //   forward  (dy == nullptr): sum (x - x0_c), sum (x - x0_c)^2, x0_c = first row (a shift that
 //                             keeps the variance formula from cancelling)
 //   backward:                 sum dy, sum dy * (x - mean_c)
-template <int V>
+//   backward through a fused ReLU (RELU): dy is first masked by [bn_val(x) > 0]
+template <int V, bool RELU>
 __global__ __launch_bounds__(BNT) void bn_partial_kernel(const float *__restrict__ x, const float *__restrict__ dy,
-                                                          const float *__restrict__ mean, float *__restrict__ part,
+                                                          const float *__restrict__ mean, const float *__restrict__ gamma,
+                                                          const float *__restrict__ beta, const float *__restrict__ istd,
+                                                          float *__restrict__ part,
                                                           int64_t M, int C, int TX, int TY, int64_t rows_per_blk)
 {
     __shared__ float red[2][BNT][V];
@@ -76,8 +83,16 @@ __global__ __launch_bounds__(BNT) void bn_partial_kernel(const float *__restrict
 #pragma unroll
     for (int i = 0; i < V; ++i) s1[i] = s2[i] = 0.f;
     if (active) {
-        float sh[V];
+        float sh[V], g[V], bt[V];
         ldv<V>((dy ? mean : x) + (int64_t)col * V, sh);
+        if (RELU) {
+            float is[V];
+            ldv<V>(gamma + (int64_t)col * V, g);
+            ldv<V>(istd + (int64_t)col * V, is);
+            ldv<V>(beta + (int64_t)col * V, bt);
+#pragma unroll
+            for (int i = 0; i < V; ++i) g[i] *= is[i];
+        }
         const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
         const int64_t r1 = r0 + rows_per_blk < M ? r0 + rows_per_blk : M;
         for (int64_t r = r0 + ty; r < r1; r += TY) {
@@ -86,6 +101,10 @@ __global__ __launch_bounds__(BNT) void bn_partial_kernel(const float *__restrict
             if (dy) {
                 float dv[V];
                 ldv<V>(dy + r * C + (int64_t)col * V, dv);
+                if (RELU) {
+#pragma unroll
+                    for (int i = 0; i < V; ++i) dv[i] = bn_val(xv[i], sh[i], g[i], bt[i]) > 0.f ? dv[i] : 0.f;
+                }
 #pragma unroll
                 for (int i = 0; i < V; ++i) { s1[i] += dv[i]; s2[i] += dv[i] * (xv[i] - sh[i]); }
             } else {
@@ -156,8 +175,8 @@ __global__ __launch_bounds__(64) void bn_grad_final_kernel(const float *__restri
     }
 }
 
-// y = gamma * (x - mean) * istd + beta
-template <int V>
+// y = gamma * (x - mean) * istd + beta, optionally followed by ReLU
+template <int V, bool RELU>
 __global__ __launch_bounds__(BNT) void bn_apply_kernel(const float *__restrict__ x, const float *__restrict__ gamma,
                                                         const float *__restrict__ beta, const float *__restrict__ mean,
                                                         const float *__restrict__ istd, float *__restrict__ y,
@@ -180,15 +199,19 @@ __global__ __launch_bounds__(BNT) void bn_apply_kernel(const float *__restrict__
         float xv[V];
         ldv<V>(x + r * C + (int64_t)col * V, xv);
 #pragma unroll
-        for (int i = 0; i < V; ++i) xv[i] = (xv[i] - mu[i]) * g[i] + b[i];
+        for (int i = 0; i < V; ++i) {
+            const float v = bn_val(xv[i], mu[i], g[i], b[i]);
+            xv[i] = RELU ? (v > 0.f ? v : 0.f) : v;
+        }
         stv<V>(y + r * C + (int64_t)col * V, xv);
     }
 }
 
 // dx (+)= gamma*istd*(dy - dbeta/m - (x-mean)*istd*dgamma/m)
-template <int V, bool ACCUM>
+template <int V, bool ACCUM, bool RELU>
 __global__ __launch_bounds__(BNT) void bn_bwd_apply_kernel(const float *__restrict__ x, const float *dy,
-                                                            const float *__restrict__ gamma, const float *__restrict__ mean,
+                                                            const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                            const float *__restrict__ mean,
                                                             const float *__restrict__ istd, const float *__restrict__ dgamma,
                                                             const float *__restrict__ dbeta, float *dx,
                                                             int64_t M, int C, int TX, int TY, int64_t rows_per_blk, float inv_m)
@@ -197,7 +220,7 @@ __global__ __launch_bounds__(BNT) void bn_bwd_apply_kernel(const float *__restri
     const int tx = tid % TX, ty = tid / TX;
     const int col = blockIdx.y * TX + tx;
     if (ty >= TY || col * V >= C) return;
-    float a[V], b[V], cc[V], mu[V];
+    float a[V], b[V], cc[V], mu[V], bt[V];
     {
         float g[V], is[V], dg[V], db[V];
         ldv<V>(gamma + (int64_t)col * V, g);
@@ -205,6 +228,7 @@ __global__ __launch_bounds__(BNT) void bn_bwd_apply_kernel(const float *__restri
         ldv<V>(dgamma + (int64_t)col * V, dg);
         ldv<V>(dbeta + (int64_t)col * V, db);
         ldv<V>(mean + (int64_t)col * V, mu);
+        if (RELU) ldv<V>(beta + (int64_t)col * V, bt);
 #pragma unroll
         for (int i = 0; i < V; ++i) { a[i] = g[i] * is[i]; b[i] = db[i] * inv_m; cc[i] = is[i] * dg[i] * inv_m; }
     }
@@ -214,6 +238,10 @@ __global__ __launch_bounds__(BNT) void bn_bwd_apply_kernel(const float *__restri
         float xv[V], dv[V];
         ldv<V>(x + r * C + (int64_t)col * V, xv);
         ldv<V>(dy + r * C + (int64_t)col * V, dv);
+        if (RELU) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) dv[i] = bn_val(xv[i], mu[i], a[i], bt[i]) > 0.f ? dv[i] : 0.f;
+        }
 #pragma unroll
         for (int i = 0; i < V; ++i) dv[i] = a[i] * (dv[i] - b[i] - (xv[i] - mu[i]) * cc[i]);
         if (ACCUM) {
@@ -227,7 +255,7 @@ __global__ __launch_bounds__(BNT) void bn_bwd_apply_kernel(const float *__restri
 }
 
 // ---- flat element-wise kernels: n4 float4 items then a scalar tail ----
-enum { EW_RELU_F, EW_RELU_B, EW_RELU_B_ACC, EW_ADD, EW_ACC, EW_COPY };
+enum { EW_RELU_F, EW_RELU_B, EW_RELU_B_ACC, EW_ADD, EW_ACC, EW_COPY, EW_ADD_RELU };
 
 template <int OP> __device__ __forceinline__ float ew(float a, float b, float d)
 {
@@ -236,6 +264,7 @@ template <int OP> __device__ __forceinline__ float ew(float a, float b, float d)
     case EW_RELU_B: return a > 0.f ? b : 0.f;            // a = y, b = dy
     case EW_RELU_B_ACC: return d + (a > 0.f ? b : 0.f);  // d = existing dx
     case EW_ADD: return a + b;
+    case EW_ADD_RELU: { const float z = a + b; return z > 0.f ? z : 0.f; }
     case EW_ACC: return d + a;                           // a = src
     default: return a;
     }
@@ -244,7 +273,7 @@ template <int OP> __device__ __forceinline__ float ew(float a, float b, float d)
 template <int OP>
 __global__ __launch_bounds__(256) void ew_kernel(const float *a, const float *b, float *d, int64_t n)
 {
-    constexpr bool USE_B = OP == EW_RELU_B || OP == EW_RELU_B_ACC || OP == EW_ADD;
+    constexpr bool USE_B = OP == EW_RELU_B || OP == EW_RELU_B_ACC || OP == EW_ADD || OP == EW_ADD_RELU;
     constexpr bool USE_D = OP == EW_RELU_B_ACC || OP == EW_ACC;
     const int64_t n4 = n / 4;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -278,6 +307,34 @@ template <int OP> hipError_t launch_ew(const float *a, const float *b, float *d,
     return hipGetLastError();
 }
 
+// backward of y = relu(a + b): m = dy where y > 0 else 0; m overwrites dy (the gradient of one
+// input takes over that buffer) and, when o1 is given, is written (mode 1) or added (mode 2) there
+template <int MODE1>
+__global__ __launch_bounds__(256) void addrelu_bwd_kernel(const float *__restrict__ y, float *dy, float *o1, int64_t n)
+{
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        const float4 yv = reinterpret_cast<const float4 *>(y)[i];
+        float4 d = reinterpret_cast<const float4 *>(dy)[i];
+        d.x = yv.x > 0.f ? d.x : 0.f; d.y = yv.y > 0.f ? d.y : 0.f; d.z = yv.z > 0.f ? d.z : 0.f; d.w = yv.w > 0.f ? d.w : 0.f;
+        reinterpret_cast<float4 *>(dy)[i] = d;
+        if (MODE1 == 1) reinterpret_cast<float4 *>(o1)[i] = d;
+        if (MODE1 == 2) {
+            float4 e = reinterpret_cast<const float4 *>(o1)[i];
+            e.x += d.x; e.y += d.y; e.z += d.z; e.w += d.w;
+            reinterpret_cast<float4 *>(o1)[i] = e;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) {
+        const int64_t i = n4 * 4 + threadIdx.x;
+        const float d = y[i] > 0.f ? dy[i] : 0.f;
+        dy[i] = d;
+        if (MODE1 == 1) o1[i] = d;
+        if (MODE1 == 2) o1[i] += d;
+    }
+}
+
 bool bn_args_ok(int64_t M, int C) { return M > 0 && C > 0 && M * (int64_t)C < ((int64_t)1 << 40); }
 
 }  // namespace
@@ -290,45 +347,49 @@ size_t bn_workspace_floats(int64_t M, int C)
 }
 
 hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const float *mean, const float *istd,
-                    float *y, int64_t M, int C, hipStream_t s)
+                    float *y, int64_t M, int C, bool relu, hipStream_t s)
 {
     if (!x || !gamma || !beta || !mean || !istd || !y || !bn_args_ok(M, C)) return hipErrorInvalidValue;
     const bool al = ((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma | (uintptr_t)beta | (uintptr_t)mean | (uintptr_t)istd) % 16 == 0;
     const Lay2D L = layout2d(M, C, al, 8192);
     const dim3 grid(L.nblk, L.gy), block(BNT);
-    if (L.V == 4) bn_apply_kernel<4><<<grid, block, 0, s>>>(x, gamma, beta, mean, istd, y, M, C, L.TX, L.TY, L.rows_per_blk);
-    else bn_apply_kernel<1><<<grid, block, 0, s>>>(x, gamma, beta, mean, istd, y, M, C, L.TX, L.TY, L.rows_per_blk);
+#define APPLY(V, R) bn_apply_kernel<V, R><<<grid, block, 0, s>>>(x, gamma, beta, mean, istd, y, M, C, L.TX, L.TY, L.rows_per_blk)
+    if (L.V == 4) { if (relu) APPLY(4, true); else APPLY(4, false); }
+    else { if (relu) APPLY(1, true); else APPLY(1, false); }
+#undef APPLY
     return hipGetLastError();
 }
 
 hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
-                  float *ws, int64_t M, int C, float eps, hipStream_t s)
+                  float *ws, int64_t M, int C, float eps, bool relu, hipStream_t s)
 {
     if (!x || !gamma || !beta || !y || !mean || !istd || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
     const bool al = ((uintptr_t)x | (uintptr_t)ws | (uintptr_t)mean) % 16 == 0;
     Lay2D L = layout2d(M, C, al, MAX_RBLK);
     const dim3 grid(L.nblk, L.gy), block(BNT);
-    if (L.V == 4) bn_partial_kernel<4><<<grid, block, 0, s>>>(x, nullptr, nullptr, ws, M, C, L.TX, L.TY, L.rows_per_blk);
-    else bn_partial_kernel<1><<<grid, block, 0, s>>>(x, nullptr, nullptr, ws, M, C, L.TX, L.TY, L.rows_per_blk);
+    if (L.V == 4) bn_partial_kernel<4, false><<<grid, block, 0, s>>>(x, nullptr, nullptr, nullptr, nullptr, nullptr, ws, M, C, L.TX, L.TY, L.rows_per_blk);
+    else bn_partial_kernel<1, false><<<grid, block, 0, s>>>(x, nullptr, nullptr, nullptr, nullptr, nullptr, ws, M, C, L.TX, L.TY, L.rows_per_blk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     bn_stats_final_kernel<<<dim3(C), dim3(64), 0, s>>>(ws, x, mean, istd, L.nblk, C, (double)M, (double)eps);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return bn_apply(x, gamma, beta, mean, istd, y, M, C, s);
+    return bn_apply(x, gamma, beta, mean, istd, y, M, C, relu, s);
 }
 
-hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const float *mean, const float *istd,
-                  float *dx, float *dgamma, float *dbeta, float *ws, int64_t M, int C, bool accumulate, hipStream_t s)
+hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const float *beta, const float *mean, const float *istd,
+                  float *dx, float *dgamma, float *dbeta, float *ws, int64_t M, int C, bool accumulate, bool relu, hipStream_t s)
 {
-    if (!x || !dy || !gamma || !mean || !istd || !dx || !dgamma || !dbeta || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    if (!x || !dy || !gamma || !beta || !mean || !istd || !dx || !dgamma || !dbeta || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
     const bool al = ((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx | (uintptr_t)ws | (uintptr_t)mean | (uintptr_t)istd |
                      (uintptr_t)gamma | (uintptr_t)dgamma | (uintptr_t)dbeta) % 16 == 0;
     Lay2D L = layout2d(M, C, al, MAX_RBLK);
     {
         const dim3 grid(L.nblk, L.gy), block(BNT);
-        if (L.V == 4) bn_partial_kernel<4><<<grid, block, 0, s>>>(x, dy, mean, ws, M, C, L.TX, L.TY, L.rows_per_blk);
-        else bn_partial_kernel<1><<<grid, block, 0, s>>>(x, dy, mean, ws, M, C, L.TX, L.TY, L.rows_per_blk);
+#define PARTIAL(V, R) bn_partial_kernel<V, R><<<grid, block, 0, s>>>(x, dy, mean, gamma, beta, istd, ws, M, C, L.TX, L.TY, L.rows_per_blk)
+        if (L.V == 4) { if (relu) PARTIAL(4, true); else PARTIAL(4, false); }
+        else { if (relu) PARTIAL(1, true); else PARTIAL(1, false); }
+#undef PARTIAL
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         bn_grad_final_kernel<<<dim3(C), dim3(64), 0, s>>>(ws, istd, dgamma, dbeta, L.nblk, C);
@@ -338,9 +399,11 @@ hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const flo
     L = layout2d(M, C, al, 8192);
     const dim3 grid(L.nblk, L.gy), block(BNT);
     const float inv_m = (float)(1.0 / (double)M);
-#define BWD_APPLY(V, A) bn_bwd_apply_kernel<V, A><<<grid, block, 0, s>>>(x, dy, gamma, mean, istd, dgamma, dbeta, dx, M, C, L.TX, L.TY, L.rows_per_blk, inv_m)
-    if (L.V == 4) { if (accumulate) BWD_APPLY(4, true); else BWD_APPLY(4, false); }
-    else { if (accumulate) BWD_APPLY(1, true); else BWD_APPLY(1, false); }
+#define BWD_APPLY(V, A, R) bn_bwd_apply_kernel<V, A, R><<<grid, block, 0, s>>>(x, dy, gamma, beta, mean, istd, dgamma, dbeta, dx, M, C, L.TX, L.TY, L.rows_per_blk, inv_m)
+#define BWD_APPLY2(V, A) do { if (relu) BWD_APPLY(V, A, true); else BWD_APPLY(V, A, false); } while (0)
+    if (L.V == 4) { if (accumulate) BWD_APPLY2(4, true); else BWD_APPLY2(4, false); }
+    else { if (accumulate) BWD_APPLY2(1, true); else BWD_APPLY2(1, false); }
+#undef BWD_APPLY2
 #undef BWD_APPLY
     return hipGetLastError();
 }
@@ -355,6 +418,25 @@ hipError_t add_fwd(const float *a, const float *b, float *z, int64_t n, hipStrea
 {
     if (!b) return hipErrorInvalidValue;
     return launch_ew<EW_ADD>(a, b, z, n, s);
+}
+hipError_t add_relu_fwd(const float *a, const float *b, float *z, int64_t n, hipStream_t s)
+{
+    if (!b) return hipErrorInvalidValue;
+    return launch_ew<EW_ADD_RELU>(a, b, z, n, s);
+}
+hipError_t add_relu_bwd(const float *y, float *dy, float *o1, int mode1, int64_t n, hipStream_t s)
+{
+    if (n < 0 || !y || !dy || (mode1 != 0 && !o1) || mode1 < 0 || mode1 > 2) return hipErrorInvalidValue;
+    if (n == 0) return hipSuccess;
+    if (((uintptr_t)y | (uintptr_t)dy | (uintptr_t)o1) % 16 != 0) return hipErrorInvalidValue;
+    int64_t blocks = (n / 4 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    const dim3 grid((unsigned)blocks), block(256);
+    if (mode1 == 0) addrelu_bwd_kernel<0><<<grid, block, 0, s>>>(y, dy, o1, n);
+    else if (mode1 == 1) addrelu_bwd_kernel<1><<<grid, block, 0, s>>>(y, dy, o1, n);
+    else addrelu_bwd_kernel<2><<<grid, block, 0, s>>>(y, dy, o1, n);
+    return hipGetLastError();
 }
 hipError_t accumulate(float *dst, const float *src, int64_t n, hipStream_t s) { return launch_ew<EW_ACC>(src, nullptr, dst, n, s); }
 hipError_t copy(float *dst, const float *src, int64_t n, hipStream_t s) { return launch_ew<EW_COPY>(src, nullptr, dst, n, s); }

@@ -8,7 +8,10 @@
 
 namespace pooch {
 
-enum Op : int { OP_INPUT = 0, OP_CONV, OP_BN, OP_RELU, OP_ADD, OP_MAXPOOL, OP_GAVGPOOL, OP_FC, OP_LOSS };
+enum Op : int { OP_INPUT = 0, OP_CONV, OP_BN, OP_RELU, OP_ADD, OP_MAXPOOL, OP_GAVGPOOL, OP_FC, OP_LOSS,
+                // produced by fusion: BN / add executed inside the ReLU that is their only consumer; the BN /
+                // add node itself becomes OP_DEAD (no output, no commands)
+                OP_BNRELU, OP_ADDRELU, OP_DEAD };
 
 enum : int { CLS_KEEP = 0, CLS_SWAP = 1, CLS_RECOMPUTE = 2 };
 
@@ -36,7 +39,9 @@ struct Node {
 
 struct Graph {
     std::vector<Node> nodes;
+    bool fuse = true;
     // filled by analyze()
+    std::vector<int> fused_into;                // BN / add node -> the ReLU node that executes it, or -1
     std::vector<int64_t> bytes;                 // arena bytes of each node's output (0 for the loss)
     std::vector<std::vector<int>> inputs;       // as given (may repeat)
     std::vector<std::vector<int>> consumers;    // forward consumers, ascending, unique

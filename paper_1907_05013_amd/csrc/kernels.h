@@ -37,20 +37,25 @@ const char *conv_wgrad_kernel(const ConvGeom &g);
 
 // number of floats of scratch the BN reductions need for an [M][C] tensor
 size_t bn_workspace_floats(int64_t M, int C);
-// batch statistics (mean, 1/sqrt(var+eps)) then y = gamma*(x-mean)*istd + beta
+// batch statistics (mean, 1/sqrt(var+eps)) then y = gamma*(x-mean)*istd + beta; relu: y = max(y, 0)
 hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
-                  float *ws, int64_t M, int C, float eps, hipStream_t s);
+                  float *ws, int64_t M, int C, float eps, bool relu, hipStream_t s);
 // apply only, with saved statistics (used when a BN output is recomputed)
 hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const float *mean, const float *istd,
-                    float *y, int64_t M, int C, hipStream_t s);
-// dgamma, dbeta and dx (dx may alias dy); accumulate adds into dx instead of overwriting
-hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const float *mean, const float *istd,
-                  float *dx, float *dgamma, float *dbeta, float *ws, int64_t M, int C, bool accumulate, hipStream_t s);
+                    float *y, int64_t M, int C, bool relu, hipStream_t s);
+// dgamma, dbeta and dx (dx may alias dy); accumulate adds into dx instead of overwriting.
+// relu: dy is the gradient of max(bn(x), 0); the decision bn(x) > 0 is re-derived from x.
+hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const float *beta, const float *mean, const float *istd,
+                  float *dx, float *dgamma, float *dbeta, float *ws, int64_t M, int C, bool accumulate, bool relu, hipStream_t s);
 
 hipError_t relu_fwd(const float *x, float *y, int64_t n, hipStream_t s);
 // dx (+)= dy where y > 0 (dx may alias dy when not accumulating)
 hipError_t relu_bwd(const float *y, const float *dy, float *dx, int64_t n, bool accumulate, hipStream_t s);
 hipError_t add_fwd(const float *a, const float *b, float *z, int64_t n, hipStream_t s);
+// z = max(a + b, 0)
+hipError_t add_relu_fwd(const float *a, const float *b, float *z, int64_t n, hipStream_t s);
+// m = dy where y > 0 else 0, written over dy; mode1 1: o1 = m, 2: o1 += m, 0: o1 unused
+hipError_t add_relu_bwd(const float *y, float *dy, float *o1, int mode1, int64_t n, hipStream_t s);
 // dst += src
 hipError_t accumulate(float *dst, const float *src, int64_t n, hipStream_t s);
 hipError_t copy(float *dst, const float *src, int64_t n, hipStream_t s);

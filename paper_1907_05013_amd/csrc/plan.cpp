@@ -366,6 +366,7 @@ struct Walker {
         const int n = G.n();
         for (int i = 1; i < n; ++i) {
             const std::vector<int> &ins = G.inputs[i];
+            if (G.nodes[i].op == OP_DEAD) continue;
             if (G.nodes[i].op == OP_LOSS) {
                 emit(K_FWD, i, OFF_NONE, loc[ins[0]], OFF_NONE);
             } else {
@@ -412,7 +413,7 @@ struct Walker {
             int64_t o[2] = {OFF_NONE, OFF_NONE};
             int m[2] = {M_NONE, M_NONE};
             bool transferred = false;
-            if (op == OP_RELU || op == OP_BN) {
+            if (op == OP_RELU || op == OP_BN || op == OP_BNRELU) {
                 const int x = ins[0];
                 if (x == 0) {
                 } else if (gloc[x] == LOC_NONE) {
@@ -424,7 +425,7 @@ struct Walker {
                     o[0] = gloc[x];
                     m[0] = M_ACC;
                 }
-            } else if (op == OP_ADD) {
+            } else if (op == OP_ADD || op == OP_ADDRELU) {
                 for (int j = 0; j < 2; ++j) {
                     const int u = ins[j];
                     if (u == 0) continue;
@@ -481,27 +482,53 @@ std::string Graph::analyze()
     bytes.assign(n, 0);
     consumers.assign(n, {});
     needs.assign(n, {});
+    fused_into.assign(n, -1);
     for (int i = 0; i < n; ++i) {
         const Node &nd = nodes[i];
         if (i > 0 && nd.op == OP_INPUT) return "only one input node is supported";
         if (nd.op == OP_LOSS && i != n - 1) return "softmax_ce must be the terminal node";
+        if (nd.op == OP_BNRELU || nd.op == OP_ADDRELU || nd.op == OP_DEAD) return "graph was already analysed";
         for (int j = 0; j < nd.nin; ++j) {
             if (nd.in[j] < 0 || nd.in[j] >= i) return "layer input does not precede it";
             if (nodes[nd.in[j]].op == OP_LOSS) return "the loss has no consumers";
-            inputs[i].push_back(nd.in[j]);
         }
-        bytes[i] = nd.op == OP_LOSS ? 0 : round_up(4 * nd.numel());
+    }
+    if (fuse) {
+        std::vector<std::vector<int>> raw(n);
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < nodes[i].nin; ++j) {
+                const int t = nodes[i].in[j];
+                if (std::find(raw[t].begin(), raw[t].end(), i) == raw[t].end()) raw[t].push_back(i);
+            }
+        for (int i = 0; i < n; ++i) {
+            if ((nodes[i].op != OP_BN && nodes[i].op != OP_ADD) || raw[i].size() != 1 || nodes[raw[i][0]].op != OP_RELU) continue;
+            Node &r = nodes[raw[i][0]];
+            Node &b = nodes[i];
+            r.op = b.op == OP_BN ? OP_BNRELU : OP_ADDRELU;
+            r.nin = b.nin;
+            r.in[0] = b.in[0];
+            r.in[1] = b.in[1];
+            r.eps = b.eps;
+            fused_into[i] = raw[i][0];
+            b.op = OP_DEAD;
+            b.nin = 0;
+        }
+    }
+    for (int i = 0; i < n; ++i) {
+        const Node &nd = nodes[i];
+        for (int j = 0; j < nd.nin; ++j) inputs[i].push_back(nd.in[j]);
+        bytes[i] = (nd.op == OP_LOSS || nd.op == OP_DEAD) ? 0 : round_up(4 * nd.numel());
         for (int t : inputs[i])
             if (std::find(consumers[t].begin(), consumers[t].end(), i) == consumers[t].end()) consumers[t].push_back(i);
         switch (nd.op) {
-        case OP_CONV: case OP_BN: case OP_MAXPOOL: case OP_FC: case OP_LOSS: needs[i] = {inputs[i][0]}; break;
-        case OP_RELU: needs[i] = {i}; break;
+        case OP_CONV: case OP_BN: case OP_BNRELU: case OP_MAXPOOL: case OP_FC: case OP_LOSS: needs[i] = {inputs[i][0]}; break;
+        case OP_RELU: case OP_ADDRELU: needs[i] = {i}; break;
         default: break;
         }
     }
     last_consumer.assign(n, -1);
     for (int t = 0; t < n; ++t) {
-        if (t != n - 1 && consumers[t].empty()) return "a layer output is never consumed";
+        if (t != n - 1 && consumers[t].empty() && nodes[t].op != OP_DEAD) return "a layer output is never consumed";
         for (int c : consumers[t]) last_consumer[t] = std::max(last_consumer[t], c);
     }
     std::vector<char> needed(n, 0);

@@ -178,16 +178,18 @@ struct Exec {
         hipStream_t s = c->st[S_COMPUTE];
         switch (nd.op) {
         case OP_CONV: return pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i), s);
-        case OP_BN: {
+        case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
+            const bool relu = nd.op == OP_BNRELU;
             if (refwd)
                 return pk::bn_apply(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), R(c->off_mean[i]), R(c->off_istd[i]),
-                                    D(out), M, (int)nd.C, s);
+                                    D(out), M, (int)nd.C, relu, s);
             return pk::bn_fwd(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), D(out), R(c->off_mean[i]), R(c->off_istd[i]),
-                              R(c->off_ws_bn), M, (int)nd.C, nd.eps, s);
+                              R(c->off_ws_bn), M, (int)nd.C, nd.eps, relu, s);
         }
         case OP_RELU: return pk::relu_fwd(D(in0), D(out), nd.numel(), s);
         case OP_ADD: return pk::add_fwd(D(in0), D(in1), D(out), nd.numel(), s);
+        case OP_ADDRELU: return pk::add_relu_fwd(D(in0), D(in1), D(out), nd.numel(), s);
         case OP_MAXPOOL: return pk::maxpool_fwd(D(in0), D(out), pool_geom(G, i), s);
         case OP_GAVGPOOL: {
             const Node &x = G.nodes[nd.in[0]];
@@ -239,11 +241,30 @@ struct Exec {
             if (m0 == M_NONE) return hipSuccess;
             return pk::conv_dgrad(D(dy), R(P(i, 0).off_val_t), D(o0), g, m0 == M_ACC, s);
         }
-        case OP_BN: {
+        case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
             float *dx = m0 == M_NONE ? D(dy) : D(o0);
-            return pk::bn_bwd(D(need), D(dy), R(P(i, 0).off_val), R(c->off_mean[i]), R(c->off_istd[i]), dx,
-                              R(P(i, 0).off_grad), R(P(i, 1).off_grad), R(c->off_ws_bn), M, (int)nd.C, m0 == M_ACC, s);
+            return pk::bn_bwd(D(need), D(dy), R(P(i, 0).off_val), R(P(i, 1).off_val), R(c->off_mean[i]), R(c->off_istd[i]), dx,
+                              R(P(i, 0).off_grad), R(P(i, 1).off_grad), R(c->off_ws_bn), M, (int)nd.C, m0 == M_ACC,
+                              nd.op == OP_BNRELU, s);
+        }
+        case OP_ADDRELU: {
+            // the masked gradient overwrites dy (one input may take that buffer over); the first
+            // input that wants its own copy gets it in the same pass, a second one in a pass of its own
+            const int64_t offs[2] = {o0, o1};
+            const int modes[2] = {m0, m1};
+            int first = -1;
+            for (int j = 0; j < 2; ++j)
+                if (first < 0 && (modes[j] == M_WRITE || modes[j] == M_ACC)) first = j;
+            hipError_t e = pk::add_relu_bwd(D(need), D(dy), first < 0 ? nullptr : D(offs[first]),
+                                            first < 0 ? 0 : (modes[first] == M_WRITE ? 1 : 2), nd.numel(), s);
+            if (e != hipSuccess) return e;
+            for (int j = first + 1; first >= 0 && j < 2; ++j)
+                if (modes[j] == M_WRITE || modes[j] == M_ACC) {
+                    e = pass_on(dy, offs[j], modes[j], nd.numel());
+                    if (e != hipSuccess) return e;
+                }
+            return hipSuccess;
         }
         case OP_RELU:
             if (m0 == M_NONE) return hipSuccess;
@@ -620,6 +641,20 @@ int32_t pooch_softmax_ce(pooch_ctx *c, int32_t logits)
     return add_node(c, nd);
 }
 
+pooch_status pooch_set_fusion(pooch_ctx *c, int enable)
+{
+    GRAPH_OPEN(c);
+    c->G.fuse = enable != 0;
+    return POOCH_OK;
+}
+
+int32_t pooch_node_fused(pooch_ctx *c, int32_t id)
+{
+    if (!c || !c->finalized) return POOCH_E_STATE;
+    if (id < 0 || id >= c->G.n()) return POOCH_E_INVALID;
+    return c->G.fused_into[id];
+}
+
 pooch_status pooch_finalize(pooch_ctx *c)
 {
     GRAPH_OPEN(c);
@@ -653,7 +688,7 @@ pooch_status pooch_finalize(pooch_ctx *c)
                 nd.param[1] = (int)c->params.size();
                 c->params.push_back(b);
             }
-        } else if (nd.op == OP_BN) {
+        } else if (nd.op == OP_BN || (nd.op == OP_DEAD && G.nodes[G.fused_into[i]].op == OP_BNRELU)) {
             for (int w = 0; w < 2; ++w) {
                 ParamInfo p{i, w, nd.C, take(nd.C * 4), -1, take(nd.C * 4)};
                 nd.param[w] = (int)c->params.size();
@@ -664,6 +699,15 @@ pooch_status pooch_finalize(pooch_ctx *c)
             ws_bn = std::max(ws_bn, pk::bn_workspace_floats(nd.numel() / nd.C, (int)nd.C) * 4);
         } else if (nd.op == OP_LOSS) {
             c->nclasses = (int)G.nodes[nd.in[0]].C;
+        }
+    }
+    for (int i = 0; i < n; ++i) {
+        const int j = G.fused_into[i];
+        if (j >= 0 && G.nodes[j].op == OP_BNRELU) {
+            G.nodes[j].param[0] = G.nodes[i].param[0];
+            G.nodes[j].param[1] = G.nodes[i].param[1];
+            c->off_mean[j] = c->off_mean[i];
+            c->off_istd[j] = c->off_istd[i];
         }
     }
     c->off_ws_wgrad = take((int64_t)ws_wgrad);
@@ -752,6 +796,7 @@ pooch_status pooch_capture_tensor(pooch_ctx *c, int32_t id, float *host)
 {
     NEED_FINAL(c);
     if (id <= 0 || id >= c->G.n() || c->G.nodes[id].op == OP_LOSS) return fail(c, POOCH_E_INVALID, "capture: not a layer output");
+    if (c->G.nodes[id].op == OP_DEAD) return fail(c, POOCH_E_STATE, "capture: this layer is fused into its consumer, its output is never materialised");
     c->capture[id] = host;
     return POOCH_OK;
 }
@@ -760,7 +805,7 @@ pooch_status pooch_get_bn_stats(pooch_ctx *c, int32_t node, float *mean, float *
 {
     NEED_FINAL(c);
     if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
-    if (node < 0 || node >= c->G.n() || c->G.nodes[node].op != OP_BN) return fail(c, POOCH_E_INVALID, "not a bn node");
+    if (node < 0 || node >= c->G.n() || c->off_mean[node] < 0) return fail(c, POOCH_E_INVALID, "not a bn node");
     const size_t bytes = (size_t)c->G.nodes[node].C * 4;
     if (mean) HIPCHK(hipMemcpy(mean, c->arena + c->off_mean[node], bytes, hipMemcpyDeviceToHost));
     if (istd) HIPCHK(hipMemcpy(istd, c->arena + c->off_istd[node], bytes, hipMemcpyDeviceToHost));

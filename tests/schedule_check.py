@@ -50,6 +50,9 @@ def _accesses(G, c):
                 assert off == dy
                 if op == "add":
                     relabel.append((off, ("g", t)))
+                elif op == "addrelu":
+                    # masked in place: a read-modify-write of the dy buffer, which changes owner
+                    acc.append((off, G.bytes[t], True, ("g", t)))
                 else:
                     acc.append((off, G.bytes[t], True, ("g", t)))
     return acc, relabel

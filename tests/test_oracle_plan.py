@@ -63,6 +63,18 @@ def test_resnet50_feature_map_arithmetic():
     assert sum(b[-gold["table3_keep"]:]) < cap
 
 
+def test_fusion_keeps_the_feature_map_set():
+    """executing a BN / add inside the ReLU that alone consumes it removes a transient tensor,
+    not a feature map: still table 3's 105 maps and the same bytes"""
+    net = workloads.resnet50(batch=640)
+    G0, G1 = P.Graph(net), P.Graph(net, fuse=True)
+    assert G0.fmaps == G1.fmaps and G0.fmap_bytes() == G1.fmap_bytes() and len(G1.fmaps) == 105
+    assert G1.ops.count("bnrelu") == 33 and G1.ops.count("addrelu") == 16 and G1.ops.count("bn") == 20
+    for i, j in enumerate(G1.fused_into):
+        if j >= 0:
+            assert G1.bytes[i] == 0 and G0.consumers[i] == [j] and G0.ops[j] == "relu"
+
+
 # ---- allocator ---------------------------------------------------------------------------
 
 def test_arena_random_against_bitmap():
@@ -187,10 +199,11 @@ def small_nets():
     }
 
 
+@pytest.mark.parametrize("fuse", [False, True])
 @pytest.mark.parametrize("name", ["tiny", "res", "c3d", "chain"])
-def test_random_plans_schedule_valid(name):
+def test_random_plans_schedule_valid(name, fuse):
     net = small_nets()[name]
-    G = P.Graph(net)
+    G = P.Graph(net, fuse=fuse)
     nf = len(G.fmaps)
     rng = np.random.default_rng(11)
     incore = P.build_schedule(G, [P.KEEP] * nf, BIG)

@@ -29,10 +29,10 @@ def nets():
     }
 
 
-def lib_ctx(net, dyn_cap):
-    probe = B.Context(net, 1 << 40, device=None)
+def lib_ctx(net, dyn_cap, fuse=True):
+    probe = B.Context(net, 1 << 40, device=None, fuse=fuse)
     res = probe.resident_bytes()
-    return B.Context(net, res + dyn_cap, device=None), res
+    return B.Context(net, res + dyn_cap, device=None, fuse=fuse), res
 
 
 def rand_profile(G, rng, link=1.0):
@@ -50,14 +50,17 @@ def as_rows(S):
     return np.array(rows, np.int64).reshape(-1, 8)
 
 
+@pytest.mark.parametrize("fuse", [False, True])
 @pytest.mark.parametrize("name", ["tiny", "res", "c3d", "bott"])
-def test_feature_maps_and_command_lists_identical(name):
+def test_feature_maps_and_command_lists_identical(name, fuse):
     net = nets()[name]
-    G = P.Graph(net)
+    G = P.Graph(net, fuse=fuse)
     nf = len(G.fmaps)
     incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
-    c, _ = lib_ctx(net, BIG)
+    c, _ = lib_ctx(net, BIG, fuse)
     assert [(G.bytes[t], t) for t in G.fmaps] == c.fmaps()
+    assert [c.node_fused(i) for i in range(G.n)] == G.fused_into
+    assert any(v >= 0 for v in G.fused_into) == fuse
     rng = np.random.default_rng(21)
     prof = rand_profile(G, rng)
     oprof = P.Profile(*[list(v) for v in prof])
@@ -65,7 +68,7 @@ def test_feature_maps_and_command_lists_identical(name):
     for trial in range(40):
         cls = [int(v) for v in rng.integers(0, 3, nf)] if trial else [P.KEEP] * nf
         cap = BIG if trial == 0 else int(incore.peak * rng.uniform(0.35, 1.2)) // 256 * 256
-        c, _ = lib_ctx(net, cap)
+        c, _ = lib_ctx(net, cap, fuse)
         c.set_profile(*prof)
         for ahead in (True, False):
             try:
@@ -90,13 +93,14 @@ def test_feature_maps_and_command_lists_identical(name):
 def test_every_mode_picks_the_oracles_plan(seed):
     rng = np.random.default_rng(100 + seed)
     net = list(nets().values())[seed % 4]
-    G = P.Graph(net)
+    fuse = seed % 2 == 0
+    G = P.Graph(net, fuse=fuse)
     nf = len(G.fmaps)
     incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
     cap = int(incore.peak * rng.uniform(0.45, 0.95)) // 256 * 256
     prof = rand_profile(G, rng, link=float(rng.choice([0.2, 1.0, 4.0])))
     oprof = P.Profile(*[list(v) for v in prof])
-    c, _ = lib_ctx(net, cap)
+    c, _ = lib_ctx(net, cap, fuse)
     c.set_profile(*prof)
     bits = 5
     for mode in ("swapall_nosched", "swapall", "swapopt", "pooch", "refine"):
@@ -145,7 +149,7 @@ def test_resnet50_b640_plan_fits_16gib():
     """the paper's headline case as a planning problem: 105 maps, > 50 GB, 16 GiB arena"""
     net = workloads.resnet50(batch=640)
     c = B.Context(net, 16 << 30, device=None)
-    G = P.Graph(net)
+    G = P.Graph(net, fuse=True)
     rng = np.random.default_rng(9)
     prof = rand_profile(G, rng)
     c.set_profile(*prof)
