@@ -9,6 +9,8 @@
 // workgroups into a workspace and summed in a fixed order.
 #include "kernels.h"
 
+#include <cstdlib>
+
 namespace pk {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -18,6 +20,10 @@ namespace {
 constexpr int BK = 16;   // reduction slice per main-loop iteration
 constexpr int LDK = 20;  // LDS row stride (floats) of [row][k] tiles: 16-byte rows, conflict-free b128 reads
 constexpr int NXCD = 8;
+
+// 16 zero bytes every kernel may read: elements that do not exist (padding, rows or slices past
+// the end) are loaded from here instead of being branched around or masked afterwards
+__device__ __attribute__((aligned(16))) const float g_zero4[4] = {0.f, 0.f, 0.f, 0.f};
 
 struct IGemmP {
     const float *src;  // forward: x; data gradient: dy (channels-last)
@@ -40,15 +46,11 @@ __device__ __forceinline__ bool src_coord(int base, int a, int s, int S, int &q)
         q = base + a;
         return (unsigned)q < (unsigned)S;
     } else {
+        // q*s == base - a must hold exactly; no branches so that callers stay straight-line
         const int t = base - a;
-        if (t < 0) return false;
-        if (s == 1) {
-            q = t;
-        } else {
-            q = t / s;
-            if (q * s != t) return false;
-        }
-        return q < S;
+        const int tt = t < 0 ? 0 : t;
+        q = s == 1 ? tt : tt / s;
+        return (t >= 0) & (q * s == tt) & (q < S);
     }
 }
 
@@ -56,17 +58,23 @@ __device__ __forceinline__ bool src_coord(int base, int a, int s, int S, int &q)
 // XCDs; give each XCD a contiguous range of tiles so that neighbours share its L2.
 __device__ __forceinline__ int remap_tile(int wg, int chunk) { return (wg % NXCD) * chunk + wg / NXCD; }
 
-template <int WGM, int WGN, int TM, int TN, bool VEC, bool DGRAD, bool ACCUM>
+template <int WGM, int WGN, int TM, int TN, int BKT, bool VEC, bool LIN, bool DGRAD, bool ACCUM>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 {
+    // BKT = reduction slice per main-loop iteration; LDS rows are BKT + 4 floats apart (16-byte
+    // aligned, conflict-free 128-bit reads)
     constexpr int NT = 64 * WGM * WGN;
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    constexpr int A_V = (BM * 4 + NT - 1) / NT, B_V = (BN * 4 + NT - 1) / NT;  // float4 loads per thread (VEC)
-    constexpr int A_S = BM * 16 / NT, B_S = BN * 16 / NT;                      // scalar loads per thread
-    static_assert(BM * 16 % NT == 0 && BN * 16 % NT == 0, "tile/threads mismatch");
+    constexpr int LDT = BKT + 4;
+    constexpr int KQ = BKT / 4;                      // float4 per tile row
+    constexpr int RPP = NT / KQ;                     // rows covered per pass of vector loads
+    constexpr int A_V = (BM + RPP - 1) / RPP, B_V = (BN + RPP - 1) / RPP;
+    constexpr int RPS = NT / BKT;                    // rows per pass of scalar loads
+    constexpr int A_S = BM / RPS, B_S = BN / RPS;
+    static_assert(NT % KQ == 0 && NT % BKT == 0 && BM % RPS == 0 && BN % RPS == 0, "tile/threads mismatch");
 
-    __shared__ __attribute__((aligned(16))) float As[BM * LDK];
-    __shared__ __attribute__((aligned(16))) float Bs[BN * LDK];
+    __shared__ __attribute__((aligned(16))) float As[BM * LDT];
+    __shared__ __attribute__((aligned(16))) float Bs[BN * LDT];
     __shared__ int4 rowinfo[BM];
     __shared__ int rowdst[BM];
 
@@ -98,45 +106,118 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     float4 av[VEC ? A_V : 1], bv[VEC ? B_V : 1];
     float as[VEC ? 1 : A_S], bs[VEC ? 1 : B_S];
     int4 ri_reg[VEC ? A_V : 1];
+    unsigned amask = 0, bmask = 0;                   // vector path: which prefetched float4 hold real data
+    const int vrow = tid / KQ, vk = 4 * (tid % KQ);  // vector path: this thread's row within a pass, k offset
     if (VEC) {
 #pragma unroll
-        for (int i = 0; i < A_V; ++i) ri_reg[i] = rowinfo[(tid / 4 + i * (NT / 4)) % BM];
+        for (int i = 0; i < A_V; ++i) {
+            ri_reg[i] = rowinfo[(vrow + i * RPP) % BM];
+            if (vrow + i * RPP >= BM) ri_reg[i].x = -1;
+        }
     }
+    // when every filter tap spans a whole number of slices, the tap of a slice is the same for
+    // all threads: its decomposition then runs on the scalar unit
+    const bool tap_uniform = p.Cs % BKT == 0;
 
+    // LIN (requires Cs % BKT == 0, and unit strides for the data gradient): the source element of
+    // row i at the current slice is abase[i] + delta, where delta depends only on the slice (scalar
+    // unit) and abase[i] is fixed for the tile.  Per slice and row that leaves three coordinate
+    // range checks and one 64-bit add on the vector unit -- no multiplies, no divisions.
+    int64_t abase[LIN ? A_V : 1];
+    const float *bptr[LIN ? B_V : 1];
+    bool brow[LIN ? B_V : 1];
+    int ta = 0, tb = 0, te = 0, tc = 0;              // tap (a, b, e) and channel offset of the slice start
+    if (LIN) {
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) {
+            const int4 ri = ri_reg[i];
+            abase[i] = ((((int64_t)ri.x * p.Ds + ri.y) * p.Hs + ri.z) * p.Ws + ri.w) * p.Cs + vk;
+        }
+#pragma unroll
+        for (int i = 0; i < B_V; ++i) {
+            const int n = n0 + vrow + i * RPP;
+            brow[i] = (vrow + i * RPP < BN) & (n < p.Nout);
+            bptr[i] = p.wgt + (brow[i] ? (int64_t)n * p.Kred + vk : 0);
+        }
+    }
+    auto load_tiles_lin = [&](bool live) {
+        const int64_t tapoff = (((int64_t)ta * p.Hs + tb) * p.Ws + te) * p.Cs;
+        const int64_t delta = (DGRAD ? -tapoff : tapoff) + tc;
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) {
+            const int4 ri = ri_reg[i];
+            const int qd = DGRAD ? ri.y - ta : ri.y + ta;
+            const int qh = DGRAD ? ri.z - tb : ri.z + tb;
+            const int qw = DGRAD ? ri.w - te : ri.w + te;
+            const bool ok = live & (ri.x >= 0) & ((unsigned)qd < (unsigned)p.Ds) & ((unsigned)qh < (unsigned)p.Hs) &
+                            ((unsigned)qw < (unsigned)p.Ws);
+            av[i] = *reinterpret_cast<const float4 *>(ok ? p.src + (abase[i] + delta) : g_zero4);
+        }
+        amask = ~0u;
+        bmask = ~0u;
+#pragma unroll
+        for (int i = 0; i < B_V; ++i) {
+            const bool ok = live & brow[i];
+            bv[i] = *reinterpret_cast<const float4 *>(ok ? bptr[i] : g_zero4);
+            bptr[i] += BKT;
+        }
+        tc += BKT;
+        if (tc == p.Cs) {
+            tc = 0;
+            if (++te == p.kw) {
+                te = 0;
+                if (++tb == p.kh) {
+                    tb = 0;
+                    ++ta;
+                }
+            }
+        }
+    };
+
+    // The vector path is branch-free on purpose: addresses of elements that do not exist are
+    // clamped to offset 0 (always readable) and the value is zeroed when it is stored to LDS.
+    // Straight-line code lets the scheduler spread this address arithmetic and the loads
+    // between the MFMAs of the slice being multiplied, instead of running them as a separate phase.
     auto load_tiles = [&](int k0) {
         if (VEC) {
-            const int k = k0 + 4 * (tid % 4);
+            const int k = k0 + vk;
             const bool kok = k < p.Kred;
-            int a = 0, b = 0, e = 0, c = 0;
-            if (kok) {
-                const int tap = k / p.Cs;
-                c = k - tap * p.Cs;
-                e = tap % p.kw;
-                const int t2 = tap / p.kw;
-                b = t2 % p.kh;
-                a = t2 / p.kh;
+            int tap, c;
+            if (tap_uniform) {
+                tap = k0 / p.Cs;
+                c = k0 - tap * p.Cs + vk;
+            } else {
+                const int kc = kok ? k : 0;
+                tap = kc / p.Cs;
+                c = kc - tap * p.Cs;
             }
+            const int e = tap % p.kw;
+            const int t2 = tap / p.kw;
+            const int b = t2 % p.kh;
+            const int a = t2 / p.kh;
+            amask = 0;
 #pragma unroll
             for (int i = 0; i < A_V; ++i) {
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 const int4 ri = ri_reg[i];
                 int qd, qh, qw;
-                if (kok && tid / 4 + i * (NT / 4) < BM && ri.x >= 0 && src_coord<DGRAD>(ri.y, a, p.sd, p.Ds, qd) &&
-                    src_coord<DGRAD>(ri.z, b, p.sh, p.Hs, qh) && src_coord<DGRAD>(ri.w, e, p.sw, p.Ws, qw)) {
-                    const int64_t off = ((((int64_t)ri.x * p.Ds + qd) * p.Hs + qh) * p.Ws + qw) * p.Cs + c;
-                    v = *reinterpret_cast<const float4 *>(p.src + off);
-                }
-                av[i] = v;
+                const bool vd = src_coord<DGRAD>(ri.y, a, p.sd, p.Ds, qd);
+                const bool vh = src_coord<DGRAD>(ri.z, b, p.sh, p.Hs, qh);
+                const bool vw = src_coord<DGRAD>(ri.w, e, p.sw, p.Ws, qw);
+                const bool ok = kok & (ri.x >= 0) & vd & vh & vw;
+                const int64_t off = ((((int64_t)ri.x * p.Ds + qd) * p.Hs + qh) * p.Ws + qw) * p.Cs + c;
+                av[i] = *reinterpret_cast<const float4 *>(p.src + (ok ? off : 0));
+                amask |= (ok ? 1u : 0u) << i;
             }
+            bmask = 0;
 #pragma unroll
             for (int i = 0; i < B_V; ++i) {
-                const int n = n0 + tid / 4 + i * (NT / 4);
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (kok && tid / 4 + i * (NT / 4) < BN && n < p.Nout) v = *reinterpret_cast<const float4 *>(p.wgt + (int64_t)n * p.Kred + k);
-                bv[i] = v;
+                const int n = n0 + vrow + i * RPP;
+                const bool ok = kok & (vrow + i * RPP < BN) & (n < p.Nout);
+                bv[i] = *reinterpret_cast<const float4 *>(p.wgt + (ok ? (int64_t)n * p.Kred + k : 0));
+                bmask |= (ok ? 1u : 0u) << i;
             }
         } else {
-            const int k = k0 + (tid % 16);
+            const int k = k0 + (tid % BKT);
             const bool kok = k < p.Kred;
             int a = 0, b = 0, e = 0, c = 0;
             if (kok) {
@@ -150,7 +231,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 #pragma unroll
             for (int i = 0; i < A_S; ++i) {
                 float v = 0.f;
-                const int4 ri = rowinfo[tid / 16 + i * (NT / 16)];
+                const int4 ri = rowinfo[tid / BKT + i * RPS];
                 int qd, qh, qw;
                 if (kok && ri.x >= 0 && src_coord<DGRAD>(ri.y, a, p.sd, p.Ds, qd) &&
                     src_coord<DGRAD>(ri.z, b, p.sh, p.Hs, qh) && src_coord<DGRAD>(ri.w, e, p.sw, p.Ws, qw)) {
@@ -161,7 +242,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             }
 #pragma unroll
             for (int i = 0; i < B_S; ++i) {
-                const int n = n0 + tid / 16 + i * (NT / 16);
+                const int n = n0 + tid / BKT + i * RPS;
                 bs[i] = (kok && n < p.Nout) ? p.wgt[(int64_t)n * p.Kred + k] : 0.f;
             }
         }
@@ -171,17 +252,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
         if (VEC) {
 #pragma unroll
             for (int i = 0; i < A_V; ++i)
-                if (tid / 4 + i * (NT / 4) < BM)
-                    *reinterpret_cast<float4 *>(&As[(tid / 4 + i * (NT / 4)) * LDK + 4 * (tid % 4)]) = av[i];
+                if (vrow + i * RPP < BM)
+                    *reinterpret_cast<float4 *>(&As[(vrow + i * RPP) * LDT + vk]) = (LIN || ((amask >> i) & 1u)) ? av[i] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
             for (int i = 0; i < B_V; ++i)
-                if (tid / 4 + i * (NT / 4) < BN)
-                    *reinterpret_cast<float4 *>(&Bs[(tid / 4 + i * (NT / 4)) * LDK + 4 * (tid % 4)]) = bv[i];
+                if (vrow + i * RPP < BN)
+                    *reinterpret_cast<float4 *>(&Bs[(vrow + i * RPP) * LDT + vk]) = (LIN || ((bmask >> i) & 1u)) ? bv[i] : make_float4(0.f, 0.f, 0.f, 0.f);
         } else {
 #pragma unroll
-            for (int i = 0; i < A_S; ++i) As[(tid / 16 + i * (NT / 16)) * LDK + (tid % 16)] = as[i];
+            for (int i = 0; i < A_S; ++i) As[(tid / BKT + i * RPS) * LDT + (tid % BKT)] = as[i];
 #pragma unroll
-            for (int i = 0; i < B_S; ++i) Bs[(tid / 16 + i * (NT / 16)) * LDK + (tid % 16)] = bs[i];
+            for (int i = 0; i < B_S; ++i) Bs[(tid / BKT + i * RPS) * LDT + (tid % BKT)] = bs[i];
         }
     };
 
@@ -197,38 +278,44 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     const int wm = wave / WGN, wn = wave % WGN;
     const int r = lane % 32, h = lane / 32;
 
-    const int nk = (p.Kred + BK - 1) / BK;
-    load_tiles(0);
+    const int nk = (p.Kred + BKT - 1) / BKT;
+    if (LIN) load_tiles_lin(true);
+    else load_tiles(0);
     for (int it = 0; it < nk; ++it) {
         store_tiles();
         __syncthreads();
-        if (it + 1 < nk) load_tiles((it + 1) * BK);
+        if (LIN) load_tiles_lin(it + 1 < nk);          // past the end: every element is masked off
+        else if (VEC) load_tiles((it + 1) * BKT);
+        else if (it + 1 < nk) load_tiles((it + 1) * BKT);
 
-        // lane half h covers k = 8h .. 8h+7 of the slice; MFMA step t multiplies k = 8h + t
-        float af[TM][8], bf[TN][8];
+        // per 16-wide sub-slice s: lane half h covers k = 16s + 8h .. 16s + 8h + 7; MFMA step t multiplies k = 16s + 8h + t
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const float *ap = &As[(wm * TM * 32 + i * 32 + r) * LDK + h * 8];
-            const float4 lo = *reinterpret_cast<const float4 *>(ap);
-            const float4 hi = *reinterpret_cast<const float4 *>(ap + 4);
-            af[i][0] = lo.x; af[i][1] = lo.y; af[i][2] = lo.z; af[i][3] = lo.w;
-            af[i][4] = hi.x; af[i][5] = hi.y; af[i][6] = hi.z; af[i][7] = hi.w;
+        for (int sub = 0; sub < BKT / 16; ++sub) {
+            float af[TM][8], bf[TN][8];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const float *ap = &As[(wm * TM * 32 + i * 32 + r) * LDT + sub * 16 + h * 8];
+                const float4 lo = *reinterpret_cast<const float4 *>(ap);
+                const float4 hi = *reinterpret_cast<const float4 *>(ap + 4);
+                af[i][0] = lo.x; af[i][1] = lo.y; af[i][2] = lo.z; af[i][3] = lo.w;
+                af[i][4] = hi.x; af[i][5] = hi.y; af[i][6] = hi.z; af[i][7] = hi.w;
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float *bp = &Bs[(wn * TN * 32 + j * 32 + r) * LDT + sub * 16 + h * 8];
+                const float4 lo = *reinterpret_cast<const float4 *>(bp);
+                const float4 hi = *reinterpret_cast<const float4 *>(bp + 4);
+                bf[j][0] = lo.x; bf[j][1] = lo.y; bf[j][2] = lo.z; bf[j][3] = lo.w;
+                bf[j][4] = hi.x; bf[j][5] = hi.y; bf[j][6] = hi.z; bf[j][7] = hi.w;
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
         }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const float *bp = &Bs[(wn * TN * 32 + j * 32 + r) * LDK + h * 8];
-            const float4 lo = *reinterpret_cast<const float4 *>(bp);
-            const float4 hi = *reinterpret_cast<const float4 *>(bp + 4);
-            bf[j][0] = lo.x; bf[j][1] = lo.y; bf[j][2] = lo.z; bf[j][3] = lo.w;
-            bf[j][4] = hi.x; bf[j][5] = hi.y; bf[j][6] = hi.z; bf[j][7] = hi.w;
-        }
-#pragma unroll
-        for (int t = 0; t < 8; ++t)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
         __syncthreads();
     }
 
@@ -251,8 +338,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
         }
 }
 
-template <int WGM, int WGN, int TM, int TN, bool DGRAD>
-hipError_t launch_igemm(IGemmP p, bool vec, bool accum, hipStream_t s)
+template <int WGM, int WGN, int TM, int TN, int BKT, bool DGRAD>
+hipError_t launch_igemm(IGemmP p, bool vec, bool lin, bool accum, hipStream_t s)
 {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     const int tiles_m = (p.M + BM - 1) / BM;
@@ -260,23 +347,36 @@ hipError_t launch_igemm(IGemmP p, bool vec, bool accum, hipStream_t s)
     p.total_tiles = tiles_m * p.tiles_n;
     p.chunk = (p.total_tiles + NXCD - 1) / NXCD;
     const dim3 grid(p.chunk * NXCD), block(64 * WGM * WGN);
-    if (vec) {
-        if (accum) igemm_kernel<WGM, WGN, TM, TN, true, DGRAD, true><<<grid, block, 0, s>>>(p);
-        else igemm_kernel<WGM, WGN, TM, TN, true, DGRAD, false><<<grid, block, 0, s>>>(p);
+    if (vec && lin) {
+        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, true, true, DGRAD, true><<<grid, block, 0, s>>>(p);
+        else igemm_kernel<WGM, WGN, TM, TN, BKT, true, true, DGRAD, false><<<grid, block, 0, s>>>(p);
+    } else if (vec) {
+        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, true, false, DGRAD, true><<<grid, block, 0, s>>>(p);
+        else igemm_kernel<WGM, WGN, TM, TN, BKT, true, false, DGRAD, false><<<grid, block, 0, s>>>(p);
     } else {
-        if (accum) igemm_kernel<WGM, WGN, TM, TN, false, DGRAD, true><<<grid, block, 0, s>>>(p);
-        else igemm_kernel<WGM, WGN, TM, TN, false, DGRAD, false><<<grid, block, 0, s>>>(p);
+        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, false, false, DGRAD, true><<<grid, block, 0, s>>>(p);
+        else igemm_kernel<WGM, WGN, TM, TN, BKT, false, false, DGRAD, false><<<grid, block, 0, s>>>(p);
     }
     return hipGetLastError();
+}
+
+// the linear fast path of the vector kernel: whole slices per tap; the data gradient also needs unit strides
+template <bool DGRAD>
+bool igemm_linear(const IGemmP &p)
+{
+    static const bool off = getenv("POOCH_NO_LINEAR") != nullptr;
+    if (off || p.Cs % BK != 0) return false;
+    return !DGRAD || (p.sd == 1 && p.sh == 1 && p.sw == 1);
 }
 
 template <bool DGRAD>
 hipError_t dispatch_igemm(const IGemmP &p, bool accum, hipStream_t s)
 {
     const bool vec = (p.Cs % 4 == 0) && ((uintptr_t)p.src % 16 == 0) && ((uintptr_t)p.wgt % 16 == 0);
-    if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, DGRAD>(p, vec, accum, s);
-    if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, DGRAD>(p, vec, accum, s);
-    return launch_igemm<2, 2, 2, 2, DGRAD>(p, vec, accum, s);
+    const bool lin = vec && igemm_linear<DGRAD>(p);
+    if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s);
+    if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, BK, DGRAD>(p, vec, lin, accum, s);
+    return launch_igemm<2, 2, 2, 2, BK, DGRAD>(p, vec, lin, accum, s);
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, int64_t n)
