@@ -104,6 +104,24 @@ def lib():
     return _lib
 
 
+_hip = None
+
+
+def _hip_rt():
+    """the HIP runtime already in the process (torch's), for pinned host allocations that are
+    returned to the system as soon as a context closes (torch caches its own pinned blocks)"""
+    global _hip
+    if _hip is None:
+        import torch  # noqa: F401
+        h = C.CDLL("libamdhip64.so.7")
+        h.hipHostMalloc.restype = C.c_int
+        h.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), _sz, C.c_uint]
+        h.hipHostFree.restype = C.c_int
+        h.hipHostFree.argtypes = [C.c_void_p]
+        _hip = h
+    return _hip
+
+
 class PoochError(RuntimeError):
     def __init__(self, status, msg):
         RuntimeError.__init__(self, "pooch status %d: %s" % (status, msg))
@@ -144,9 +162,14 @@ class Context:
             self.arena = torch.empty(self.budget_bytes, dtype=torch.uint8, device=self.device)
             assert self.arena.data_ptr() % 256 == 0
             arena_ptr = self.arena.data_ptr()
+            self._pinned_ptr = None
             if pinned_bytes > 0:
-                self.pinned = torch.empty(int(pinned_bytes), dtype=torch.uint8, pin_memory=True)
-                pinned_ptr = self.pinned.data_ptr()
+                ptr = C.c_void_p()
+                err = _hip_rt().hipHostMalloc(C.byref(ptr), int(pinned_bytes), 0)
+                if err != 0 or not ptr.value:
+                    raise MemoryError("hipHostMalloc of %d bytes of pinned host memory failed (HIP error %d)" % (pinned_bytes, err))
+                self._pinned_ptr = ptr
+                pinned_ptr = ptr.value
             self.streams = [torch.cuda.Stream(device=self.device) for _ in range(3)]
             streams = [s.cuda_stream for s in self.streams]
         h = _ctx()
@@ -170,6 +193,10 @@ class Context:
                 self.torch.cuda.synchronize()
             self.L.pooch_destroy(self.h)
             self.h = None
+            if getattr(self, "_pinned_ptr", None) is not None:
+                _hip_rt().hipHostFree(self._pinned_ptr)
+                self._pinned_ptr = None
+            self.arena = None
 
     def __del__(self):
         try:

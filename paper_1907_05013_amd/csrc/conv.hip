@@ -14,6 +14,7 @@
 namespace pk {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     }
     __syncthreads();
 
-    float4 av[VEC ? A_V : 1], bv[VEC ? B_V : 1];
+    f32x4 av[VEC ? A_V : 1], bv[VEC ? B_V : 1];
     float as[VEC ? 1 : A_S], bs[VEC ? 1 : B_S];
     int4 ri_reg[VEC ? A_V : 1];
     unsigned amask = 0, bmask = 0;                   // vector path: which prefetched float4 hold real data
@@ -151,14 +152,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             const int qw = DGRAD ? ri.w - te : ri.w + te;
             const bool ok = live & (ri.x >= 0) & ((unsigned)qd < (unsigned)p.Ds) & ((unsigned)qh < (unsigned)p.Hs) &
                             ((unsigned)qw < (unsigned)p.Ws);
-            av[i] = *reinterpret_cast<const float4 *>(ok ? p.src + (abase[i] + delta) : g_zero4);
+            av[i] = *reinterpret_cast<const f32x4 *>(ok ? p.src + (abase[i] + delta) : g_zero4);
         }
         amask = ~0u;
         bmask = ~0u;
 #pragma unroll
         for (int i = 0; i < B_V; ++i) {
             const bool ok = live & brow[i];
-            bv[i] = *reinterpret_cast<const float4 *>(ok ? bptr[i] : g_zero4);
+            bv[i] = *reinterpret_cast<const f32x4 *>(ok ? bptr[i] : g_zero4);
             bptr[i] += BKT;
         }
         tc += BKT;
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
                 const bool vw = src_coord<DGRAD>(ri.w, e, p.sw, p.Ws, qw);
                 const bool ok = kok & (ri.x >= 0) & vd & vh & vw;
                 const int64_t off = ((((int64_t)ri.x * p.Ds + qd) * p.Hs + qh) * p.Ws + qw) * p.Cs + c;
-                av[i] = *reinterpret_cast<const float4 *>(p.src + (ok ? off : 0));
+                av[i] = *reinterpret_cast<const f32x4 *>(p.src + (ok ? off : 0));
                 amask |= (ok ? 1u : 0u) << i;
             }
             bmask = 0;
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             for (int i = 0; i < B_V; ++i) {
                 const int n = n0 + vrow + i * RPP;
                 const bool ok = kok & (vrow + i * RPP < BN) & (n < p.Nout);
-                bv[i] = *reinterpret_cast<const float4 *>(p.wgt + (ok ? (int64_t)n * p.Kred + k : 0));
+                bv[i] = *reinterpret_cast<const f32x4 *>(p.wgt + (ok ? (int64_t)n * p.Kred + k : 0));
                 bmask |= (ok ? 1u : 0u) << i;
             }
         } else {
@@ -253,11 +254,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 #pragma unroll
             for (int i = 0; i < A_V; ++i)
                 if (vrow + i * RPP < BM)
-                    *reinterpret_cast<float4 *>(&As[(vrow + i * RPP) * LDT + vk]) = (LIN || ((amask >> i) & 1u)) ? av[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    *reinterpret_cast<f32x4 *>(&As[(vrow + i * RPP) * LDT + vk]) = (LIN || ((amask >> i) & 1u)) ? av[i] : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int i = 0; i < B_V; ++i)
                 if (vrow + i * RPP < BN)
-                    *reinterpret_cast<float4 *>(&Bs[(vrow + i * RPP) * LDT + vk]) = (LIN || ((bmask >> i) & 1u)) ? bv[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    *reinterpret_cast<f32x4 *>(&Bs[(vrow + i * RPP) * LDT + vk]) = (LIN || ((bmask >> i) & 1u)) ? bv[i] : f32x4{0.f, 0.f, 0.f, 0.f};
         } else {
 #pragma unroll
             for (int i = 0; i < A_S; ++i) As[(tid / BKT + i * RPS) * LDT + (tid % BKT)] = as[i];
@@ -295,16 +296,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const float *ap = &As[(wm * TM * 32 + i * 32 + r) * LDT + sub * 16 + h * 8];
-                const float4 lo = *reinterpret_cast<const float4 *>(ap);
-                const float4 hi = *reinterpret_cast<const float4 *>(ap + 4);
+                const f32x4 lo = *reinterpret_cast<const f32x4 *>(ap);
+                const f32x4 hi = *reinterpret_cast<const f32x4 *>(ap + 4);
                 af[i][0] = lo.x; af[i][1] = lo.y; af[i][2] = lo.z; af[i][3] = lo.w;
                 af[i][4] = hi.x; af[i][5] = hi.y; af[i][6] = hi.z; af[i][7] = hi.w;
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const float *bp = &Bs[(wn * TN * 32 + j * 32 + r) * LDT + sub * 16 + h * 8];
-                const float4 lo = *reinterpret_cast<const float4 *>(bp);
-                const float4 hi = *reinterpret_cast<const float4 *>(bp + 4);
+                const f32x4 lo = *reinterpret_cast<const f32x4 *>(bp);
+                const f32x4 hi = *reinterpret_cast<const f32x4 *>(bp + 4);
                 bf[j][0] = lo.x; bf[j][1] = lo.y; bf[j][2] = lo.z; bf[j][3] = lo.w;
                 bf[j][4] = hi.x; bf[j][5] = hi.y; bf[j][6] = hi.z; bf[j][7] = hi.w;
             }
@@ -437,6 +438,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
 
     __shared__ __attribute__((aligned(16))) float As[BK * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
+    // fast path (both operands vectorised): where the rows of the next SEG reduction steps start
+    // in x -- element offset of the window's first tap and that tap's coordinates -- computed once
+    // per segment so that the main loop has no divisions
+    constexpr bool TAB = VECA && VECB;
+    constexpr int SEG = 512;
+    __shared__ int4 rowc[TAB ? SEG : 1];
+    __shared__ int64_t rowb[TAB ? SEG : 1];
 
     const int tid = threadIdx.x;
     const int k0 = (blockIdx.x / p.tiles_n) * BM;  // first output channel of the tile
@@ -447,6 +455,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
 
     float4 av[VECA ? A_V : 1], bv[VECB ? B_V : 1];
     float as[VECA ? 1 : A_S], bs[VECB ? 1 : B_S];
+    f32x4 tav[A_V], tbv[B_V];   // prefetch registers of the fast path (native vectors: they must stay registers)
 
     // column of x-patches this thread gathers (fixed for the whole kernel in the VECB path)
     int vb_a = 0, vb_b = 0, vb_e = 0, vb_c = 0;
@@ -476,6 +485,56 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
         off = ((((int64_t)n * p.D + id) * p.H + ih) * p.W + iw) * p.C + c;
         return true;
     };
+
+    auto fill_rows = [&](int seg0) {
+        for (int q = tid; q < SEG; q += NT) {
+            const int m = seg0 + q;
+            int4 rc = make_int4(-1, 0, 0, 0);
+            int64_t rb = 0;
+            if (m < mend) {
+                const int ow = m % p.Wo;
+                int t = m / p.Wo;
+                const int oh = t % p.Ho;
+                t /= p.Ho;
+                const int od = t % p.Do;
+                const int n = t / p.Do;
+                rc = make_int4(n, od * p.sd - p.pd, oh * p.sh - p.ph, ow * p.sw - p.pw);
+                rb = ((((int64_t)n * p.D + rc.y) * p.H + rc.z) * p.W + rc.w) * p.C;
+            }
+            rowc[q] = rc;
+            rowb[q] = rb;
+        }
+    };
+    // per-thread constants of the fast path: its x column as an element offset from a window's
+    // first tap, its dy column, and the dy pointer of its first row (advanced by BK rows per step)
+    const int64_t tapoff = (((int64_t)vb_a * p.H + vb_b) * p.W + vb_e) * p.C + vb_c;
+    const float *acur = p.dy;                          // this thread's dy element of pass 0, current step
+    const int64_t astep = (int64_t)(NT / (BM / 4)) * p.K;  // between the rows of consecutive passes
+    bool acol_ok = false;
+    if (TAB) {
+        const int col = k0 + 4 * (tid % (BM / 4));
+        acol_ok = col < p.K;
+        acur = p.dy + (int64_t)(mbeg + tid / (BM / 4)) * p.K + (acol_ok ? col : 0);
+    }
+    // (a macro, not a lambda: the prefetch registers av / bv must stay registers)
+#define WGRAD_TAB_LOAD(MB)                                                                                                   \
+    do {                                                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < A_V; ++i)                                                                      \
+        {                                                                                                                    \
+            const int m = (MB) + (tid + i * NT) / (BM / 4);                                                                  \
+            tav[i] = *reinterpret_cast<const f32x4 *>((acol_ok & (m < mend)) ? acur + i * astep : g_zero4);                  \
+        }                                                                                                                    \
+        acur += (int64_t)BK * p.K;                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < B_V; ++i)                                                                      \
+        {                                                                                                                    \
+            const int q = ((MB) - mbeg) % SEG + (tid + i * NT) / (BN / 4);                                                   \
+            const int4 rc = rowc[q];                                                                                         \
+            const int64_t rb = rowb[q];                                                                                      \
+            const bool ok = vb_ok & (rc.x >= 0) & ((unsigned)(rc.y + vb_a) < (unsigned)p.D) &                                \
+                            ((unsigned)(rc.z + vb_b) < (unsigned)p.H) & ((unsigned)(rc.w + vb_e) < (unsigned)p.W);           \
+            tbv[i] = *reinterpret_cast<const f32x4 *>(ok ? p.x + (rb + tapoff) : g_zero4);                                   \
+        }                                                                                                                    \
+    } while (0)
 
     auto load_tiles = [&](int mb) {
         if (VECA) {
@@ -525,6 +584,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
     };
 
     auto store_tiles = [&]() {
+        if (TAB) return;   // the fast path stores inline (see the main loop)
         if (VECA) {
 #pragma unroll
             for (int i = 0; i < A_V; ++i) {
@@ -565,11 +625,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
     const int wm = wave / WGN, wn = wave % WGN;
     const int r = lane % 32, h = lane / 32;
 
-    if (mbeg < mend) load_tiles(mbeg);
+    if (TAB) {
+        fill_rows(mbeg);
+        __syncthreads();
+        WGRAD_TAB_LOAD(mbeg);
+    } else if (mbeg < mend) {
+        load_tiles(mbeg);
+    }
     for (int mb = mbeg; mb < mend; mb += BK) {
         store_tiles();
+        if (TAB) {
+#pragma unroll
+            for (int i = 0; i < A_V; ++i) {
+                const int f = tid + i * NT;
+                *reinterpret_cast<f32x4 *>(&As[(f / (BM / 4)) * LDA + 4 * (f % (BM / 4))]) = tav[i];
+            }
+#pragma unroll
+            for (int i = 0; i < B_V; ++i) {
+                const int f = tid + i * NT;
+                *reinterpret_cast<f32x4 *>(&Bs[(f / (BN / 4)) * LDB + 4 * (f % (BN / 4))]) = tbv[i];
+            }
+        }
+        // the rows of the next step open a new segment: every load of the old one has been issued
+        if (TAB && (mb + BK - mbeg) % SEG == 0) fill_rows(mb + BK);
         __syncthreads();
-        if (mb + BK < mend) load_tiles(mb + BK);
+        if (TAB) WGRAD_TAB_LOAD(mb + BK);   // past the end: every row is marked absent
+        else if (mb + BK < mend) load_tiles(mb + BK);
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             float af[TM], bf[TN];
@@ -599,6 +680,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
             }
         }
 }
+
+#undef WGRAD_TAB_LOAD
 
 // dw[e] = sum over splits, in a fixed order: lane group g adds splits g, g+4, g+8, ... and the
 // four group sums are combined as ((s0 + s1) + s2) + s3

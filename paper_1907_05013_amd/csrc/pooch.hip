@@ -23,7 +23,8 @@ namespace {
 struct ParamInfo {
     int node;
     int which;            // 0: filter / gamma / fc weight, 1: beta / fc bias
-    int64_t numel;
+    int64_t numel;        // logical element count (what the caller passes in and gets back)
+    int64_t dev_numel;    // elements on the device (larger when the input channels are padded)
     int64_t off_val;      // resident offsets (bytes from the arena base)
     int64_t off_val_t;    // transposed filter copy for the data gradient, or -1
     int64_t off_grad;
@@ -51,6 +52,10 @@ struct pooch_ctx {
     int64_t off_input = 0, off_labels = 0, off_ws_wgrad = 0, off_ws_bn = 0, off_loss_ps = 0, off_loss = 0;
     int64_t resident_bytes = 0;
     int nclasses = 0;
+    // device channel count of the network input: a 3-channel input read only by convolutions is
+    // stored with a zero fourth channel (and those filters with a zero fourth input channel), so
+    // that its rows are 16-byte vectors like every other tensor's
+    int in_cdev = 0;
 
     Profile prof;
     bool has_plan = false;
@@ -84,12 +89,12 @@ pooch_status fail(pooch_ctx *c, pooch_status s, const std::string &msg)
         if (e_ != hipSuccess) return fail(c, POOCH_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
     } while (0)
 
-pk::ConvGeom conv_geom(const Graph &G, int i)
+pk::ConvGeom conv_geom(const Graph &G, int i, int in_cdev)
 {
     const Node &nd = G.nodes[i];
     const Node &x = G.nodes[nd.in[0]];
     pk::ConvGeom g;
-    g.N = (int)x.N; g.C = (int)x.C; g.D = (int)x.sp[0]; g.H = (int)x.sp[1]; g.W = (int)x.sp[2];
+    g.N = (int)x.N; g.C = nd.in[0] == 0 ? in_cdev : (int)x.C; g.D = (int)x.sp[0]; g.H = (int)x.sp[1]; g.W = (int)x.sp[2];
     g.K = (int)nd.C;
     g.Do = (int)nd.sp[0]; g.Ho = (int)nd.sp[1]; g.Wo = (int)nd.sp[2];
     if (nd.op == OP_FC) {
@@ -116,33 +121,33 @@ pk::PoolGeom pool_geom(const Graph &G, int i)
     return g;
 }
 
-// logical K,C,taps  <->  device K,taps,C and C,taps,K
-void filter_to_device_layouts(const float *kcr, int64_t K, int64_t C, int64_t T, float *krc, float *crk)
+// logical K,C,taps  <->  device K,taps,Cd and Cd,taps,K (Cd >= C; device buffers pre-zeroed by the caller)
+void filter_to_device_layouts(const float *kcr, int64_t K, int64_t C, int64_t Cd, int64_t T, float *krc, float *crk)
 {
     for (int64_t k = 0; k < K; ++k)
         for (int64_t c = 0; c < C; ++c)
             for (int64_t t = 0; t < T; ++t) {
                 const float v = kcr[(k * C + c) * T + t];
-                krc[(k * T + t) * C + c] = v;
+                krc[(k * T + t) * Cd + c] = v;
                 crk[(c * T + t) * K + k] = v;
             }
 }
 
-void filter_from_device_layout(const float *krc, int64_t K, int64_t C, int64_t T, float *kcr)
+void filter_from_device_layout(const float *krc, int64_t K, int64_t C, int64_t Cd, int64_t T, float *kcr)
 {
     for (int64_t k = 0; k < K; ++k)
         for (int64_t c = 0; c < C; ++c)
-            for (int64_t t = 0; t < T; ++t) kcr[(k * C + c) * T + t] = krc[(k * T + t) * C + c];
+            for (int64_t t = 0; t < T; ++t) kcr[(k * C + c) * T + t] = krc[(k * T + t) * Cd + c];
 }
 
-// logical N,C,S <-> device N,S,C
-void act_to_device_layout(const float *ncs, int64_t N, int64_t C, int64_t S, float *nsc)
+// logical N,C,S <-> device N,S,Cd (Cd >= C; device buffer pre-zeroed by the caller)
+void act_to_device_layout(const float *ncs, int64_t N, int64_t C, int64_t Cd, int64_t S, float *nsc)
 {
     for (int64_t n = 0; n < N; ++n)
         for (int64_t c = 0; c < C; ++c) {
             const float *src = ncs + (n * C + c) * S;
-            float *dst = nsc + n * S * C + c;
-            for (int64_t s = 0; s < S; ++s) dst[s * C] = src[s];
+            float *dst = nsc + n * S * Cd + c;
+            for (int64_t s = 0; s < S; ++s) dst[s * Cd] = src[s];
         }
 }
 
@@ -177,7 +182,7 @@ struct Exec {
         const Node &nd = G.nodes[i];
         hipStream_t s = c->st[S_COMPUTE];
         switch (nd.op) {
-        case OP_CONV: return pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i), s);
+        case OP_CONV: return pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i, c->in_cdev), s);
         case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
             const bool relu = nd.op == OP_BNRELU;
@@ -196,7 +201,7 @@ struct Exec {
             return pk::gavgpool_fwd(D(in0), D(out), (int)x.N, x.sp[0] * x.sp[1] * x.sp[2], (int)x.C, s);
         }
         case OP_FC: {
-            hipError_t e = pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i), s);
+            hipError_t e = pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i, c->in_cdev), s);
             if (e != hipSuccess) return e;
             return pk::bias_add(D(out), R(P(i, 1).off_val), (int)nd.N, (int)nd.C, s);
         }
@@ -227,7 +232,7 @@ struct Exec {
         const int m0 = (int)a[3], m1 = (int)a[5];
         switch (nd.op) {
         case OP_CONV: case OP_FC: {
-            const pk::ConvGeom g = conv_geom(G, i);
+            const pk::ConvGeom g = conv_geom(G, i, c->in_cdev);
             hipError_t e = pk::conv_wgrad(D(dy), D(need), R(P(i, 0).off_grad), R(c->off_ws_wgrad), g, s);
             if (e != hipSuccess) return e;
             if (nd.op == OP_FC) {
@@ -664,7 +669,13 @@ pooch_status pooch_finalize(pooch_ctx *c)
     const int n = G.n();
     int64_t off = 0;
     auto take = [&](int64_t bytes) { const int64_t o = off; off += round_up(bytes); return o; };
-    c->off_input = take(G.nodes[0].numel() * 4);
+    c->in_cdev = (int)G.nodes[0].C;
+    if (G.nodes[0].C == 3) {
+        bool only_convs = true;
+        for (int u : G.consumers[0]) only_convs = only_convs && G.nodes[u].op == OP_CONV;
+        if (only_convs) c->in_cdev = 4;
+    }
+    c->off_input = take(G.nodes[0].numel() / G.nodes[0].C * c->in_cdev * 4);
     c->off_labels = take(G.nodes[0].N * 4);
     c->off_mean.assign(n, -1);
     c->off_istd.assign(n, -1);
@@ -673,24 +684,25 @@ pooch_status pooch_finalize(pooch_ctx *c)
     for (int i = 0; i < n; ++i) {
         Node &nd = G.nodes[i];
         if (nd.op == OP_CONV || nd.op == OP_FC) {
-            const pk::ConvGeom g = conv_geom(G, i);
+            const pk::ConvGeom g = conv_geom(G, i, c->in_cdev);
             // the conv kernels index rows and reduction lengths with 32 bits
             const int64_t lim = ((int64_t)1 << 31) - 4096;
             if (g.rows_in() >= lim || g.rows_out() >= lim || g.taps() * std::max(g.C, g.K) >= lim)
                 return fail(c, POOCH_E_INVALID, "conv/fc: tensor too large for the kernels' 32-bit row index");
-            const int64_t numel = (int64_t)g.K * g.C * g.taps();
-            ParamInfo p{i, 0, numel, take(numel * 4), take(numel * 4), take(numel * 4)};
+            const int64_t dev_numel = (int64_t)g.K * g.C * g.taps();
+            const int64_t numel = (int64_t)g.K * G.nodes[nd.in[0]].C * g.taps();
+            ParamInfo p{i, 0, numel, dev_numel, take(dev_numel * 4), take(dev_numel * 4), take(dev_numel * 4)};
             nd.param[0] = (int)c->params.size();
             c->params.push_back(p);
             ws_wgrad = std::max(ws_wgrad, pk::conv_wgrad_workspace(g));
             if (nd.op == OP_FC) {
-                ParamInfo b{i, 1, nd.C, take(nd.C * 4), -1, take(nd.C * 4)};
+                ParamInfo b{i, 1, nd.C, nd.C, take(nd.C * 4), -1, take(nd.C * 4)};
                 nd.param[1] = (int)c->params.size();
                 c->params.push_back(b);
             }
         } else if (nd.op == OP_BN || (nd.op == OP_DEAD && G.nodes[G.fused_into[i]].op == OP_BNRELU)) {
             for (int w = 0; w < 2; ++w) {
-                ParamInfo p{i, w, nd.C, take(nd.C * 4), -1, take(nd.C * 4)};
+                ParamInfo p{i, w, nd.C, nd.C, take(nd.C * 4), -1, take(nd.C * 4)};
                 nd.param[w] = (int)c->params.size();
                 c->params.push_back(p);
             }
@@ -752,11 +764,12 @@ pooch_status pooch_set_param(pooch_ctx *c, int32_t i, const float *host)
         HIPCHK(hipMemcpy(c->arena + p.off_val, host, (size_t)p.numel * 4, hipMemcpyHostToDevice));
         return POOCH_OK;
     }
-    const pk::ConvGeom g = conv_geom(c->G, p.node);
-    std::vector<float> krc((size_t)p.numel), crk((size_t)p.numel);
-    filter_to_device_layouts(host, g.K, g.C, g.taps(), krc.data(), crk.data());
-    HIPCHK(hipMemcpy(c->arena + p.off_val, krc.data(), (size_t)p.numel * 4, hipMemcpyHostToDevice));
-    HIPCHK(hipMemcpy(c->arena + p.off_val_t, crk.data(), (size_t)p.numel * 4, hipMemcpyHostToDevice));
+    const pk::ConvGeom g = conv_geom(c->G, p.node, c->in_cdev);
+    std::vector<float> krc((size_t)p.dev_numel, 0.f), crk((size_t)p.dev_numel, 0.f);
+    const int64_t Clog = p.numel / ((int64_t)g.K * g.taps());
+    filter_to_device_layouts(host, g.K, Clog, g.C, g.taps(), krc.data(), crk.data());
+    HIPCHK(hipMemcpy(c->arena + p.off_val, krc.data(), (size_t)p.dev_numel * 4, hipMemcpyHostToDevice));
+    HIPCHK(hipMemcpy(c->arena + p.off_val_t, crk.data(), (size_t)p.dev_numel * 4, hipMemcpyHostToDevice));
     return POOCH_OK;
 }
 
@@ -770,10 +783,10 @@ pooch_status pooch_get_grad(pooch_ctx *c, int32_t i, float *host)
         HIPCHK(hipMemcpy(host, c->arena + p.off_grad, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
         return POOCH_OK;
     }
-    const pk::ConvGeom g = conv_geom(c->G, p.node);
-    std::vector<float> krc((size_t)p.numel);
-    HIPCHK(hipMemcpy(krc.data(), c->arena + p.off_grad, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
-    filter_from_device_layout(krc.data(), g.K, g.C, g.taps(), host);
+    const pk::ConvGeom g = conv_geom(c->G, p.node, c->in_cdev);
+    std::vector<float> krc((size_t)p.dev_numel);
+    HIPCHK(hipMemcpy(krc.data(), c->arena + p.off_grad, (size_t)p.dev_numel * 4, hipMemcpyDeviceToHost));
+    filter_from_device_layout(krc.data(), g.K, p.numel / ((int64_t)g.K * g.taps()), g.C, g.taps(), host);
     return POOCH_OK;
 }
 
@@ -785,8 +798,8 @@ pooch_status pooch_set_batch(pooch_ctx *c, const float *x_host, const int32_t *l
     const Node &in = c->G.nodes[0];
     for (int64_t n = 0; n < in.N; ++n)
         if (labels_host[n] < 0 || labels_host[n] >= c->nclasses) return fail(c, POOCH_E_INVALID, "set_batch: label out of range");
-    std::vector<float> tmp((size_t)in.numel());
-    act_to_device_layout(x_host, in.N, in.C, in.sp[0] * in.sp[1] * in.sp[2], tmp.data());
+    std::vector<float> tmp((size_t)(in.numel() / in.C * c->in_cdev), 0.f);
+    act_to_device_layout(x_host, in.N, in.C, c->in_cdev, in.sp[0] * in.sp[1] * in.sp[2], tmp.data());
     HIPCHK(hipMemcpy(c->arena + c->off_input, tmp.data(), tmp.size() * 4, hipMemcpyHostToDevice));
     HIPCHK(hipMemcpy(c->arena + c->off_labels, labels_host, (size_t)in.N * 4, hipMemcpyHostToDevice));
     return POOCH_OK;
@@ -1089,7 +1102,7 @@ const char *pooch_node_kernel(pooch_ctx *c, int32_t node, int part)
     if (!c || !c->finalized || node < 0 || node >= c->G.n() || part < 0 || part > 2) return "";
     const Op op = c->G.nodes[node].op;
     if (op != OP_CONV && op != OP_FC) return "";
-    const pk::ConvGeom g = conv_geom(c->G, node);
+    const pk::ConvGeom g = conv_geom(c->G, node, c->in_cdev);
     return part == 0 ? pk::conv_fwd_kernel(g) : (part == 1 ? pk::conv_dgrad_kernel(g) : pk::conv_wgrad_kernel(g));
 }
 
