@@ -183,6 +183,7 @@ def main():
     ap.add_argument("--mode", default="refine", choices=["swapall_nosched", "swapall", "swapopt", "pooch", "refine"],
                     help="planner whose step is reported as `value`; refine = the paper's two steps + local search")
     ap.add_argument("--bits", type=int, default=4, help="cap on the exponential part of the keep/swap search")
+    ap.add_argument("--restarts", type=int, default=48, help="perturbed restarts of the refine mode's local search")
     ap.add_argument("--no-paper-mode", action="store_true", help="skip the extra leg that times the paper's own two-step plan")
     ap.add_argument("--no-incore", action="store_true")
     ap.add_argument("--dump-profile", default=None, help="write the measured profile (ms per layer / map) to this .npz file")
@@ -241,7 +242,7 @@ def main():
             log("[bench] paper's two-step plan: %.1f ms/step (predicted %.1f), keep/swap/recompute %d/%d/%d" %
                 (sec_p * 1e3, pred_p, stp.n_keep, stp.n_swap, stp.n_recompute))
         t1b = time.perf_counter()
-        cls, predicted = ctx.plan(args.mode, args.bits)
+        cls, predicted = ctx.plan(args.mode, args.bits, restarts=args.restarts)
         t2 = time.perf_counter()
         st = ctx.stats()
         log("[bench] profile %.1f s, plan %.1f s (%d simulations): keep/swap/recompute %d/%d/%d, predicted %.1f ms" %

@@ -59,8 +59,8 @@ enum {
     POOCH_MODE_SWAPALL = 2,         /* all swap; swap-ins moved up as far as memory allows (section 4.3) */
     POOCH_MODE_SWAPOPT = 3,         /* keep/swap search only (section 4.4.2) */
     POOCH_MODE_POOCH = 4,           /* keep/swap search, then swap/recompute classification (section 4.4.3) */
-    POOCH_MODE_REFINE = 5           /* not in the paper: POOCH followed by a local search over single class changes,
-                                       judged by the same timeline simulation */
+    POOCH_MODE_REFINE = 5           /* not in the paper: POOCH followed by an iterated local search over single class
+                                       changes, judged by the same timeline simulation */
 };
 
 /* ---- context ------------------------------------------------------------------------
@@ -152,6 +152,9 @@ pooch_status pooch_set_profile(pooch_ctx *, const double *t_fwd, const double *t
  * pooch_set_plan installs an explicit classification (num_fmaps bytes, POOCH_KEEP/SWAP/
  * RECOMPUTE) after validating it the same way; `sched` != 0 enables moved-up swap-ins. */
 pooch_status pooch_plan(pooch_ctx *, int mode, int max_bruteforce_bits, double *predicted_ms);
+/* number of perturbed restarts of POOCH_MODE_REFINE's local search (default 8; deterministic: the
+ * perturbations come from a fixed-seed generator) */
+pooch_status pooch_set_search_effort(pooch_ctx *, int restarts);
 pooch_status pooch_get_plan(pooch_ctx *, uint8_t *cls);
 pooch_status pooch_set_plan(pooch_ctx *, const uint8_t *cls, int sched);
 /* simulate without installing: step time (ms) and peak bytes of the dynamic region for an

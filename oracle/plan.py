@@ -14,8 +14,8 @@ TEST INFRASTRUCTURE ONLY (slow, obvious, no sharing with the HIP library).  It c
   * the two-step heuristic search (section 4.4): L_O / L_I extraction on the all-swap
     timeline, binary tree over L_I with a greedy scan of L_O \\ L_I from the output layer,
     then r(X) = recompute_overhead / swap_overhead (equation 1) for the maps left in swap,
-  * mode "refine" (not in the paper): the two steps followed by a local search over single
-    class changes, judged by the same simulation.
+  * mode "refine" (not in the paper): the two steps followed by an iterated local search over
+    single class changes, judged by the same simulation.
 
 Where the paper is silent the readings are those listed in DESIGN.md ("Readings").
 """
@@ -594,9 +594,20 @@ def simulate(G, S, P):
 
 # ------------------------------------------------------------------ classification search
 
+def _splitmix64(state):
+    """one step of the splitmix64 generator: (new state, 64-bit output)"""
+    m = (1 << 64) - 1
+    state = (state + 0x9E3779B97F4A7C15) & m
+    z = state
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & m
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & m
+    return state, z ^ (z >> 31)
+
+
 class Planner:
-    def __init__(self, G, P, cap, pinned_cap=None, max_bits=10):
+    def __init__(self, G, P, cap, pinned_cap=None, max_bits=10, restarts=8):
         self.G, self.P, self.cap, self.pinned_cap, self.max_bits = G, P, cap, pinned_cap, max_bits
+        self.restarts = restarts
         self.evals = 0
         self.LO, self.LI = set(), set()
 
@@ -709,11 +720,10 @@ class Planner:
             T0 = self.evaluate(cls)
         return cls, T0
 
-    def refine(self, cls, T0):
-        """Not in the paper: a local search on top of its two steps, with the same simulator
-        and the same three classes.  Each round evaluates every single-map change of class
-        and applies the one with the smallest simulated step time (first in (map, class)
-        order on ties) if it is strictly faster; stops when no change helps."""
+    def _descend(self, cls, T0):
+        """each round evaluates every single-map change of class and applies the one with the
+        smallest simulated step time (first in (map, class) order on ties) if it is strictly
+        faster; stops when no change helps"""
         cls = list(cls)
         while True:
             best = None
@@ -732,3 +742,25 @@ class Planner:
                 return cls, T0
             T0, k, v = best
             cls[k] = v
+
+    def refine(self, cls, T0):
+        """Not in the paper: an iterated local search on top of its two steps, with the same
+        simulator and the same three classes.  Descend from the two-step plan; then `restarts`
+        times: give 6 maps drawn by splitmix64 (seed 1907050130) a drawn class each, descend
+        again if that plan fits, and keep the result if it is strictly faster than the best."""
+        best, best_T = self._descend(cls, T0)
+        state = 1907050130
+        nf = len(best)
+        for _ in range(self.restarts):
+            trial = list(best)
+            for _ in range(6):
+                state, a = _splitmix64(state)
+                state, b = _splitmix64(state)
+                trial[a % nf] = b % 3
+            T = self.evaluate(trial)
+            if T is None:
+                continue
+            trial, T = self._descend(trial, T)
+            if T < best_T:
+                best, best_T = trial, T
+        return best, best_T

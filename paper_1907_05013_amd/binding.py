@@ -69,6 +69,7 @@ SYMBOLS = {
     "pooch_get_profile": (_i32, [_ctx, _pd, _pd, _pd, _pd, _pd]),
     "pooch_set_profile": (_i32, [_ctx, _pd, _pd, _pd, _pd, _pd]),
     "pooch_plan": (_i32, [_ctx, C.c_int, C.c_int, _pd]),
+    "pooch_set_search_effort": (_i32, [_ctx, C.c_int]),
     "pooch_get_plan": (_i32, [_ctx, _pu8]),
     "pooch_set_plan": (_i32, [_ctx, _pu8, C.c_int]),
     "pooch_simulate": (_i32, [_ctx, _pu8, C.c_int, _pd, C.POINTER(_sz)]),
@@ -309,7 +310,9 @@ class Context:
         assert [len(v) for v in a] == [self.n_nodes] * 3 + [self.n_fmaps] * 2
         self._chk(self.L.pooch_set_profile(self.h, *[_dptr(v) for v in a]))
 
-    def plan(self, mode, max_bits=0):
+    def plan(self, mode, max_bits=0, restarts=None):
+        if restarts is not None:
+            self._chk(self.L.pooch_set_search_effort(self.h, restarts))
         t = _dbl()
         self._chk(self.L.pooch_plan(self.h, MODES[mode] if isinstance(mode, str) else mode, max_bits, C.byref(t)))
         return self.get_plan(), t.value

@@ -92,6 +92,7 @@ struct Planner {
     const Profile &P;
     int64_t cap, pinned_cap;
     int max_bits;
+    int restarts = 8;  // perturbed restarts of the local search in refine()
     int64_t evals = 0;
     std::vector<int> LO, LI;
     Planner(const Graph &g, const Profile &p, int64_t cap_, int64_t pinned_cap_, int max_bits_)
@@ -102,6 +103,7 @@ struct Planner {
     bool plan(int mode, std::vector<uint8_t> &cls, double &T, bool &ahead);
     void step1(const std::vector<uint8_t> &allswap, double T_all, std::vector<uint8_t> &best, double &best_T);
     void step2(std::vector<uint8_t> &cls, double &T0);
+    void descend(std::vector<uint8_t> &cls, double &T0);
     void refine(std::vector<uint8_t> &cls, double &T0);
 };
 

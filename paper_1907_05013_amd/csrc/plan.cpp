@@ -755,9 +755,8 @@ void Planner::step2(std::vector<uint8_t> &cls, double &T0)
     }
 }
 
-// Not in the paper: local search over single class changes on top of the two steps, judged by
-// the same simulation; best strictly-improving change per round, first in (map, class) order.
-void Planner::refine(std::vector<uint8_t> &cls, double &T0)
+// best strictly-improving single class change per round, first in (map, class) order; until none helps
+void Planner::descend(std::vector<uint8_t> &cls, double &T0)
 {
     for (;;) {
         double best_T = T0;
@@ -778,6 +777,42 @@ void Planner::refine(std::vector<uint8_t> &cls, double &T0)
         if (best_k < 0) return;
         T0 = best_T;
         cls[best_k] = (uint8_t)best_v;
+    }
+}
+
+namespace {
+uint64_t splitmix64(uint64_t &state)
+{
+    state += 0x9E3779B97F4A7C15ull;
+    uint64_t z = state;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+}  // namespace
+
+// Not in the paper: iterated local search on top of the two steps, judged by the same simulation.
+// Descend from the two-step plan; then `restarts` times give 6 drawn maps a drawn class each
+// (splitmix64, fixed seed), descend again if that plan fits, keep it if strictly faster.
+void Planner::refine(std::vector<uint8_t> &cls, double &T0)
+{
+    descend(cls, T0);
+    uint64_t state = 1907050130ull;
+    const uint64_t nf = cls.size();
+    for (int r = 0; r < restarts; ++r) {
+        std::vector<uint8_t> trial = cls;
+        for (int j = 0; j < 6; ++j) {
+            const uint64_t a = splitmix64(state);
+            const uint64_t b = splitmix64(state);
+            trial[a % nf] = (uint8_t)(b % 3);
+        }
+        double T = evaluate(trial);
+        if (T < 0.0) continue;
+        descend(trial, T);
+        if (T < T0) {
+            cls = trial;
+            T0 = T;
+        }
     }
 }
 

@@ -64,6 +64,7 @@ struct pooch_ctx {
     Schedule sched;
     double predicted_ms = 0.0;
     int64_t evals = 0;
+    int restarts = 8;
     double last_step_ms = 0.0;
 
     std::vector<hipEvent_t> sync_events;    // no timing
@@ -941,6 +942,7 @@ pooch_status pooch_plan(pooch_ctx *c, int mode, int max_bruteforce_bits, double 
     if (bits > 20) bits = 20;
     const int64_t cap = (int64_t)c->arena_bytes - c->resident_bytes;
     Planner pl(c->G, P, cap, c->arena ? (int64_t)c->pinned_bytes : -1, bits);
+    pl.restarts = c->restarts;
     std::vector<uint8_t> cls;
     double T = 0.0;
     bool ahead = true;
@@ -950,6 +952,14 @@ pooch_status pooch_plan(pooch_ctx *c, int mode, int max_bruteforce_bits, double 
     const pooch_status ps = install(c, cls, ahead, T);
     if (ps != POOCH_OK) return ps;
     if (predicted_ms) *predicted_ms = T;
+    return POOCH_OK;
+}
+
+pooch_status pooch_set_search_effort(pooch_ctx *c, int restarts)
+{
+    if (!c) return POOCH_E_INVALID;
+    if (restarts < 0 || restarts > 100000) return fail(c, POOCH_E_INVALID, "search effort out of range");
+    c->restarts = restarts;
     return POOCH_OK;
 }
 

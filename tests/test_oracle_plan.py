@@ -262,7 +262,7 @@ def test_modes_monotone_and_feasible_vs_brute_force(seed):
     prof = random_profile(G, rng, link=rng.choice([0.3, 1.0, 3.0]))
     incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
     cap = int(incore.peak * rng.uniform(0.5, 0.9)) // 256 * 256
-    pl = P.Planner(G, prof, cap)
+    pl = P.Planner(G, prof, cap, restarts=4)
     try:
         T_ns = pl.plan("swapall_nosched")[1]
     except P.Budget:

@@ -104,14 +104,14 @@ def test_every_mode_picks_the_oracles_plan(seed):
     c.set_profile(*prof)
     bits = 5
     for mode in ("swapall_nosched", "swapall", "swapopt", "pooch", "refine"):
-        pl = P.Planner(G, oprof, cap, max_bits=bits)
+        pl = P.Planner(G, oprof, cap, max_bits=bits, restarts=3)
         try:
             ocls, oT = pl.plan(mode)
         except P.Budget:
             with pytest.raises(B.BudgetError):
-                c.plan(mode, bits)
+                c.plan(mode, bits, restarts=3)
             continue
-        cls, T = c.plan(mode, bits)
+        cls, T = c.plan(mode, bits, restarts=3)
         assert list(cls) == list(ocls)
         assert T == oT
         assert c.plan_evaluations() == pl.evals
