@@ -30,6 +30,16 @@ PEAK_MFMA_FP32 = 157.3e12   # MI355X dense fp32 matrix FLOP/s
 PEAK_HBM = 8.0e12           # bytes/s
 PAPER_B640_IMG_S = 195.0    # paper, ResNet50 batch 640 on V100 16 GB + PCIe3 (316 img/s in-core, 38 % degradation)
 
+# HBM traffic per launch of a kernel, measured offline with two `rocprofv3 --pmc` runs of this
+# script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, averaged over the kernel's launches) and
+# scaled by what the same counters read for a plain 1 GiB copy (csrc/hbm_copy_probe.hip):
+# FETCH_SIZE reads 0.5 GiB there, WRITE_SIZE 1.0 GiB, so fetch x 2.0, write x 1.0.
+# Source: profiles/resnet50_b640_16g_hbm_traffic.txt.  (workload, kernel) -> (fetch KiB, write KiB)
+MEASURED_TRAFFIC_KIB = {
+    ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+lin,fwd>"): (339396.0, 485375.0),
+}
+TRAFFIC_SCALE = (2.0, 1.0)
+
 WORKLOADS = {
     # name: (config loader name, overrides, default budget in GiB or fraction of in-core peak)
     "resnet50_b640_16g": ("resnet50_b640", {}, 16.0),
@@ -99,28 +109,35 @@ def kernel_report(ctx, net, ms, nrefwd_counts=None):
     n_el = elem_counts(net)
     by_kernel = {}
 
-    def add(name, flops, t, launches=1):
+    def add(name, flops, t, launches=1, nbytes=0.0):
         if t <= 0:
             return
-        k = by_kernel.setdefault(name, [0.0, 0.0, 0])
+        k = by_kernel.setdefault(name, [0.0, 0.0, 0, 0.0])
         k[0] += flops
         k[1] += t
         k[2] += launches
+        k[3] += nbytes * launches
+
+    shp = workloads.shapes(net)
 
     conv_flops = conv_ms = 0.0
     for i, (M, N, K) in geo.items():
         fl = 2.0 * M * N * K
+        # algorithmic bytes: both operands read once, the result written once
+        b_in, b_out, b_w = 4.0 * n_el[net[i]["x"]], 4.0 * n_el[i], 4.0 * N * K
+        nbytes = b_in + b_out + b_w
         parts = [(0, fwd[i], 1), (1, bwd[i] - bwf[i], 1), (2, bwf[i], 1)]
         for part, t, _ in parts:
             if part == 1 and net[i].get("x") == 0:
                 continue            # the first layer has no data gradient
-            add(ctx.node_kernel(i, part), fl, t)
+            add(ctx.node_kernel(i, part), fl, t, 1, nbytes)
             if net[i]["op"] == "conv":
                 conv_flops += fl
                 conv_ms += t
         if refwd[i] > 0:
             n = max(1, int(round(refwd[i] / max(fwd[i], 1e-9))))
-            add(ctx.node_kernel(i, 0), fl * n, refwd[i], n)
+            add(ctx.node_kernel(i, 0), fl, refwd[i], n, nbytes)
+            by_kernel[ctx.node_kernel(i, 0)][0] += fl * (n - 1)
             conv_flops += fl * n
             conv_ms += refwd[i]
     # algorithmic bytes per element: BN (alone or with a fused ReLU) forward 12 (x for the statistics,
@@ -278,6 +295,8 @@ def main():
     by_kernel, (cfl, cms), (bnb, bnms), (ewb, ewms) = rep
     dom = max(by_kernel.items(), key=lambda kv: kv[1][1])
     dom_tflops = dom[1][0] / (dom[1][1] * 1e-3)
+    meas = MEASURED_TRAFFIC_KIB.get((args.workload, dom[0]))
+    traffic = (meas[0] * TRAFFIC_SCALE[0] + meas[1] * TRAFFIC_SCALE[1]) * 1024.0 if meas else None
     out = {
         "metric": "images/sec per train step under budget",
         "value": batch / sec,
@@ -296,7 +315,10 @@ def main():
                    "under_budget": under_budget},
         "loss": loss,
         "roofline": {"bound": "mfma", "kernel": dom[0], "achieved": dom_tflops / 1e12, "peak": PEAK_MFMA_FP32 / 1e12,
-                     "unit": "TFLOP/s", "frac": dom_tflops / PEAK_MFMA_FP32, "traffic": None,
+                     "unit": "TFLOP/s", "frac": dom_tflops / PEAK_MFMA_FP32, "traffic": traffic,
+                     "traffic_unit": "HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated)",
+                     "algorithmic_bytes_per_launch": dom[1][3] / max(dom[1][2], 1),
+                     "algorithmic_flops_per_launch": dom[1][0] / max(dom[1][2], 1),
                      "launches_per_step": dom[1][2], "avg_launch_ms": dom[1][1] / max(dom[1][2], 1)},
         "conv_mfma_util": (cfl / (cms * 1e-3)) / PEAK_MFMA_FP32 if cms > 0 else None,
         "conv_TFLOPs": cfl / (cms * 1e-3) / 1e12 if cms > 0 else None,

@@ -5,6 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpooch.so")
+PROBE = os.path.join(HERE, "hbm_copy_probe.bin")
 SOURCES = ["pooch.hip", "plan.cpp", "conv.hip", "bn_elt.hip", "pool_loss.hip"]
 # packed fp32 instructions are switched off on purpose (the compiler would otherwise form
 # v_pk_*_f32 from ordinary float code)
@@ -32,6 +33,8 @@ def build(verbose=False):
     subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB])
     for o in objs:
         os.remove(o)
+    # counter-calibration aid (a plain copy kernel of known size), see csrc/hbm_copy_probe.hip
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", os.path.join(CSRC, "hbm_copy_probe.hip"), "-o", PROBE])
     return LIB
 
 

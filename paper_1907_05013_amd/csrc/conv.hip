@@ -789,25 +789,33 @@ hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const Con
     return dispatch_igemm<true>(p, accumulate, s);
 }
 
-const char *conv_fwd_kernel(const ConvGeom &g)
+namespace {
+// tag of the igemm instantiation dispatch_igemm() picks: tile shape, load path, direction
+const char *igemm_tag(int nout, int cs, bool unit_stride, bool dgrad)
 {
-    const bool vec = g.C % 4 == 0;
-    if (g.K <= 32) return vec ? "igemm_kernel<4,1,2,1,vec,fwd>" : "igemm_kernel<4,1,2,1,scalar,fwd>";
-    if (g.K <= 64) return vec ? "igemm_kernel<4,1,2,2,vec,fwd>" : "igemm_kernel<4,1,2,2,scalar,fwd>";
-    return vec ? "igemm_kernel<2,2,2,2,vec,fwd>" : "igemm_kernel<2,2,2,2,scalar,fwd>";
+    static const char *names[3][3][2] = {
+        {{"igemm_kernel<4,1,2,1,scalar,fwd>", "igemm_kernel<4,1,2,1,scalar,dgrad>"},
+         {"igemm_kernel<4,1,2,1,vec,fwd>", "igemm_kernel<4,1,2,1,vec,dgrad>"},
+         {"igemm_kernel<4,1,2,1,vec+lin,fwd>", "igemm_kernel<4,1,2,1,vec+lin,dgrad>"}},
+        {{"igemm_kernel<4,1,2,2,scalar,fwd>", "igemm_kernel<4,1,2,2,scalar,dgrad>"},
+         {"igemm_kernel<4,1,2,2,vec,fwd>", "igemm_kernel<4,1,2,2,vec,dgrad>"},
+         {"igemm_kernel<4,1,2,2,vec+lin,fwd>", "igemm_kernel<4,1,2,2,vec+lin,dgrad>"}},
+        {{"igemm_kernel<2,2,2,2,scalar,fwd>", "igemm_kernel<2,2,2,2,scalar,dgrad>"},
+         {"igemm_kernel<2,2,2,2,vec,fwd>", "igemm_kernel<2,2,2,2,vec,dgrad>"},
+         {"igemm_kernel<2,2,2,2,vec+lin,fwd>", "igemm_kernel<2,2,2,2,vec+lin,dgrad>"}}};
+    const int tile = nout <= 32 ? 0 : (nout <= 64 ? 1 : 2);
+    const bool vec = cs % 4 == 0;
+    const bool lin = vec && cs % BK == 0 && (!dgrad || unit_stride) && getenv("POOCH_NO_LINEAR") == nullptr;
+    return names[tile][lin ? 2 : (vec ? 1 : 0)][dgrad ? 1 : 0];
 }
+}  // namespace
+
+const char *conv_fwd_kernel(const ConvGeom &g) { return igemm_tag(g.K, g.C, true, false); }
 
 const char *conv_dgrad_kernel(const ConvGeom &g)
 {
-    const bool vec = g.K % 4 == 0;
-    if (pointwise_strided(g)) {
-        if (g.C <= 32) return vec ? "igemm_kernel<4,1,2,1,vec,fwd>" : "igemm_kernel<4,1,2,1,scalar,fwd>";
-        if (g.C <= 64) return vec ? "igemm_kernel<4,1,2,2,vec,fwd>" : "igemm_kernel<4,1,2,2,scalar,fwd>";
-        return vec ? "igemm_kernel<2,2,2,2,vec,fwd>" : "igemm_kernel<2,2,2,2,scalar,fwd>";
-    }
-    if (g.C <= 32) return vec ? "igemm_kernel<4,1,2,1,vec,dgrad>" : "igemm_kernel<4,1,2,1,scalar,dgrad>";
-    if (g.C <= 64) return vec ? "igemm_kernel<4,1,2,2,vec,dgrad>" : "igemm_kernel<4,1,2,2,scalar,dgrad>";
-    return vec ? "igemm_kernel<2,2,2,2,vec,dgrad>" : "igemm_kernel<2,2,2,2,scalar,dgrad>";
+    if (pointwise_strided(g)) return igemm_tag(g.C, g.K, true, false);   // scatter GEMM over the output rows
+    return igemm_tag(g.C, g.K, g.sd == 1 && g.sh == 1 && g.sw == 1, true);
 }
 
 const char *conv_wgrad_kernel(const ConvGeom &g)
