@@ -315,28 +315,46 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bf[j][t], af[i][t], acc[i][j], 0, 0, 0);
         }
         __syncthreads();
     }
 
-    // accumulator element v of a lane is row 8*(v/4) + 4*h + v%4, column r of the 32x32 tile
+    // The MFMA is issued with the operands swapped (B, A), so each 32x32 block comes out transposed:
+    // accumulator element v of a lane belongs to GEMM row r and GEMM column 8*(v/4) + 4*h + v%4.
+    // A lane therefore owns runs of four consecutive output channels: 16-byte stores (and loads, when
+    // accumulating) instead of four scalar ones.
+    const bool vec_out = p.Nout % 4 == 0;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+        const int m = rowdst[wm * TM * 32 + i * 32 + r];
+        if (m < 0) continue;
+        float *drow = p.dst + (int64_t)m * p.Nout;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * TN * 32 + j * 32 + r;
+            const int cbase = n0 + wn * TN * 32 + j * 32 + 4 * h;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = rowdst[wm * TM * 32 + i * 32 + (v / 4) * 8 + h * 4 + (v % 4)];
-                if (m >= 0 && col < p.Nout) {
-                    const int64_t idx = (int64_t)m * p.Nout + col;
-                    float val = acc[i][j][v];
-                    if (ACCUM) val = p.dst[idx] + val;
-                    p.dst[idx] = val;
+            for (int g = 0; g < 4; ++g) {
+                const int col = cbase + 8 * g;
+                if (vec_out) {
+                    if (col < p.Nout) {
+                        f32x4 val = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                        f32x4 *dp = reinterpret_cast<f32x4 *>(drow + col);
+                        if (ACCUM) val = *dp + val;
+                        *dp = val;
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (col + q < p.Nout) {
+                            float val = acc[i][j][4 * g + q];
+                            if (ACCUM) val = drow[col + q] + val;
+                            drow[col + q] = val;
+                        }
                 }
             }
         }
+    }
 }
 
 template <int WGM, int WGN, int TM, int TN, int BKT, bool DGRAD>
