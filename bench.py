@@ -167,11 +167,11 @@ def cpu_baseline(name, budget_s=20.0):
     from oracle.net import OracleNet
     cfg, kw, _ = WORKLOADS[name]
     if cfg.startswith("resnet50"):
-        sample = {"batch": 2}
+        sample = {"batch": 16}
     elif cfg == "bottleneck":
-        sample = {"batch": 8}
+        sample = {"batch": 32}
     else:
-        sample = {"size": 48}
+        sample = {"size": 64}
     net, seed = workloads.load(cfg, **dict(kw, **sample))
     params = workloads.make_params(net, seed)
     x, t = workloads.make_batch(net, seed)
@@ -184,9 +184,9 @@ def cpu_baseline(name, budget_s=20.0):
     desc = "one oracle step of %s with %s (%.1f s)" % (cfg, ", ".join("%s=%s" % kv for kv in sample.items()), dt)
     value = batch / dt
     if cfg == "cnn3d":
-        # per-voxel cost is size-independent: scale the 48^3 sample to the 192^3 volume
-        value = value / (192 / 48) ** 3
-        desc += ", scaled by (48/192)^3 to the full volume"
+        # per-voxel cost is size-independent: scale the 64^3 sample to the 192^3 volume
+        value = value / (192 / 64) ** 3
+        desc += ", scaled by (64/192)^3 to the full volume"
     return {"value": value, "unit": "images/sec", "cores": cores, "kind": "oracle", "sample": desc}
 
 
@@ -202,6 +202,9 @@ def main():
     ap.add_argument("--bits", type=int, default=4, help="cap on the exponential part of the keep/swap search")
     ap.add_argument("--restarts", type=int, default=48, help="perturbed restarts of the refine mode's local search")
     ap.add_argument("--no-paper-mode", action="store_true", help="skip the extra leg that times the paper's own two-step plan")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time every planning mode (the experiment of the paper's section 5.1 plus the static policy "
+                         "of section 5.2) and report simulated against measured step time")
     ap.add_argument("--no-incore", action="store_true")
     ap.add_argument("--dump-profile", default=None, help="write the measured profile (ms per layer / map) to this .npz file")
     ap.add_argument("--no-cpu", action="store_true")
@@ -258,6 +261,23 @@ def main():
                 "keep": stp.n_keep, "swap": stp.n_swap, "recompute": stp.n_recompute, "swap_out_GB": stp.swap_out_bytes / 1e9}
             log("[bench] paper's two-step plan: %.1f ms/step (predicted %.1f), keep/swap/recompute %d/%d/%d" %
                 (sec_p * 1e3, pred_p, stp.n_keep, stp.n_swap, stp.n_recompute))
+        if args.ablation:
+            table = {}
+            for m in ("swapall_nosched", "swapall", "swapopt", "pooch", "superneurons", "refine"):
+                try:
+                    _, pred_m = ctx.plan(m, args.bits, restarts=args.restarts)
+                except B.BudgetError as e:
+                    table[m] = {"error": "does not fit: %s" % e}
+                    log("[bench] ablation %-16s does not fit" % m)
+                    continue
+                sec_m, _, _ = timed_steps(ctx, torch, max(1, min(args.steps, 2)), 1)
+                stm = ctx.stats()
+                table[m] = {"images_per_sec": batch / sec_m, "ms_per_step": sec_m * 1e3, "predicted_ms": pred_m,
+                            "keep": stm.n_keep, "swap": stm.n_swap, "recompute": stm.n_recompute,
+                            "swap_out_GB": stm.swap_out_bytes / 1e9}
+                log("[bench] ablation %-16s %8.1f ms/step (predicted %8.1f)  keep/swap/recompute %d/%d/%d" %
+                    (m, sec_m * 1e3, pred_m, stm.n_keep, stm.n_swap, stm.n_recompute))
+            result_extra["ablation"] = table
         t1b = time.perf_counter()
         cls, predicted = ctx.plan(args.mode, args.bits, restarts=args.restarts)
         t2 = time.perf_counter()

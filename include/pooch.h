@@ -52,15 +52,19 @@ enum {
 /* classes of a feature map, section 4.1.1 */
 enum { POOCH_KEEP = 0, POOCH_SWAP = 1, POOCH_RECOMPUTE = 2 };
 
-/* planning modes: in-core (everything kept), the four methods compared in section 5.1, and one extension */
+/* planning modes: in-core (everything kept), the four methods compared in section 5.1, one extension, and the
+ * static policy of section 5.2 */
 enum {
     POOCH_MODE_INCORE = 0,
     POOCH_MODE_SWAPALL_NOSCHED = 1, /* all swap; each swap-in starts with the previous backward computation */
     POOCH_MODE_SWAPALL = 2,         /* all swap; swap-ins moved up as far as memory allows (section 4.3) */
     POOCH_MODE_SWAPOPT = 3,         /* keep/swap search only (section 4.4.2) */
     POOCH_MODE_POOCH = 4,           /* keep/swap search, then swap/recompute classification (section 4.4.3) */
-    POOCH_MODE_REFINE = 5           /* not in the paper: POOCH followed by an iterated local search over single class
+    POOCH_MODE_REFINE = 5,          /* not in the paper: POOCH followed by an iterated local search over single class
                                        changes, judged by the same timeline simulation */
+    POOCH_MODE_SUPERNEURONS = 6     /* the static policy section 5.2 compares against: keep from the output layer while
+                                       it fits, then convolution outputs swap and the rest is recomputed; swap-ins
+                                       are not moved up */
 };
 
 /* ---- context ------------------------------------------------------------------------

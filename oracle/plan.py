@@ -14,6 +14,8 @@ TEST INFRASTRUCTURE ONLY (slow, obvious, no sharing with the HIP library).  It c
   * the two-step heuristic search (section 4.4): L_O / L_I extraction on the all-swap
     timeline, binary tree over L_I with a greedy scan of L_O \\ L_I from the output layer,
     then r(X) = recompute_overhead / swap_overhead (equation 1) for the maps left in swap,
+  * mode "superneurons": the static policy of section 5.2 (keep from the output end, then
+    convolution outputs swap, the rest is recomputed; swap-ins not moved up),
   * mode "refine" (not in the paper): the two steps followed by an iterated local search over
     single class changes, judged by the same simulation.
 
@@ -629,6 +631,8 @@ class Planner:
             if T is None:
                 raise Budget("in-core does not fit")
             return cls, T
+        if mode == "superneurons":
+            return self.superneurons()
         allswap = [SWAP] * nf
         if mode == "swapall_nosched":
             T = self.evaluate(allswap, ahead=False)
@@ -647,6 +651,24 @@ class Planner:
         if mode == "pooch":
             return cls, T
         return self.refine(cls, T)
+
+    def superneurons(self):
+        """the static policy the paper compares against (section 5.2): keep maps from the output
+        layer backwards while they fit; of the rest, convolution outputs swap and all others
+        are recomputed; each swap-in starts with the preceding backward computation"""
+        G = self.G
+        cls = [SWAP if G.ops[t] == "conv" else RECOMPUTE for t in G.fmaps]
+        T = self.evaluate(cls, ahead=False)
+        if T is None:
+            raise Budget("the static policy does not fit")
+        for k in range(len(cls) - 1, -1, -1):
+            trial = list(cls)
+            trial[k] = KEEP
+            Tt = self.evaluate(trial, ahead=False)
+            if Tt is None:
+                break
+            cls, T = trial, Tt
+        return cls, T
 
     def step1(self, allswap, T_all):
         """keep/swap search (section 4.4.2)"""

@@ -19,8 +19,8 @@ LIB_PATH = os.path.join(HERE, "libpooch.so")
 
 OK, E_INVALID, E_STATE, E_BUDGET, E_HIP, E_NOPROFILE = 0, -1, -2, -3, -4, -5
 KEEP, SWAP, RECOMPUTE = 0, 1, 2
-MODE_INCORE, MODE_SWAPALL_NOSCHED, MODE_SWAPALL, MODE_SWAPOPT, MODE_POOCH, MODE_REFINE = range(6)
-MODES = {"incore": 0, "swapall_nosched": 1, "swapall": 2, "swapopt": 3, "pooch": 4, "refine": 5}
+MODE_INCORE, MODE_SWAPALL_NOSCHED, MODE_SWAPALL, MODE_SWAPOPT, MODE_POOCH, MODE_REFINE, MODE_SUPERNEURONS = range(7)
+MODES = {"incore": 0, "swapall_nosched": 1, "swapall": 2, "swapopt": 3, "pooch": 4, "refine": 5, "superneurons": 6}
 
 
 class Stats(C.Structure):

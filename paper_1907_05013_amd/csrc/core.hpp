@@ -85,7 +85,7 @@ struct SimResult {
 };
 SimResult simulate(const Graph &G, const Schedule &S, const Profile &P);
 
-enum : int { MODE_INCORE = 0, MODE_SWAPALL_NOSCHED = 1, MODE_SWAPALL = 2, MODE_SWAPOPT = 3, MODE_POOCH = 4, MODE_REFINE = 5 };
+enum : int { MODE_INCORE = 0, MODE_SWAPALL_NOSCHED = 1, MODE_SWAPALL = 2, MODE_SWAPOPT = 3, MODE_POOCH = 4, MODE_REFINE = 5, MODE_SUPERNEURONS = 6 };
 
 struct Planner {
     const Graph &G;

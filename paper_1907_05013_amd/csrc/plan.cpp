@@ -641,6 +641,24 @@ bool Planner::plan(int mode, std::vector<uint8_t> &cls, double &T, bool &ahead)
         T = evaluate(cls);
         return T >= 0.0;
     }
+    if (mode == MODE_SUPERNEURONS) {
+        // the static policy of section 5.2: keep from the output layer backwards while it fits; of the
+        // rest convolution outputs swap, all others are recomputed; swap-ins are not moved up
+        ahead = false;
+        cls.resize(nf);
+        for (size_t k = 0; k < nf; ++k) cls[k] = G.nodes[G.fmaps[k]].op == OP_CONV ? CLS_SWAP : CLS_RECOMPUTE;
+        T = evaluate(cls, false);
+        if (T < 0.0) return false;
+        for (int k = (int)nf - 1; k >= 0; --k) {
+            std::vector<uint8_t> trial = cls;
+            trial[k] = CLS_KEEP;
+            const double Tt = evaluate(trial, false);
+            if (Tt < 0.0) break;
+            cls = trial;
+            T = Tt;
+        }
+        return true;
+    }
     const std::vector<uint8_t> allswap(nf, CLS_SWAP);
     if (mode == MODE_SWAPALL_NOSCHED) {
         cls = allswap;

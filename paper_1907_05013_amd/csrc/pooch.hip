@@ -934,8 +934,8 @@ pooch_status pooch_set_profile(pooch_ctx *c, const double *t_fwd, const double *
 pooch_status pooch_plan(pooch_ctx *c, int mode, int max_bruteforce_bits, double *predicted_ms)
 {
     NEED_FINAL(c);
-    if (mode < POOCH_MODE_INCORE || mode > POOCH_MODE_REFINE) return fail(c, POOCH_E_INVALID, "plan: unknown mode");
-    if (!c->prof.valid && mode >= POOCH_MODE_SWAPOPT) return fail(c, POOCH_E_NOPROFILE, "plan: the search needs a profile");
+    if (mode < POOCH_MODE_INCORE || mode > POOCH_MODE_SUPERNEURONS) return fail(c, POOCH_E_INVALID, "plan: unknown mode");
+    if (!c->prof.valid && mode >= POOCH_MODE_SWAPOPT && mode != POOCH_MODE_SUPERNEURONS) return fail(c, POOCH_E_NOPROFILE, "plan: the search needs a profile");
     const Profile zero = c->prof.valid ? Profile() : zero_profile(c->G);
     const Profile &P = c->prof.valid ? c->prof : zero;
     int bits = max_bruteforce_bits <= 0 ? 10 : max_bruteforce_bits;

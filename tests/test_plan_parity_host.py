@@ -103,7 +103,7 @@ def test_every_mode_picks_the_oracles_plan(seed):
     c, _ = lib_ctx(net, cap, fuse)
     c.set_profile(*prof)
     bits = 5
-    for mode in ("swapall_nosched", "swapall", "swapopt", "pooch", "refine"):
+    for mode in ("swapall_nosched", "swapall", "swapopt", "pooch", "refine", "superneurons"):
         pl = P.Planner(G, oprof, cap, max_bits=bits, restarts=3)
         try:
             ocls, oT = pl.plan(mode)
