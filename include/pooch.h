@@ -119,6 +119,11 @@ pooch_status pooch_param_info(pooch_ctx *, int32_t i, int64_t *numel, int32_t *n
 pooch_status pooch_set_param(pooch_ctx *, int32_t i, const float *host);
 pooch_status pooch_get_grad(pooch_ctx *, int32_t i, float *host);
 pooch_status pooch_set_batch(pooch_ctx *, const float *x_host, const int32_t *labels_host);
+/* Plain SGD on every parameter with the gradients of the last step: p -= lr * grad (section 2.1's third
+ * phase; the paper leaves it out of its timelines because it is short).  Synchronises.
+ * pooch_get_param reads parameter i back in the layout pooch_set_param takes. */
+pooch_status pooch_sgd_update(pooch_ctx *, float lr);
+pooch_status pooch_get_param(pooch_ctx *, int32_t i, float *host);
 /* parity aid: during every following step, right after the forward of layer `id` has run,
  * its output is copied to `host` in logical layout (the step synchronises there, so this is
  * for tests, not for timed runs).  host == NULL cancels the capture of that layer.  The
@@ -143,6 +148,12 @@ size_t pooch_resident_bytes(pooch_ctx *);
  * Array lengths: t_fwd, t_bwd, t_refwd -> num_nodes; t_out, t_in -> num_fmaps.
  * set_profile injects a profile (tests, CPU-only planning). */
 pooch_status pooch_profile(pooch_ctx *, int warmup, int iters);
+/* The same, one iteration at a time, for callers whose first training iterations double as the
+ * profiling phase (section 4.1.2: "profiling is done during the first several iterations"): each call
+ * runs one all-swap step (forward + backward, gradients valid afterwards); timed != 0 adds its
+ * durations to the samples.  pooch_finish_profile turns the samples into the profile (median). */
+pooch_status pooch_profile_step(pooch_ctx *, int timed, float *loss_out);
+pooch_status pooch_finish_profile(pooch_ctx *);
 pooch_status pooch_get_profile(pooch_ctx *, double *t_fwd, double *t_bwd, double *t_refwd, double *t_out, double *t_in);
 pooch_status pooch_set_profile(pooch_ctx *, const double *t_fwd, const double *t_bwd, const double *t_refwd,
                                const double *t_out, const double *t_in);

@@ -66,6 +66,10 @@ SYMBOLS = {
     "pooch_fmap_info": (_i32, [_ctx, _i32, C.POINTER(_sz), _pi32]),
     "pooch_resident_bytes": (_sz, [_ctx]),
     "pooch_profile": (_i32, [_ctx, C.c_int, C.c_int]),
+    "pooch_profile_step": (_i32, [_ctx, C.c_int, _pf]),
+    "pooch_finish_profile": (_i32, [_ctx]),
+    "pooch_sgd_update": (_i32, [_ctx, C.c_float]),
+    "pooch_get_param": (_i32, [_ctx, _i32, C.c_void_p]),
     "pooch_get_profile": (_i32, [_ctx, _pd, _pd, _pd, _pd, _pd]),
     "pooch_set_profile": (_i32, [_ctx, _pd, _pd, _pd, _pd, _pd]),
     "pooch_plan": (_i32, [_ctx, C.c_int, C.c_int, _pd]),
@@ -262,6 +266,25 @@ class Context:
             self._chk(self.L.pooch_get_grad(self.h, i, g.ctypes.data))
             out.append(g.reshape(shapes[i]) if shapes is not None else g)
         return out
+
+    def get_params(self, shapes=None):
+        out = []
+        for i in range(self.n_params):
+            p = np.empty(self.param_info(i)[0], np.float32)
+            self._chk(self.L.pooch_get_param(self.h, i, p.ctypes.data))
+            out.append(p.reshape(shapes[i]) if shapes is not None else p)
+        return out
+
+    def sgd_update(self, lr):
+        self._chk(self.L.pooch_sgd_update(self.h, lr))
+
+    def profile_step(self, timed=True):
+        loss = C.c_float()
+        self._chk(self.L.pooch_profile_step(self.h, 1 if timed else 0, C.byref(loss)))
+        return loss.value
+
+    def finish_profile(self):
+        self._chk(self.L.pooch_finish_profile(self.h))
 
     def set_batch(self, x, labels):
         x = np.ascontiguousarray(x, np.float32)

@@ -335,6 +335,27 @@ __global__ __launch_bounds__(256) void addrelu_bwd_kernel(const float *__restric
     }
 }
 
+// p -= lr * g
+__global__ __launch_bounds__(256) void sgd_kernel(float *__restrict__ p, const float *__restrict__ g, float lr, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = p[i] - lr * g[i];
+}
+
+// filter copy for the data gradient: crk[c][t][k] = krc[k][t][c]
+__global__ __launch_bounds__(256) void filter_transpose_kernel(const float *__restrict__ krc, float *__restrict__ crk, int K, int64_t T, int C)
+{
+    const int64_t n = (int64_t)K * T * C;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const int k = (int)(i % K);
+        const int64_t ct = i / K;
+        const int64_t t = ct % T;
+        const int c = (int)(ct / T);
+        crk[i] = krc[((int64_t)k * T + t) * C + c];
+    }
+}
+
 bool bn_args_ok(int64_t M, int C) { return M > 0 && C > 0 && M * (int64_t)C < ((int64_t)1 << 40); }
 
 }  // namespace
@@ -436,6 +457,22 @@ hipError_t add_relu_bwd(const float *y, float *dy, float *o1, int mode1, int64_t
     if (mode1 == 0) addrelu_bwd_kernel<0><<<grid, block, 0, s>>>(y, dy, o1, n);
     else if (mode1 == 1) addrelu_bwd_kernel<1><<<grid, block, 0, s>>>(y, dy, o1, n);
     else addrelu_bwd_kernel<2><<<grid, block, 0, s>>>(y, dy, o1, n);
+    return hipGetLastError();
+}
+hipError_t sgd_update(float *p, const float *g, float lr, int64_t n, hipStream_t s)
+{
+    if (!p || !g || n <= 0) return hipErrorInvalidValue;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    sgd_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(p, g, lr, n);
+    return hipGetLastError();
+}
+hipError_t filter_transpose(const float *krc, float *crk, int K, int64_t T, int C, hipStream_t s)
+{
+    if (!krc || !crk || K <= 0 || T <= 0 || C <= 0) return hipErrorInvalidValue;
+    int64_t blocks = ((int64_t)K * T * C + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    filter_transpose_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(krc, crk, K, T, C);
     return hipGetLastError();
 }
 hipError_t accumulate(float *dst, const float *src, int64_t n, hipStream_t s) { return launch_ew<EW_ACC>(src, nullptr, dst, n, s); }

@@ -60,6 +60,11 @@ hipError_t add_relu_bwd(const float *y, float *dy, float *o1, int mode1, int64_t
 hipError_t accumulate(float *dst, const float *src, int64_t n, hipStream_t s);
 hipError_t copy(float *dst, const float *src, int64_t n, hipStream_t s);
 
+// plain SGD: p -= lr * g
+hipError_t sgd_update(float *p, const float *g, float lr, int64_t n, hipStream_t s);
+// crk[c][t][k] = krc[k][t][c]: refreshes the filter copy the data gradient reads
+hipError_t filter_transpose(const float *krc, float *crk, int K, int64_t T, int C, hipStream_t s);
+
 struct PoolGeom {
     int N, C, D, H, W, Do, Ho, Wo, kd, kh, kw, sd, sh, sw, pd, ph, pw;
 };

@@ -66,6 +66,10 @@ struct pooch_ctx {
     int64_t evals = 0;
     int restarts = 8;
     double last_step_ms = 0.0;
+    // samples gathered by pooch_profile_step, turned into a profile by pooch_finish_profile
+    std::vector<std::vector<double>> smp_f, smp_b, smp_r, smp_o, smp_i;
+    Schedule prof_sched;
+    bool prof_sched_ok = false;
 
     std::vector<hipEvent_t> sync_events;    // no timing
     std::vector<hipEvent_t> timing_events;  // with timing
@@ -849,53 +853,140 @@ pooch_status pooch_fmap_info(pooch_ctx *c, int32_t i, size_t *bytes, int32_t *pr
 
 size_t pooch_resident_bytes(pooch_ctx *c) { return (c && c->finalized) ? (size_t)c->resident_bytes : 0; }
 
+}  // extern "C" (reopened below)
+
+namespace {
+
+pooch_status profile_begin(pooch_ctx *c)
+{
+    const Graph &G = c->G;
+    const std::vector<uint8_t> allswap(G.fmaps.size(), CLS_SWAP);
+    std::string why;
+    c->prof_sched = Schedule();
+    if (!build_schedule(G, allswap, (int64_t)c->arena_bytes - c->resident_bytes, true, (int64_t)c->pinned_bytes, c->prof_sched, &why))
+        return fail(c, POOCH_E_BUDGET, "profiling runs every map as swap and that does not fit: " + why);
+    c->prof_sched_ok = true;
+    c->smp_f.assign(G.n(), {}); c->smp_b.assign(G.n(), {}); c->smp_r.assign(G.n(), {});
+    c->smp_o.assign(G.fmaps.size(), {}); c->smp_i.assign(G.fmaps.size(), {});
+    return POOCH_OK;
+}
+
+// one all-swap step; timed: every command's duration is added to the samples
+pooch_status profile_one(pooch_ctx *c, bool timed, float *loss_out)
+{
+    const Graph &G = c->G;
+    const Schedule &S = c->prof_sched;
+    Timing tm;
+    pooch_status ps = run_schedule(c, S, timed ? &tm : nullptr, timed, loss_out);
+    if (ps != POOCH_OK || !timed) return ps;
+    for (size_t k = 0; k < S.cmds.size(); ++k) {
+        if (tm.start[k] < 0) continue;
+        const Cmd &cm = S.cmds[k];
+        double ms;
+        ps = elapsed(c, tm.start[k], tm.stop[k], ms);
+        if (ps != POOCH_OK) return ps;
+        switch (cm.kind) {
+        case K_FWD: c->smp_f[cm.id].push_back(ms); break;
+        case K_REFWD: c->smp_r[cm.id].push_back(ms); break;
+        case K_BWD: c->smp_b[cm.id].push_back(ms); break;
+        case K_OUT: c->smp_o[G.fidx[cm.id]].push_back(ms); break;
+        case K_IN: c->smp_i[G.fidx[cm.id]].push_back(ms); break;
+        default: break;
+        }
+        if (tm.rstart[k] >= 0) {
+            ps = elapsed(c, tm.rstart[k], tm.rstop[k], ms);
+            if (ps != POOCH_OK) return ps;
+            c->smp_r[cm.id].push_back(ms);
+        }
+    }
+    return POOCH_OK;
+}
+
+pooch_status profile_end(pooch_ctx *c)
+{
+    const int n = c->G.n();
+    const size_t nf = c->G.fmaps.size();
+    bool any = false;
+    for (int i = 1; i < n; ++i) any = any || !c->smp_f[i].empty();
+    if (!any) return fail(c, POOCH_E_NOPROFILE, "no timed profiling step was run");
+    Profile P;
+    P.t_fwd.resize(n); P.t_bwd.resize(n); P.t_refwd.resize(n); P.t_out.resize(nf); P.t_in.resize(nf);
+    for (int i = 0; i < n; ++i) { P.t_fwd[i] = median(c->smp_f[i]); P.t_bwd[i] = median(c->smp_b[i]); P.t_refwd[i] = median(c->smp_r[i]); }
+    for (size_t k = 0; k < nf; ++k) { P.t_out[k] = median(c->smp_o[k]); P.t_in[k] = median(c->smp_i[k]); }
+    P.valid = true;
+    c->prof = P;
+    c->prof_sched_ok = false;
+    return POOCH_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 pooch_status pooch_profile(pooch_ctx *c, int warmup, int iters)
 {
     NEED_FINAL(c);
     if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
     if (warmup < 0 || iters <= 0) return fail(c, POOCH_E_INVALID, "profile: bad iteration counts");
-    const Graph &G = c->G;
-    const std::vector<uint8_t> allswap(G.fmaps.size(), CLS_SWAP);
-    Schedule S;
-    std::string why;
-    if (!build_schedule(G, allswap, (int64_t)c->arena_bytes - c->resident_bytes, true, (int64_t)c->pinned_bytes, S, &why))
-        return fail(c, POOCH_E_BUDGET, "profiling runs every map as swap and that does not fit: " + why);
-    const int n = G.n();
-    const size_t nf = G.fmaps.size();
-    std::vector<std::vector<double>> f(n), b(n), r(n), o(nf), in(nf);
-    Timing tm;
+    pooch_status ps = profile_begin(c);
+    if (ps != POOCH_OK) return ps;
     for (int it = 0; it < warmup + iters; ++it) {
-        const bool timed = it >= warmup;
-        pooch_status ps = run_schedule(c, S, timed ? &tm : nullptr, timed, nullptr);
+        ps = profile_one(c, it >= warmup, nullptr);
         if (ps != POOCH_OK) return ps;
-        if (!timed) continue;
-        for (size_t k = 0; k < S.cmds.size(); ++k) {
-            if (tm.start[k] < 0) continue;
-            const Cmd &cm = S.cmds[k];
-            double ms;
-            ps = elapsed(c, tm.start[k], tm.stop[k], ms);
-            if (ps != POOCH_OK) return ps;
-            switch (cm.kind) {
-            case K_FWD: f[cm.id].push_back(ms); break;
-            case K_REFWD: r[cm.id].push_back(ms); break;
-            case K_BWD: b[cm.id].push_back(ms); break;
-            case K_OUT: o[G.fidx[cm.id]].push_back(ms); break;
-            case K_IN: in[G.fidx[cm.id]].push_back(ms); break;
-            default: break;
-            }
-            if (tm.rstart[k] >= 0) {
-                ps = elapsed(c, tm.rstart[k], tm.rstop[k], ms);
-                if (ps != POOCH_OK) return ps;
-                r[cm.id].push_back(ms);
-            }
+    }
+    return profile_end(c);
+}
+
+pooch_status pooch_profile_step(pooch_ctx *c, int timed, float *loss_out)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (!c->prof_sched_ok) {
+        const pooch_status ps = profile_begin(c);
+        if (ps != POOCH_OK) return ps;
+    }
+    return profile_one(c, timed != 0, loss_out);
+}
+
+pooch_status pooch_finish_profile(pooch_ctx *c)
+{
+    NEED_FINAL(c);
+    if (!c->prof_sched_ok) return fail(c, POOCH_E_STATE, "finish_profile: no profiling step was run");
+    return profile_end(c);
+}
+
+pooch_status pooch_sgd_update(pooch_ctx *c, float lr)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (!(lr == lr)) return fail(c, POOCH_E_INVALID, "sgd_update: learning rate is NaN");
+    hipStream_t s = c->st[S_COMPUTE];
+    for (const ParamInfo &p : c->params) {
+        float *val = reinterpret_cast<float *>(c->arena + p.off_val);
+        HIPCHK(pk::sgd_update(val, reinterpret_cast<const float *>(c->arena + p.off_grad), lr, p.dev_numel, s));
+        if (p.off_val_t >= 0) {
+            const pk::ConvGeom g = conv_geom(c->G, p.node, c->in_cdev);
+            HIPCHK(pk::filter_transpose(val, reinterpret_cast<float *>(c->arena + p.off_val_t), g.K, g.taps(), g.C, s));
         }
     }
-    Profile P;
-    P.t_fwd.resize(n); P.t_bwd.resize(n); P.t_refwd.resize(n); P.t_out.resize(nf); P.t_in.resize(nf);
-    for (int i = 0; i < n; ++i) { P.t_fwd[i] = median(f[i]); P.t_bwd[i] = median(b[i]); P.t_refwd[i] = median(r[i]); }
-    for (size_t k = 0; k < nf; ++k) { P.t_out[k] = median(o[k]); P.t_in[k] = median(in[k]); }
-    P.valid = true;
-    c->prof = P;
+    HIPCHK(hipStreamSynchronize(s));
+    return POOCH_OK;
+}
+
+pooch_status pooch_get_param(pooch_ctx *c, int32_t i, float *host)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (i < 0 || i >= (int32_t)c->params.size() || !host) return fail(c, POOCH_E_INVALID, "get_param: bad argument");
+    const ParamInfo &p = c->params[i];
+    if (p.off_val_t < 0) {
+        HIPCHK(hipMemcpy(host, c->arena + p.off_val, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
+        return POOCH_OK;
+    }
+    const pk::ConvGeom g = conv_geom(c->G, p.node, c->in_cdev);
+    std::vector<float> krc((size_t)p.dev_numel);
+    HIPCHK(hipMemcpy(krc.data(), c->arena + p.off_val, (size_t)p.dev_numel * 4, hipMemcpyDeviceToHost));
+    filter_from_device_layout(krc.data(), g.K, p.numel / ((int64_t)g.K * g.taps()), g.C, g.taps(), host);
     return POOCH_OK;
 }
 

@@ -198,6 +198,61 @@ def test_unfused_layers_vs_oracle_and_fused_run(monkeypatch):
         assert rel(a, b) <= 1e-5
 
 
+def test_training_loop_profile_then_plan_vs_oracle():
+    """the paper's user flow (section 4.1.2): the first iterations run with every map swapped and are
+    profiled, then the classification is made, then training continues under the plan -- with a plain
+    SGD update after every step.  Parameters after six iterations against the oracle doing the same six
+    steps, and against an in-core run of the library (bit-exact)."""
+    net = reduced_nets()["resnet"]
+    seed, lr, iters, prof_iters = 31, 0.05, 6, 3
+    params = workloads.make_params(net, seed, perturb=True)
+    x, t = workloads.make_batch(net, seed)
+    shapes = [s for _, _, s in workloads.param_shapes(net)]
+    # oracle: plain loop
+    op = [p.copy() for p in params]
+    olosses = []
+    for _ in range(iters):
+        loss, grads, _ = OracleNet(net, op, np.float32).step(x, t)
+        olosses.append(loss)
+        op = [(p - np.float32(lr) * g).astype(np.float32) for p, g in zip(op, grads)]
+    res, peak = plan_sizes(net)
+    G = OP.Graph(net, fuse=FUSE)
+    runs = {}
+    for tag, dyn in (("incore", 2 * peak), ("budget", int(peak * 0.6) // 256 * 256)):
+        c = B.Context(net, res + dyn, pinned_bytes=sum(G.fmap_bytes()) + 256, fuse=FUSE)
+        c.set_params(params)
+        c.set_batch(x, t)
+        losses = []
+        if tag == "incore":
+            c.set_plan([B.KEEP] * c.n_fmaps)
+            for _ in range(iters):
+                losses.append(c.step())
+                c.sgd_update(lr)
+        else:
+            for it in range(prof_iters):
+                losses.append(c.profile_step(timed=it > 0))
+                c.sgd_update(lr)
+            c.finish_profile()
+            cls, _ = c.plan("refine", 4, restarts=2)
+            assert any(v != B.KEEP for v in cls)
+            for _ in range(iters - prof_iters):
+                losses.append(c.step())
+                c.sgd_update(lr)
+        runs[tag] = (losses, c.get_params(shapes))
+        c.close()
+    l_in, p_in = runs["incore"]
+    l_b, p_b = runs["budget"]
+    assert [np.float32(v).tobytes() for v in l_in] == [np.float32(v).tobytes() for v in l_b]
+    for a, b in zip(p_in, p_b):
+        assert a.tobytes() == b.tobytes()
+    for a, b in zip(l_in, olosses):
+        assert abs(a - b) <= RTOL * abs(b)
+    assert l_in[-1] < l_in[0]                                  # it learns the fixed batch
+    worst = max(rel(a, b) for a, b in zip(p_in, op))
+    assert worst <= RTOL, worst
+    say("[ok] training loop: losses", ["%.4f" % v for v in l_in], "worst parameter error %.2e" % worst)
+
+
 # ------------------------------------------------------------------ reduced copies of configs 2-5
 
 def reduced_nets():
