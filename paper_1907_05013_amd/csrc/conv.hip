@@ -403,6 +403,8 @@ hipError_t dispatch_igemm(const IGemmP &p, bool accum, hipStream_t s)
 {
     const bool vec = (p.Cs % 4 == 0) && ((uintptr_t)p.src % 16 == 0) && ((uintptr_t)p.wgt % 16 == 0);
     const bool lin = vec && igemm_linear<DGRAD>(p);
+    // too few 128x128 tiles to fill 256 compute units three workgroups deep: quarter-size tiles
+    if (p.Nout > 64 && ((int64_t)(p.M + 127) / 128) * ((p.Nout + 127) / 128) < 640) return launch_igemm<2, 2, 1, 1, BK, DGRAD>(p, vec, lin, accum, s);
     if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s);
     if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, BK, DGRAD>(p, vec, lin, accum, s);
     return launch_igemm<2, 2, 2, 2, BK, DGRAD>(p, vec, lin, accum, s);
@@ -822,9 +824,9 @@ hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const Con
 
 namespace {
 // tag of the igemm instantiation dispatch_igemm() picks: tile shape, load path, direction
-const char *igemm_tag(int nout, int cs, bool unit_stride, bool dgrad)
+const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgrad)
 {
-    static const char *names[3][3][2] = {
+    static const char *names[4][3][2] = {
         {{"igemm_kernel<4,1,2,1,scalar,fwd>", "igemm_kernel<4,1,2,1,scalar,dgrad>"},
          {"igemm_kernel<4,1,2,1,vec,fwd>", "igemm_kernel<4,1,2,1,vec,dgrad>"},
          {"igemm_kernel<4,1,2,1,vec+lin,fwd>", "igemm_kernel<4,1,2,1,vec+lin,dgrad>"}},
@@ -833,20 +835,24 @@ const char *igemm_tag(int nout, int cs, bool unit_stride, bool dgrad)
          {"igemm_kernel<4,1,2,2,vec+lin,fwd>", "igemm_kernel<4,1,2,2,vec+lin,dgrad>"}},
         {{"igemm_kernel<2,2,2,2,scalar,fwd>", "igemm_kernel<2,2,2,2,scalar,dgrad>"},
          {"igemm_kernel<2,2,2,2,vec,fwd>", "igemm_kernel<2,2,2,2,vec,dgrad>"},
-         {"igemm_kernel<2,2,2,2,vec+lin,fwd>", "igemm_kernel<2,2,2,2,vec+lin,dgrad>"}}};
-    const int tile = nout <= 32 ? 0 : (nout <= 64 ? 1 : 2);
+         {"igemm_kernel<2,2,2,2,vec+lin,fwd>", "igemm_kernel<2,2,2,2,vec+lin,dgrad>"}},
+        {{"igemm_kernel<2,2,1,1,scalar,fwd>", "igemm_kernel<2,2,1,1,scalar,dgrad>"},
+         {"igemm_kernel<2,2,1,1,vec,fwd>", "igemm_kernel<2,2,1,1,vec,dgrad>"},
+         {"igemm_kernel<2,2,1,1,vec+lin,fwd>", "igemm_kernel<2,2,1,1,vec+lin,dgrad>"}}};
+    int tile = nout <= 32 ? 0 : (nout <= 64 ? 1 : 2);
+    if (nout > 64 && ((rows + 127) / 128) * ((nout + 127) / 128) < 640) tile = 3;
     const bool vec = cs % 4 == 0;
     const bool lin = vec && cs % BK == 0 && (!dgrad || unit_stride) && getenv("POOCH_NO_LINEAR") == nullptr;
     return names[tile][lin ? 2 : (vec ? 1 : 0)][dgrad ? 1 : 0];
 }
 }  // namespace
 
-const char *conv_fwd_kernel(const ConvGeom &g) { return igemm_tag(g.K, g.C, true, false); }
+const char *conv_fwd_kernel(const ConvGeom &g) { return igemm_tag(g.rows_out(), g.K, g.C, true, false); }
 
 const char *conv_dgrad_kernel(const ConvGeom &g)
 {
-    if (pointwise_strided(g)) return igemm_tag(g.C, g.K, true, false);   // scatter GEMM over the output rows
-    return igemm_tag(g.C, g.K, g.sd == 1 && g.sh == 1 && g.sw == 1, true);
+    if (pointwise_strided(g)) return igemm_tag(g.rows_out(), g.C, g.K, true, false);   // scatter GEMM over the output rows
+    return igemm_tag(g.rows_in(), g.C, g.K, g.sd == 1 && g.sh == 1 && g.sw == 1, true);
 }
 
 const char *conv_wgrad_kernel(const ConvGeom &g)
