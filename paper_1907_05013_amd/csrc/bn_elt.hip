@@ -15,6 +15,7 @@ namespace {
 
 constexpr int BNT = 256;        // threads per block in the 2-d (row, channel-vector) kernels
 constexpr int MAX_RBLK = 2048;  // cap on row blocks of a reduction
+constexpr int APPLY_BLOCKS = 1 << 22;  // cap on blocks of an apply kernel
 
 struct Lay2D {
     int V;          // floats per lane access (4 when C % 4 == 0, else 1)
@@ -25,7 +26,10 @@ struct Lay2D {
     int64_t rows_per_blk;
 };
 
-Lay2D layout2d(int64_t M, int C, bool vec_ok, int target_blocks)
+// rows_per_thread: how many rows one thread walks before its block is done.  The reductions take
+// long walks (few partial results); the apply kernels take short ones: many small blocks, each
+// streaming a few KB, measured closest to the HBM peak on this chip.
+Lay2D layout2d(int64_t M, int C, bool vec_ok, int target_blocks, int rows_per_thread = 32)
 {
     Lay2D L;
     L.V = (vec_ok && C % 4 == 0) ? 4 : 1;
@@ -33,7 +37,7 @@ Lay2D layout2d(int64_t M, int C, bool vec_ok, int target_blocks)
     L.TX = L.CV < BNT ? L.CV : BNT;
     L.TY = BNT / L.TX;
     L.gy = (L.CV + L.TX - 1) / L.TX;
-    int64_t nb = (M + (int64_t)L.TY * 32 - 1) / ((int64_t)L.TY * 32);
+    int64_t nb = (M + (int64_t)L.TY * rows_per_thread - 1) / ((int64_t)L.TY * rows_per_thread);
     int64_t cap = target_blocks / L.gy;
     if (cap < 1) cap = 1;
     if (nb > cap) nb = cap;
@@ -42,6 +46,8 @@ Lay2D layout2d(int64_t M, int C, bool vec_ok, int target_blocks)
     L.nblk = (int)((M + L.rows_per_blk - 1) / L.rows_per_blk);
     return L;
 }
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <int V> __device__ __forceinline__ void ldv(const float *p, float (&o)[V])
 {
@@ -56,6 +62,26 @@ template <int V> __device__ __forceinline__ void stv(float *p, const float (&o)[
 {
     if constexpr (V == 4) *reinterpret_cast<float4 *>(p) = make_float4(o[0], o[1 % V], o[2 % V], o[3 % V]);
     else *p = o[0];
+}
+// Streaming accessors for the big tensors: every element is touched once per kernel, so the
+// loads and stores carry the non-temporal hint and leave the caches to the per-channel vectors.
+template <int V> __device__ __forceinline__ void ldnt(const float *p, float (&o)[V])
+{
+    if constexpr (V == 4) {
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+        o[0] = t.x; o[1 % V] = t.y; o[2 % V] = t.z; o[3 % V] = t.w;
+    } else {
+        o[0] = __builtin_nontemporal_load(p);
+    }
+}
+template <int V> __device__ __forceinline__ void stnt(float *p, const float (&o)[V])
+{
+    if constexpr (V == 4) {
+        const f32x4 t = {o[0], o[1 % V], o[2 % V], o[3 % V]};
+        __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(p));
+    } else {
+        __builtin_nontemporal_store(o[0], p);
+    }
 }
 
 // The one expression every kernel uses for a normalised value (g = gamma * istd): forward, the
@@ -95,12 +121,8 @@ __global__ __launch_bounds__(BNT) void bn_partial_kernel(const float *__restrict
         }
         const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
         const int64_t r1 = r0 + rows_per_blk < M ? r0 + rows_per_blk : M;
-        for (int64_t r = r0 + ty; r < r1; r += TY) {
-            float xv[V];
-            ldv<V>(x + r * C + (int64_t)col * V, xv);
+        auto take = [&](const float (&xv)[V], float (&dv)[V]) {
             if (dy) {
-                float dv[V];
-                ldv<V>(dy + r * C + (int64_t)col * V, dv);
                 if (RELU) {
 #pragma unroll
                     for (int i = 0; i < V; ++i) dv[i] = bn_val(xv[i], sh[i], g[i], bt[i]) > 0.f ? dv[i] : 0.f;
@@ -111,6 +133,26 @@ __global__ __launch_bounds__(BNT) void bn_partial_kernel(const float *__restrict
 #pragma unroll
                 for (int i = 0; i < V; ++i) { const float d = xv[i] - sh[i]; s1[i] += d; s2[i] += d * d; }
             }
+        };
+        // UR rows in flight per thread; the sums still take the rows in ascending order
+        constexpr int UR = 4;
+        int64_t r = r0 + ty;
+        for (; r + (int64_t)(UR - 1) * TY < r1; r += (int64_t)UR * TY) {
+            float xv[UR][V], dv[UR][V];
+#pragma unroll
+            for (int u = 0; u < UR; ++u) ldnt<V>(x + (r + (int64_t)u * TY) * C + (int64_t)col * V, xv[u]);
+            if (dy) {
+#pragma unroll
+                for (int u = 0; u < UR; ++u) ldnt<V>(dy + (r + (int64_t)u * TY) * C + (int64_t)col * V, dv[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < UR; ++u) take(xv[u], dv[u]);
+        }
+        for (; r < r1; r += TY) {
+            float xv[V], dv[V];
+            ldnt<V>(x + r * C + (int64_t)col * V, xv);
+            if (dy) ldnt<V>(dy + r * C + (int64_t)col * V, dv);
+            take(xv, dv);
         }
     }
 #pragma unroll
@@ -195,15 +237,30 @@ __global__ __launch_bounds__(BNT) void bn_apply_kernel(const float *__restrict__
     for (int i = 0; i < V; ++i) g[i] *= is[i];
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
     const int64_t r1 = r0 + rows_per_blk < M ? r0 + rows_per_blk : M;
-    for (int64_t r = r0 + ty; r < r1; r += TY) {
-        float xv[V];
-        ldv<V>(x + r * C + (int64_t)col * V, xv);
+    auto apply = [&](float (&xv)[V]) {
 #pragma unroll
         for (int i = 0; i < V; ++i) {
             const float v = bn_val(xv[i], mu[i], g[i], b[i]);
             xv[i] = RELU ? (v > 0.f ? v : 0.f) : v;
         }
-        stv<V>(y + r * C + (int64_t)col * V, xv);
+    };
+    constexpr int UR = 4;
+    int64_t r = r0 + ty;
+    for (; r + (int64_t)(UR - 1) * TY < r1; r += (int64_t)UR * TY) {
+        float xv[UR][V];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) ldnt<V>(x + (r + (int64_t)u * TY) * C + (int64_t)col * V, xv[u]);
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            apply(xv[u]);
+            stnt<V>(y + (r + (int64_t)u * TY) * C + (int64_t)col * V, xv[u]);
+        }
+    }
+    for (; r < r1; r += TY) {
+        float xv[V];
+        ldnt<V>(x + r * C + (int64_t)col * V, xv);
+        apply(xv);
+        stnt<V>(y + r * C + (int64_t)col * V, xv);
     }
 }
 
@@ -234,23 +291,46 @@ __global__ __launch_bounds__(BNT) void bn_bwd_apply_kernel(const float *__restri
     }
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
     const int64_t r1 = r0 + rows_per_blk < M ? r0 + rows_per_blk : M;
-    for (int64_t r = r0 + ty; r < r1; r += TY) {
-        float xv[V], dv[V];
-        ldv<V>(x + r * C + (int64_t)col * V, xv);
-        ldv<V>(dy + r * C + (int64_t)col * V, dv);
+    auto grad = [&](const float (&xv)[V], float (&dv)[V]) {
         if (RELU) {
 #pragma unroll
             for (int i = 0; i < V; ++i) dv[i] = bn_val(xv[i], mu[i], a[i], bt[i]) > 0.f ? dv[i] : 0.f;
         }
 #pragma unroll
         for (int i = 0; i < V; ++i) dv[i] = a[i] * (dv[i] - b[i] - (xv[i] - mu[i]) * cc[i]);
+    };
+    constexpr int UR = 2;
+    int64_t r = r0 + ty;
+    for (; r + (int64_t)(UR - 1) * TY < r1; r += (int64_t)UR * TY) {
+        float xv[UR][V], dv[UR][V], ov[UR][V];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            ldnt<V>(x + (r + (int64_t)u * TY) * C + (int64_t)col * V, xv[u]);
+            ldnt<V>(dy + (r + (int64_t)u * TY) * C + (int64_t)col * V, dv[u]);
+            if (ACCUM) ldnt<V>(dx + (r + (int64_t)u * TY) * C + (int64_t)col * V, ov[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            grad(xv[u], dv[u]);
+            if (ACCUM) {
+#pragma unroll
+                for (int i = 0; i < V; ++i) dv[u][i] = ov[u][i] + dv[u][i];
+            }
+            stnt<V>(dx + (r + (int64_t)u * TY) * C + (int64_t)col * V, dv[u]);
+        }
+    }
+    for (; r < r1; r += TY) {
+        float xv[V], dv[V];
+        ldnt<V>(x + r * C + (int64_t)col * V, xv);
+        ldnt<V>(dy + r * C + (int64_t)col * V, dv);
+        grad(xv, dv);
         if (ACCUM) {
             float ov[V];
-            ldv<V>(dx + r * C + (int64_t)col * V, ov);
+            ldnt<V>(dx + r * C + (int64_t)col * V, ov);
 #pragma unroll
             for (int i = 0; i < V; ++i) dv[i] = ov[i] + dv[i];
         }
-        stv<V>(dx + r * C + (int64_t)col * V, dv);
+        stnt<V>(dx + r * C + (int64_t)col * V, dv);
     }
 }
 
@@ -270,40 +350,45 @@ template <int OP> __device__ __forceinline__ float ew(float a, float b, float d)
     }
 }
 
+// One float4 per thread and no loop: many short-lived blocks, each streaming 4 KB per tensor.
 template <int OP>
 __global__ __launch_bounds__(256) void ew_kernel(const float *a, const float *b, float *d, int64_t n)
 {
     constexpr bool USE_B = OP == EW_RELU_B || OP == EW_RELU_B_ACC || OP == EW_ADD || OP == EW_ADD_RELU;
     constexpr bool USE_D = OP == EW_RELU_B_ACC || OP == EW_ACC;
     const int64_t n4 = n / 4;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        const float4 av = reinterpret_cast<const float4 *>(a)[i];
-        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f), dv = bv;
-        if (USE_B) bv = reinterpret_cast<const float4 *>(b)[i];
-        if (USE_D) dv = reinterpret_cast<const float4 *>(d)[i];
-        float4 o;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) {
+        const f32x4 av = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a) + i);
+        f32x4 bv = {0.f, 0.f, 0.f, 0.f}, dv = bv;
+        if (USE_B) bv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(b) + i);
+        if (USE_D) dv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(d) + i);
+        f32x4 o;
         o.x = ew<OP>(av.x, bv.x, dv.x);
         o.y = ew<OP>(av.y, bv.y, dv.y);
         o.z = ew<OP>(av.z, bv.z, dv.z);
         o.w = ew<OP>(av.w, bv.w, dv.w);
-        reinterpret_cast<float4 *>(d)[i] = o;
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(d) + i);
     }
     if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) {
-        const int64_t i = n4 * 4 + threadIdx.x;
-        d[i] = ew<OP>(a[i], USE_B ? b[i] : 0.f, USE_D ? d[i] : 0.f);
+        const int64_t t = n4 * 4 + threadIdx.x;
+        d[t] = ew<OP>(a[t], USE_B ? b[t] : 0.f, USE_D ? d[t] : 0.f);
     }
+}
+
+// blocks of a one-float4-per-thread launch over n floats
+unsigned ew_blocks(int64_t n)
+{
+    const int64_t blocks = (n / 4 + 255) / 256;
+    return (unsigned)(blocks < 1 ? 1 : blocks);
 }
 
 template <int OP> hipError_t launch_ew(const float *a, const float *b, float *d, int64_t n, hipStream_t s)
 {
-    if (n < 0 || !a || !d) return hipErrorInvalidValue;
+    if (n < 0 || n >= ((int64_t)1 << 40) || !a || !d) return hipErrorInvalidValue;
     if (n == 0) return hipSuccess;
     if (((uintptr_t)a | (uintptr_t)b | (uintptr_t)d) % 16 != 0) return hipErrorInvalidValue;
-    int64_t blocks = (n / 4 + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    if (blocks < 1) blocks = 1;
-    ew_kernel<OP><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a, b, d, n);
+    ew_kernel<OP><<<dim3(ew_blocks(n)), dim3(256), 0, s>>>(a, b, d, n);
     return hipGetLastError();
 }
 
@@ -313,25 +398,26 @@ template <int MODE1>
 __global__ __launch_bounds__(256) void addrelu_bwd_kernel(const float *__restrict__ y, float *dy, float *o1, int64_t n)
 {
     const int64_t n4 = n / 4;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        const float4 yv = reinterpret_cast<const float4 *>(y)[i];
-        float4 d = reinterpret_cast<const float4 *>(dy)[i];
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) {
+        const f32x4 yv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(y) + i);
+        f32x4 d = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(dy) + i);
+        f32x4 e = {0.f, 0.f, 0.f, 0.f};
+        if (MODE1 == 2) e = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(o1) + i);
         d.x = yv.x > 0.f ? d.x : 0.f; d.y = yv.y > 0.f ? d.y : 0.f; d.z = yv.z > 0.f ? d.z : 0.f; d.w = yv.w > 0.f ? d.w : 0.f;
-        reinterpret_cast<float4 *>(dy)[i] = d;
-        if (MODE1 == 1) reinterpret_cast<float4 *>(o1)[i] = d;
+        __builtin_nontemporal_store(d, reinterpret_cast<f32x4 *>(dy) + i);
+        if (MODE1 == 1) __builtin_nontemporal_store(d, reinterpret_cast<f32x4 *>(o1) + i);
         if (MODE1 == 2) {
-            float4 e = reinterpret_cast<const float4 *>(o1)[i];
             e.x += d.x; e.y += d.y; e.z += d.z; e.w += d.w;
-            reinterpret_cast<float4 *>(o1)[i] = e;
+            __builtin_nontemporal_store(e, reinterpret_cast<f32x4 *>(o1) + i);
         }
     }
     if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) {
-        const int64_t i = n4 * 4 + threadIdx.x;
-        const float d = y[i] > 0.f ? dy[i] : 0.f;
-        dy[i] = d;
-        if (MODE1 == 1) o1[i] = d;
-        if (MODE1 == 2) o1[i] += d;
+        const int64_t t = n4 * 4 + threadIdx.x;
+        const float d = y[t] > 0.f ? dy[t] : 0.f;
+        dy[t] = d;
+        if (MODE1 == 1) o1[t] = d;
+        if (MODE1 == 2) o1[t] += d;
     }
 }
 
@@ -372,7 +458,7 @@ hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const
 {
     if (!x || !gamma || !beta || !mean || !istd || !y || !bn_args_ok(M, C)) return hipErrorInvalidValue;
     const bool al = ((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma | (uintptr_t)beta | (uintptr_t)mean | (uintptr_t)istd) % 16 == 0;
-    const Lay2D L = layout2d(M, C, al, 8192);
+    const Lay2D L = layout2d(M, C, al, APPLY_BLOCKS, 4);
     const dim3 grid(L.nblk, L.gy), block(BNT);
 #define APPLY(V, R) bn_apply_kernel<V, R><<<grid, block, 0, s>>>(x, gamma, beta, mean, istd, y, M, C, L.TX, L.TY, L.rows_per_blk)
     if (L.V == 4) { if (relu) APPLY(4, true); else APPLY(4, false); }
@@ -417,7 +503,7 @@ hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const flo
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    L = layout2d(M, C, al, 8192);
+    L = layout2d(M, C, al, APPLY_BLOCKS, 4);
     const dim3 grid(L.nblk, L.gy), block(BNT);
     const float inv_m = (float)(1.0 / (double)M);
 #define BWD_APPLY(V, A, R) bn_bwd_apply_kernel<V, A, R><<<grid, block, 0, s>>>(x, dy, gamma, beta, mean, istd, dgamma, dbeta, dx, M, C, L.TX, L.TY, L.rows_per_blk, inv_m)
@@ -447,13 +533,10 @@ hipError_t add_relu_fwd(const float *a, const float *b, float *z, int64_t n, hip
 }
 hipError_t add_relu_bwd(const float *y, float *dy, float *o1, int mode1, int64_t n, hipStream_t s)
 {
-    if (n < 0 || !y || !dy || (mode1 != 0 && !o1) || mode1 < 0 || mode1 > 2) return hipErrorInvalidValue;
+    if (n < 0 || n >= ((int64_t)1 << 40) || !y || !dy || (mode1 != 0 && !o1) || mode1 < 0 || mode1 > 2) return hipErrorInvalidValue;
     if (n == 0) return hipSuccess;
     if (((uintptr_t)y | (uintptr_t)dy | (uintptr_t)o1) % 16 != 0) return hipErrorInvalidValue;
-    int64_t blocks = (n / 4 + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    if (blocks < 1) blocks = 1;
-    const dim3 grid((unsigned)blocks), block(256);
+    const dim3 grid(ew_blocks(n)), block(256);
     if (mode1 == 0) addrelu_bwd_kernel<0><<<grid, block, 0, s>>>(y, dy, o1, n);
     else if (mode1 == 1) addrelu_bwd_kernel<1><<<grid, block, 0, s>>>(y, dy, o1, n);
     else addrelu_bwd_kernel<2><<<grid, block, 0, s>>>(y, dy, o1, n);
