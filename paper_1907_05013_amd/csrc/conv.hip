@@ -59,7 +59,7 @@ __device__ __forceinline__ bool src_coord(int base, int a, int s, int S, int &q)
 // XCDs; give each XCD a contiguous range of tiles so that neighbours share its L2.
 __device__ __forceinline__ int remap_tile(int wg, int chunk) { return (wg % NXCD) * chunk + wg / NXCD; }
 
-template <int WGM, int WGN, int TM, int TN, int BKT, bool VEC, bool LIN, bool DGRAD, bool ACCUM>
+template <int WGM, int WGN, int TM, int TN, int BKT, bool VEC, int LIN, bool DGRAD, bool ACCUM>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 {
     // BKT = reduction slice per main-loop iteration; LDS rows are BKT + 4 floats apart (16-byte
@@ -74,8 +74,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     constexpr int A_S = BM / RPS, B_S = BN / RPS;
     static_assert(NT % KQ == 0 && NT % BKT == 0 && BM % RPS == 0 && BN % RPS == 0, "tile/threads mismatch");
 
-    __shared__ __attribute__((aligned(16))) float As[BM * LDT];
-    __shared__ __attribute__((aligned(16))) float Bs[BN * LDT];
+    // operand tiles during the main loop; afterwards the same memory stages each wavefront's
+    // 32 x (TN*32) accumulator blocks on their way out (row stride CST floats)
+    constexpr int CST = TN * 32 + 4;
+    constexpr int SM_AB = (BM + BN) * LDT, SM_C = WGM * WGN * 32 * CST;
+    __shared__ __attribute__((aligned(16))) float smem[SM_AB > SM_C ? SM_AB : SM_C];
+    float *const As = smem;
+    float *const Bs = smem + BM * LDT;
     __shared__ int4 rowinfo[BM];
     __shared__ int rowdst[BM];
 
@@ -124,15 +129,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     // row i at the current slice is abase[i] + delta, where delta depends only on the slice (scalar
     // unit) and abase[i] is fixed for the tile.  Per slice and row that leaves three coordinate
     // range checks and one 64-bit add on the vector unit -- no multiplies, no divisions.
+    // LIN == 2 (forward only; Cs divides BKT, e.g. a 4-channel first layer): a slice spans BKT / Cs
+    // taps, so the tap belongs to the thread (it is fixed by the thread's k offset) and advances by
+    // BKT / Cs per slice with carries -- still no divisions after the set-up.
     int64_t abase[LIN ? A_V : 1];
     const float *bptr[LIN ? B_V : 1];
     bool brow[LIN ? B_V : 1];
     int ta = 0, tb = 0, te = 0, tc = 0;              // tap (a, b, e) and channel offset of the slice start
+    int pk = vk;                                     // LIN == 2: this thread's position in the reduction
+    if (LIN == 2) {
+        const int tap = vk / p.Cs;
+        te = tap % p.kw;
+        tb = (tap / p.kw) % p.kh;
+        ta = tap / (p.kw * p.kh);
+    }
     if (LIN) {
 #pragma unroll
         for (int i = 0; i < A_V; ++i) {
             const int4 ri = ri_reg[i];
-            abase[i] = ((((int64_t)ri.x * p.Ds + ri.y) * p.Hs + ri.z) * p.Ws + ri.w) * p.Cs + vk;
+            abase[i] = ((((int64_t)ri.x * p.Ds + ri.y) * p.Hs + ri.z) * p.Ws + ri.w) * p.Cs + (LIN == 2 ? vk % p.Cs : vk);
         }
 #pragma unroll
         for (int i = 0; i < B_V; ++i) {
@@ -141,6 +156,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             bptr[i] = p.wgt + (brow[i] ? (int64_t)n * p.Kred + vk : 0);
         }
     }
+    auto load_tiles_tap = [&](bool live) {
+        const bool kok = live & (pk < p.Kred);
+        const int64_t tapoff = (((int64_t)ta * p.Hs + tb) * p.Ws + te) * p.Cs;
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) {
+            const int4 ri = ri_reg[i];
+            const bool ok = kok & (ri.x >= 0) & ((unsigned)(ri.y + ta) < (unsigned)p.Ds) & ((unsigned)(ri.z + tb) < (unsigned)p.Hs) &
+                            ((unsigned)(ri.w + te) < (unsigned)p.Ws);
+            av[i] = *reinterpret_cast<const f32x4 *>(ok ? p.src + (abase[i] + tapoff) : g_zero4);
+        }
+#pragma unroll
+        for (int i = 0; i < B_V; ++i) {
+            const bool ok = kok & brow[i];
+            bv[i] = *reinterpret_cast<const f32x4 *>(ok ? bptr[i] : g_zero4);
+            bptr[i] += BKT;
+        }
+        pk += BKT;
+        te += BKT / p.Cs;
+        while (te >= p.kw) {
+            te -= p.kw;
+            if (++tb == p.kh) {
+                tb = 0;
+                ++ta;
+            }
+        }
+    };
     auto load_tiles_lin = [&](bool live) {
         const int64_t tapoff = (((int64_t)ta * p.Hs + tb) * p.Ws + te) * p.Cs;
         const int64_t delta = (DGRAD ? -tapoff : tapoff) + tc;
@@ -280,12 +321,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     const int r = lane % 32, h = lane / 32;
 
     const int nk = (p.Kred + BKT - 1) / BKT;
-    if (LIN) load_tiles_lin(true);
+    if (LIN == 2) load_tiles_tap(true);
+    else if (LIN) load_tiles_lin(true);
     else load_tiles(0);
     for (int it = 0; it < nk; ++it) {
         store_tiles();
         __syncthreads();
-        if (LIN) load_tiles_lin(it + 1 < nk);          // past the end: every element is masked off
+        if (LIN == 2) load_tiles_tap(it + 1 < nk);
+        else if (LIN) load_tiles_lin(it + 1 < nk);     // past the end: every element is masked off
         else if (VEC) load_tiles((it + 1) * BKT);
         else if (it + 1 < nk) load_tiles((it + 1) * BKT);
 
@@ -335,6 +378,39 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     // A lane therefore owns runs of four consecutive output channels: 16-byte stores (and loads, when
     // accumulating) instead of four scalar ones.
     const bool vec_out = p.Nout % 4 == 0;
+    if (vec_out) {
+        // Through LDS, so that a store instruction of the wavefront covers whole rows of its block
+        // (TN*128 contiguous bytes each) instead of 32-byte pieces of 32 different rows.
+        constexpr int LPR = TN * 8;          // lanes per row, 16 bytes each
+        constexpr int RPI = 64 / LPR;        // rows per store instruction
+        float *cw = smem + wave * 32 * CST;
+        const int orow = lane / LPR, ocol = 4 * (lane % LPR);
+        const int ncol = n0 + wn * TN * 32 + ocol;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 val = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                    *reinterpret_cast<f32x4 *>(&cw[r * CST + j * 32 + 8 * g + 4 * h]) = val;
+                }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < 32 / RPI; ++q) {
+                const int row = q * RPI + orow;
+                const int m = rowdst[wm * TM * 32 + i * 32 + row];
+                if (m >= 0 && ncol < p.Nout) {
+                    f32x4 val = *reinterpret_cast<const f32x4 *>(&cw[row * CST + ocol]);
+                    f32x4 *dp = reinterpret_cast<f32x4 *>(p.dst + (int64_t)m * p.Nout + ncol);
+                    if (ACCUM) val = __builtin_nontemporal_load(dp) + val;
+                    __builtin_nontemporal_store(val, dp);
+                }
+            }
+            if (i + 1 < TM) __syncthreads();
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = rowdst[wm * TM * 32 + i * 32 + r];
@@ -346,29 +422,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int col = cbase + 8 * g;
-                if (vec_out) {
-                    if (col < p.Nout) {
-                        f32x4 val = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        f32x4 *dp = reinterpret_cast<f32x4 *>(drow + col);
-                        if (ACCUM) val = *dp + val;
-                        *dp = val;
-                    }
-                } else {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (col + q < p.Nout) {
-                            float val = acc[i][j][4 * g + q];
-                            if (ACCUM) val = drow[col + q] + val;
-                            drow[col + q] = val;
-                        }
-                }
+                for (int q = 0; q < 4; ++q)
+                    if (col + q < p.Nout) {
+                        float val = acc[i][j][4 * g + q];
+                        if (ACCUM) val = drow[col + q] + val;
+                        drow[col + q] = val;
+                    }
             }
         }
     }
 }
 
 template <int WGM, int WGN, int TM, int TN, int BKT, bool DGRAD>
-hipError_t launch_igemm(IGemmP p, bool vec, bool lin, bool accum, hipStream_t s)
+hipError_t launch_igemm(IGemmP p, bool vec, int lin, bool accum, hipStream_t s)
 {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     const int tiles_m = (p.M + BM - 1) / BM;
@@ -376,33 +443,43 @@ hipError_t launch_igemm(IGemmP p, bool vec, bool lin, bool accum, hipStream_t s)
     p.total_tiles = tiles_m * p.tiles_n;
     p.chunk = (p.total_tiles + NXCD - 1) / NXCD;
     const dim3 grid(p.chunk * NXCD), block(64 * WGM * WGN);
-    if (vec && lin) {
-        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, true, true, DGRAD, true><<<grid, block, 0, s>>>(p);
-        else igemm_kernel<WGM, WGN, TM, TN, BKT, true, true, DGRAD, false><<<grid, block, 0, s>>>(p);
+    if (vec && lin == 2) {
+        if constexpr (!DGRAD) {
+            if (accum) return hipErrorInvalidValue;
+            igemm_kernel<WGM, WGN, TM, TN, BKT, true, 2, false, false><<<grid, block, 0, s>>>(p);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else if (vec && lin) {
+        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, true, 1, DGRAD, true><<<grid, block, 0, s>>>(p);
+        else igemm_kernel<WGM, WGN, TM, TN, BKT, true, 1, DGRAD, false><<<grid, block, 0, s>>>(p);
     } else if (vec) {
-        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, true, false, DGRAD, true><<<grid, block, 0, s>>>(p);
-        else igemm_kernel<WGM, WGN, TM, TN, BKT, true, false, DGRAD, false><<<grid, block, 0, s>>>(p);
+        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, true, 0, DGRAD, true><<<grid, block, 0, s>>>(p);
+        else igemm_kernel<WGM, WGN, TM, TN, BKT, true, 0, DGRAD, false><<<grid, block, 0, s>>>(p);
     } else {
-        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, false, false, DGRAD, true><<<grid, block, 0, s>>>(p);
-        else igemm_kernel<WGM, WGN, TM, TN, BKT, false, false, DGRAD, false><<<grid, block, 0, s>>>(p);
+        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, false, 0, DGRAD, true><<<grid, block, 0, s>>>(p);
+        else igemm_kernel<WGM, WGN, TM, TN, BKT, false, 0, DGRAD, false><<<grid, block, 0, s>>>(p);
     }
     return hipGetLastError();
 }
 
 // the linear fast path of the vector kernel: whole slices per tap; the data gradient also needs unit strides
-template <bool DGRAD>
-bool igemm_linear(const IGemmP &p)
+// 0: general; 1: whole slices per tap (the data gradient also needs unit strides); 2: several
+// whole taps per slice (forward, plain write)
+int igemm_linear_mode(int cs, bool dgrad, bool unit_stride, bool accum)
 {
     static const bool off = getenv("POOCH_NO_LINEAR") != nullptr;
-    if (off || p.Cs % BK != 0) return false;
-    return !DGRAD || (p.sd == 1 && p.sh == 1 && p.sw == 1);
+    if (off || cs % 4 != 0) return 0;
+    if (cs % BK == 0) return (!dgrad || unit_stride) ? 1 : 0;
+    if (BK % cs == 0 && !dgrad && !accum) return 2;
+    return 0;
 }
 
 template <bool DGRAD>
 hipError_t dispatch_igemm(const IGemmP &p, bool accum, hipStream_t s)
 {
     const bool vec = (p.Cs % 4 == 0) && ((uintptr_t)p.src % 16 == 0) && ((uintptr_t)p.wgt % 16 == 0);
-    const bool lin = vec && igemm_linear<DGRAD>(p);
+    const int lin = vec ? igemm_linear_mode(p.Cs, DGRAD, p.sd == 1 && p.sh == 1 && p.sw == 1, accum) : 0;
     // too few 128x128 tiles to fill 256 compute units three workgroups deep: quarter-size tiles
     if (p.Nout > 64 && ((int64_t)(p.M + 127) / 128) * ((p.Nout + 127) / 128) < 640) return launch_igemm<2, 2, 1, 1, BK, DGRAD>(p, vec, lin, accum, s);
     if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s);
@@ -826,24 +903,28 @@ namespace {
 // tag of the igemm instantiation dispatch_igemm() picks: tile shape, load path, direction
 const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgrad)
 {
-    static const char *names[4][3][2] = {
+    static const char *names[4][4][2] = {
         {{"igemm_kernel<4,1,2,1,scalar,fwd>", "igemm_kernel<4,1,2,1,scalar,dgrad>"},
          {"igemm_kernel<4,1,2,1,vec,fwd>", "igemm_kernel<4,1,2,1,vec,dgrad>"},
-         {"igemm_kernel<4,1,2,1,vec+lin,fwd>", "igemm_kernel<4,1,2,1,vec+lin,dgrad>"}},
+         {"igemm_kernel<4,1,2,1,vec+lin,fwd>", "igemm_kernel<4,1,2,1,vec+lin,dgrad>"},
+         {"igemm_kernel<4,1,2,1,vec+tap,fwd>", ""}},
         {{"igemm_kernel<4,1,2,2,scalar,fwd>", "igemm_kernel<4,1,2,2,scalar,dgrad>"},
          {"igemm_kernel<4,1,2,2,vec,fwd>", "igemm_kernel<4,1,2,2,vec,dgrad>"},
-         {"igemm_kernel<4,1,2,2,vec+lin,fwd>", "igemm_kernel<4,1,2,2,vec+lin,dgrad>"}},
+         {"igemm_kernel<4,1,2,2,vec+lin,fwd>", "igemm_kernel<4,1,2,2,vec+lin,dgrad>"},
+         {"igemm_kernel<4,1,2,2,vec+tap,fwd>", ""}},
         {{"igemm_kernel<2,2,2,2,scalar,fwd>", "igemm_kernel<2,2,2,2,scalar,dgrad>"},
          {"igemm_kernel<2,2,2,2,vec,fwd>", "igemm_kernel<2,2,2,2,vec,dgrad>"},
-         {"igemm_kernel<2,2,2,2,vec+lin,fwd>", "igemm_kernel<2,2,2,2,vec+lin,dgrad>"}},
+         {"igemm_kernel<2,2,2,2,vec+lin,fwd>", "igemm_kernel<2,2,2,2,vec+lin,dgrad>"},
+         {"igemm_kernel<2,2,2,2,vec+tap,fwd>", ""}},
         {{"igemm_kernel<2,2,1,1,scalar,fwd>", "igemm_kernel<2,2,1,1,scalar,dgrad>"},
          {"igemm_kernel<2,2,1,1,vec,fwd>", "igemm_kernel<2,2,1,1,vec,dgrad>"},
-         {"igemm_kernel<2,2,1,1,vec+lin,fwd>", "igemm_kernel<2,2,1,1,vec+lin,dgrad>"}}};
+         {"igemm_kernel<2,2,1,1,vec+lin,fwd>", "igemm_kernel<2,2,1,1,vec+lin,dgrad>"},
+         {"igemm_kernel<2,2,1,1,vec+tap,fwd>", ""}}};
     int tile = nout <= 32 ? 0 : (nout <= 64 ? 1 : 2);
     if (nout > 64 && ((rows + 127) / 128) * ((nout + 127) / 128) < 640) tile = 3;
     const bool vec = cs % 4 == 0;
-    const bool lin = vec && cs % BK == 0 && (!dgrad || unit_stride) && getenv("POOCH_NO_LINEAR") == nullptr;
-    return names[tile][lin ? 2 : (vec ? 1 : 0)][dgrad ? 1 : 0];
+    const int lin = vec ? igemm_linear_mode(cs, dgrad, unit_stride, false) : 0;
+    return names[tile][lin ? 1 + lin : (vec ? 1 : 0)][dgrad ? 1 : 0];
 }
 }  // namespace
 
