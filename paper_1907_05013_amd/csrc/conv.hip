@@ -487,20 +487,19 @@ hipError_t dispatch_igemm(const IGemmP &p, bool accum, hipStream_t s)
     return launch_igemm<2, 2, 2, 2, BK, DGRAD>(p, vec, lin, accum, s);
 }
 
+// one float4 per thread, no loop: short-lived blocks stream closest to the HBM peak
 __global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, int64_t n)
 {
     const int64_t n4 = n / 4;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
-        reinterpret_cast<float4 *>(p)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) __builtin_nontemporal_store(f32x4{0.f, 0.f, 0.f, 0.f}, reinterpret_cast<f32x4 *>(p) + i);
     if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) p[n4 * 4 + threadIdx.x] = 0.f;
 }
 
 hipError_t fill_zero(float *p, int64_t n, hipStream_t s)
 {
-    if ((uintptr_t)p % 16 != 0) return hipErrorInvalidValue;
+    if ((uintptr_t)p % 16 != 0 || n < 0 || n >= ((int64_t)1 << 40)) return hipErrorInvalidValue;
     int64_t blocks = (n / 4 + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
     fill_zero_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(p, n);
     return hipGetLastError();
@@ -532,6 +531,7 @@ struct WGradP {
     int Do, Ho, Wo, D, H, W;
     int kd, kh, kw, sd, sh, sw, pd, ph, pw;
     int tiles_n, chunk_rows, nsplit;
+    int tiles, total, chunk;  // tiles per split, workgroups that have work, workgroups per XCD
 };
 
 template <int WGM, int WGN, int TM, int TN, bool VECA, bool VECB>
@@ -542,6 +542,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
     constexpr int LDA = (BM + 63) / 64 * 64 + 32, LDB = (BN + 63) / 64 * 64 + 32;
     constexpr int A_V = 4 * BM / NT, B_V = 4 * BN / NT, A_S = 16 * BM / NT, B_S = 16 * BN / NT;
     static_assert(4 * BM % NT == 0 && 4 * BN % NT == 0, "tile/threads mismatch");
+    // the vector paths give every thread one fixed column of each operand for all its passes
+    static_assert(NT % (BM / 4) == 0 && NT % (BN / 4) == 0, "a thread's column must not depend on the pass");
 
     __shared__ __attribute__((aligned(16))) float As[BK * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
@@ -554,9 +556,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
     __shared__ int64_t rowb[TAB ? SEG : 1];
 
     const int tid = threadIdx.x;
-    const int k0 = (blockIdx.x / p.tiles_n) * BM;  // first output channel of the tile
-    const int j0 = (blockIdx.x % p.tiles_n) * BN;  // first (tap, c) column of the tile
-    const int split = blockIdx.y;
+    // all tiles of one split run next to each other on one XCD: they stream the same rows of dy and
+    // (shifted by a tap) of x, which its L2 then fetches once instead of once per tile
+    const int logical = remap_tile(blockIdx.x, p.chunk);
+    if (logical >= p.total) return;
+    const int tile = logical % p.tiles, split = logical / p.tiles;
+    const int k0 = (tile / p.tiles_n) * BM;  // first output channel of the tile
+    const int j0 = (tile % p.tiles_n) * BN;  // first (tap, c) column of the tile
     const int mbeg = split * p.chunk_rows;
     const int mend = min(p.M, mbeg + p.chunk_rows);
 
@@ -818,10 +824,11 @@ WGradCfg wgrad_cfg(const ConvGeom &g)
     WGradCfg c;
     const int64_t M = g.rows_out(), Kred = g.taps() * g.C;
     c.bm = g.K <= 32 ? 32 : (g.K <= 64 ? 64 : 128);
-    // few output channels: 64-wide column tiles keep four waves per workgroup busy.  Measured on the
-    // 64-channel ResNet-50 layers: 1.76 ms against 2.16 ms (128 wide) and 2.15 ms (256 wide) although dy is
-    // re-read once per column tile; not for the stem, whose 4-channel taps gather 16 bytes at a time
-    c.bn = (Kred <= 64 || (g.K <= 64 && g.C % 16 == 0)) ? 64 : 128;
+    // column tiles: 128 wide; 64 when that already covers the row, and for few output channels under
+    // several 16-channel-aligned taps.  Measured on the 64-output-channel ResNet-50 layers at batch 640:
+    // 1x1 256->64 0.62 ms at 128 (four waves of 32 x 64) against 0.70 ms at 64; 3x3 64->64 1.90 ms at 64
+    // against 1.96 ms at 128; the 4-channel stem 2.5 ms with four waves of 32 x 64 against 3.5 ms with two of 64 x 64
+    c.bn = (Kred <= 64 || (g.K <= 64 && g.C % 16 == 0 && g.taps() > 1)) ? 64 : 128;
     const int64_t tiles = ((g.K + c.bm - 1) / c.bm) * ((Kred + c.bn - 1) / c.bn);
     // enough workgroups to fill 256 compute units several times over, but each split keeps at
     // least 256 rows so that its epilogue (a full tile written to the workspace) stays small
@@ -844,7 +851,10 @@ hipError_t launch_wgrad(WGradP p, bool veca, bool vecb, hipStream_t s)
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     const int tiles_m = (p.K + BM - 1) / BM;
     p.tiles_n = (p.Kred + BN - 1) / BN;
-    const dim3 grid(tiles_m * p.tiles_n, p.nsplit), block(64 * WGM * WGN);
+    p.tiles = tiles_m * p.tiles_n;
+    p.total = p.tiles * p.nsplit;
+    p.chunk = (p.total + NXCD - 1) / NXCD;
+    const dim3 grid(p.chunk * NXCD), block(64 * WGM * WGN);
     if (veca && vecb) wgrad_kernel<WGM, WGN, TM, TN, true, true><<<grid, block, 0, s>>>(p);
     else if (veca) wgrad_kernel<WGM, WGN, TM, TN, true, false><<<grid, block, 0, s>>>(p);
     else if (vecb) wgrad_kernel<WGM, WGN, TM, TN, false, true><<<grid, block, 0, s>>>(p);
@@ -940,7 +950,7 @@ const char *conv_wgrad_kernel(const ConvGeom &g)
 {
     const WGradCfg c = wgrad_cfg(g);
     if (c.bn == 64) return c.bm == 32 ? "wgrad_kernel<1,2,1,1>" : (c.bm == 64 ? "wgrad_kernel<2,2,1,1>" : "wgrad_kernel<2,2,2,1>");
-    return c.bm == 32 ? "wgrad_kernel<1,2,1,2>" : (c.bm == 64 ? "wgrad_kernel<1,2,2,2>" : "wgrad_kernel<2,2,2,2>");
+    return c.bm == 32 ? "wgrad_kernel<1,2,1,2>" : (c.bm == 64 ? "wgrad_kernel<2,2,1,2>" : "wgrad_kernel<2,2,2,2>");
 }
 
 size_t conv_wgrad_workspace(const ConvGeom &g)
@@ -970,7 +980,7 @@ hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *wo
         else e = launch_wgrad<2, 2, 2, 1>(p, veca, vecb, s);
     } else {
         if (c.bm == 32) e = launch_wgrad<1, 2, 1, 2>(p, veca, vecb, s);
-        else if (c.bm == 64) e = launch_wgrad<1, 2, 2, 2>(p, veca, vecb, s);
+        else if (c.bm == 64) e = launch_wgrad<2, 2, 1, 2>(p, veca, vecb, s);
         else e = launch_wgrad<2, 2, 2, 2>(p, veca, vecb, s);
     }
     if (e != hipSuccess) return e;
