@@ -197,6 +197,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="resnet50_b640_16g", choices=sorted(WORKLOADS))
     ap.add_argument("--budget-gib", type=float, default=None)
+    ap.add_argument("--batch", type=int, default=None,
+                    help="override the workload's batch size (the paper's batch sweep: --batch 64 ... 640 under the same arena)")
     ap.add_argument("--mode", default="refine", choices=["swapall_nosched", "swapall", "swapopt", "pooch", "refine"],
                     help="planner whose step is reported as `value`; refine = the paper's two steps + local search")
     ap.add_argument("--bits", type=int, default=4, help="cap on the exponential part of the keep/swap search")
@@ -218,6 +220,10 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
 
     cfg, kw, budget = WORKLOADS[args.workload]
+    if args.batch is not None:
+        if args.batch < 1:
+            sys.exit("bench.py: --batch must be positive")
+        kw = dict(kw, batch=args.batch)
     net, seed = workloads.load(cfg, **kw)
     batch = net[0]["shape"][0]
     params = workloads.make_params(net, seed)
@@ -327,7 +333,8 @@ def main():
         "ms_per_step": sec * 1e3,
         "higher_is_better": True,
         "scaling": "weak",
-        "vs_baseline": (batch / sec) / PAPER_B640_IMG_S if args.workload == "resnet50_b640_16g" else None,
+        "vs_baseline": (batch / sec) / PAPER_B640_IMG_S if (args.workload == "resnet50_b640_16g" and batch == 640 and
+                                                              abs(arena_bytes - 16 * 2 ** 30) < 2 ** 20) else None,
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "batch": batch, "arena_GiB": arena_bytes / 2 ** 30,
