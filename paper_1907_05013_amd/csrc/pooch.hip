@@ -675,7 +675,7 @@ pooch_status pooch_finalize(pooch_ctx *c)
     int64_t off = 0;
     auto take = [&](int64_t bytes) { const int64_t o = off; off += round_up(bytes); return o; };
     c->in_cdev = (int)G.nodes[0].C;
-    if (G.nodes[0].C == 3) {
+    if (G.nodes[0].C < 4) {   // one to three input channels: stored with zero channels up to four (16-byte taps)
         bool only_convs = true;
         for (int u : G.consumers[0]) only_convs = only_convs && G.nodes[u].op == OP_CONV;
         if (only_convs) c->in_cdev = 4;

@@ -242,17 +242,23 @@ __global__ __launch_bounds__(256) void maxpool_tiled_bwd_kernel(const float *__r
             }
 }
 
-// y[n][c] = (1/S) sum_s x[n][s][c], s ascending
+// y[n][c] = (1/S) sum_s x[n][s][c].  One block per (image, 64 channels): four wavefronts take every
+// fourth position each (ascending), and the four partial sums are added in a fixed order.
 __global__ __launch_bounds__(256) void gavgpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int N, int64_t S, int C)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (int64_t)N * C) return;
-    const int c = (int)(i % C);
-    const int64_t n = i / C;
-    const float *p = x + n * S * C + c;
+    __shared__ float part[4][64];
+    const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+    const int cblocks = (C + 63) / 64;
+    const int64_t n = blockIdx.x / cblocks;
+    const int c = (int)(blockIdx.x % cblocks) * 64 + lane;
     float s = 0.f;
-    for (int64_t k = 0; k < S; ++k) s += p[k * C];
-    y[i] = s / (float)S;
+    if (c < C) {
+        const float *p = x + n * S * C + c;
+        for (int64_t k = w; k < S; k += 4) s += p[k * C];
+    }
+    part[w][lane] = s;
+    __syncthreads();
+    if (w == 0 && c < C) y[n * C + c] = (((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]) / (float)S;
 }
 
 template <bool ACCUM>
@@ -405,7 +411,7 @@ hipError_t maxpool_bwd(const float *x, const float *dy, float *dx, const PoolGeo
 hipError_t gavgpool_fwd(const float *x, float *y, int N, int64_t S, int C, hipStream_t s)
 {
     if (!x || !y || N <= 0 || S <= 0 || C <= 0) return hipErrorInvalidValue;
-    gavgpool_fwd_kernel<<<blocks_for((int64_t)N * C), dim3(256), 0, s>>>(x, y, N, S, C);
+    gavgpool_fwd_kernel<<<dim3((unsigned)((int64_t)N * ((C + 63) / 64))), dim3(256), 0, s>>>(x, y, N, S, C);
     return hipGetLastError();
 }
 
