@@ -141,14 +141,15 @@ def kernel_report(ctx, net, ms, nrefwd_counts=None):
             conv_flops += fl * n
             conv_ms += refwd[i]
     # algorithmic bytes per element: BN (alone or with a fused ReLU) forward 12 (x for the statistics,
-    # x again, y), backward 20 (x and dy twice, dx), re-forward 8; ReLU 8 / 12; add 12;
+    # x again, y) or 8 when the producing conv supplies the statistics, backward 20 (x and dy twice, dx),
+    # re-forward 8; ReLU 8 / 12; add 12;
     # add + ReLU fused: forward 12, backward 12 (y, dy, masked dy) + 4 or 8 for a second output
     fused = {ctx.node_fused(i): L["op"] for i, L in enumerate(net) if ctx.node_fused(i) >= 0}
     bn_bytes = bn_ms = ew_bytes = ew_ms = 0.0
     for i, L in enumerate(net):
         nre = max(1, int(round(refwd[i] / max(fwd[i], 1e-9)))) if refwd[i] > 0 else 0
         if (L["op"] == "bn" and ctx.node_fused(i) < 0) or fused.get(i) == "bn":
-            bn_bytes += (12 + 20 + 8 * nre) * n_el[i]
+            bn_bytes += ((8 if ctx.bn_stats_source(i) >= 0 else 12) + 20 + 8 * nre) * n_el[i]
             bn_ms += fwd[i] + bwd[i] + refwd[i]
         elif L["op"] == "relu" and fused.get(i) == "add":
             ew_bytes += (12 + 16 + 12 * nre) * n_el[i]

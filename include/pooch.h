@@ -104,6 +104,13 @@ int32_t pooch_softmax_ce(pooch_ctx *, int32_t logits);
  * pooch_node_fused: id of the relu a layer was fused into, -1 if it executes on its own. */
 pooch_status pooch_set_fusion(pooch_ctx *, int enable);
 int32_t pooch_node_fused(pooch_ctx *, int32_t id);
+/* A convolution whose result goes directly into a batch normalisation also produces that
+ * layer's batch statistics while its results are still on chip, which saves the normalisation
+ * one of its three passes over the tensor (section 3.3 counts these layers as pure memory
+ * traffic).  pooch_bn_stats_source: id of the conv that supplies layer `id`'s statistics in a
+ * forward pass, -1 if the layer reads its input for them itself (also for ids that are no bn).
+ * A re-forward in backward always re-applies the saved statistics. */
+int32_t pooch_bn_stats_source(pooch_ctx *, int32_t id);
 /* Freezes the graph: shapes, liveness, the feature-map list (every tensor some backward
  * reads, except the network input, which is caller data and stays resident), the parameter
  * list and the layout of the resident region at the bottom of the arena.

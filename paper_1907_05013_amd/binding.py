@@ -53,6 +53,7 @@ SYMBOLS = {
     "pooch_softmax_ce": (_i32, [_ctx, _i32]),
     "pooch_set_fusion": (_i32, [_ctx, C.c_int]),
     "pooch_node_fused": (_i32, [_ctx, _i32]),
+    "pooch_bn_stats_source": (_i32, [_ctx, _i32]),
     "pooch_finalize": (_i32, [_ctx]),
     "pooch_num_params": (_i32, [_ctx]),
     "pooch_param_info": (_i32, [_ctx, _i32, _pi64, _pi32]),
@@ -245,6 +246,10 @@ class Context:
     def node_fused(self, node):
         """id of the relu this layer is executed in, or -1"""
         return self.L.pooch_node_fused(self.h, node)
+
+    def bn_stats_source(self, node):
+        """id of the conv whose forward also produces this bn layer's batch statistics, or -1"""
+        return self.L.pooch_bn_stats_source(self.h, node)
 
     # ---- parameters and data
     def param_info(self, i):

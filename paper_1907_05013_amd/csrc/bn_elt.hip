@@ -199,6 +199,80 @@ __global__ __launch_bounds__(64) void bn_stats_final_kernel(const float *__restr
     }
 }
 
+// Statistics from per-tile (mean, M2) pairs: each lane merges every 64th tile in ascending order,
+// then the 64 lane results are merged pairwise in a fixed tree -- all in double, by the update
+// n = na + nb, d = mb - ma, mean = ma + d nb / n, M2 = M2a + M2b + d^2 na nb / n.
+__global__ __launch_bounds__(64) void bn_tiles_final_kernel(const float *__restrict__ tiles, float *__restrict__ mean,
+                                                             float *__restrict__ istd, int tiles_m, int rows_per_tile, int64_t M,
+                                                             int C, double eps)
+{
+    const int c = blockIdx.x, lane = threadIdx.x;
+    double n = 0.0, mu = 0.0, m2 = 0.0;
+    for (int t = lane; t < tiles_m; t += 64) {
+        int64_t rows = M - (int64_t)t * rows_per_tile;
+        if (rows > rows_per_tile) rows = rows_per_tile;
+        if (rows <= 0) continue;
+        const double nb = (double)rows, mb = (double)tiles[((int64_t)t * 2 + 0) * C + c], qb = (double)tiles[((int64_t)t * 2 + 1) * C + c];
+        const double tot = n + nb, d = mb - mu;
+        mu += d * (nb / tot);
+        m2 += qb + d * d * (n * nb / tot);
+        n = tot;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double nb = __shfl_down(n, off, 64), mb = __shfl_down(mu, off, 64), qb = __shfl_down(m2, off, 64);
+        if (nb > 0.0) {
+            const double tot = n + nb, d = mb - mu;
+            mu += d * (nb / tot);
+            m2 += qb + d * d * (n * nb / tot);
+            n = tot;
+        }
+    }
+    if (lane == 0) {
+        double var = m2 / (double)M;
+        if (var < 0.0) var = 0.0;
+        mean[c] = (float)mu;
+        istd[c] = (float)(1.0 / sqrt(var + eps));
+    }
+}
+
+// Coarsening of per-tile statistics: `group` consecutive tiles become one (the last group and the
+// last tile may be short).  One block per (group, 64 channels); the four wavefronts take every
+// fourth tile of the group.  Two passes over the few values involved, in double: the group's
+// mean, then M2 = sum of (M2_t + n_t (mean_t - mean)^2); partial sums are combined in wavefront order.
+__global__ __launch_bounds__(256) void bn_tiles_group_kernel(const float *__restrict__ tiles, float *__restrict__ out, int tiles_m,
+                                                              int rows_per_tile, int group, int64_t M, int C)
+{
+    __shared__ double red[4][64];
+    const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+    const int c = blockIdx.y * 64 + lane;
+    const int t0 = blockIdx.x * group, t1 = min(tiles_m, t0 + group);
+    const bool live = c < C;
+    auto rows_of = [&](int t) {
+        int64_t rows = M - (int64_t)t * rows_per_tile;
+        return (double)(rows > rows_per_tile ? rows_per_tile : (rows < 0 ? 0 : rows));
+    };
+    double s = 0.0;
+    if (live)
+        for (int t = t0 + w; t < t1; t += 4) s += rows_of(t) * (double)tiles[((int64_t)t * 2 + 0) * C + c];
+    red[w][lane] = s;
+    __syncthreads();
+    const double ng = rows_of(t0) + (t1 - t0 > 1 ? (double)(t1 - t0 - 2) * rows_per_tile + rows_of(t1 - 1) : 0.0);
+    const double mu = ng > 0.0 ? (((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane]) / ng : 0.0;
+    __syncthreads();
+    double q = 0.0;
+    for (int t = t0 + w; live && t < t1; t += 4) {
+        const double nt = rows_of(t), d = (double)tiles[((int64_t)t * 2 + 0) * C + c] - mu;
+        q += (double)tiles[((int64_t)t * 2 + 1) * C + c] + nt * d * d;
+    }
+    red[w][lane] = q;
+    __syncthreads();
+    if (w == 0 && live) {
+        out[((int64_t)blockIdx.x * 2 + 0) * C + c] = (float)mu;
+        out[((int64_t)blockIdx.x * 2 + 1) * C + c] = (float)(((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane]);
+    }
+}
+
 __global__ __launch_bounds__(64) void bn_grad_final_kernel(const float *__restrict__ part, const float *__restrict__ istd,
                                                             float *__restrict__ dgamma, float *__restrict__ dbeta,
                                                             int nblk, int C)
@@ -446,6 +520,19 @@ bool bn_args_ok(int64_t M, int C) { return M > 0 && C > 0 && M * (int64_t)C < ((
 
 }  // namespace
 
+namespace {
+// tiles folded into one before the final per-channel merge (1: none)
+int bn_tiles_group(int tiles_m) { return tiles_m > 1024 ? (tiles_m + 511) / 512 : 1; }
+}  // namespace
+
+size_t bn_tiles_workspace_floats(int tiles_m, int C)
+{
+    if (tiles_m <= 0 || C <= 0) return 0;
+    const int group = bn_tiles_group(tiles_m);
+    const size_t groups = group > 1 ? (size_t)(tiles_m + group - 1) / group : 0;
+    return (size_t)2 * C * ((size_t)tiles_m + groups);
+}
+
 size_t bn_workspace_floats(int64_t M, int C)
 {
     if (!bn_args_ok(M, C)) return 0;
@@ -480,6 +567,29 @@ hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *
     if (e != hipSuccess) return e;
     bn_stats_final_kernel<<<dim3(C), dim3(64), 0, s>>>(ws, x, mean, istd, L.nblk, C, (double)M, (double)eps);
     e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return bn_apply(x, gamma, beta, mean, istd, y, M, C, relu, s);
+}
+
+hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
+                             float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, bool relu, hipStream_t s)
+{
+    if (!x || !gamma || !beta || !y || !mean || !istd || !tiles || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    if (tiles_m <= 0 || rows_per_tile <= 0 || (int64_t)tiles_m * rows_per_tile < M || (int64_t)(tiles_m - 1) * rows_per_tile >= M)
+        return hipErrorInvalidValue;
+    const int group = bn_tiles_group(tiles_m);
+    if (group > 1) {
+        // many tiles: first fold groups of them, so that the per-channel wavefronts below have little to walk
+        const int groups = (tiles_m + group - 1) / group;
+        float *folded = tiles + (size_t)2 * tiles_m * C;
+        bn_tiles_group_kernel<<<dim3(groups, (C + 63) / 64), dim3(256), 0, s>>>(tiles, folded, tiles_m, rows_per_tile, group, M, C);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        bn_tiles_final_kernel<<<dim3(C), dim3(64), 0, s>>>(folded, mean, istd, groups, rows_per_tile * group, M, C, (double)eps);
+    } else {
+        bn_tiles_final_kernel<<<dim3(C), dim3(64), 0, s>>>(tiles, mean, istd, tiles_m, rows_per_tile, M, C, (double)eps);
+    }
+    const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return bn_apply(x, gamma, beta, mean, istd, y, M, C, relu, s);
 }

@@ -30,6 +30,7 @@ struct IGemmP {
     const float *src;  // forward: x; data gradient: dy (channels-last)
     const float *wgt;  // [Nout][Kred]
     float *dst;        // [M][Nout]
+    float *stats;      // STATS kernels: per row tile, mean[Nout] then M2[Nout] of the tile's rows of dst
     int M, Nout, Kred, Cs;
     int Dr, Hr, Wr;  // spatial dims the GEMM rows enumerate
     int Ds, Hs, Ws;  // spatial dims of src
@@ -59,7 +60,7 @@ __device__ __forceinline__ bool src_coord(int base, int a, int s, int S, int &q)
 // XCDs; give each XCD a contiguous range of tiles so that neighbours share its L2.
 __device__ __forceinline__ int remap_tile(int wg, int chunk) { return (wg % NXCD) * chunk + wg / NXCD; }
 
-template <int WGM, int WGN, int TM, int TN, int BKT, bool VEC, int LIN, bool DGRAD, bool ACCUM>
+template <int WGM, int WGN, int TM, int TN, int BKT, bool VEC, int LIN, bool DGRAD, bool ACCUM, bool STATS = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 {
     // BKT = reduction slice per main-loop iteration; LDS rows are BKT + 4 floats apart (16-byte
@@ -383,9 +384,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
         // (TN*128 contiguous bytes each) instead of 32-byte pieces of 32 different rows.
         constexpr int LPR = TN * 8;          // lanes per row, 16 bytes each
         constexpr int RPI = 64 / LPR;        // rows per store instruction
+        constexpr int NQ = 32 / RPI;
         float *cw = smem + wave * 32 * CST;
         const int orow = lane / LPR, ocol = 4 * (lane % LPR);
         const int ncol = n0 + wn * TN * 32 + ocol;
+        // STATS: count, mean and sum of squared deviations (M2) of this lane's four columns over the
+        // rows this wavefront has written so far.  Per 32-row block: mean, then M2 about that mean
+        // (no cancellation), merged into the running triple by the pairwise update of Chan et al.
+        float rn = 0.f;
+        f32x4 rmean = {0.f, 0.f, 0.f, 0.f}, rm2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -396,18 +403,88 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
                     *reinterpret_cast<f32x4 *>(&cw[r * CST + j * 32 + 8 * g + 4 * h]) = val;
                 }
             __syncthreads();
+            f32x4 vq[STATS ? NQ : 1];
+            bool okq[STATS ? NQ : 1];
 #pragma unroll
-            for (int q = 0; q < 32 / RPI; ++q) {
+            for (int q = 0; q < NQ; ++q) {
                 const int row = q * RPI + orow;
                 const int m = rowdst[wm * TM * 32 + i * 32 + row];
+                f32x4 val = *reinterpret_cast<const f32x4 *>(&cw[row * CST + ocol]);
+                if constexpr (STATS) {
+                    vq[q] = val;
+                    okq[q] = m >= 0;
+                }
                 if (m >= 0 && ncol < p.Nout) {
-                    f32x4 val = *reinterpret_cast<const f32x4 *>(&cw[row * CST + ocol]);
                     f32x4 *dp = reinterpret_cast<f32x4 *>(p.dst + (int64_t)m * p.Nout + ncol);
                     if (ACCUM) val = __builtin_nontemporal_load(dp) + val;
                     __builtin_nontemporal_store(val, dp);
                 }
             }
-            if (i + 1 < TM) __syncthreads();
+            if constexpr (STATS) {
+                // rows that exist form a prefix of the block
+                int nb = p.M - (m0 + (wm * TM + i) * 32);
+                nb = nb < 0 ? 0 : (nb > 32 ? 32 : nb);
+                if (nb > 0) {   // uniform over the wavefront
+                    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q)
+                        if (okq[q]) sum += vq[q];
+#pragma unroll
+                    for (int mask = LPR; mask < 64; mask <<= 1) {
+                        sum.x += __shfl_xor(sum.x, mask, 64); sum.y += __shfl_xor(sum.y, mask, 64);
+                        sum.z += __shfl_xor(sum.z, mask, 64); sum.w += __shfl_xor(sum.w, mask, 64);
+                    }
+                    const float nbf = (float)nb;
+                    const f32x4 mb = sum / nbf;
+                    f32x4 d2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q)
+                        if (okq[q]) {
+                            const f32x4 d = vq[q] - mb;
+                            d2 += d * d;
+                        }
+#pragma unroll
+                    for (int mask = LPR; mask < 64; mask <<= 1) {
+                        d2.x += __shfl_xor(d2.x, mask, 64); d2.y += __shfl_xor(d2.y, mask, 64);
+                        d2.z += __shfl_xor(d2.z, mask, 64); d2.w += __shfl_xor(d2.w, mask, 64);
+                    }
+                    const float tot = rn + nbf;
+                    const f32x4 delta = mb - rmean;
+                    rmean += delta * (nbf / tot);
+                    rm2 += d2 + delta * delta * (rn * nbf / tot);
+                    rn = tot;
+                }
+            }
+            if (i + 1 < TM || STATS) __syncthreads();
+        }
+        if constexpr (STATS) {
+            // the wavefronts that share these columns (same wn) are merged in wm order by the first
+            float *sm = smem;   // [wave][mean, M2][TN * 32]
+            if (orow == 0) {
+                *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 0) * TN * 32 + ocol]) = rmean;
+                *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 1) * TN * 32 + ocol]) = rm2;
+            }
+            __syncthreads();
+            if (wm == 0 && orow == 0 && ncol < p.Nout) {
+#pragma unroll
+                for (int w2 = 1; w2 < WGM; ++w2) {
+                    int nb = p.M - (m0 + w2 * TM * 32);
+                    nb = nb < 0 ? 0 : (nb > TM * 32 ? TM * 32 : nb);
+                    if (nb > 0) {
+                        const int ow = w2 * WGN + wn;
+                        const f32x4 mb = *reinterpret_cast<const f32x4 *>(&sm[(ow * 2 + 0) * TN * 32 + ocol]);
+                        const f32x4 d2 = *reinterpret_cast<const f32x4 *>(&sm[(ow * 2 + 1) * TN * 32 + ocol]);
+                        const float nbf = (float)nb, tot = rn + nbf;
+                        const f32x4 delta = mb - rmean;
+                        rmean += delta * (nbf / tot);
+                        rm2 += d2 + delta * delta * (rn * nbf / tot);
+                        rn = tot;
+                    }
+                }
+                const int64_t tm = m0 / BM;
+                *reinterpret_cast<f32x4 *>(p.stats + (tm * 2 + 0) * p.Nout + ncol) = rmean;
+                *reinterpret_cast<f32x4 *>(p.stats + (tm * 2 + 1) * p.Nout + ncol) = rm2;
+            }
         }
         return;
     }
@@ -435,7 +512,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 }
 
 template <int WGM, int WGN, int TM, int TN, int BKT, bool DGRAD>
-hipError_t launch_igemm(IGemmP p, bool vec, int lin, bool accum, hipStream_t s)
+hipError_t launch_igemm(IGemmP p, bool vec, int lin, bool accum, hipStream_t s, int *stats_tiles = nullptr)
 {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     const int tiles_m = (p.M + BM - 1) / BM;
@@ -443,7 +520,20 @@ hipError_t launch_igemm(IGemmP p, bool vec, int lin, bool accum, hipStream_t s)
     p.total_tiles = tiles_m * p.tiles_n;
     p.chunk = (p.total_tiles + NXCD - 1) / NXCD;
     const dim3 grid(p.chunk * NXCD), block(64 * WGM * WGN);
-    if (vec && lin == 2) {
+    if (stats_tiles) {   // layout query of the statistics a STATS launch writes: row tiles, rows per tile
+        stats_tiles[0] = tiles_m;
+        stats_tiles[1] = BM;
+        return hipSuccess;
+    }
+    if (p.stats) {
+        if constexpr (!DGRAD) {
+            if (!vec || lin == 0 || accum || p.dst_strided || p.Nout % 4 != 0) return hipErrorInvalidValue;
+            if (lin == 2) igemm_kernel<WGM, WGN, TM, TN, BKT, true, 2, false, false, true><<<grid, block, 0, s>>>(p);
+            else igemm_kernel<WGM, WGN, TM, TN, BKT, true, 1, false, false, true><<<grid, block, 0, s>>>(p);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else if (vec && lin == 2) {
         if constexpr (!DGRAD) {
             if (accum) return hipErrorInvalidValue;
             igemm_kernel<WGM, WGN, TM, TN, BKT, true, 2, false, false><<<grid, block, 0, s>>>(p);
@@ -476,15 +566,15 @@ int igemm_linear_mode(int cs, bool dgrad, bool unit_stride, bool accum)
 }
 
 template <bool DGRAD>
-hipError_t dispatch_igemm(const IGemmP &p, bool accum, hipStream_t s)
+hipError_t dispatch_igemm(const IGemmP &p, bool accum, hipStream_t s, int *stats_tiles = nullptr)
 {
     const bool vec = (p.Cs % 4 == 0) && ((uintptr_t)p.src % 16 == 0) && ((uintptr_t)p.wgt % 16 == 0);
     const int lin = vec ? igemm_linear_mode(p.Cs, DGRAD, p.sd == 1 && p.sh == 1 && p.sw == 1, accum) : 0;
     // too few 128x128 tiles to fill 256 compute units three workgroups deep: quarter-size tiles
-    if (p.Nout > 64 && ((int64_t)(p.M + 127) / 128) * ((p.Nout + 127) / 128) < 640) return launch_igemm<2, 2, 1, 1, BK, DGRAD>(p, vec, lin, accum, s);
-    if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s);
-    if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, BK, DGRAD>(p, vec, lin, accum, s);
-    return launch_igemm<2, 2, 2, 2, BK, DGRAD>(p, vec, lin, accum, s);
+    if (p.Nout > 64 && ((int64_t)(p.M + 127) / 128) * ((p.Nout + 127) / 128) < 640) return launch_igemm<2, 2, 1, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
+    if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
+    if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
+    return launch_igemm<2, 2, 2, 2, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
 }
 
 // one float4 per thread, no loop: short-lived blocks stream closest to the HBM peak
@@ -865,15 +955,41 @@ hipError_t launch_wgrad(WGradP p, bool veca, bool vecb, hipStream_t s)
 
 }  // namespace
 
-hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s)
+namespace {
+IGemmP fwd_params(const float *x, const float *w_krsc, float *y, const ConvGeom &g)
 {
-    if (!x || !w_krsc || !y || !geom_ok(g)) return hipErrorInvalidValue;
     IGemmP p;
-    p.src = x; p.wgt = w_krsc; p.dst = y;
+    p.src = x; p.wgt = w_krsc; p.dst = y; p.stats = nullptr;
     p.M = (int)g.rows_out(); p.Nout = g.K; p.Kred = (int)(g.taps() * g.C); p.Cs = g.C;
     p.Dr = g.Do; p.Hr = g.Ho; p.Wr = g.Wo; p.Ds = g.D; p.Hs = g.H; p.Ws = g.W;
     p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
     p.dst_strided = 0; p.DD = p.HD = p.WD = p.SD = p.SH = p.SW = 0;
+    return p;
+}
+}  // namespace
+
+bool conv_fwd_bn_tiles(const float *x, const float *w_krsc, const ConvGeom &g, int *tiles_m, int *rows_per_tile)
+{
+    if (!geom_ok(g) || !tiles_m || !rows_per_tile || g.K % 4 != 0) return false;
+    const IGemmP p = fwd_params(x, w_krsc, nullptr, g);
+    const bool vec = (p.Cs % 4 == 0) && ((uintptr_t)p.src % 16 == 0) && ((uintptr_t)p.wgt % 16 == 0);
+    if (!vec || igemm_linear_mode(p.Cs, false, true, false) == 0) return false;
+    int lay[2] = {0, 0};
+    if (dispatch_igemm<false>(p, false, nullptr, lay) != hipSuccess) return false;
+    *tiles_m = lay[0];
+    *rows_per_tile = lay[1];
+    return true;
+}
+
+hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s, float *bn_tiles)
+{
+    if (!x || !w_krsc || !y || !geom_ok(g)) return hipErrorInvalidValue;
+    IGemmP p = fwd_params(x, w_krsc, y, g);
+    if (bn_tiles) {
+        int tm, rows;
+        if ((uintptr_t)bn_tiles % 16 != 0 || !conv_fwd_bn_tiles(x, w_krsc, g, &tm, &rows)) return hipErrorInvalidValue;
+        p.stats = bn_tiles;
+    }
     return dispatch_igemm<false>(p, false, s);
 }
 
@@ -889,6 +1005,7 @@ hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const Con
 {
     if (!dy || !w_crsk || !dx || !geom_ok(g)) return hipErrorInvalidValue;
     IGemmP p;
+    p.stats = nullptr;
     if (pointwise_strided(g)) {
         if (!accumulate) {
             const hipError_t e = fill_zero(dx, g.rows_in() * g.C, s);

@@ -21,8 +21,15 @@ struct ConvGeom {
     int64_t taps() const { return (int64_t)kd * kh * kw; }
 };
 
-// y[N,Do,Ho,Wo,K] = cross-correlation of x with w_krsc (implicit GEMM M=rows_out, N=K, K=taps*C)
-hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s);
+// y[N,Do,Ho,Wo,K] = cross-correlation of x with w_krsc (implicit GEMM M=rows_out, N=K, K=taps*C).
+// bn_tiles (optional, 16-byte aligned, 2 * tiles_m * K floats): the kernel also leaves, per tile of
+// consecutive output rows, the per-channel mean [K] and sum of squared deviations from it [K] of that
+// tile's rows of y -- the batch-normalisation statistics pass, taken while the results are still on chip.
+// Only where conv_fwd_bn_tiles() says so.
+hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s, float *bn_tiles = nullptr);
+// whether conv_fwd can produce bn_tiles for these operands, and their layout: tile t covers output
+// rows [t * rows_per_tile, min(rows_out, (t + 1) * rows_per_tile))
+bool conv_fwd_bn_tiles(const float *x, const float *w_krsc, const ConvGeom &g, int *tiles_m, int *rows_per_tile);
 // dx[N,D,H,W,C] (+)= data gradient; w_crsk is the transposed filter copy
 hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g, bool accumulate, hipStream_t s);
 // bytes of split-K workspace conv_wgrad needs for this geometry (0 if none)
@@ -40,6 +47,12 @@ size_t bn_workspace_floats(int64_t M, int C);
 // batch statistics (mean, 1/sqrt(var+eps)) then y = gamma*(x-mean)*istd + beta; relu: y = max(y, 0)
 hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
                   float *ws, int64_t M, int C, float eps, bool relu, hipStream_t s);
+// floats of the buffer conv_fwd's bn_tiles and bn_fwd_from_tiles share (the tiles plus room to fold them)
+size_t bn_tiles_workspace_floats(int tiles_m, int C);
+// the same from per-tile statistics left by conv_fwd (tiles[t][0][C] = mean, tiles[t][1][C] = sum of squared
+// deviations of rows [t * rows_per_tile, ...)): merges them per channel in double, then applies
+hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
+                             float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, bool relu, hipStream_t s);
 // apply only, with saved statistics (used when a BN output is recomputed)
 hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const float *mean, const float *istd,
                     float *y, int64_t M, int C, bool relu, hipStream_t s);

@@ -12,6 +12,8 @@
 #include "kernels.h"
 
 #include <algorithm>
+#include <array>
+#include <cstdlib>
 #include <chrono>
 #include <cstring>
 #include <new>
@@ -56,6 +58,11 @@ struct pooch_ctx {
     // stored with a zero fourth channel (and those filters with a zero fourth input channel), so
     // that its rows are 16-byte vectors like every other tensor's
     int in_cdev = 0;
+    // A convolution whose result goes straight into a batch normalisation leaves that layer's
+    // statistics per row tile while it writes (stats_to[conv] = the BN node, stats_from[bn] = the
+    // conv node, stats_tiles[bn] = {row tiles, rows per tile}); -1 where the BN reads its input itself.
+    std::vector<int> stats_to, stats_from;
+    std::vector<std::array<int, 2>> stats_tiles;
 
     Profile prof;
     bool has_plan = false;
@@ -187,13 +194,19 @@ struct Exec {
         const Node &nd = G.nodes[i];
         hipStream_t s = c->st[S_COMPUTE];
         switch (nd.op) {
-        case OP_CONV: return pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i, c->in_cdev), s);
+        case OP_CONV:
+            return pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i, c->in_cdev), s,
+                                (!refwd && c->stats_to[i] >= 0) ? R(c->off_ws_bn) : nullptr);
         case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
             const bool relu = nd.op == OP_BNRELU;
             if (refwd)
                 return pk::bn_apply(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), R(c->off_mean[i]), R(c->off_istd[i]),
                                     D(out), M, (int)nd.C, relu, s);
+            if (c->stats_from[i] >= 0)   // the convolution that has just run left the statistics per row tile
+                return pk::bn_fwd_from_tiles(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), D(out), R(c->off_mean[i]),
+                                             R(c->off_istd[i]), R(c->off_ws_bn), c->stats_tiles[i][0], c->stats_tiles[i][1], M,
+                                             (int)nd.C, nd.eps, relu, s);
             return pk::bn_fwd(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), D(out), R(c->off_mean[i]), R(c->off_istd[i]),
                               R(c->off_ws_bn), M, (int)nd.C, nd.eps, relu, s);
         }
@@ -665,6 +678,13 @@ int32_t pooch_node_fused(pooch_ctx *c, int32_t id)
     return c->G.fused_into[id];
 }
 
+int32_t pooch_bn_stats_source(pooch_ctx *c, int32_t id)
+{
+    if (!c || !c->finalized) return POOCH_E_STATE;
+    if (id < 0 || id >= c->G.n()) return POOCH_E_INVALID;
+    return c->stats_from[id];
+}
+
 pooch_status pooch_finalize(pooch_ctx *c)
 {
     GRAPH_OPEN(c);
@@ -725,6 +745,25 @@ pooch_status pooch_finalize(pooch_ctx *c)
             G.nodes[j].param[1] = G.nodes[i].param[1];
             c->off_mean[j] = c->off_mean[i];
             c->off_istd[j] = c->off_istd[i];
+        }
+    }
+    // convolutions followed directly by their batch normalisation hand it the statistics
+    c->stats_to.assign(n, -1);
+    c->stats_from.assign(n, -1);
+    c->stats_tiles.assign(n, std::array<int, 2>{0, 0});
+    if (getenv("POOCH_NO_CONV_STATS") == nullptr) {
+        const float *aligned = reinterpret_cast<const float *>((uintptr_t)ALIGN);   // every tensor is ALIGN-byte aligned
+        for (int i = 0; i < n; ++i) {
+            if (G.nodes[i].op != OP_CONV) continue;
+            int j = i + 1;
+            while (j < n && G.nodes[j].op == OP_DEAD) ++j;
+            if (j >= n || (G.nodes[j].op != OP_BN && G.nodes[j].op != OP_BNRELU) || G.nodes[j].in[0] != i) continue;
+            int tiles_m = 0, rows = 0;
+            if (!pk::conv_fwd_bn_tiles(aligned, aligned, conv_geom(G, i, c->in_cdev), &tiles_m, &rows)) continue;
+            c->stats_to[i] = j;
+            c->stats_from[j] = i;
+            c->stats_tiles[j] = {tiles_m, rows};
+            ws_bn = std::max(ws_bn, pk::bn_tiles_workspace_floats(tiles_m, (int)G.nodes[i].C) * 4);
         }
     }
     c->off_ws_wgrad = take((int64_t)ws_wgrad);

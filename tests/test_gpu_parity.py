@@ -173,6 +173,67 @@ def test_layer_zoo_vs_oracle(batch, cin, size, c1, c2, k1, s1, p1):
     check_against_oracle("zoo %s" % ((batch, cin, size, c1, c2, k1, s1, p1),), net, 77 + size)
 
 
+@pytest.mark.parametrize("shape,cout,k,stride,pad,offset", [
+    ((1, 4, 520, 520), 8, 3, 1, 1, 0.0),      # 270 400 output rows: more than 1024 row tiles (folded in groups), short last tile
+    ((3, 8, 37, 41), 136, 1, 1, 0, 0.0),      # small problem: 64x64 tiles, two column tiles, ragged rows
+    ((2, 16, 61, 59), 64, 3, 2, 1, 0.0),      # uniform-tap path, strided
+    ((2, 4, 96, 96), 32, 5, 1, 2, 40.0),      # mean far from zero (|mean| about 100 standard deviations): no cancellation
+])
+def test_bn_statistics_from_the_conv_epilogue(shape, cout, k, stride, pad, offset, monkeypatch):
+    """a convolution followed by a batch normalisation leaves the per-channel statistics itself
+    (per row tile, merged afterwards).  Checked against the definition -- mean and biased variance in
+    float64 of the convolution output as the GPU wrote it -- and against the run in which the
+    normalisation takes its own statistics pass."""
+    net = workloads.Net()
+    t = net.input(shape)
+    t = net.relu(net.bn(net.conv(t, cout, (k, k), (stride, stride), (pad, pad))))
+    t = net.fc(net.gavgpool(t), 5)
+    net.softmax_ce(t)
+    params = workloads.make_params(net, 11, perturb=True)
+    if offset:
+        params[0] = (np.abs(params[0]) * 0.05 + 0.05).astype(np.float32)     # all-positive filter on a shifted input
+    x, lab = workloads.make_batch(net, 11)
+    x = (x + np.float32(offset)).astype(np.float32)
+    res, peak = plan_sizes(net)
+    eps = [L for L in net if L["op"] == "bn"][0]["eps"]
+
+    def run():
+        c = B.Context(net, res + 2 * peak, fuse=FUSE)
+        c.set_params(params)
+        c.set_batch(x, lab)
+        c.set_plan([B.KEEP] * c.n_fmaps)
+        y = np.full(workloads.shapes(net)[1], np.nan, np.float32)
+        c.capture(1, y)
+        bn_node = 3 if c.node_fused(2) == 3 else 2
+        src = c.bn_stats_source(bn_node)
+        loss = c.step()
+        mean, istd = c.bn_stats(bn_node, cout)
+        grads = c.get_grads([sh for _, _, sh in workloads.param_shapes(net)])
+        c.close()
+        return src, y, mean, istd, loss, grads
+
+    src, y, mean, istd, loss, grads = run()
+    assert src == 1, "the convolution should supply the statistics here"
+    y64 = y.astype(np.float64).transpose(1, 0, 2, 3).reshape(cout, -1)
+    mu = y64.mean(axis=1)
+    var = y64.var(axis=1)
+    sd = np.sqrt(var)
+    say("[case] conv-epilogue statistics", shape, "->", cout, "max |mean|/sd %.1f" % float(np.max(np.abs(mu) / sd)))
+    assert np.max(np.abs(mean - mu) / sd) <= 2e-6 * max(1.0, float(np.max(np.abs(mu) / sd)))
+    assert np.max(np.abs(istd * np.sqrt(var + eps) - 1.0)) <= 1e-5
+    monkeypatch.setenv("POOCH_NO_CONV_STATS", "1")
+    src2, y2, mean2, istd2, loss2, grads2 = run()
+    assert src2 == -1
+    assert y2.tobytes() == y.tobytes()
+    assert np.max(np.abs(mean2 - mean) / sd) <= 2e-6 * max(1.0, float(np.max(np.abs(mu) / sd)))
+    assert np.max(np.abs(istd2 / istd - 1.0)) <= 1e-5
+    assert abs(loss2 - loss) <= 1e-5 * abs(loss)
+    # (with the mean far from zero the filter gradient is what is left after the normalisation's
+    # backward has cancelled the mean's share: last-bit differences of the statistics are amplified)
+    for a, b in zip(grads, grads2):
+        assert rel(a, b) <= (RTOL if offset else 1e-4)
+
+
 def test_fc_on_spatial_input_and_3d():
     """fc directly on a feature map with spatial extent (flattened in logical C,D,H,W order)"""
     net = workloads.Net()
