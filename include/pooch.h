@@ -164,6 +164,14 @@ pooch_status pooch_finish_profile(pooch_ctx *);
 pooch_status pooch_get_profile(pooch_ctx *, double *t_fwd, double *t_bwd, double *t_refwd, double *t_out, double *t_in);
 pooch_status pooch_set_profile(pooch_ctx *, const double *t_fwd, const double *t_bwd, const double *t_refwd,
                                const double *t_out, const double *t_in);
+/* Beyond the paper: a second look at the durations.  The profiling pass above times every layer while
+ * every map is being copied out and in (section 4.2), which slows the layers; a plan that copies little
+ * then runs faster than simulated, and was chosen from pessimistic numbers.  pooch_refine_profile runs
+ * `iters` >= 1 steps under the installed plan (ordinary iterations: loss and gradients are valid
+ * afterwards) and replaces the forward, backward and re-forward durations of the layers that ran by
+ * their medians in those steps; copy durations stay.  Call pooch_plan again afterwards.
+ * POOCH_E_STATE without an installed plan, POOCH_E_NOPROFILE without a profile. */
+pooch_status pooch_refine_profile(pooch_ctx *, int iters, float *loss_out);
 
 /* ---- phase 2: classification (section 4.4) -----------------------------------------------
  * pooch_plan searches a classification for `mode` by simulating the step's timeline and

@@ -54,6 +54,7 @@ SYMBOLS = {
     "pooch_set_fusion": (_i32, [_ctx, C.c_int]),
     "pooch_node_fused": (_i32, [_ctx, _i32]),
     "pooch_bn_stats_source": (_i32, [_ctx, _i32]),
+    "pooch_refine_profile": (_i32, [_ctx, C.c_int, _pf]),
     "pooch_finalize": (_i32, [_ctx]),
     "pooch_num_params": (_i32, [_ctx]),
     "pooch_param_info": (_i32, [_ctx, _i32, _pi64, _pi32]),
@@ -327,6 +328,12 @@ class Context:
     def profile(self, warmup=1, iters=3):
         self._chk(self.L.pooch_profile(self.h, warmup, iters))
         return self.get_profile()
+
+    def refine_profile(self, iters=2):
+        """re-time the layers under the installed plan (ordinary steps); returns the last loss"""
+        loss = C.c_float()
+        self._chk(self.L.pooch_refine_profile(self.h, iters, C.byref(loss)))
+        return loss.value
 
     def get_profile(self):
         a = [np.empty(self.n_nodes) for _ in range(3)] + [np.empty(self.n_fmaps) for _ in range(2)]

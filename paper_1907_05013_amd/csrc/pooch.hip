@@ -1237,6 +1237,35 @@ pooch_status pooch_step_timed(pooch_ctx *c, float *loss_out, double *ms_fwd, dou
     return POOCH_OK;
 }
 
+pooch_status pooch_refine_profile(pooch_ctx *c, int iters, float *loss_out)
+{
+    NEED_FINAL(c);
+    if (!c->has_plan) return fail(c, POOCH_E_STATE, "refine_profile: no plan installed");
+    if (!c->prof.valid) return fail(c, POOCH_E_NOPROFILE, "refine_profile: no profile to refine");
+    if (iters < 1) return fail(c, POOCH_E_INVALID, "refine_profile: iters must be positive");
+    const int n = c->G.n();
+    std::vector<std::vector<double>> f(n), b(n), r(n);
+    for (int it = 0; it < iters; ++it) {
+        Timing tm;
+        pooch_status ps = run_schedule(c, c->sched, &tm, false, loss_out);
+        if (ps != POOCH_OK) return ps;
+        for (size_t k = 0; k < c->sched.cmds.size(); ++k) {
+            const Cmd &cm = c->sched.cmds[k];
+            if (cm.kind > K_BWD) continue;
+            double ms;
+            ps = elapsed(c, tm.start[k], tm.stop[k], ms);
+            if (ps != POOCH_OK) return ps;
+            (cm.kind == K_FWD ? f : (cm.kind == K_BWD ? b : r))[cm.id].push_back(ms);
+        }
+    }
+    for (int i = 0; i < n; ++i) {
+        if (!f[i].empty()) c->prof.t_fwd[i] = median(f[i]);
+        if (!b[i].empty()) c->prof.t_bwd[i] = median(b[i]);
+        if (!r[i].empty()) c->prof.t_refwd[i] = median(r[i]);
+    }
+    return POOCH_OK;
+}
+
 const char *pooch_node_kernel(pooch_ctx *c, int32_t node, int part)
 {
     if (!c || !c->finalized || node < 0 || node >= c->G.n() || part < 0 || part > 2) return "";

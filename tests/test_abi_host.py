@@ -97,6 +97,9 @@ def test_dangling_output_and_state_errors():
     with pytest.raises(B.PoochError) as e:
         c.plan("pooch")
     assert e.value.status == B.E_NOPROFILE
+    with pytest.raises(B.PoochError) as e:
+        c.refine_profile(1)                                       # nothing installed to run
+    assert e.value.status == B.E_STATE
     assert B.lib().pooch_relu(c.h, 1) == B.E_STATE              # graph is frozen
     with pytest.raises(B.PoochError) as e:
         c.set_plan([7] * c.n_fmaps)

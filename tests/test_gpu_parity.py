@@ -433,6 +433,20 @@ def test_config2_bottleneck_full_size_profile_plan_execute():
             (mode, T, ms, st.n_keep, st.n_swap, st.n_recompute))
     # the search never makes the simulated step slower (section 5.1's ordering)
     assert results["pooch"][0] <= results["swapopt"][0] + 1e-9 <= results["swapall"][0] + 2e-9
+    # re-timing the layers under the installed plan: ordinary steps (same bits), the layers that ran get new
+    # durations, copies keep theirs, and a plan made from the refined profile still reproduces the in-core run
+    before = c.get_profile()
+    l2 = c.refine_profile(2)
+    assert np.float32(l2).tobytes() == np.float32(loss).tobytes()
+    after = c.get_profile()
+    assert all((a >= 0).all() and np.array_equal(a > 0, b > 0) for a, b in zip(after[:2], before[:2]))
+    assert np.array_equal(before[3], after[3]) and np.array_equal(before[4], after[4])
+    assert not np.array_equal(before[0], after[0])
+    cls, T = c.plan("refine", 4, restarts=4)
+    l3 = c.step()
+    assert_bit_exact("config2 refine after re-profiling", (loss, grads),
+                     (l3, c.get_grads([s for _, _, s in workloads.param_shapes(net)])))
+    say("[config2] refine after re-profiling: predicted %.2f ms measured %.2f ms" % (T, c.stats().step_ms))
     c.close()
 
 
