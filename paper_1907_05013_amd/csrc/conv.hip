@@ -22,6 +22,15 @@ constexpr int BK = 16;   // reduction slice per main-loop iteration
 constexpr int LDK = 20;  // LDS row stride (floats) of [row][k] tiles: 16-byte rows, conflict-free b128 reads
 constexpr int NXCD = 8;
 
+// Loads of tensor data name the global address space.  A pointer that comes out of a parameter
+// struct is a generic one to the compiler, and a generic ("flat") load is also counted by the
+// counter LDS reads are waited on: the wait before a slice's first MFMA would then sit out the
+// whole latency of the prefetch issued just before it.
+typedef const __attribute__((address_space(1))) f32x4 *gvec4_ptr;
+typedef const __attribute__((address_space(1))) float *gfloat_ptr;
+__device__ __forceinline__ f32x4 ldg4(const float *p) { return *(gvec4_ptr)(p); }
+__device__ __forceinline__ float ldg1(const float *p) { return *(gfloat_ptr)(p); }
+
 // 16 zero bytes every kernel may read: elements that do not exist (padding, rows or slices past
 // the end) are loaded from here instead of being branched around or masked afterwards
 __device__ __attribute__((aligned(16))) const float g_zero4[4] = {0.f, 0.f, 0.f, 0.f};
@@ -165,12 +174,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             const int4 ri = ri_reg[i];
             const bool ok = kok & (ri.x >= 0) & ((unsigned)(ri.y + ta) < (unsigned)p.Ds) & ((unsigned)(ri.z + tb) < (unsigned)p.Hs) &
                             ((unsigned)(ri.w + te) < (unsigned)p.Ws);
-            av[i] = *reinterpret_cast<const f32x4 *>(ok ? p.src + (abase[i] + tapoff) : g_zero4);
+            av[i] = ldg4(ok ? p.src + (abase[i] + tapoff) : g_zero4);
         }
 #pragma unroll
         for (int i = 0; i < B_V; ++i) {
             const bool ok = kok & brow[i];
-            bv[i] = *reinterpret_cast<const f32x4 *>(ok ? bptr[i] : g_zero4);
+            bv[i] = ldg4(ok ? bptr[i] : g_zero4);
             bptr[i] += BKT;
         }
         pk += BKT;
@@ -194,14 +203,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             const int qw = DGRAD ? ri.w - te : ri.w + te;
             const bool ok = live & (ri.x >= 0) & ((unsigned)qd < (unsigned)p.Ds) & ((unsigned)qh < (unsigned)p.Hs) &
                             ((unsigned)qw < (unsigned)p.Ws);
-            av[i] = *reinterpret_cast<const f32x4 *>(ok ? p.src + (abase[i] + delta) : g_zero4);
+            av[i] = ldg4(ok ? p.src + (abase[i] + delta) : g_zero4);
         }
         amask = ~0u;
         bmask = ~0u;
 #pragma unroll
         for (int i = 0; i < B_V; ++i) {
             const bool ok = live & brow[i];
-            bv[i] = *reinterpret_cast<const f32x4 *>(ok ? bptr[i] : g_zero4);
+            bv[i] = ldg4(ok ? bptr[i] : g_zero4);
             bptr[i] += BKT;
         }
         tc += BKT;
@@ -248,7 +257,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
                 const bool vw = src_coord<DGRAD>(ri.w, e, p.sw, p.Ws, qw);
                 const bool ok = kok & (ri.x >= 0) & vd & vh & vw;
                 const int64_t off = ((((int64_t)ri.x * p.Ds + qd) * p.Hs + qh) * p.Ws + qw) * p.Cs + c;
-                av[i] = *reinterpret_cast<const f32x4 *>(p.src + (ok ? off : 0));
+                av[i] = ldg4(p.src + (ok ? off : 0));
                 amask |= (ok ? 1u : 0u) << i;
             }
             bmask = 0;
@@ -256,7 +265,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             for (int i = 0; i < B_V; ++i) {
                 const int n = n0 + vrow + i * RPP;
                 const bool ok = kok & (vrow + i * RPP < BN) & (n < p.Nout);
-                bv[i] = *reinterpret_cast<const f32x4 *>(p.wgt + (ok ? (int64_t)n * p.Kred + k : 0));
+                bv[i] = ldg4(p.wgt + (ok ? (int64_t)n * p.Kred + k : 0));
                 bmask |= (ok ? 1u : 0u) << i;
             }
         } else {
@@ -279,14 +288,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
                 if (kok && ri.x >= 0 && src_coord<DGRAD>(ri.y, a, p.sd, p.Ds, qd) &&
                     src_coord<DGRAD>(ri.z, b, p.sh, p.Hs, qh) && src_coord<DGRAD>(ri.w, e, p.sw, p.Ws, qw)) {
                     const int64_t off = ((((int64_t)ri.x * p.Ds + qd) * p.Hs + qh) * p.Ws + qw) * p.Cs + c;
-                    v = p.src[off];
+                    v = ldg1(p.src + off);
                 }
                 as[i] = v;
             }
 #pragma unroll
             for (int i = 0; i < B_S; ++i) {
                 const int n = n0 + tid / BKT + i * RPS;
-                bs[i] = (kok && n < p.Nout) ? p.wgt[(int64_t)n * p.Kred + k] : 0.f;
+                bs[i] = (kok && n < p.Nout) ? ldg1(p.wgt + ((int64_t)n * p.Kred + k)) : 0.f;
             }
         }
     };
@@ -725,7 +734,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
         _Pragma("unroll") for (int i = 0; i < A_V; ++i)                                                                      \
         {                                                                                                                    \
             const int m = (MB) + (tid + i * NT) / (BM / 4);                                                                  \
-            tav[i] = *reinterpret_cast<const f32x4 *>((acol_ok & (m < mend)) ? acur + i * astep : g_zero4);                  \
+            tav[i] = ldg4((acol_ok & (m < mend)) ? acur + i * astep : g_zero4);                                              \
         }                                                                                                                    \
         acur += (int64_t)BK * p.K;                                                                                           \
         _Pragma("unroll") for (int i = 0; i < B_V; ++i)                                                                      \
@@ -735,7 +744,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void wgrad_kernel(WGradP p)
             const int64_t rb = rowb[q];                                                                                      \
             const bool ok = vb_ok & (rc.x >= 0) & ((unsigned)(rc.y + vb_a) < (unsigned)p.D) &                                \
                             ((unsigned)(rc.z + vb_b) < (unsigned)p.H) & ((unsigned)(rc.w + vb_e) < (unsigned)p.W);           \
-            tbv[i] = *reinterpret_cast<const f32x4 *>(ok ? p.x + (rb + tapoff) : g_zero4);                                   \
+            tbv[i] = ldg4(ok ? p.x + (rb + tapoff) : g_zero4);                                                               \
         }                                                                                                                    \
     } while (0)
 
