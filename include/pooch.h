@@ -26,6 +26,10 @@
  *     priority.
  *   - A context created with arena == NULL is "planning only": graph, profile injection,
  *     planning and simulation work (no GPU needed), compute calls return POOCH_E_STATE.
+ *   - Two environment variables switch kernel paths off for A/B measurements (results stay
+ *     within rounding): POOCH_NO_CONV_STATS (read by pooch_finalize: batch normalisations take
+ *     their own statistics pass), POOCH_NO_LINEAR (read at the first convolution launch: the
+ *     convolution kernels recompute every tile address from scratch).
  */
 #ifndef POOCH_H
 #define POOCH_H
