@@ -36,7 +36,7 @@ PAPER_B640_IMG_S = 195.0    # paper, ResNet50 batch 640 on V100 16 GB + PCIe3 (3
 # FETCH_SIZE reads 0.5 GiB there, WRITE_SIZE 1.0 GiB, so fetch x 2.0, write x 1.0.
 # Source: profiles/resnet50_b640_16g_hbm_traffic.txt.  (workload, kernel) -> (fetch KiB, write KiB)
 MEASURED_TRAFFIC_KIB = {
-    ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+lin,fwd>"): (345310.0, 496061.0),
+    ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+lin,fwd+bnstats>"): (349926.0, 473597.0),
 }
 TRAFFIC_SCALE = (2.0, 1.0)
 
@@ -136,8 +136,8 @@ def kernel_report(ctx, net, ms, nrefwd_counts=None):
                 conv_ms += t
         if refwd[i] > 0:
             n = max(1, int(round(refwd[i] / max(fwd[i], 1e-9))))
-            add(ctx.node_kernel(i, 0), fl, refwd[i], n, nbytes)
-            by_kernel[ctx.node_kernel(i, 0)][0] += fl * (n - 1)
+            add(ctx.node_kernel(i, 3), fl, refwd[i], n, nbytes)
+            by_kernel[ctx.node_kernel(i, 3)][0] += fl * (n - 1)
             conv_flops += fl * n
             conv_ms += refwd[i]
     # algorithmic bytes per element: BN (alone or with a fused ReLU) forward 12 (x for the statistics,
@@ -168,7 +168,7 @@ def cpu_baseline(name, budget_s=20.0):
     from oracle.net import OracleNet
     cfg, kw, _ = WORKLOADS[name]
     if cfg.startswith("resnet50"):
-        sample = {"batch": 16}
+        sample = {"batch": 32}
     elif cfg == "bottleneck":
         sample = {"batch": 32}
     else:

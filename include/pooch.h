@@ -238,7 +238,8 @@ pooch_status pooch_get_stats(pooch_ctx *, pooch_stats *);
 pooch_status pooch_step_timed(pooch_ctx *, float *loss_out, double *ms_fwd, double *ms_bwd, double *ms_refwd,
                               double *ms_bwd_filter);
 /* name of the GPU kernel variant a conv / fc layer launches for part 0 forward, 1 data
- * gradient, 2 filter gradient (static string, "" for other layers): lets a benchmark group
+ * gradient, 2 filter gradient, 3 forward when the layer is recomputed in backward (no
+ * statistics for a following bn then) (static string, "" for other layers): lets a benchmark group
  * per-layer times by kernel, as a profiler's per-kernel summary does. */
 const char *pooch_node_kernel(pooch_ctx *, int32_t node, int part);
 

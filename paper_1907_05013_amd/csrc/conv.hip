@@ -10,6 +10,8 @@
 #include "kernels.h"
 
 #include <cstdlib>
+#include <map>
+#include <string>
 
 namespace pk {
 
@@ -1065,7 +1067,19 @@ const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgr
 }
 }  // namespace
 
-const char *conv_fwd_kernel(const ConvGeom &g) { return igemm_tag(g.rows_out(), g.K, g.C, true, false); }
+const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
+{
+    const char *plain = igemm_tag(g.rows_out(), g.K, g.C, true, false);
+    if (!bn_tiles) return plain;
+    // the variant that also leaves batch-normalisation statistics is a kernel of its own
+    static std::map<std::string, std::string> names;
+    std::string &v = names[plain];
+    if (v.empty()) {
+        v = plain;
+        v.insert(v.size() - 1, "+bnstats");
+    }
+    return v.c_str();
+}
 
 const char *conv_dgrad_kernel(const ConvGeom &g)
 {

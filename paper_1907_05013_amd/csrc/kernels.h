@@ -38,7 +38,7 @@ size_t conv_wgrad_workspace(const ConvGeom &g);
 hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *workspace, const ConvGeom &g, hipStream_t s);
 
 // names of the kernel variants the three launchers above pick for a geometry
-const char *conv_fwd_kernel(const ConvGeom &g);
+const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles = false);
 const char *conv_dgrad_kernel(const ConvGeom &g);
 const char *conv_wgrad_kernel(const ConvGeom &g);
 

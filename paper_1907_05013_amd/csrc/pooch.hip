@@ -1268,11 +1268,13 @@ pooch_status pooch_refine_profile(pooch_ctx *c, int iters, float *loss_out)
 
 const char *pooch_node_kernel(pooch_ctx *c, int32_t node, int part)
 {
-    if (!c || !c->finalized || node < 0 || node >= c->G.n() || part < 0 || part > 2) return "";
+    if (!c || !c->finalized || node < 0 || node >= c->G.n() || part < 0 || part > 3) return "";
     const Op op = c->G.nodes[node].op;
     if (op != OP_CONV && op != OP_FC) return "";
     const pk::ConvGeom g = conv_geom(c->G, node, c->in_cdev);
-    return part == 0 ? pk::conv_fwd_kernel(g) : (part == 1 ? pk::conv_dgrad_kernel(g) : pk::conv_wgrad_kernel(g));
+    if (part == 0) return pk::conv_fwd_kernel(g, c->stats_to[node] >= 0);
+    if (part == 3) return pk::conv_fwd_kernel(g, false);
+    return part == 1 ? pk::conv_dgrad_kernel(g) : pk::conv_wgrad_kernel(g);
 }
 
 pooch_status pooch_measure_link(pooch_ctx *c, size_t bytes, int iters, double *d2h_gbs, double *h2d_gbs)
