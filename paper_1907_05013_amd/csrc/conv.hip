@@ -916,6 +916,7 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restr
 
 struct WGradCfg {
     int bm, bn, nsplit, chunk_rows;
+    int big;   // 0: the bm x bn tile with four waves; 1: 256 x 128 with eight; 2: 128 x 256 with eight
 };
 
 constexpr size_t WGRAD_WS_CAP = (size_t)64 << 20;
@@ -944,6 +945,15 @@ WGradCfg wgrad_cfg(const ConvGeom &g)
     chunk = (chunk + BK - 1) / BK * BK;
     c.chunk_rows = (int)chunk;
     c.nsplit = (int)((M + chunk - 1) / chunk);
+    // Eight waves on a double tile where the output has room for it (the split count stays the one
+    // of the 128 x 128 tiling: half as many workgroups of twice the size).  Measured at batch 640:
+    // 256 x 128 on 256 or more output channels 126 - 130 TFLOP/s against 117 - 119; 128 x 256 on 1x1
+    // filters into 128 channels 0.535 against 0.571 ms -- but 1.77 against 1.25 ms under 3x3 taps, hence not there
+    c.big = 0;
+    if (c.bm == 128 && c.bn == 128) {
+        if (g.K >= 256) c.big = 1;
+        else if (Kred >= 256 && g.taps() == 1) c.big = 2;
+    }
     return c;
 }
 
@@ -1091,6 +1101,7 @@ const char *conv_wgrad_kernel(const ConvGeom &g)
 {
     const WGradCfg c = wgrad_cfg(g);
     if (c.bn == 64) return c.bm == 32 ? "wgrad_kernel<1,2,1,1>" : (c.bm == 64 ? "wgrad_kernel<2,2,1,1>" : "wgrad_kernel<2,2,2,1>");
+    if (c.big) return c.big == 1 ? "wgrad_kernel<4,2,2,2>" : "wgrad_kernel<2,4,2,2>";
     return c.bm == 32 ? "wgrad_kernel<1,2,1,2>" : (c.bm == 64 ? "wgrad_kernel<2,2,1,2>" : "wgrad_kernel<2,2,2,2>");
 }
 
@@ -1122,6 +1133,8 @@ hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *wo
     } else {
         if (c.bm == 32) e = launch_wgrad<1, 2, 1, 2>(p, veca, vecb, s);
         else if (c.bm == 64) e = launch_wgrad<2, 2, 1, 2>(p, veca, vecb, s);
+        else if (c.big == 1) e = launch_wgrad<4, 2, 2, 2>(p, veca, vecb, s);
+        else if (c.big == 2) e = launch_wgrad<2, 4, 2, 2>(p, veca, vecb, s);
         else e = launch_wgrad<2, 2, 2, 2>(p, veca, vecb, s);
     }
     if (e != hipSuccess) return e;
