@@ -167,6 +167,9 @@ def zoo_net(batch, cin, size, c1, c2, k1, s1, p1):
     (2, 8, 16, 40, 136, 3, 2, 1),     # more than one 128-wide output-channel tile, strided 3x3
     (2, 4, 13, 8, 12, 3, 1, 1),       # odd extent into the 3x3/2 max-pool with C % 4 == 0
     (2, 8, 15, 16, 64, 1, 2, 0),      # strided 1x1 convolution (its data gradient is a scatter)
+    (2, 8, 16, 264, 136, 3, 2, 1),    # filter gradients on the eight-wave tiles with ragged edges: 264 output channels
+                                      # (256-row tiles), then 1x1 264 -> 136 (256-column tiles); three forward column tiles
+    (3, 16, 20, 520, 72, 1, 1, 0),    # 1x1 into 520 channels (three 256-row tiles), 1x1 520 -> 72 (64 x 128 tiles)
 ])
 def test_layer_zoo_vs_oracle(batch, cin, size, c1, c2, k1, s1, p1):
     net = zoo_net(batch, cin, size, c1, c2, k1, s1, p1)
