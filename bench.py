@@ -203,7 +203,7 @@ def main():
     ap.add_argument("--mode", default="refine", choices=["swapall_nosched", "swapall", "swapopt", "pooch", "refine"],
                     help="planner whose step is reported as `value`; refine = the paper's two steps + local search")
     ap.add_argument("--bits", type=int, default=4, help="cap on the exponential part of the keep/swap search")
-    ap.add_argument("--restarts", type=int, default=48, help="perturbed restarts of the refine mode's local search")
+    ap.add_argument("--restarts", type=int, default=300, help="perturbed restarts of the refine mode's local search")
     ap.add_argument("--no-paper-mode", action="store_true", help="skip the extra leg that times the paper's own two-step plan")
     ap.add_argument("--ablation", action="store_true",
                     help="also time every planning mode (the experiment of the paper's section 5.1 plus the static policy "

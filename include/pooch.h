@@ -65,7 +65,10 @@ enum {
     POOCH_MODE_SWAPOPT = 3,         /* keep/swap search only (section 4.4.2) */
     POOCH_MODE_POOCH = 4,           /* keep/swap search, then swap/recompute classification (section 4.4.3) */
     POOCH_MODE_REFINE = 5,          /* not in the paper: POOCH followed by an iterated local search over single class
-                                       changes, judged by the same timeline simulation */
+                                       changes, judged by the same timeline simulation.  If the profile has been
+                                       replaced or refined since the installed plan was made, that plan competes
+                                       with the two-step plan as the search's starting point (the faster one by
+                                       simulation under the current profile is taken) */
     POOCH_MODE_SUPERNEURONS = 6     /* the static policy section 5.2 compares against: keep from the output layer while
                                        it fits, then convolution outputs swap and the rest is recomputed; swap-ins
                                        are not moved up */

@@ -607,9 +607,12 @@ def _splitmix64(state):
 
 
 class Planner:
-    def __init__(self, G, P, cap, pinned_cap=None, max_bits=10, restarts=8):
+    def __init__(self, G, P, cap, pinned_cap=None, max_bits=10, restarts=8, seed=None):
         self.G, self.P, self.cap, self.pinned_cap, self.max_bits = G, P, cap, pinned_cap, max_bits
         self.restarts = restarts
+        # refine mode only (not in the paper): a classification made earlier, e.g. from a coarser
+        # profile, that competes with the two-step plan as the starting point of the local search
+        self.seed = seed
         self.evals = 0
         self.LO, self.LI = set(), set()
 
@@ -650,6 +653,10 @@ class Planner:
         cls, T = self.step2(cls, T)
         if mode == "pooch":
             return cls, T
+        if self.seed is not None and len(self.seed) == nf:
+            Ts = self.evaluate(list(self.seed))
+            if Ts is not None and Ts < T:
+                cls, T = list(self.seed), Ts
         return self.refine(cls, T)
 
     def superneurons(self):

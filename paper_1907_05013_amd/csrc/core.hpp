@@ -93,6 +93,8 @@ struct Planner {
     int64_t cap, pinned_cap;
     int max_bits;
     int restarts = 8;  // perturbed restarts of the local search in refine()
+    // refine mode: a classification that competes with the two-step plan as the search's starting point
+    const std::vector<uint8_t> *seed = nullptr;
     int64_t evals = 0;
     std::vector<int> LO, LI;
     Planner(const Graph &g, const Profile &p, int64_t cap_, int64_t pinned_cap_, int max_bits_)

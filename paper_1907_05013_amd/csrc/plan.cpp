@@ -678,6 +678,13 @@ bool Planner::plan(int mode, std::vector<uint8_t> &cls, double &T, bool &ahead)
     if (mode == MODE_SWAPOPT) return true;
     step2(cls, T);
     if (mode == MODE_POOCH) return true;
+    if (seed && seed->size() == cls.size()) {
+        const double Ts = evaluate(*seed);
+        if (Ts >= 0.0 && Ts < T) {
+            cls = *seed;
+            T = Ts;
+        }
+    }
     refine(cls, T);
     return true;
 }

@@ -66,6 +66,7 @@ struct pooch_ctx {
 
     Profile prof;
     bool has_plan = false;
+    bool profile_newer_than_plan = false;   // the profile changed while a plan was installed (see pooch_plan)
     std::vector<uint8_t> cls;
     bool ahead = true;
     Schedule sched;
@@ -954,6 +955,7 @@ pooch_status profile_end(pooch_ctx *c)
     for (size_t k = 0; k < nf; ++k) { P.t_out[k] = median(c->smp_o[k]); P.t_in[k] = median(c->smp_i[k]); }
     P.valid = true;
     c->prof = P;
+    c->profile_newer_than_plan = c->has_plan;
     c->prof_sched_ok = false;
     return POOCH_OK;
 }
@@ -1058,6 +1060,7 @@ pooch_status pooch_set_profile(pooch_ctx *c, const double *t_fwd, const double *
     P.t_out.assign(t_out, t_out + nf); P.t_in.assign(t_in, t_in + nf);
     P.valid = true;
     c->prof = P;
+    c->profile_newer_than_plan = c->has_plan;
     return POOCH_OK;
 }
 
@@ -1073,6 +1076,9 @@ pooch_status pooch_plan(pooch_ctx *c, int mode, int max_bruteforce_bits, double 
     const int64_t cap = (int64_t)c->arena_bytes - c->resident_bytes;
     Planner pl(c->G, P, cap, c->arena ? (int64_t)c->pinned_bytes : -1, bits);
     pl.restarts = c->restarts;
+    // a plan made from an earlier state of the profile competes as the refine search's starting point
+    const std::vector<uint8_t> seed = c->cls;
+    if (mode == POOCH_MODE_REFINE && c->has_plan && c->ahead && c->profile_newer_than_plan) pl.seed = &seed;
     std::vector<uint8_t> cls;
     double T = 0.0;
     bool ahead = true;
@@ -1081,6 +1087,7 @@ pooch_status pooch_plan(pooch_ctx *c, int mode, int max_bruteforce_bits, double 
     if (!ok) return fail(c, POOCH_E_BUDGET, "plan: not even the safest plan of this mode fits the budget");
     const pooch_status ps = install(c, cls, ahead, T);
     if (ps != POOCH_OK) return ps;
+    c->profile_newer_than_plan = false;
     if (predicted_ms) *predicted_ms = T;
     return POOCH_OK;
 }
@@ -1263,6 +1270,7 @@ pooch_status pooch_refine_profile(pooch_ctx *c, int iters, float *loss_out)
         if (!b[i].empty()) c->prof.t_bwd[i] = median(b[i]);
         if (!r[i].empty()) c->prof.t_refwd[i] = median(r[i]);
     }
+    c->profile_newer_than_plan = true;
     return POOCH_OK;
 }
 

@@ -121,6 +121,40 @@ def test_every_mode_picks_the_oracles_plan(seed):
             assert {G.fmaps[k] for k in range(nf) if li[k]} == pl.LI
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_refine_after_a_profile_change_starts_from_the_installed_plan_too(seed):
+    """plan under one profile, replace the profile, plan again in refine mode: the library tries the
+    installed plan as a starting point exactly as the oracle does when given it as `seed`"""
+    rng = np.random.default_rng(500 + seed)
+    net = list(nets().values())[seed % 4]
+    G = P.Graph(net, fuse=True)
+    nf = len(G.fmaps)
+    incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
+    prof1 = rand_profile(G, rng, link=1.0)
+    prof2 = [np.asarray(v) * rng.uniform(0.5, 1.5, size=len(v)) for v in prof1]
+    for frac in (rng.uniform(0.5, 0.8), 0.9, 0.97):       # the smallest of these arenas that all-swap fits
+        cap = int(incore.peak * frac) // 256 * 256
+        c, _ = lib_ctx(net, cap, True)
+        c.set_profile(*prof1)
+        try:
+            cls1, _ = c.plan("refine", 4, restarts=2)
+            break
+        except B.BudgetError:
+            continue
+    else:
+        pytest.fail("no arena below the in-core peak admits the all-swap plan")
+    c.set_profile(*prof2)
+    cls2, T2 = c.plan("refine", 4, restarts=2)
+    pl = P.Planner(G, P.Profile(*[list(v) for v in prof2]), cap, max_bits=4, restarts=2, seed=list(cls1))
+    ocls, oT = pl.plan("refine")
+    assert list(cls2) == list(ocls) and T2 == oT and c.plan_evaluations() == pl.evals
+    # and without a profile change in between there is no seed: same as a fresh planner
+    cls3, T3 = c.plan("refine", 4, restarts=2)
+    pl0 = P.Planner(G, P.Profile(*[list(v) for v in prof2]), cap, max_bits=4, restarts=2)
+    ocls0, oT0 = pl0.plan("refine")
+    assert list(cls3) == list(ocls0) and T3 == oT0 and c.plan_evaluations() == pl0.evals
+
+
 def test_paper_eight_layer_example_through_the_library():
     """section 4.4.2's worked example: L_O = {5,6,7}, L_I = {4,6,7} on the all-swap timeline"""
     with open(os.path.join(GOLD, "eight_layer_example.json")) as f:
