@@ -121,3 +121,27 @@ def test_budget_errors_at_planning_time():
         c.set_plan([B.KEEP] * c.n_fmaps)
     with pytest.raises(B.BudgetError):
         c.simulate([B.SWAP] * c.n_fmaps, want_time=False)
+
+
+def test_which_batch_normalisations_take_their_statistics_from_the_conv():
+    """pooch_bn_stats_source: a bn fed directly by a conv with a 16-byte-vector channel count gets its
+    statistics from that conv's epilogue; one fed by anything else, or by a conv with an odd channel
+    count, takes its own pass; every ResNet-50 bn is of the first kind"""
+    c = B.Context(workloads.tiny_cnn(), 1 << 30, device=None)        # conv 1, bn 2 (inside relu 3), conv 4, ...
+    assert [c.bn_stats_source(i) for i in (3, 6, 9, 12)] == [1, 4, 7, 10]
+    assert c.bn_stats_source(1) == -1 and c.bn_stats_source(2) == -1
+    c = B.Context(workloads.tiny_cnn(), 1 << 30, device=None, fuse=False)
+    assert [c.bn_stats_source(i) for i in (2, 5, 8, 11)] == [1, 4, 7, 10]
+    net = workloads.Net()
+    t = net.input((2, 3, 8, 8))
+    t = net.bn(net.conv(t, 6, (3, 3), (1, 1), (1, 1)))                # 6 output channels: no 16-byte rows
+    t = net.bn(net.maxpool(t, (2, 2), (2, 2), (0, 0)))                # bn after a pool
+    t = net.fc(net.gavgpool(net.relu(t)), 3)
+    net.softmax_ce(t)
+    c = B.Context(net, 1 << 30, device=None, fuse=False)
+    assert [c.bn_stats_source(i) for i in range(len(net))] == [-1] * len(net)
+    net, _ = workloads.load("resnet50_b64")
+    c = B.Context(net, 1 << 40, device=None)
+    bns = [i for i, L in enumerate(net) if L["op"] == "bn"]
+    live = [i if c.node_fused(i) < 0 else c.node_fused(i) for i in bns]
+    assert len(bns) == 53 and all(c.bn_stats_source(j) == net[i]["x"] for i, j in zip(bns, live))
