@@ -450,6 +450,7 @@ def _walk(G, cls, cap, ahead, info):
 
     # ---------------- backward
     in_backward[0] = True
+    shared = {}     # gradient buffer offset -> node that still has to read it while another tensor owns it
     if not dry:
         for t in info["touch_seq"]:
             if t in klass and klass[t] == SWAP:
@@ -492,12 +493,24 @@ def _walk(G, cls, cap, ahead, info):
             x = ins[0]
             if x == 0:
                 outs.append((OFF_NONE, M_NONE))
-            elif gloc[x] is None:
+            elif gloc[x] is None and dy not in shared:
                 gloc[x] = dy
                 transferred = True
                 outs.append((dy, M_TRANSFER))
+            elif gloc[x] is None:
+                # dy is also another tensor's gradient (see _shared_reader): leave it untouched
+                gloc[x] = alloc_c(G.bytes[x])
+                outs.append((gloc[x], M_WRITE))
             else:
                 outs.append((gloc[x], M_ACC))
+        elif op in ("add", "addrelu") and _shared_reader(G, i, gloc) is not None:
+            # both inputs take the (masked) dy buffer over: one of them only reads it, before anything
+            # is accumulated into the other's gradient -- no copy
+            shared[dy] = ins[_shared_reader(G, i, gloc)]
+            for u in ins:
+                gloc[u] = dy
+                outs.append((dy, M_TRANSFER))
+            transferred = True
         elif op in ("add", "addrelu"):
             for u in ins:
                 if u == 0:
@@ -524,7 +537,9 @@ def _walk(G, cls, cap, ahead, info):
             outs.append((OFF_NONE, M_NONE))
         emit(KB, i, dy, need_off, outs[0][0], outs[0][1], outs[1][0], outs[1][1])
         if op != "softmax_ce":
-            if not transferred:
+            if shared.get(dy) == i:
+                del shared[dy]          # its other owner keeps the buffer
+            elif not transferred:
                 free_c(dy, G.bytes[i])
             gloc[i] = None
         if not dry:
@@ -539,6 +554,24 @@ def _walk(G, cls, cap, ahead, info):
     S.peak = arena.peak
     S.extent = 0 if arena.lo is None else arena.hi - arena.lo
     return S
+
+
+def _shared_reader(G, i, gloc):
+    """Backward of z = a + b hands dy to both inputs.  When one input u is consumed by this add alone,
+    is produced after the other input t and after every other consumer of t, and its own backward
+    never needs to modify dy, then u's backward has read dy before anything is accumulated into t's
+    gradient: both gradients can be the one dy buffer.  Returns the position of u in the inputs, or None."""
+    ins = G.inputs[i]
+    if len(ins) != 2 or ins[0] == ins[1] or 0 in ins or gloc[ins[0]] is not None or gloc[ins[1]] is not None:
+        return None
+    for ju in (0, 1):
+        u, t = ins[ju], ins[1 - ju]
+        if G.consumers[u] != [i] or G.ops[u] in ("add", "addrelu") or t > u:
+            continue
+        if any(c != i and c > u for c in G.consumers[t]):
+            continue
+        return ju
+    return None
 
 
 # ------------------------------------------------------------------ timeline simulation

@@ -17,6 +17,7 @@
 #include "core.hpp"
 
 #include <algorithm>
+#include <map>
 #include <deque>
 
 namespace pooch {
@@ -379,6 +380,27 @@ struct Walker {
         }
 
         in_backward = true;
+        // gradient buffer offset -> node that still has to read it while another tensor owns it
+        std::map<int64_t, int> shared;
+        // Backward of z = a + b hands dy to both inputs.  When one input u is consumed by this add
+        // alone, is produced after the other input t and after every other consumer of t, and its
+        // own backward never needs to modify dy, then u's backward has read dy before anything is
+        // accumulated into t's gradient: both gradients can be the one dy buffer.  Position of u, or -1.
+        auto shared_reader = [&](int i) -> int {
+            const std::vector<int> &in2 = G.inputs[i];
+            if (in2.size() != 2 || in2[0] == in2[1] || in2[0] == 0 || in2[1] == 0) return -1;
+            if (gloc[in2[0]] != LOC_NONE || gloc[in2[1]] != LOC_NONE) return -1;
+            for (int ju = 0; ju < 2; ++ju) {
+                const int u = in2[ju], t = in2[1 - ju];
+                if (G.consumers[u].size() != 1 || G.consumers[u][0] != i) continue;
+                if (G.nodes[u].op == OP_ADD || G.nodes[u].op == OP_ADDRELU || t > u) continue;
+                bool late = false;
+                for (int c : G.consumers[t]) late = late || (c != i && c > u);
+                if (late) continue;
+                return ju;
+            }
+            return -1;
+        };
         std::vector<std::vector<int>> free_at;
         std::vector<int> next_step;
         if (!dry) {
@@ -413,18 +435,34 @@ struct Walker {
             int64_t o[2] = {OFF_NONE, OFF_NONE};
             int m[2] = {M_NONE, M_NONE};
             bool transferred = false;
+            const int reader = (op == OP_ADD || op == OP_ADDRELU) ? shared_reader(i) : -1;
             if (op == OP_RELU || op == OP_BN || op == OP_BNRELU) {
                 const int x = ins[0];
                 if (x == 0) {
-                } else if (gloc[x] == LOC_NONE) {
+                } else if (gloc[x] == LOC_NONE && !shared.count(dy)) {
                     gloc[x] = dy;
                     transferred = true;
                     o[0] = dy;
                     m[0] = M_TRANSFER;
+                } else if (gloc[x] == LOC_NONE) {
+                    // dy is also another tensor's gradient (see shared_reader): leave it untouched
+                    gloc[x] = alloc_c(G.bytes[x]);
+                    o[0] = gloc[x];
+                    m[0] = M_WRITE;
                 } else {
                     o[0] = gloc[x];
                     m[0] = M_ACC;
                 }
+            } else if (reader >= 0) {
+                // both inputs take the (masked) dy buffer over: one of them only reads it, before
+                // anything is accumulated into the other's gradient -- no copy
+                shared[dy] = ins[reader];
+                for (int j = 0; j < 2; ++j) {
+                    gloc[ins[j]] = dy;
+                    o[j] = dy;
+                    m[j] = M_TRANSFER;
+                }
+                transferred = true;
             } else if (op == OP_ADD || op == OP_ADDRELU) {
                 for (int j = 0; j < 2; ++j) {
                     const int u = ins[j];
@@ -457,7 +495,9 @@ struct Walker {
             }
             emit(K_BWD, i, dy, need_off, o[0], m[0], o[1], m[1]);
             if (op != OP_LOSS) {
-                if (!transferred) free_c(dy, G.bytes[i]);
+                const auto sh = shared.find(dy);
+                if (sh != shared.end() && sh->second == i) shared.erase(sh);   // its other owner keeps the buffer
+                else if (!transferred) free_c(dy, G.bytes[i]);
                 gloc[i] = LOC_NONE;
             }
             if (!dry)

@@ -102,19 +102,26 @@ def check(G, cmds, cap):
             assert a_before_b or b_before_a, ("unordered conflicting accesses", recs[ar][5], recs[br][5])
         active.append((a0, a1, aw, ar))
 
-    # contents, replayed in emission order
-    live = {}   # offset -> (size, label)
+    # contents, replayed in emission order.  A range may hold several tensors at once: the backward of
+    # an add can hand its dy buffer to both inputs (one of them only ever reads it).
+    live = {}   # offset -> (size, set of labels)
     for s, p, vc, acc, relabel, c in recs:
         for off, size, w, label in acc:
             if size == 0:
                 continue
             if not w:
-                assert off in live and live[off] == (size, label), ("read finds wrong contents", c, off, live.get(off))
+                assert off in live and live[off][0] == size and label in live[off][1], ("read finds wrong contents", c, off, live.get(off))
+        written = {}
         for off, size, w, label in acc:
             if w and size > 0:
-                for o in [o for o, (sz, _) in live.items() if o < off + size and off < o + sz]:
-                    del live[o]
-                live[off] = (size, label)
+                written.setdefault((off, size), set()).add(label)
+        for (off, size), labels in written.items():
+            for o in [o for o, (sz, _) in live.items() if o < off + size and off < o + sz]:
+                del live[o]
+            live[off] = (size, labels)
+        renamed = {}
         for off, label in relabel:
-            live[off] = (live[off][0], label)
+            renamed.setdefault(off, set()).add(label)
+        for off, labels in renamed.items():
+            live[off] = (live[off][0], labels)
     return len(recs)
