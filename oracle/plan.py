@@ -757,7 +757,13 @@ class Planner:
             for k in L:
                 res = list(cls)
                 res[k] = KEEP
-                T_res = self.evaluate(res, cap=self.cap + G.bytes[G.fmaps[k]])
+                # reference: X resident in an arena enlarged by X's size -- or by 2, 4, 8 times that,
+                # then without limit, when the allocator cannot place the plan in the smallest one
+                T_res = None
+                for f in (1, 2, 4, 8, None):
+                    T_res = self.evaluate(res, cap=(self.cap + f * G.bytes[G.fmaps[k]]) if f else (1 << 46))
+                    if T_res is not None:
+                        break
                 rec = list(cls)
                 rec[k] = RECOMPUTE
                 T_rec = self.evaluate(rec)

@@ -792,7 +792,11 @@ void Planner::step2(std::vector<uint8_t> &cls, double &T0)
         for (int k : L) {
             std::vector<uint8_t> res = cls;
             res[k] = CLS_KEEP;
-            const double T_res = evaluate(res, true, cap + G.bytes[G.fmaps[k]]);
+            // reference: X resident, in an arena enlarged by X's size -- or by more (2, 4, 8 times, then
+            // without limit) when the allocator cannot place that plan in the smallest enlargement
+            double T_res = -1.0;
+            for (int f = 1; f <= 16 && T_res < 0.0; f *= 2)
+                T_res = evaluate(res, true, f <= 8 ? cap + f * G.bytes[G.fmaps[k]] : ((int64_t)1 << 46));
             std::vector<uint8_t> rc = cls;
             rc[k] = CLS_RECOMPUTE;
             const double T_rec = evaluate(rc);
