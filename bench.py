@@ -36,7 +36,7 @@ PAPER_B640_IMG_S = 195.0    # paper, ResNet50 batch 640 on V100 16 GB + PCIe3 (3
 # FETCH_SIZE reads 0.5 GiB there, WRITE_SIZE 1.0 GiB, so fetch x 2.0, write x 1.0.
 # Source: profiles/resnet50_b640_16g_hbm_traffic.txt.  (workload, kernel) -> (fetch KiB, write KiB)
 MEASURED_TRAFFIC_KIB = {
-    ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+lin,fwd+bnstats>"): (349917.0, 473598.0),
+    ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+lin,fwd+bnstats>"): (350062.0, 473599.0),
 }
 TRAFFIC_SCALE = (2.0, 1.0)
 
@@ -143,8 +143,10 @@ def kernel_report(ctx, net, ms, nrefwd_counts=None):
     # algorithmic bytes per element: BN (alone or with a fused ReLU) forward 12 (x for the statistics,
     # x again, y) or 8 when the producing conv supplies the statistics, backward 20 (x and dy twice, dx),
     # re-forward 8; ReLU 8 / 12; add 12;
-    # add + ReLU fused: forward 12, backward 12 (y, dy, masked dy) + 4 or 8 for a second output
+    # add + ReLU fused: forward 12, backward 12 (y, dy, masked dy) + 4 when a second output is written
     fused = {ctx.node_fused(i): L["op"] for i, L in enumerate(net) if ctx.node_fused(i) >= 0}
+    # adds whose backward hands the one (masked) dy buffer to both inputs: no copy is written
+    shared_add = {int(r[1]) for r in ctx.commands() if r[0] == 2 and r[5] == 3 and r[7] == 3}
     bn_bytes = bn_ms = ew_bytes = ew_ms = 0.0
     for i, L in enumerate(net):
         nre = max(1, int(round(refwd[i] / max(fwd[i], 1e-9)))) if refwd[i] > 0 else 0
@@ -152,7 +154,7 @@ def kernel_report(ctx, net, ms, nrefwd_counts=None):
             bn_bytes += ((8 if ctx.bn_stats_source(i) >= 0 else 12) + 20 + 8 * nre) * n_el[i]
             bn_ms += fwd[i] + bwd[i] + refwd[i]
         elif L["op"] == "relu" and fused.get(i) == "add":
-            ew_bytes += (12 + 16 + 12 * nre) * n_el[i]
+            ew_bytes += (12 + (12 if i in shared_add else 16) + 12 * nre) * n_el[i]
             ew_ms += fwd[i] + bwd[i] + refwd[i]
         elif L["op"] == "relu":
             ew_bytes += (8 + 12 + 8 * nre) * n_el[i]
