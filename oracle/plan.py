@@ -741,7 +741,7 @@ class Planner:
                 trial[G.fidx[t]] = KEEP
                 T = self.evaluate(trial)
                 if T is None:
-                    continue
+                    break       # kept "as long as it can fit", in order from the output layer: the scan ends here
                 cur = trial
                 if T < best_T:
                     best_T, best = T, list(cur)

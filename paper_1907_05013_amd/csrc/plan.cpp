@@ -769,7 +769,7 @@ void Planner::step1(const std::vector<uint8_t> &allswap, double T_all, std::vect
             std::vector<uint8_t> trial = cur;
             trial[G.fidx[t]] = CLS_KEEP;
             const double T = evaluate(trial);
-            if (T < 0.0) continue;
+            if (T < 0.0) break;   // "as long as it can fit", in order from the output layer: the scan ends here
             cur = trial;
             if (T < best_T) {
                 best_T = T;
