@@ -142,15 +142,28 @@ def kernel_report(ctx, net, ms, nrefwd_counts=None):
             conv_ms += refwd[i]
     # algorithmic bytes per element: BN (alone or with a fused ReLU) forward 12 (x for the statistics,
     # x again, y) or 8 when the producing conv supplies the statistics, backward 20 (x and dy twice, dx),
-    # re-forward 8; ReLU 8 / 12; add 12;
+    # re-forward 8; a BN applied inside the add + ReLU that consumes it moves nothing of its own in the
+    # forward pass beyond the statistics (4 when it reads x for them, 0 when the conv supplies them);
+    # ReLU 8 / 12; add 12;
     # add + ReLU fused: forward 12, backward 12 (y, dy, masked dy) + 4 when a second output is written
-    fused = {ctx.node_fused(i): L["op"] for i, L in enumerate(net) if ctx.node_fused(i) >= 0}
+    fused, applied = {}, set()
+    for i, L in enumerate(net):
+        f = ctx.node_fused(i)
+        if f < 0:
+            continue
+        if L["op"] == "bn" and net[f].get("x") != i:
+            applied.add(i)          # node_fused names the add + ReLU node that applies it
+        else:
+            fused[f] = L["op"]
     # adds whose backward hands the one (masked) dy buffer to both inputs: no copy is written
     shared_add = {int(r[1]) for r in ctx.commands() if r[0] == 2 and r[5] == 3 and r[7] == 3}
     bn_bytes = bn_ms = ew_bytes = ew_ms = 0.0
     for i, L in enumerate(net):
         nre = max(1, int(round(refwd[i] / max(fwd[i], 1e-9)))) if refwd[i] > 0 else 0
-        if (L["op"] == "bn" and ctx.node_fused(i) < 0) or fused.get(i) == "bn":
+        if i in applied:
+            bn_bytes += ((0 if ctx.bn_stats_source(i) >= 0 else 4) + 20) * n_el[net[i]["x"]]
+            bn_ms += fwd[i] + bwd[i]
+        elif (L["op"] == "bn" and ctx.node_fused(i) < 0) or fused.get(i) == "bn":
             bn_bytes += ((8 if ctx.bn_stats_source(i) >= 0 else 12) + 20 + 8 * nre) * n_el[i]
             bn_ms += fwd[i] + bwd[i] + refwd[i]
         elif L["op"] == "relu" and fused.get(i) == "add":

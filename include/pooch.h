@@ -108,7 +108,10 @@ int32_t pooch_softmax_ce(pooch_ctx *, int32_t logits);
  * relu is executed inside that relu, so its output is never written to memory.  Results are
  * those of the unfused layers; the feature-map set is unchanged (backward of a fused bn+relu
  * reads the bn's input and re-derives the relu decision from it).
- * pooch_node_fused: id of the relu a layer was fused into, -1 if it executes on its own. */
+ * A bn whose only consumer is the add of such an add + relu is applied inside that kernel as well
+ * (the first such input of the add): its forward step is the batch statistics alone, its output is
+ * never written, its backward is unchanged.
+ * pooch_node_fused: id of the relu a layer's output is produced in, -1 if the layer writes its own. */
 pooch_status pooch_set_fusion(pooch_ctx *, int enable);
 int32_t pooch_node_fused(pooch_ctx *, int32_t id);
 /* A convolution whose result goes directly into a batch normalisation also produces that

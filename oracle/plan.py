@@ -52,7 +52,13 @@ class Graph:
     is executed inside that ReLU ("bnrelu", "addrelu"); the BN / add output is then never
     materialised (op "dead", zero bytes, no commands).  The feature-map set does not change:
     backward of a bnrelu reads the BN's input (the ReLU decision is re-derived from it),
-    backward of an addrelu reads the ReLU's output."""
+    backward of an addrelu reads the ReLU's output.
+    One more step: a BN whose only consumer is the add of such an addrelu is applied inside the
+    addrelu's forward kernel (apply_into[bn] = addrelu; the first such input only).  The BN node stays:
+    its forward is the statistics alone and writes no tensor (zero bytes), its backward is unchanged
+    and still receives the gradient along the edge from the addrelu.  Hence two edge sets:
+    `inputs` / `consumers` carry gradients, `finputs` / `fconsumers` say what a forward kernel reads
+    (the addrelu reads the BN's input in place of the BN's output) and decide how long tensors live."""
 
     def __init__(self, net, fuse=False):
         self.net = net
@@ -83,18 +89,34 @@ class Graph:
                     self.ops[i] = "dead"
                     self.inputs[i] = []
                     self.fused_into[i] = j
+        self.apply_into = [-1] * n
+        if fuse:
+            for a in range(n):
+                if self.ops[a] != "addrelu":
+                    continue
+                for b in self.inputs[a]:
+                    if self.ops[b] == "bn" and len(raw[b]) == 1 and self.fused_into[raw[b][0]] == a:
+                        self.apply_into[b] = a
+                        break
+        self.finputs = []
+        for i in range(n):
+            self.finputs.append([self.inputs[t][0] if self.apply_into[t] == i else t for t in self.inputs[i]])
         self.bytes = []
         for i in range(n):
             numel = 1
             for v in self.shape[i]:
                 numel *= v
-            self.bytes.append(0 if self.ops[i] in ("softmax_ce", "dead") else _round(4 * numel))
+            self.bytes.append(0 if self.ops[i] in ("softmax_ce", "dead") or self.apply_into[i] >= 0 else _round(4 * numel))
         self.consumers = [[] for _ in range(n)]
+        self.fconsumers = [[] for _ in range(n)]
         for i in range(n):
             for t in self.inputs[i]:
                 if i not in self.consumers[t]:
                     self.consumers[t].append(i)
-        self.last_consumer = [max(c) if c else -1 for c in self.consumers]
+            for t in self.finputs[i]:
+                if i not in self.fconsumers[t]:
+                    self.fconsumers[t].append(i)
+        self.last_consumer = [max(c) if c else -1 for c in self.fconsumers]
         # tensors the backward of node i reads
         self.needs = []
         for i, op in enumerate(self.ops):
@@ -421,11 +443,11 @@ def _walk(G, cls, cap, ahead, info):
             emit(KWAIT, S_COMPUTE, S.arrive_event[t])
             state[t] = "in"
             return
-        ins = _uniq(G.inputs[t])
+        ins = _uniq(G.finputs[t])
         for u in ins:
             ensure(u, step)
         loc[t] = alloc_c(G.bytes[t])
-        raw = G.inputs[t]
+        raw = G.finputs[t]
         emit(KR, t, loc[t], loc[raw[0]], loc[raw[1]] if len(raw) > 1 else OFF_NONE)
         S.n_refwd += 1
         for u in ins:
@@ -435,10 +457,11 @@ def _walk(G, cls, cap, ahead, info):
 
     # ---------------- forward
     for i in range(1, n):
-        ins = G.inputs[i]
+        ins = G.finputs[i]
         if G.ops[i] == "dead":
             continue
-        if G.ops[i] == "softmax_ce":
+        if G.ops[i] == "softmax_ce" or G.apply_into[i] >= 0:
+            # no output tensor: the loss, and a BN that is applied inside its consumer (statistics only)
             emit(KF, i, OFF_NONE, loc[ins[0]], OFF_NONE)
         else:
             top = i in klass and klass[i] == KEEP

@@ -338,6 +338,59 @@ __global__ __launch_bounds__(BNT) void bn_apply_kernel(const float *__restrict__
     }
 }
 
+// z = max(bn(x) + other, 0): the normalisation of a residual branch applied inside the add + ReLU that
+// consumes it (bn(x) is rounded to fp32 before the add, exactly as when it is stored and re-read)
+template <int V>
+__global__ __launch_bounds__(BNT) void bn_add_relu_kernel(const float *__restrict__ x, const float *__restrict__ other,
+                                                           const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                           const float *__restrict__ mean, const float *__restrict__ istd,
+                                                           float *__restrict__ z, int64_t M, int C, int TX, int TY, int64_t rows_per_blk)
+{
+    const int tid = threadIdx.x;
+    const int tx = tid % TX, ty = tid / TX;
+    const int col = blockIdx.y * TX + tx;
+    if (ty >= TY || col * V >= C) return;
+    float g[V], b[V], mu[V], is[V];
+    ldv<V>(gamma + (int64_t)col * V, g);
+    ldv<V>(beta + (int64_t)col * V, b);
+    ldv<V>(mean + (int64_t)col * V, mu);
+    ldv<V>(istd + (int64_t)col * V, is);
+#pragma unroll
+    for (int i = 0; i < V; ++i) g[i] *= is[i];
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
+    const int64_t r1 = r0 + rows_per_blk < M ? r0 + rows_per_blk : M;
+    constexpr int UR = 2;
+    int64_t r = r0 + ty;
+    for (; r + (int64_t)(UR - 1) * TY < r1; r += (int64_t)UR * TY) {
+        float xv[UR][V], ov[UR][V];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            ldnt<V>(x + (r + (int64_t)u * TY) * C + (int64_t)col * V, xv[u]);
+            ldnt<V>(other + (r + (int64_t)u * TY) * C + (int64_t)col * V, ov[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                const float v = bn_val(xv[u][i], mu[i], g[i], b[i]) + ov[u][i];
+                xv[u][i] = v > 0.f ? v : 0.f;
+            }
+            stnt<V>(z + (r + (int64_t)u * TY) * C + (int64_t)col * V, xv[u]);
+        }
+    }
+    for (; r < r1; r += TY) {
+        float xv[V], ov[V];
+        ldnt<V>(x + r * C + (int64_t)col * V, xv);
+        ldnt<V>(other + r * C + (int64_t)col * V, ov);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const float v = bn_val(xv[i], mu[i], g[i], b[i]) + ov[i];
+            xv[i] = v > 0.f ? v : 0.f;
+        }
+        stnt<V>(z + r * C + (int64_t)col * V, xv);
+    }
+}
+
 // dx (+)= gamma*istd*(dy - dbeta/m - (x-mean)*istd*dgamma/m)
 template <int V, bool ACCUM, bool RELU>
 __global__ __launch_bounds__(BNT) void bn_bwd_apply_kernel(const float *__restrict__ x, const float *dy,
@@ -554,10 +607,9 @@ hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const
     return hipGetLastError();
 }
 
-hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
-                  float *ws, int64_t M, int C, float eps, bool relu, hipStream_t s)
+hipError_t bn_stats(const float *x, float *mean, float *istd, float *ws, int64_t M, int C, float eps, hipStream_t s)
 {
-    if (!x || !gamma || !beta || !y || !mean || !istd || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    if (!x || !mean || !istd || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
     const bool al = ((uintptr_t)x | (uintptr_t)ws | (uintptr_t)mean) % 16 == 0;
     Lay2D L = layout2d(M, C, al, MAX_RBLK);
     const dim3 grid(L.nblk, L.gy), block(BNT);
@@ -566,15 +618,35 @@ hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     bn_stats_final_kernel<<<dim3(C), dim3(64), 0, s>>>(ws, x, mean, istd, L.nblk, C, (double)M, (double)eps);
-    e = hipGetLastError();
+    return hipGetLastError();
+}
+
+hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
+                  float *ws, int64_t M, int C, float eps, bool relu, hipStream_t s)
+{
+    if (!gamma || !beta || !y) return hipErrorInvalidValue;
+    const hipError_t e = bn_stats(x, mean, istd, ws, M, C, eps, s);
     if (e != hipSuccess) return e;
     return bn_apply(x, gamma, beta, mean, istd, y, M, C, relu, s);
 }
 
-hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
-                             float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, bool relu, hipStream_t s)
+hipError_t bn_add_relu_fwd(const float *x, const float *other, const float *gamma, const float *beta, const float *mean,
+                           const float *istd, float *z, int64_t M, int C, hipStream_t s)
 {
-    if (!x || !gamma || !beta || !y || !mean || !istd || !tiles || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    if (!x || !other || !gamma || !beta || !mean || !istd || !z || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    const bool al = ((uintptr_t)x | (uintptr_t)other | (uintptr_t)z | (uintptr_t)gamma | (uintptr_t)beta | (uintptr_t)mean |
+                     (uintptr_t)istd) % 16 == 0;
+    const Lay2D L = layout2d(M, C, al, APPLY_BLOCKS, 4);
+    const dim3 grid(L.nblk, L.gy), block(BNT);
+    if (L.V == 4) bn_add_relu_kernel<4><<<grid, block, 0, s>>>(x, other, gamma, beta, mean, istd, z, M, C, L.TX, L.TY, L.rows_per_blk);
+    else bn_add_relu_kernel<1><<<grid, block, 0, s>>>(x, other, gamma, beta, mean, istd, z, M, C, L.TX, L.TY, L.rows_per_blk);
+    return hipGetLastError();
+}
+
+hipError_t bn_stats_from_tiles(float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, float *mean, float *istd,
+                               hipStream_t s)
+{
+    if (!mean || !istd || !tiles || !bn_args_ok(M, C)) return hipErrorInvalidValue;
     if (tiles_m <= 0 || rows_per_tile <= 0 || (int64_t)tiles_m * rows_per_tile < M || (int64_t)(tiles_m - 1) * rows_per_tile >= M)
         return hipErrorInvalidValue;
     const int group = bn_tiles_group(tiles_m);
@@ -589,7 +661,14 @@ hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *be
     } else {
         bn_tiles_final_kernel<<<dim3(C), dim3(64), 0, s>>>(tiles, mean, istd, tiles_m, rows_per_tile, M, C, (double)eps);
     }
-    const hipError_t e = hipGetLastError();
+    return hipGetLastError();
+}
+
+hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
+                             float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, bool relu, hipStream_t s)
+{
+    if (!x || !gamma || !beta || !y) return hipErrorInvalidValue;
+    const hipError_t e = bn_stats_from_tiles(tiles, tiles_m, rows_per_tile, M, C, eps, mean, istd, s);
     if (e != hipSuccess) return e;
     return bn_apply(x, gamma, beta, mean, istd, y, M, C, relu, s);
 }

@@ -43,8 +43,16 @@ struct Graph {
     // filled by analyze()
     std::vector<int> fused_into;                // BN / add node -> the ReLU node that executes it, or -1
     std::vector<int64_t> bytes;                 // arena bytes of each node's output (0 for the loss)
+    // A BN whose only consumer is the add of an add+ReLU node is applied inside that node's forward
+    // kernel (apply_into[bn] = the add+ReLU node; the first such input only).  The BN node stays: its
+    // forward is the statistics alone and writes no tensor (zero bytes), its backward is unchanged and
+    // still receives the gradient along the edge from the add.  Hence two edge sets: inputs / consumers
+    // carry gradients; finputs / fconsumers say what a forward kernel reads (the add+ReLU reads the
+    // BN's input in place of the BN's output) and decide how long tensors live (last_consumer).
+    std::vector<int> apply_into;
     std::vector<std::vector<int>> inputs;       // as given (may repeat)
-    std::vector<std::vector<int>> consumers;    // forward consumers, ascending, unique
+    std::vector<std::vector<int>> consumers;    // consumers along the gradient edges, ascending, unique
+    std::vector<std::vector<int>> finputs, fconsumers;
     std::vector<int> last_consumer;
     std::vector<std::vector<int>> needs;        // tensors the backward of a node reads
     std::vector<int> fmaps;                     // tensor id of every feature map, ascending

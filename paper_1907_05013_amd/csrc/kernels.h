@@ -53,6 +53,13 @@ size_t bn_tiles_workspace_floats(int tiles_m, int C);
 // deviations of rows [t * rows_per_tile, ...)): merges them per channel in double, then applies
 hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
                              float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, bool relu, hipStream_t s);
+// the statistics alone (for a normalisation that is applied inside its consumer), from x or from conv_fwd's tiles
+hipError_t bn_stats(const float *x, float *mean, float *istd, float *ws, int64_t M, int C, float eps, hipStream_t s);
+hipError_t bn_stats_from_tiles(float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, float *mean, float *istd,
+                               hipStream_t s);
+// z = max(bn(x) + other, 0) with given statistics: a residual branch's normalisation inside the add + ReLU
+hipError_t bn_add_relu_fwd(const float *x, const float *other, const float *gamma, const float *beta, const float *mean,
+                           const float *istd, float *z, int64_t M, int C, hipStream_t s);
 // apply only, with saved statistics (used when a BN output is recomputed)
 hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const float *mean, const float *istd,
                     float *y, int64_t M, int C, bool relu, hipStream_t s);

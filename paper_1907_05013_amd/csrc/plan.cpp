@@ -341,10 +341,10 @@ struct Walker {
             state[t] = ST_IN;
             return;
         }
-        const std::vector<int> ins = uniq(G.inputs[t]);
+        const std::vector<int> ins = uniq(G.finputs[t]);
         for (int u : ins) ensure(u, step);
         loc[t] = alloc_c(G.bytes[t]);
-        const std::vector<int> &raw = G.inputs[t];
+        const std::vector<int> &raw = G.finputs[t];
         emit(K_REFWD, t, loc[t], loc[raw[0]], raw.size() > 1 ? loc[raw[1]] : OFF_NONE);
         S.n_refwd++;
         for (int u : ins)
@@ -366,9 +366,10 @@ struct Walker {
     {
         const int n = G.n();
         for (int i = 1; i < n; ++i) {
-            const std::vector<int> &ins = G.inputs[i];
+            const std::vector<int> &ins = G.finputs[i];
             if (G.nodes[i].op == OP_DEAD) continue;
-            if (G.nodes[i].op == OP_LOSS) {
+            if (G.nodes[i].op == OP_LOSS || G.apply_into[i] >= 0) {
+                // no output tensor: the loss, and a BN that is applied inside its consumer (statistics only)
                 emit(K_FWD, i, OFF_NONE, loc[ins[0]], OFF_NONE);
             } else {
                 const bool top = klass(i) == CLS_KEEP;
@@ -521,8 +522,11 @@ std::string Graph::analyze()
     inputs.assign(n, {});
     bytes.assign(n, 0);
     consumers.assign(n, {});
+    finputs.assign(n, {});
+    fconsumers.assign(n, {});
     needs.assign(n, {});
     fused_into.assign(n, -1);
+    apply_into.assign(n, -1);
     for (int i = 0; i < n; ++i) {
         const Node &nd = nodes[i];
         if (i > 0 && nd.op == OP_INPUT) return "only one input node is supported";
@@ -553,13 +557,28 @@ std::string Graph::analyze()
             b.op = OP_DEAD;
             b.nin = 0;
         }
+        for (int a = 0; a < n; ++a) {
+            if (nodes[a].op != OP_ADDRELU) continue;
+            for (int j = 0; j < nodes[a].nin; ++j) {
+                const int b = nodes[a].in[j];
+                if (nodes[b].op == OP_BN && raw[b].size() == 1 && fused_into[raw[b][0]] == a) {
+                    apply_into[b] = a;
+                    break;
+                }
+            }
+        }
     }
     for (int i = 0; i < n; ++i) {
         const Node &nd = nodes[i];
-        for (int j = 0; j < nd.nin; ++j) inputs[i].push_back(nd.in[j]);
-        bytes[i] = (nd.op == OP_LOSS || nd.op == OP_DEAD) ? 0 : round_up(4 * nd.numel());
+        for (int j = 0; j < nd.nin; ++j) {
+            inputs[i].push_back(nd.in[j]);
+            finputs[i].push_back(apply_into[nd.in[j]] == i ? nodes[nd.in[j]].in[0] : nd.in[j]);
+        }
+        bytes[i] = (nd.op == OP_LOSS || nd.op == OP_DEAD || apply_into[i] >= 0) ? 0 : round_up(4 * nd.numel());
         for (int t : inputs[i])
             if (std::find(consumers[t].begin(), consumers[t].end(), i) == consumers[t].end()) consumers[t].push_back(i);
+        for (int t : finputs[i])
+            if (std::find(fconsumers[t].begin(), fconsumers[t].end(), i) == fconsumers[t].end()) fconsumers[t].push_back(i);
         switch (nd.op) {
         case OP_CONV: case OP_BN: case OP_BNRELU: case OP_MAXPOOL: case OP_FC: case OP_LOSS: needs[i] = {inputs[i][0]}; break;
         case OP_RELU: case OP_ADDRELU: needs[i] = {i}; break;
@@ -569,7 +588,7 @@ std::string Graph::analyze()
     last_consumer.assign(n, -1);
     for (int t = 0; t < n; ++t) {
         if (t != n - 1 && consumers[t].empty() && nodes[t].op != OP_DEAD) return "a layer output is never consumed";
-        for (int c : consumers[t]) last_consumer[t] = std::max(last_consumer[t], c);
+        for (int c : fconsumers[t]) last_consumer[t] = std::max(last_consumer[t], c);
     }
     std::vector<char> needed(n, 0);
     for (int i = 0; i < n; ++i)

@@ -201,6 +201,12 @@ struct Exec {
         case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
             const bool relu = nd.op == OP_BNRELU;
+            if (G.apply_into[i] >= 0) {   // applied inside the add + ReLU that consumes it: statistics only
+                if (c->stats_from[i] >= 0)
+                    return pk::bn_stats_from_tiles(R(c->off_ws_bn), c->stats_tiles[i][0], c->stats_tiles[i][1], M, (int)nd.C,
+                                                   nd.eps, R(c->off_mean[i]), R(c->off_istd[i]), s);
+                return pk::bn_stats(D(in0), R(c->off_mean[i]), R(c->off_istd[i]), R(c->off_ws_bn), M, (int)nd.C, nd.eps, s);
+            }
             if (refwd)
                 return pk::bn_apply(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), R(c->off_mean[i]), R(c->off_istd[i]),
                                     D(out), M, (int)nd.C, relu, s);
@@ -213,7 +219,16 @@ struct Exec {
         }
         case OP_RELU: return pk::relu_fwd(D(in0), D(out), nd.numel(), s);
         case OP_ADD: return pk::add_fwd(D(in0), D(in1), D(out), nd.numel(), s);
-        case OP_ADDRELU: return pk::add_relu_fwd(D(in0), D(in1), D(out), nd.numel(), s);
+        case OP_ADDRELU: {
+            // an input whose normalisation is applied here: in0 / in1 then is that layer's input
+            for (int j = 0; j < 2; ++j) {
+                const int b = nd.in[j];
+                if (G.apply_into[b] != i) continue;
+                return pk::bn_add_relu_fwd(D(j == 0 ? in0 : in1), D(j == 0 ? in1 : in0), R(P(b, 0).off_val), R(P(b, 1).off_val),
+                                           R(c->off_mean[b]), R(c->off_istd[b]), D(out), nd.numel() / nd.C, (int)nd.C, s);
+            }
+            return pk::add_relu_fwd(D(in0), D(in1), D(out), nd.numel(), s);
+        }
         case OP_MAXPOOL: return pk::maxpool_fwd(D(in0), D(out), pool_geom(G, i), s);
         case OP_GAVGPOOL: {
             const Node &x = G.nodes[nd.in[0]];
@@ -676,7 +691,7 @@ int32_t pooch_node_fused(pooch_ctx *c, int32_t id)
 {
     if (!c || !c->finalized) return POOCH_E_STATE;
     if (id < 0 || id >= c->G.n()) return POOCH_E_INVALID;
-    return c->G.fused_into[id];
+    return c->G.fused_into[id] >= 0 ? c->G.fused_into[id] : c->G.apply_into[id];
 }
 
 int32_t pooch_bn_stats_source(pooch_ctx *c, int32_t id)
@@ -854,7 +869,8 @@ pooch_status pooch_capture_tensor(pooch_ctx *c, int32_t id, float *host)
 {
     NEED_FINAL(c);
     if (id <= 0 || id >= c->G.n() || c->G.nodes[id].op == OP_LOSS) return fail(c, POOCH_E_INVALID, "capture: not a layer output");
-    if (c->G.nodes[id].op == OP_DEAD) return fail(c, POOCH_E_STATE, "capture: this layer is fused into its consumer, its output is never materialised");
+    if (c->G.nodes[id].op == OP_DEAD || c->G.apply_into[id] >= 0)
+        return fail(c, POOCH_E_STATE, "capture: this layer is fused into its consumer, its output is never materialised");
     c->capture[id] = host;
     return POOCH_OK;
 }

@@ -18,7 +18,7 @@ def _accesses(G, c):
     relabel = []
     if k in (KF, KR):
         i = c[1]
-        ins = G.inputs[i]
+        ins = G.finputs[i]
         offs = [c[3], c[4]]
         for j, t in enumerate(ins):
             if offs[j] >= 0:

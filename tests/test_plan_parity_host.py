@@ -59,7 +59,8 @@ def test_feature_maps_and_command_lists_identical(name, fuse):
     incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
     c, _ = lib_ctx(net, BIG, fuse)
     assert [(G.bytes[t], t) for t in G.fmaps] == c.fmaps()
-    assert [c.node_fused(i) for i in range(G.n)] == G.fused_into
+    assert [c.node_fused(i) for i in range(G.n)] == [
+        f if f >= 0 else a for f, a in zip(G.fused_into, G.apply_into)]
     assert any(v >= 0 for v in G.fused_into) == fuse
     rng = np.random.default_rng(21)
     prof = rand_profile(G, rng)
