@@ -149,6 +149,20 @@ pooch_status pooch_capture_tensor(pooch_ctx *, int32_t id, float *host);
 /* gradient of the loss w.r.t. saved BN statistics is internal; the per-channel batch mean
  * and 1/sqrt(var+eps) of BN node `node` (C floats each) can be read back for tests. */
 pooch_status pooch_get_bn_stats(pooch_ctx *, int32_t node, float *mean, float *istd);
+/* Running averages of a BN layer's batch statistics, the quantities a trained network normalises with at
+ * inference time (part of the training loop of section 2.1, though no step's loss or gradient depends on
+ * them): every forward execution of the layer -- in pooch_step, and in the profiling passes, which are real
+ * iterations (section 4.2) -- replaces
+ *     mean <- decay * mean + (1 - decay) * batch mean
+ *     var  <- decay * var  + (1 - decay) * batch variance * m / max(m - 1, 1)      (m = values per channel)
+ * A re-forward (recompute class) normalises with the statistics saved by the forward pass and leaves the
+ * averages alone, so they do not depend on the plan.  They start at mean 0, variance 1 when the graph is
+ * finalized; decay defaults to 0.9 and may be changed at any time (1 freezes the averages, 0 keeps the last
+ * batch's statistics).  get / set copy C floats each between host buffers and the context (a NULL pointer
+ * skips that half); both synchronise.  POOCH_E_INVALID: not a BN layer, or decay outside [0, 1]. */
+pooch_status pooch_set_bn_decay(pooch_ctx *, float decay);
+pooch_status pooch_get_bn_running(pooch_ctx *, int32_t node, float *mean, float *var);
+pooch_status pooch_set_bn_running(pooch_ctx *, int32_t node, const float *mean, const float *var);
 
 /* ---- feature maps: the units being classified (section 4.1.1) --------------------------*/
 int32_t pooch_num_nodes(pooch_ctx *);

@@ -9,6 +9,12 @@ sections 3.1 and 3.2), so the definition of the in-core step is the oracle for a
 A tensor consumed by several layers receives the sum of their gradients, added in the
 order the backward pass reaches the consumers (reverse insertion order).
 
+Each forward pass also moves every batch normalisation's running averages (the statistics a
+trained network normalises with; part of the training loop of section 2.1, used by no step):
+mean <- d mean + (1 - d) batch mean, var <- d var + (1 - d) batch variance m / max(m - 1, 1),
+m values per channel, from mean 0 and variance 1, d = 0.9 -- the convention of the framework
+the paper's implementation sits in (section 5).  Kept in float64 whatever the step's dtype.
+
 Test infrastructure only; imports nothing from the HIP library or its binding.
 """
 import numpy as np
@@ -25,9 +31,11 @@ def _inputs(layer):
 
 
 class OracleNet:
-    def __init__(self, net, params, dtype=np.float32):
+    def __init__(self, net, params, dtype=np.float32, decay=0.9):
         self.net = net
         self.dtype = np.dtype(dtype)
+        self.decay = float(decay)
+        self.running = {}       # bn layer -> [mean, var], float64
         self.params = {}
         it = iter(params)
         for i, layer in enumerate(net):
@@ -50,6 +58,7 @@ class OracleNet:
                 g, b = self.params[i]
                 y, mean, istd = L.bn_fwd(out[layer["x"]], g, b, layer["eps"])
                 self.aux[i] = (mean, istd)
+                self._update_running(i, out[layer["x"]])
             elif op == "relu":
                 y = L.relu_fwd(out[layer["x"]])
             elif op == "add":
@@ -70,6 +79,16 @@ class OracleNet:
             out.append(y)
         self.out = out
         return out[-1]
+
+    def _update_running(self, i, x):
+        cn = x.shape[1]
+        v = np.moveaxis(np.asarray(x, np.float64), 1, 0).reshape(cn, -1)
+        m = v.shape[1]
+        mu = v.sum(axis=1) / m
+        var = ((v - mu[:, None]) ** 2).sum(axis=1) / m
+        rm, rv = self.running.get(i, (np.zeros(cn), np.ones(cn)))
+        d = self.decay
+        self.running[i] = [d * rm + (1.0 - d) * mu, d * rv + (1.0 - d) * var * (m / max(m - 1, 1))]
 
     def backward(self):
         """returns (param grads in parameter order, gradient of the loss w.r.t. the input)"""

@@ -63,6 +63,9 @@ SYMBOLS = {
     "pooch_set_batch": (_i32, [_ctx, C.c_void_p, C.c_void_p]),
     "pooch_capture_tensor": (_i32, [_ctx, _i32, C.c_void_p]),
     "pooch_get_bn_stats": (_i32, [_ctx, _i32, C.c_void_p, C.c_void_p]),
+    "pooch_set_bn_decay": (_i32, [_ctx, C.c_float]),
+    "pooch_get_bn_running": (_i32, [_ctx, _i32, C.c_void_p, C.c_void_p]),
+    "pooch_set_bn_running": (_i32, [_ctx, _i32, C.c_void_p, C.c_void_p]),
     "pooch_num_nodes": (_i32, [_ctx]),
     "pooch_num_fmaps": (_i32, [_ctx]),
     "pooch_fmap_info": (_i32, [_ctx, _i32, C.POINTER(_sz), _pi32]),
@@ -310,6 +313,20 @@ class Context:
         istd = np.empty(channels, np.float32)
         self._chk(self.L.pooch_get_bn_stats(self.h, node, mean.ctypes.data, istd.ctypes.data))
         return mean, istd
+
+    def set_bn_decay(self, decay):
+        self._chk(self.L.pooch_set_bn_decay(self.h, float(decay)))
+
+    def get_bn_running(self, node, channels):
+        mean = np.empty(channels, np.float32)
+        var = np.empty(channels, np.float32)
+        self._chk(self.L.pooch_get_bn_running(self.h, node, mean.ctypes.data, var.ctypes.data))
+        return mean, var
+
+    def set_bn_running(self, node, mean, var):
+        mean = np.ascontiguousarray(mean, np.float32)
+        var = np.ascontiguousarray(var, np.float32)
+        self._chk(self.L.pooch_set_bn_running(self.h, node, mean.ctypes.data, var.ctypes.data))
 
     # ---- feature maps
     def fmaps(self):

@@ -177,10 +177,19 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;  // lane 0 holds the total
 }
 
+// running averages: the batch mean, and the batch variance with the factor m / (m - 1) that makes it unbiased
+__device__ __forceinline__ void run_update(const BnRun &run, int c, double mean, double var, double m)
+{
+    if (!run.mean) return;
+    const double d = (double)run.decay, adjust = m / (m > 1.0 ? m - 1.0 : 1.0);
+    run.mean[c] = (float)(d * (double)run.mean[c] + (1.0 - d) * mean);
+    run.var[c] = (float)(d * (double)run.var[c] + (1.0 - d) * var * adjust);
+}
+
 // Stage 2: one wavefront per channel sums the row-block partials in double.
 __global__ __launch_bounds__(64) void bn_stats_final_kernel(const float *__restrict__ part, const float *__restrict__ x,
                                                              float *__restrict__ mean, float *__restrict__ istd,
-                                                             int nblk, int C, double m, double eps)
+                                                             int nblk, int C, double m, double eps, BnRun run)
 {
     const int c = blockIdx.x, lane = threadIdx.x;
     double a = 0.0, b = 0.0;
@@ -196,6 +205,7 @@ __global__ __launch_bounds__(64) void bn_stats_final_kernel(const float *__restr
         if (var < 0.0) var = 0.0;
         mean[c] = (float)((double)x[c] + d1);
         istd[c] = (float)(1.0 / sqrt(var + eps));
+        run_update(run, c, (double)x[c] + d1, var, m);
     }
 }
 
@@ -204,7 +214,7 @@ __global__ __launch_bounds__(64) void bn_stats_final_kernel(const float *__restr
 // n = na + nb, d = mb - ma, mean = ma + d nb / n, M2 = M2a + M2b + d^2 na nb / n.
 __global__ __launch_bounds__(64) void bn_tiles_final_kernel(const float *__restrict__ tiles, float *__restrict__ mean,
                                                              float *__restrict__ istd, int tiles_m, int rows_per_tile, int64_t M,
-                                                             int C, double eps)
+                                                             int C, double eps, BnRun run)
 {
     const int c = blockIdx.x, lane = threadIdx.x;
     double n = 0.0, mu = 0.0, m2 = 0.0;
@@ -233,6 +243,7 @@ __global__ __launch_bounds__(64) void bn_tiles_final_kernel(const float *__restr
         if (var < 0.0) var = 0.0;
         mean[c] = (float)mu;
         istd[c] = (float)(1.0 / sqrt(var + eps));
+        run_update(run, c, mu, var, (double)M);
     }
 }
 
@@ -607,9 +618,9 @@ hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const
     return hipGetLastError();
 }
 
-hipError_t bn_stats(const float *x, float *mean, float *istd, float *ws, int64_t M, int C, float eps, hipStream_t s)
+hipError_t bn_stats(const float *x, float *mean, float *istd, float *ws, int64_t M, int C, float eps, BnRun run, hipStream_t s)
 {
-    if (!x || !mean || !istd || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    if (!x || !mean || !istd || !ws || !bn_args_ok(M, C) || !run.mean != !run.var) return hipErrorInvalidValue;
     const bool al = ((uintptr_t)x | (uintptr_t)ws | (uintptr_t)mean) % 16 == 0;
     Lay2D L = layout2d(M, C, al, MAX_RBLK);
     const dim3 grid(L.nblk, L.gy), block(BNT);
@@ -617,15 +628,15 @@ hipError_t bn_stats(const float *x, float *mean, float *istd, float *ws, int64_t
     else bn_partial_kernel<1, false><<<grid, block, 0, s>>>(x, nullptr, nullptr, nullptr, nullptr, nullptr, ws, M, C, L.TX, L.TY, L.rows_per_blk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    bn_stats_final_kernel<<<dim3(C), dim3(64), 0, s>>>(ws, x, mean, istd, L.nblk, C, (double)M, (double)eps);
+    bn_stats_final_kernel<<<dim3(C), dim3(64), 0, s>>>(ws, x, mean, istd, L.nblk, C, (double)M, (double)eps, run);
     return hipGetLastError();
 }
 
 hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
-                  float *ws, int64_t M, int C, float eps, bool relu, hipStream_t s)
+                  float *ws, int64_t M, int C, float eps, bool relu, BnRun run, hipStream_t s)
 {
     if (!gamma || !beta || !y) return hipErrorInvalidValue;
-    const hipError_t e = bn_stats(x, mean, istd, ws, M, C, eps, s);
+    const hipError_t e = bn_stats(x, mean, istd, ws, M, C, eps, run, s);
     if (e != hipSuccess) return e;
     return bn_apply(x, gamma, beta, mean, istd, y, M, C, relu, s);
 }
@@ -644,9 +655,9 @@ hipError_t bn_add_relu_fwd(const float *x, const float *other, const float *gamm
 }
 
 hipError_t bn_stats_from_tiles(float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, float *mean, float *istd,
-                               hipStream_t s)
+                               BnRun run, hipStream_t s)
 {
-    if (!mean || !istd || !tiles || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    if (!mean || !istd || !tiles || !bn_args_ok(M, C) || !run.mean != !run.var) return hipErrorInvalidValue;
     if (tiles_m <= 0 || rows_per_tile <= 0 || (int64_t)tiles_m * rows_per_tile < M || (int64_t)(tiles_m - 1) * rows_per_tile >= M)
         return hipErrorInvalidValue;
     const int group = bn_tiles_group(tiles_m);
@@ -657,18 +668,19 @@ hipError_t bn_stats_from_tiles(float *tiles, int tiles_m, int rows_per_tile, int
         bn_tiles_group_kernel<<<dim3(groups, (C + 63) / 64), dim3(256), 0, s>>>(tiles, folded, tiles_m, rows_per_tile, group, M, C);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        bn_tiles_final_kernel<<<dim3(C), dim3(64), 0, s>>>(folded, mean, istd, groups, rows_per_tile * group, M, C, (double)eps);
+        bn_tiles_final_kernel<<<dim3(C), dim3(64), 0, s>>>(folded, mean, istd, groups, rows_per_tile * group, M, C, (double)eps, run);
     } else {
-        bn_tiles_final_kernel<<<dim3(C), dim3(64), 0, s>>>(tiles, mean, istd, tiles_m, rows_per_tile, M, C, (double)eps);
+        bn_tiles_final_kernel<<<dim3(C), dim3(64), 0, s>>>(tiles, mean, istd, tiles_m, rows_per_tile, M, C, (double)eps, run);
     }
     return hipGetLastError();
 }
 
 hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
-                             float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, bool relu, hipStream_t s)
+                             float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, bool relu, BnRun run,
+                             hipStream_t s)
 {
     if (!x || !gamma || !beta || !y) return hipErrorInvalidValue;
-    const hipError_t e = bn_stats_from_tiles(tiles, tiles_m, rows_per_tile, M, C, eps, mean, istd, s);
+    const hipError_t e = bn_stats_from_tiles(tiles, tiles_m, rows_per_tile, M, C, eps, mean, istd, run, s);
     if (e != hipSuccess) return e;
     return bn_apply(x, gamma, beta, mean, istd, y, M, C, relu, s);
 }

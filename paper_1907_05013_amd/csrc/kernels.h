@@ -42,21 +42,28 @@ const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles = false);
 const char *conv_dgrad_kernel(const ConvGeom &g);
 const char *conv_wgrad_kernel(const ConvGeom &g);
 
+// running averages a statistics pass also updates (both pointers null: none):
+// mean <- decay * mean + (1 - decay) * batch mean, var <- decay * var + (1 - decay) * batch variance * M / max(M - 1, 1)
+struct BnRun {
+    float *mean = nullptr, *var = nullptr;
+    float decay = 0.f;
+};
 // number of floats of scratch the BN reductions need for an [M][C] tensor
 size_t bn_workspace_floats(int64_t M, int C);
 // batch statistics (mean, 1/sqrt(var+eps)) then y = gamma*(x-mean)*istd + beta; relu: y = max(y, 0)
 hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
-                  float *ws, int64_t M, int C, float eps, bool relu, hipStream_t s);
+                  float *ws, int64_t M, int C, float eps, bool relu, BnRun run, hipStream_t s);
 // floats of the buffer conv_fwd's bn_tiles and bn_fwd_from_tiles share (the tiles plus room to fold them)
 size_t bn_tiles_workspace_floats(int tiles_m, int C);
 // the same from per-tile statistics left by conv_fwd (tiles[t][0][C] = mean, tiles[t][1][C] = sum of squared
 // deviations of rows [t * rows_per_tile, ...)): merges them per channel in double, then applies
 hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *beta, float *y, float *mean, float *istd,
-                             float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, bool relu, hipStream_t s);
+                             float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, bool relu, BnRun run,
+                             hipStream_t s);
 // the statistics alone (for a normalisation that is applied inside its consumer), from x or from conv_fwd's tiles
-hipError_t bn_stats(const float *x, float *mean, float *istd, float *ws, int64_t M, int C, float eps, hipStream_t s);
+hipError_t bn_stats(const float *x, float *mean, float *istd, float *ws, int64_t M, int C, float eps, BnRun run, hipStream_t s);
 hipError_t bn_stats_from_tiles(float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, float *mean, float *istd,
-                               hipStream_t s);
+                               BnRun run, hipStream_t s);
 // z = max(bn(x) + other, 0) with given statistics: a residual branch's normalisation inside the add + ReLU
 hipError_t bn_add_relu_fwd(const float *x, const float *other, const float *gamma, const float *beta, const float *mean,
                            const float *istd, float *z, int64_t M, int C, hipStream_t s);

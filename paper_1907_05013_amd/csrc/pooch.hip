@@ -51,6 +51,8 @@ struct pooch_ctx {
     bool finalized = false;
     std::vector<ParamInfo> params;
     std::vector<int64_t> off_mean, off_istd;  // per node (BN only), resident offsets
+    std::vector<int64_t> off_rmean, off_rvar; // running averages of the same layers
+    float bn_decay = 0.9f;
     int64_t off_input = 0, off_labels = 0, off_ws_wgrad = 0, off_ws_bn = 0, off_loss_ps = 0, off_loss = 0;
     int64_t resident_bytes = 0;
     int nclasses = 0;
@@ -201,11 +203,14 @@ struct Exec {
         case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
             const bool relu = nd.op == OP_BNRELU;
+            // every forward execution moves the running averages; a re-forward uses the saved statistics and does not
+            const pk::BnRun run{R(c->off_rmean[i]), R(c->off_rvar[i]), c->bn_decay};
             if (G.apply_into[i] >= 0) {   // applied inside the add + ReLU that consumes it: statistics only
+                if (refwd) return hipSuccess;   // nothing to recompute: the statistics are saved, there is no output
                 if (c->stats_from[i] >= 0)
                     return pk::bn_stats_from_tiles(R(c->off_ws_bn), c->stats_tiles[i][0], c->stats_tiles[i][1], M, (int)nd.C,
-                                                   nd.eps, R(c->off_mean[i]), R(c->off_istd[i]), s);
-                return pk::bn_stats(D(in0), R(c->off_mean[i]), R(c->off_istd[i]), R(c->off_ws_bn), M, (int)nd.C, nd.eps, s);
+                                                   nd.eps, R(c->off_mean[i]), R(c->off_istd[i]), run, s);
+                return pk::bn_stats(D(in0), R(c->off_mean[i]), R(c->off_istd[i]), R(c->off_ws_bn), M, (int)nd.C, nd.eps, run, s);
             }
             if (refwd)
                 return pk::bn_apply(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), R(c->off_mean[i]), R(c->off_istd[i]),
@@ -213,9 +218,9 @@ struct Exec {
             if (c->stats_from[i] >= 0)   // the convolution that has just run left the statistics per row tile
                 return pk::bn_fwd_from_tiles(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), D(out), R(c->off_mean[i]),
                                              R(c->off_istd[i]), R(c->off_ws_bn), c->stats_tiles[i][0], c->stats_tiles[i][1], M,
-                                             (int)nd.C, nd.eps, relu, s);
+                                             (int)nd.C, nd.eps, relu, run, s);
             return pk::bn_fwd(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), D(out), R(c->off_mean[i]), R(c->off_istd[i]),
-                              R(c->off_ws_bn), M, (int)nd.C, nd.eps, relu, s);
+                              R(c->off_ws_bn), M, (int)nd.C, nd.eps, relu, run, s);
         }
         case OP_RELU: return pk::relu_fwd(D(in0), D(out), nd.numel(), s);
         case OP_ADD: return pk::add_fwd(D(in0), D(in1), D(out), nd.numel(), s);
@@ -720,6 +725,8 @@ pooch_status pooch_finalize(pooch_ctx *c)
     c->off_labels = take(G.nodes[0].N * 4);
     c->off_mean.assign(n, -1);
     c->off_istd.assign(n, -1);
+    c->off_rmean.assign(n, -1);
+    c->off_rvar.assign(n, -1);
     c->params.clear();
     size_t ws_wgrad = 0, ws_bn = 0;
     for (int i = 0; i < n; ++i) {
@@ -749,6 +756,8 @@ pooch_status pooch_finalize(pooch_ctx *c)
             }
             c->off_mean[i] = take(nd.C * 4);
             c->off_istd[i] = take(nd.C * 4);
+            c->off_rmean[i] = take(nd.C * 4);
+            c->off_rvar[i] = take(nd.C * 4);
             ws_bn = std::max(ws_bn, pk::bn_workspace_floats(nd.numel() / nd.C, (int)nd.C) * 4);
         } else if (nd.op == OP_LOSS) {
             c->nclasses = (int)G.nodes[nd.in[0]].C;
@@ -761,6 +770,8 @@ pooch_status pooch_finalize(pooch_ctx *c)
             G.nodes[j].param[1] = G.nodes[i].param[1];
             c->off_mean[j] = c->off_mean[i];
             c->off_istd[j] = c->off_istd[i];
+            c->off_rmean[j] = c->off_rmean[i];
+            c->off_rvar[j] = c->off_rvar[i];
         }
     }
     // convolutions followed directly by their batch normalisation hand it the statistics
@@ -789,6 +800,14 @@ pooch_status pooch_finalize(pooch_ctx *c)
     c->resident_bytes = off;
     if ((size_t)off > c->arena_bytes) return fail(c, POOCH_E_BUDGET, "the resident region alone exceeds the arena");
     c->capture.assign(n, nullptr);
+    if (c->arena) {   // running averages start at mean 0, variance 1
+        for (int i = 0; i < n; ++i) {
+            if (c->off_rmean[i] < 0 || G.nodes[i].op == OP_DEAD) continue;
+            const std::vector<float> zero((size_t)G.nodes[i].C, 0.f), one((size_t)G.nodes[i].C, 1.f);
+            HIPCHK(hipMemcpy(c->arena + c->off_rmean[i], zero.data(), zero.size() * 4, hipMemcpyHostToDevice));
+            HIPCHK(hipMemcpy(c->arena + c->off_rvar[i], one.data(), one.size() * 4, hipMemcpyHostToDevice));
+        }
+    }
     c->finalized = true;
     return POOCH_OK;
 }
@@ -883,6 +902,36 @@ pooch_status pooch_get_bn_stats(pooch_ctx *c, int32_t node, float *mean, float *
     const size_t bytes = (size_t)c->G.nodes[node].C * 4;
     if (mean) HIPCHK(hipMemcpy(mean, c->arena + c->off_mean[node], bytes, hipMemcpyDeviceToHost));
     if (istd) HIPCHK(hipMemcpy(istd, c->arena + c->off_istd[node], bytes, hipMemcpyDeviceToHost));
+    return POOCH_OK;
+}
+
+pooch_status pooch_get_bn_running(pooch_ctx *c, int32_t node, float *mean, float *var)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (node < 0 || node >= c->G.n() || c->off_rmean[node] < 0) return fail(c, POOCH_E_INVALID, "not a bn node");
+    const size_t bytes = (size_t)c->G.nodes[node].C * 4;
+    if (mean) HIPCHK(hipMemcpy(mean, c->arena + c->off_rmean[node], bytes, hipMemcpyDeviceToHost));
+    if (var) HIPCHK(hipMemcpy(var, c->arena + c->off_rvar[node], bytes, hipMemcpyDeviceToHost));
+    return POOCH_OK;
+}
+
+pooch_status pooch_set_bn_running(pooch_ctx *c, int32_t node, const float *mean, const float *var)
+{
+    NEED_FINAL(c);
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (node < 0 || node >= c->G.n() || c->off_rmean[node] < 0) return fail(c, POOCH_E_INVALID, "not a bn node");
+    const size_t bytes = (size_t)c->G.nodes[node].C * 4;
+    if (mean) HIPCHK(hipMemcpy(c->arena + c->off_rmean[node], mean, bytes, hipMemcpyHostToDevice));
+    if (var) HIPCHK(hipMemcpy(c->arena + c->off_rvar[node], var, bytes, hipMemcpyHostToDevice));
+    return POOCH_OK;
+}
+
+pooch_status pooch_set_bn_decay(pooch_ctx *c, float decay)
+{
+    if (!c) return POOCH_E_INVALID;
+    if (!(decay >= 0.f && decay <= 1.f)) return fail(c, POOCH_E_INVALID, "bn decay must lie in [0, 1]");
+    c->bn_decay = decay;
     return POOCH_OK;
 }
 

@@ -106,6 +106,13 @@ def test_dangling_output_and_state_errors():
     assert e.value.status == B.E_INVALID
     with pytest.raises(B.PoochError):
         c.set_profile(*([[-1.0] * c.n_nodes] * 3 + [[1.0] * c.n_fmaps] * 2))
+    with pytest.raises(B.PoochError) as e:
+        c.get_bn_running(2, 1)                                    # no arena to read from
+    assert e.value.status == B.E_STATE
+    with pytest.raises(B.PoochError) as e:
+        c.set_bn_decay(1.5)
+    assert e.value.status == B.E_INVALID
+    c.set_bn_decay(0.99)
 
 
 def test_budget_errors_at_planning_time():

@@ -266,17 +266,22 @@ def test_training_loop_profile_then_plan_vs_oracle():
     """the paper's user flow (section 4.1.2): the first iterations run with every map swapped and are
     profiled, then the classification is made, then training continues under the plan -- with a plain
     SGD update after every step.  Parameters after six iterations against the oracle doing the same six
-    steps, and against an in-core run of the library (bit-exact)."""
+    steps, and against an in-core run of the library (bit-exact).  The batch normalisations' running
+    averages go through the same six updates in all three (re-forwards must not add any)."""
     net = reduced_nets()["resnet"]
     seed, lr, iters, prof_iters = 31, 0.05, 6, 3
     params = workloads.make_params(net, seed, perturb=True)
     x, t = workloads.make_batch(net, seed)
     shapes = [s for _, _, s in workloads.param_shapes(net)]
+    shp = workloads.shapes(net)
     # oracle: plain loop
     op = [p.copy() for p in params]
-    olosses = []
+    olosses, orun = [], {}
     for _ in range(iters):
-        loss, grads, _ = OracleNet(net, op, np.float32).step(x, t)
+        o = OracleNet(net, op, np.float32)
+        o.running = orun
+        loss, grads, _ = o.step(x, t)
+        orun = o.running
         olosses.append(loss)
         op = [(p - np.float32(lr) * g).astype(np.float32) for p, g in zip(op, grads)]
     res, peak = plan_sizes(net)
@@ -299,13 +304,32 @@ def test_training_loop_profile_then_plan_vs_oracle():
             c.finish_profile()
             cls, _ = c.plan("refine", 4, restarts=2)
             assert any(v != B.KEEP for v in cls)
-            for _ in range(iters - prof_iters):
+            losses.append(c.step())
+            c.sgd_update(lr)
+            # the remaining iterations under a plan that certainly recomputes
+            rng, cap = np.random.default_rng(9), int(peak * 0.6) // 256 * 256
+            while True:
+                forced = [int(v) for v in rng.integers(0, 3, c.n_fmaps)]
+                try:
+                    n_re = OP.build_schedule(G, forced, cap, True).n_refwd
+                except OP.Budget:
+                    continue
+                if n_re >= 3:
+                    break
+            c.set_plan(forced, True)
+            for _ in range(iters - prof_iters - 1):
                 losses.append(c.step())
                 c.sgd_update(lr)
-        runs[tag] = (losses, c.get_params(shapes))
+            assert c.stats().n_refwd == n_re
+        bns = [i for i, l in enumerate(net) if l["op"] == "bn"]
+        runs[tag] = (losses, c.get_params(shapes), [c.get_bn_running(i, shp[i][1]) for i in bns])
         c.close()
-    l_in, p_in = runs["incore"]
-    l_b, p_b = runs["budget"]
+    l_in, p_in, r_in = runs["incore"]
+    l_b, p_b, r_b = runs["budget"]
+    assert sorted(orun) == bns
+    for i, (m_in, v_in), (m_b, v_b) in zip(bns, r_in, r_b):
+        assert m_in.tobytes() == m_b.tobytes() and v_in.tobytes() == v_b.tobytes()
+        assert rel(m_in, orun[i][0]) <= RTOL and rel(v_in, orun[i][1]) <= RTOL, (i, rel(m_in, orun[i][0]), rel(v_in, orun[i][1]))
     assert [np.float32(v).tobytes() for v in l_in] == [np.float32(v).tobytes() for v in l_b]
     for a, b in zip(p_in, p_b):
         assert a.tobytes() == b.tobytes()

@@ -257,3 +257,43 @@ def test_f32_build_tracks_f64():
     assert abs(l32 - l64) < 1e-5 * abs(l64)
     for a, b in zip(g32, g64):
         assert np.linalg.norm(a - b) <= 1e-4 * max(np.linalg.norm(b), 1e-12)
+
+
+def test_bn_running_averages_closed_form():
+    """k forward passes over one batch: a geometric series towards numpy's mean and unbiased
+    variance (np.var, ddof=1) of the layer's input, from (0, 1); decay 0 keeps the batch's own
+    statistics (tied to the saved mean / istd of the forward pass), decay 1 never moves"""
+    net = workloads.resnet50(batch=3, size=16, nclasses=4, blocks=(1, 1), width=4)
+    params = workloads.make_params(net, 5, perturb=True)
+    x, t = workloads.make_batch(net, 5)
+    bns = [i for i, l in enumerate(net) if l["op"] == "bn"]
+    d, k = 0.8, 3
+    on = OracleNet(net, params, np.float64, decay=d)
+    for _ in range(k):
+        on.forward(x, t)
+    assert sorted(on.running) == bns
+    for i in bns:
+        v = on.out[net[i]["x"]]
+        axes = (0,) + tuple(range(2, v.ndim))
+        rm, rv = on.running[i]
+        np.testing.assert_allclose(rm, (1 - d ** k) * np.mean(v, axis=axes), rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(rv, d ** k + (1 - d ** k) * np.var(v, axis=axes, ddof=1), rtol=1e-12)
+    last = OracleNet(net, params, np.float64, decay=0.0)
+    last.forward(x, t)
+    frozen = OracleNet(net, params, np.float64, decay=1.0)
+    frozen.forward(x, t)
+    for i in bns:
+        mean, istd = last.aux[i]
+        m = last.out[net[i]["x"]].size // mean.size
+        np.testing.assert_allclose(last.running[i][0], mean, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(last.running[i][1], (1.0 / istd ** 2 - net[i]["eps"]) * m / (m - 1), rtol=1e-9)
+        assert (frozen.running[i][0] == 0).all() and (frozen.running[i][1] == 1).all()
+    # a single value per channel: the variance term is 0 and the factor m / max(m - 1, 1) is 1
+    one = workloads.Net()
+    h = one.bn(one.input((1, 3, 1, 1)))
+    one.softmax_ce(one.fc(one.gavgpool(h), 2))
+    o1 = OracleNet(one, workloads.make_params(one, 1), np.float64, decay=0.5)
+    xb, tb = workloads.make_batch(one, 1)
+    o1.forward(xb, tb)
+    np.testing.assert_allclose(o1.running[1][0], 0.5 * xb.reshape(3))
+    np.testing.assert_allclose(o1.running[1][1], 0.5)
