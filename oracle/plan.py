@@ -54,7 +54,7 @@ class Graph:
     backward of a bnrelu reads the BN's input (the ReLU decision is re-derived from it),
     backward of an addrelu reads the ReLU's output.
     One more step: a BN whose only consumer is the add of such an addrelu is applied inside the
-    addrelu's forward kernel (apply_into[bn] = addrelu; the first such input only).  The BN node stays:
+    addrelu's forward kernel (apply_into[bn] = addrelu; either input or both).  The BN node stays:
     its forward is the statistics alone and writes no tensor (zero bytes), its backward is unchanged
     and still receives the gradient along the edge from the addrelu.  Hence two edge sets:
     `inputs` / `consumers` carry gradients, `finputs` / `fconsumers` say what a forward kernel reads
@@ -97,7 +97,6 @@ class Graph:
                 for b in self.inputs[a]:
                     if self.ops[b] == "bn" and len(raw[b]) == 1 and self.fused_into[raw[b][0]] == a:
                         self.apply_into[b] = a
-                        break
         self.finputs = []
         for i in range(n):
             self.finputs.append([self.inputs[t][0] if self.apply_into[t] == i else t for t in self.inputs[i]])

@@ -350,24 +350,43 @@ __global__ __launch_bounds__(BNT) void bn_apply_kernel(const float *__restrict__
 }
 
 // z = max(bn(x) + other, 0): the normalisation of a residual branch applied inside the add + ReLU that
-// consumes it (bn(x) is rounded to fp32 before the add, exactly as when it is stored and re-read)
-template <int V>
-__global__ __launch_bounds__(BNT) void bn_add_relu_kernel(const float *__restrict__ x, const float *__restrict__ other,
-                                                           const float *__restrict__ gamma, const float *__restrict__ beta,
-                                                           const float *__restrict__ mean, const float *__restrict__ istd,
-                                                           float *__restrict__ z, int64_t M, int C, int TX, int TY, int64_t rows_per_blk)
+// consumes it (bn(x) is rounded to fp32 before the add, exactly as when it is stored and re-read).
+// BOTH: the other input is normalised here as well (a block whose shortcut is a projection):
+// z = max(bn(x) + bn2(other), 0).
+struct BnAffine {
+    const float *gamma, *beta, *mean, *istd;
+};
+
+template <int V, bool BOTH>
+__global__ __launch_bounds__(BNT) void bn_add_relu_kernel(const float *__restrict__ x, const float *__restrict__ other, BnAffine p,
+                                                           BnAffine q, float *__restrict__ z, int64_t M, int C, int TX, int TY,
+                                                           int64_t rows_per_blk)
 {
     const int tid = threadIdx.x;
     const int tx = tid % TX, ty = tid / TX;
     const int col = blockIdx.y * TX + tx;
     if (ty >= TY || col * V >= C) return;
     float g[V], b[V], mu[V], is[V];
-    ldv<V>(gamma + (int64_t)col * V, g);
-    ldv<V>(beta + (int64_t)col * V, b);
-    ldv<V>(mean + (int64_t)col * V, mu);
-    ldv<V>(istd + (int64_t)col * V, is);
+    ldv<V>(p.gamma + (int64_t)col * V, g);
+    ldv<V>(p.beta + (int64_t)col * V, b);
+    ldv<V>(p.mean + (int64_t)col * V, mu);
+    ldv<V>(p.istd + (int64_t)col * V, is);
 #pragma unroll
     for (int i = 0; i < V; ++i) g[i] *= is[i];
+    float g2[V], b2[V], mu2[V];
+    if (BOTH) {
+        ldv<V>(q.gamma + (int64_t)col * V, g2);
+        ldv<V>(q.beta + (int64_t)col * V, b2);
+        ldv<V>(q.mean + (int64_t)col * V, mu2);
+        ldv<V>(q.istd + (int64_t)col * V, is);
+#pragma unroll
+        for (int i = 0; i < V; ++i) g2[i] *= is[i];
+    }
+    auto combine = [&](float xv, float ov, int i) {
+        const float o = BOTH ? bn_val(ov, mu2[i], g2[i], b2[i]) : ov;
+        const float v = bn_val(xv, mu[i], g[i], b[i]) + o;
+        return v > 0.f ? v : 0.f;
+    };
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
     const int64_t r1 = r0 + rows_per_blk < M ? r0 + rows_per_blk : M;
     constexpr int UR = 2;
@@ -382,10 +401,7 @@ __global__ __launch_bounds__(BNT) void bn_add_relu_kernel(const float *__restric
 #pragma unroll
         for (int u = 0; u < UR; ++u) {
 #pragma unroll
-            for (int i = 0; i < V; ++i) {
-                const float v = bn_val(xv[u][i], mu[i], g[i], b[i]) + ov[u][i];
-                xv[u][i] = v > 0.f ? v : 0.f;
-            }
+            for (int i = 0; i < V; ++i) xv[u][i] = combine(xv[u][i], ov[u][i], i);
             stnt<V>(z + (r + (int64_t)u * TY) * C + (int64_t)col * V, xv[u]);
         }
     }
@@ -394,10 +410,7 @@ __global__ __launch_bounds__(BNT) void bn_add_relu_kernel(const float *__restric
         ldnt<V>(x + r * C + (int64_t)col * V, xv);
         ldnt<V>(other + r * C + (int64_t)col * V, ov);
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-            const float v = bn_val(xv[i], mu[i], g[i], b[i]) + ov[i];
-            xv[i] = v > 0.f ? v : 0.f;
-        }
+        for (int i = 0; i < V; ++i) xv[i] = combine(xv[i], ov[i], i);
         stnt<V>(z + r * C + (int64_t)col * V, xv);
     }
 }
@@ -642,15 +655,21 @@ hipError_t bn_fwd(const float *x, const float *gamma, const float *beta, float *
 }
 
 hipError_t bn_add_relu_fwd(const float *x, const float *other, const float *gamma, const float *beta, const float *mean,
-                           const float *istd, float *z, int64_t M, int C, hipStream_t s)
+                           const float *istd, const float *gamma2, const float *beta2, const float *mean2, const float *istd2,
+                           float *z, int64_t M, int C, hipStream_t s)
 {
     if (!x || !other || !gamma || !beta || !mean || !istd || !z || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    const bool both = gamma2 != nullptr;
+    if (both ? (!beta2 || !mean2 || !istd2) : (beta2 || mean2 || istd2)) return hipErrorInvalidValue;
     const bool al = ((uintptr_t)x | (uintptr_t)other | (uintptr_t)z | (uintptr_t)gamma | (uintptr_t)beta | (uintptr_t)mean |
-                     (uintptr_t)istd) % 16 == 0;
+                     (uintptr_t)istd | (uintptr_t)gamma2 | (uintptr_t)beta2 | (uintptr_t)mean2 | (uintptr_t)istd2) % 16 == 0;
     const Lay2D L = layout2d(M, C, al, APPLY_BLOCKS, 4);
     const dim3 grid(L.nblk, L.gy), block(BNT);
-    if (L.V == 4) bn_add_relu_kernel<4><<<grid, block, 0, s>>>(x, other, gamma, beta, mean, istd, z, M, C, L.TX, L.TY, L.rows_per_blk);
-    else bn_add_relu_kernel<1><<<grid, block, 0, s>>>(x, other, gamma, beta, mean, istd, z, M, C, L.TX, L.TY, L.rows_per_blk);
+    const BnAffine p{gamma, beta, mean, istd}, q{gamma2, beta2, mean2, istd2};
+#define BN_ADD_RELU(V, BOTH) bn_add_relu_kernel<V, BOTH><<<grid, block, 0, s>>>(x, other, p, q, z, M, C, L.TX, L.TY, L.rows_per_blk)
+    if (L.V == 4) { if (both) BN_ADD_RELU(4, true); else BN_ADD_RELU(4, false); }
+    else { if (both) BN_ADD_RELU(1, true); else BN_ADD_RELU(1, false); }
+#undef BN_ADD_RELU
     return hipGetLastError();
 }
 

@@ -64,9 +64,11 @@ hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *be
 hipError_t bn_stats(const float *x, float *mean, float *istd, float *ws, int64_t M, int C, float eps, BnRun run, hipStream_t s);
 hipError_t bn_stats_from_tiles(float *tiles, int tiles_m, int rows_per_tile, int64_t M, int C, float eps, float *mean, float *istd,
                                BnRun run, hipStream_t s);
-// z = max(bn(x) + other, 0) with given statistics: a residual branch's normalisation inside the add + ReLU
+// z = max(bn(x) + other, 0) with given statistics: a residual branch's normalisation inside the add + ReLU;
+// with gamma2 ... istd2 (all four or none) the other input is normalised too: z = max(bn(x) + bn2(other), 0)
 hipError_t bn_add_relu_fwd(const float *x, const float *other, const float *gamma, const float *beta, const float *mean,
-                           const float *istd, float *z, int64_t M, int C, hipStream_t s);
+                           const float *istd, const float *gamma2, const float *beta2, const float *mean2, const float *istd2,
+                           float *z, int64_t M, int C, hipStream_t s);
 // apply only, with saved statistics (used when a BN output is recomputed)
 hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const float *mean, const float *istd,
                     float *y, int64_t M, int C, bool relu, hipStream_t s);

@@ -561,10 +561,7 @@ std::string Graph::analyze()
             if (nodes[a].op != OP_ADDRELU) continue;
             for (int j = 0; j < nodes[a].nin; ++j) {
                 const int b = nodes[a].in[j];
-                if (nodes[b].op == OP_BN && raw[b].size() == 1 && fused_into[raw[b][0]] == a) {
-                    apply_into[b] = a;
-                    break;
-                }
+                if (nodes[b].op == OP_BN && raw[b].size() == 1 && fused_into[raw[b][0]] == a) apply_into[b] = a;
             }
         }
     }

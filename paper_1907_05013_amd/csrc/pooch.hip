@@ -225,12 +225,15 @@ struct Exec {
         case OP_RELU: return pk::relu_fwd(D(in0), D(out), nd.numel(), s);
         case OP_ADD: return pk::add_fwd(D(in0), D(in1), D(out), nd.numel(), s);
         case OP_ADDRELU: {
-            // an input whose normalisation is applied here: in0 / in1 then is that layer's input
-            for (int j = 0; j < 2; ++j) {
-                const int b = nd.in[j];
-                if (G.apply_into[b] != i) continue;
-                return pk::bn_add_relu_fwd(D(j == 0 ? in0 : in1), D(j == 0 ? in1 : in0), R(P(b, 0).off_val), R(P(b, 1).off_val),
-                                           R(c->off_mean[b]), R(c->off_istd[b]), D(out), nd.numel() / nd.C, (int)nd.C, s);
+            // inputs whose normalisation is applied here: in0 / in1 then is that layer's input
+            const bool ap0 = G.apply_into[nd.in[0]] == i, ap1 = G.apply_into[nd.in[1]] == i;
+            if (ap0 || ap1) {
+                const int b = nd.in[ap0 ? 0 : 1], b2 = nd.in[1];
+                const bool both = ap0 && ap1;
+                return pk::bn_add_relu_fwd(D(ap0 ? in0 : in1), D(ap0 ? in1 : in0), R(P(b, 0).off_val), R(P(b, 1).off_val),
+                                           R(c->off_mean[b]), R(c->off_istd[b]), both ? R(P(b2, 0).off_val) : nullptr,
+                                           both ? R(P(b2, 1).off_val) : nullptr, both ? R(c->off_mean[b2]) : nullptr,
+                                           both ? R(c->off_istd[b2]) : nullptr, D(out), nd.numel() / nd.C, (int)nd.C, s);
             }
             return pk::add_relu_fwd(D(in0), D(in1), D(out), nd.numel(), s);
         }

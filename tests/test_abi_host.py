@@ -150,11 +150,12 @@ def test_which_batch_normalisations_take_their_statistics_from_the_conv():
     net, _ = workloads.load("resnet50_b64")
     c = B.Context(net, 1 << 40, device=None)
     bns = [i for i, L in enumerate(net) if L["op"] == "bn"]
-    # a bn runs on its own, inside the relu it feeds (then the relu node carries it), or -- a residual branch's
-    # last bn -- is applied inside the add + relu while its statistics stay a step of its own
+    # a bn runs inside the relu it feeds (then the relu node carries it), or -- a residual branch's last bn and a
+    # projection shortcut's bn -- is applied inside the add + relu while its statistics stay a step of its own
     def source(i):
         return c.bn_stats_source(i) if c.bn_stats_source(i) >= 0 else c.bn_stats_source(c.node_fused(i))
     assert len(bns) == 53 and all(source(i) == net[i]["x"] for i in bns)
     applied_in_add = [i for i in bns if c.node_fused(i) >= 0 and net[c.node_fused(i)]["op"] == "relu"
                       and c.bn_stats_source(i) >= 0]
-    assert len(applied_in_add) == 16
+    assert len(applied_in_add) == 16 + 4          # one per block, plus the four projection shortcuts
+    assert all(c.node_fused(i) >= 0 for i in bns)  # the other 33 run inside their relu
