@@ -109,7 +109,7 @@ int32_t pooch_softmax_ce(pooch_ctx *, int32_t logits);
  * those of the unfused layers; the feature-map set is unchanged (backward of a fused bn+relu
  * reads the bn's input and re-derives the relu decision from it).
  * A bn whose only consumer is the add of such an add + relu is applied inside that kernel as well
- * (the first such input of the add): its forward step is the batch statistics alone, its output is
+ * (either input of the add, or both): its forward step is the batch statistics alone, its output is
  * never written, its backward is unchanged.
  * pooch_node_fused: id of the relu a layer's output is produced in, -1 if the layer writes its own. */
 pooch_status pooch_set_fusion(pooch_ctx *, int enable);
