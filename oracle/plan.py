@@ -101,11 +101,14 @@ class Graph:
         for i in range(n):
             self.finputs.append([self.inputs[t][0] if self.apply_into[t] == i else t for t in self.inputs[i]])
         self.bytes = []
+        self.gbytes = []
         for i in range(n):
             numel = 1
             for v in self.shape[i]:
                 numel *= v
             self.bytes.append(0 if self.ops[i] in ("softmax_ce", "dead") or self.apply_into[i] >= 0 else _round(4 * numel))
+            # its gradient: a full tensor also where the output itself is never written (apply_into)
+            self.gbytes.append(0 if self.ops[i] in ("softmax_ce", "dead") else _round(4 * numel))
         self.consumers = [[] for _ in range(n)]
         self.fconsumers = [[] for _ in range(n)]
         for i in range(n):
@@ -521,7 +524,7 @@ def _walk(G, cls, cap, ahead, info):
                 outs.append((dy, M_TRANSFER))
             elif gloc[x] is None:
                 # dy is also another tensor's gradient (see _shared_reader): leave it untouched
-                gloc[x] = alloc_c(G.bytes[x])
+                gloc[x] = alloc_c(G.gbytes[x])
                 outs.append((gloc[x], M_WRITE))
             else:
                 outs.append((gloc[x], M_ACC))
@@ -542,7 +545,7 @@ def _walk(G, cls, cap, ahead, info):
                     transferred = True
                     outs.append((dy, M_TRANSFER))
                 elif gloc[u] is None:
-                    gloc[u] = alloc_c(G.bytes[u])
+                    gloc[u] = alloc_c(G.gbytes[u])
                     outs.append((gloc[u], M_WRITE))
                 else:
                     outs.append((gloc[u], M_ACC))
@@ -551,7 +554,7 @@ def _walk(G, cls, cap, ahead, info):
             if x == 0:
                 outs.append((OFF_NONE, M_NONE))
             elif gloc[x] is None:
-                gloc[x] = alloc_c(G.bytes[x])
+                gloc[x] = alloc_c(G.gbytes[x])
                 outs.append((gloc[x], M_WRITE))
             else:
                 outs.append((gloc[x], M_ACC))
@@ -562,7 +565,7 @@ def _walk(G, cls, cap, ahead, info):
             if shared.get(dy) == i:
                 del shared[dy]          # its other owner keeps the buffer
             elif not transferred:
-                free_c(dy, G.bytes[i])
+                free_c(dy, G.gbytes[i])
             gloc[i] = None
         if not dry:
             for t in free_at.get(i, []):

@@ -43,6 +43,7 @@ struct Graph {
     // filled by analyze()
     std::vector<int> fused_into;                // BN / add node -> the ReLU node that executes it, or -1
     std::vector<int64_t> bytes;                 // arena bytes of each node's output (0 for the loss)
+    std::vector<int64_t> gbytes;                // ... of its gradient: a full tensor also where the output is never written
     // A BN whose only consumer is the add of an add+ReLU node is applied inside that node's forward
     // kernel (apply_into[bn] = the add+ReLU node; the first such input only).  The BN node stays: its
     // forward is the statistics alone and writes no tensor (zero bytes), its backward is unchanged and

@@ -447,7 +447,7 @@ struct Walker {
                     m[0] = M_TRANSFER;
                 } else if (gloc[x] == LOC_NONE) {
                     // dy is also another tensor's gradient (see shared_reader): leave it untouched
-                    gloc[x] = alloc_c(G.bytes[x]);
+                    gloc[x] = alloc_c(G.gbytes[x]);
                     o[0] = gloc[x];
                     m[0] = M_WRITE;
                 } else {
@@ -474,7 +474,7 @@ struct Walker {
                         o[j] = dy;
                         m[j] = M_TRANSFER;
                     } else if (gloc[u] == LOC_NONE) {
-                        gloc[u] = alloc_c(G.bytes[u]);
+                        gloc[u] = alloc_c(G.gbytes[u]);
                         o[j] = gloc[u];
                         m[j] = M_WRITE;
                     } else {
@@ -486,7 +486,7 @@ struct Walker {
                 const int x = ins[0];
                 if (x == 0) {
                 } else if (gloc[x] == LOC_NONE) {
-                    gloc[x] = alloc_c(G.bytes[x]);
+                    gloc[x] = alloc_c(G.gbytes[x]);
                     o[0] = gloc[x];
                     m[0] = M_WRITE;
                 } else {
@@ -498,7 +498,7 @@ struct Walker {
             if (op != OP_LOSS) {
                 const auto sh = shared.find(dy);
                 if (sh != shared.end() && sh->second == i) shared.erase(sh);   // its other owner keeps the buffer
-                else if (!transferred) free_c(dy, G.bytes[i]);
+                else if (!transferred) free_c(dy, G.gbytes[i]);
                 gloc[i] = LOC_NONE;
             }
             if (!dry)
@@ -521,6 +521,7 @@ std::string Graph::analyze()
     if (nodes[n - 1].op != OP_LOSS) return "the last node must be softmax_ce";
     inputs.assign(n, {});
     bytes.assign(n, 0);
+    gbytes.assign(n, 0);
     consumers.assign(n, {});
     finputs.assign(n, {});
     fconsumers.assign(n, {});
@@ -572,6 +573,7 @@ std::string Graph::analyze()
             finputs[i].push_back(apply_into[nd.in[j]] == i ? nodes[nd.in[j]].in[0] : nd.in[j]);
         }
         bytes[i] = (nd.op == OP_LOSS || nd.op == OP_DEAD || apply_into[i] >= 0) ? 0 : round_up(4 * nd.numel());
+        gbytes[i] = (nd.op == OP_LOSS || nd.op == OP_DEAD) ? 0 : round_up(4 * nd.numel());
         for (int t : inputs[i])
             if (std::find(consumers[t].begin(), consumers[t].end(), i) == consumers[t].end()) consumers[t].push_back(i);
         for (int t : finputs[i])

@@ -417,7 +417,7 @@ pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool prof
         case K_BWD: {
             const int i = cm.id;
             for (int j = 0; j < 2; ++j)
-                if (cm.a[3 + 2 * j] != M_NONE && !in_arena(cm.a[2 + 2 * j], G.bytes[G.nodes[i].in[j]]))
+                if (cm.a[3 + 2 * j] != M_NONE && !in_arena(cm.a[2 + 2 * j], G.gbytes[G.nodes[i].in[j]]))
                     return fail(c, POOCH_E_INVALID, "command outside the arena");
             X.mid = (tm && tm->mid[k] >= 0) ? c->timing_events[tm->mid[k]] : nullptr;
             HIPCHK(X.backward(i, cm.a));

@@ -33,7 +33,7 @@ def _accesses(G, c):
         i, dy, need = c[1], c[2], c[3]
         op = G.ops[i]
         if op != "softmax_ce":
-            acc.append((dy, G.bytes[i], False, ("g", i)))
+            acc.append((dy, G.gbytes[i], False, ("g", i)))
         if G.needs[i] and need >= 0:
             acc.append((need, G.bytes[G.needs[i][0]], False, ("v", G.needs[i][0])))
         outs = [(c[4], c[5]), (c[6], c[7])]
@@ -42,19 +42,19 @@ def _accesses(G, c):
             if mode == M_NONE:
                 continue
             if mode == M_WRITE:
-                acc.append((off, G.bytes[t], True, ("g", t)))
+                acc.append((off, G.gbytes[t], True, ("g", t)))
             elif mode == M_ACC:
-                acc.append((off, G.bytes[t], False, ("g", t)))
-                acc.append((off, G.bytes[t], True, ("g", t)))
+                acc.append((off, G.gbytes[t], False, ("g", t)))
+                acc.append((off, G.gbytes[t], True, ("g", t)))
             elif mode == M_TRANSFER:
                 assert off == dy
                 if op == "add":
                     relabel.append((off, ("g", t)))
                 elif op == "addrelu":
                     # masked in place: a read-modify-write of the dy buffer, which changes owner
-                    acc.append((off, G.bytes[t], True, ("g", t)))
+                    acc.append((off, G.gbytes[t], True, ("g", t)))
                 else:
-                    acc.append((off, G.bytes[t], True, ("g", t)))
+                    acc.append((off, G.gbytes[t], True, ("g", t)))
     return acc, relabel
 
 

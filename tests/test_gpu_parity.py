@@ -248,6 +248,34 @@ def test_fc_on_spatial_input_and_3d():
     check_against_oracle("fc on 3-d map", net, 5)
 
 
+def test_add_whose_inputs_cannot_share_one_gradient_buffer():
+    """the skip tensor of the first add has a consumer created after the branch, so the branch's batch
+    normalisation (applied inside the add + relu, its own output never written) receives a gradient buffer
+    of its own; the second add normalises both of its inputs.  Against the oracle, and under plans that
+    swap and recompute."""
+    net = workloads.late_fork(batch=3, ch=12, size=10)
+    params, x, t, loss, grads = check_against_oracle("late fork", net, 5)
+    G = OP.Graph(net, fuse=FUSE)
+    assert any(r[0] == OP.KB and G.ops[r[1]] == "addrelu" and OP.M_WRITE in (r[5], r[7])
+               for r in OP.build_schedule(G, [OP.KEEP] * len(G.fmaps), 1 << 40).cmds)
+    res, peak = plan_sizes(net)
+    rng = np.random.default_rng(3)
+    ran = 0
+    for trial in range(60):
+        cls = [int(v) for v in rng.integers(0, 3, len(G.fmaps))]
+        cap = int(peak * rng.uniform(0.5, 1.0)) // 256 * 256
+        try:
+            OP.build_schedule(G, cls, cap, True)
+        except OP.Budget:
+            continue
+        l1, g1, _, _ = gpu_step(net, params, x, t, cls=cls, sched=True, dyn_bytes=cap)
+        assert_bit_exact("late fork trial %d" % trial, (loss, grads), (l1, g1))
+        ran += 1
+        if ran >= 4:
+            break
+    assert ran >= 2
+
+
 def test_unfused_layers_vs_oracle_and_fused_run(monkeypatch):
     """the same reduced ResNet with fusion switched off: the stand-alone BN, ReLU and add kernels
     against the oracle, and the fused run against the unfused one (they may differ in the last

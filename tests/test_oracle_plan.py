@@ -196,11 +196,13 @@ def small_nets():
         "res": workloads.resnet50(batch=2, size=32, nclasses=5, blocks=(2, 1), width=4),
         "c3d": workloads.cnn3d(size=8, channels=(2, 3, 4), nclasses=2, batch=2),
         "chain": relu_chain(6),
+        # an add that cannot share its gradient buffer: the normalised branch gets a buffer of its own
+        "fork": workloads.late_fork(),
     }
 
 
 @pytest.mark.parametrize("fuse", [False, True])
-@pytest.mark.parametrize("name", ["tiny", "res", "c3d", "chain"])
+@pytest.mark.parametrize("name", ["tiny", "res", "c3d", "chain", "fork"])
 def test_random_plans_schedule_valid(name, fuse):
     net = small_nets()[name]
     G = P.Graph(net, fuse=fuse)

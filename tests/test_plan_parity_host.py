@@ -26,6 +26,7 @@ def nets():
         "res": workloads.resnet50(batch=2, size=32, nclasses=5, blocks=(2, 1), width=4),
         "c3d": workloads.cnn3d(size=8, channels=(2, 3, 4), nclasses=2, batch=2),
         "bott": workloads.bottleneck_stage(batch=2, ch=16, size=8, blocks=2),
+        "fork": workloads.late_fork(),
     }
 
 
@@ -51,7 +52,7 @@ def as_rows(S):
 
 
 @pytest.mark.parametrize("fuse", [False, True])
-@pytest.mark.parametrize("name", ["tiny", "res", "c3d", "bott"])
+@pytest.mark.parametrize("name", ["tiny", "res", "c3d", "bott", "fork"])
 def test_feature_maps_and_command_lists_identical(name, fuse):
     net = nets()[name]
     G = P.Graph(net, fuse=fuse)

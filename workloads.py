@@ -186,6 +186,21 @@ def bottleneck_stage(batch=32, ch=256, size=56, blocks=3, nclasses=10):
     return net
 
 
+def late_fork(batch=2, ch=8, size=8, nclasses=3):
+    """Test shape: a residual add whose skip tensor t gets one more consumer after the branch was built, so
+    that the add's backward cannot hand a single gradient buffer to both inputs (the branch's gradient needs
+    a buffer of its own); the late consumer's result joins a second add whose inputs are both normalised."""
+    net = Net()
+    t = net.input((batch, 3, size, size))
+    t = net.relu(net.bn(net.conv(t, ch, (3, 3), (1, 1), (1, 1))))
+    u = net.bn(net.conv(t, ch, (3, 3), (1, 1), (1, 1)))
+    v = net.bn(net.conv(t, ch, (1, 1), (1, 1), (0, 0)))
+    z = net.relu(net.add(t, u))
+    w = net.relu(net.add(net.bn(net.conv(z, ch, (1, 1), (1, 1), (0, 0))), v))
+    net.softmax_ce(net.fc(net.gavgpool(w), nclasses))
+    return net
+
+
 def resnet50(batch=64, size=224, nclasses=1000, blocks=(3, 4, 6, 3), width=64):
     """ResNet-50, original form: 7x7/2 stem, 3x3/2 maxpool pad 1, bottleneck 3-4-6-3 with a
     projection shortcut in the first block of each stage, 1000-way FC."""
