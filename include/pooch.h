@@ -93,7 +93,8 @@ const char *pooch_last_error(pooch_ctx *);
  * entries ordered (d,)h,w.  dims of the input are N,C,(D,)H,W.
  * conv: cross-correlation, zero padding, no bias.  bn: training-mode batch normalisation
  * over batch x space with learnable gamma/beta.  maxpool pads with -inf and sends the
- * gradient to the first maximal element in scan order.  fc has a bias.  softmax_ce is the
+ * gradient to the first maximal element in scan order.  fc has a bias.  add takes two
+ * different tensors of one shape (a + a is POOCH_E_INVALID).  softmax_ce is the
  * terminal node: mean over the batch of the softmax cross-entropy against int32 labels. */
 int32_t pooch_input(pooch_ctx *, const int64_t *dims, int ndim);
 int32_t pooch_conv(pooch_ctx *, int32_t x, int cout, const int *k, const int *stride, const int *pad, int nspatial);

@@ -70,6 +70,8 @@ class Graph:
             if L["op"] == "input":
                 self.inputs.append([])
             elif L["op"] == "add":
+                if L["a"] == L["b"]:
+                    raise ValueError("add takes two different tensors")
                 self.inputs.append([L["a"], L["b"]])
             else:
                 self.inputs.append([L["x"]])
@@ -446,16 +448,18 @@ def _walk(G, cls, cap, ahead, info):
             state[t] = "in"
             return
         ins = _uniq(G.finputs[t])
+        # forward-transient inputs (no feature maps) that this call has to regenerate are dropped again after
+        # use; one that is already there belongs to an outer recomputation that still reads it
+        made = [u for u in ins if u != 0 and u not in klass and loc[u] is None]
         for u in ins:
             ensure(u, step)
         loc[t] = alloc_c(G.bytes[t])
         raw = G.finputs[t]
         emit(KR, t, loc[t], loc[raw[0]], loc[raw[1]] if len(raw) > 1 else OFF_NONE)
         S.n_refwd += 1
-        for u in ins:
-            if u != 0 and u not in klass:
-                free_c(loc[u], G.bytes[u])
-                loc[u] = None
+        for u in made:
+            free_c(loc[u], G.bytes[u])
+            loc[u] = None
 
     # ---------------- forward
     for i in range(1, n):

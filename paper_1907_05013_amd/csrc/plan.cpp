@@ -342,16 +342,20 @@ struct Walker {
             return;
         }
         const std::vector<int> ins = uniq(G.finputs[t]);
+        // forward-transient inputs (no feature maps) that this call has to regenerate are dropped again after
+        // use; one that is already there belongs to an outer recomputation that still reads it
+        std::vector<int> made;
+        for (int u : ins)
+            if (u != 0 && G.fidx[u] < 0 && loc[u] == LOC_NONE) made.push_back(u);
         for (int u : ins) ensure(u, step);
         loc[t] = alloc_c(G.bytes[t]);
         const std::vector<int> &raw = G.finputs[t];
         emit(K_REFWD, t, loc[t], loc[raw[0]], raw.size() > 1 ? loc[raw[1]] : OFF_NONE);
         S.n_refwd++;
-        for (int u : ins)
-            if (u != 0 && G.fidx[u] < 0) {
-                free_c(loc[u], G.bytes[u]);
-                loc[u] = LOC_NONE;
-            }
+        for (int u : made) {
+            free_c(loc[u], G.bytes[u]);
+            loc[u] = LOC_NONE;
+        }
     }
 
     void try_prefetch()

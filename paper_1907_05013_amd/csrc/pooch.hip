@@ -620,6 +620,7 @@ int32_t pooch_add(pooch_ctx *c, int32_t a, int32_t b)
 {
     GRAPH_OPEN(c);
     if (!valid_tensor(c, a) || !valid_tensor(c, b)) return fail(c, POOCH_E_INVALID, "add: bad argument");
+    if (a == b) return fail(c, POOCH_E_INVALID, "add: the two inputs must be different tensors");
     const Node &A = c->G.nodes[a], &B = c->G.nodes[b];
     if (A.N != B.N || A.C != B.C || A.sp[0] != B.sp[0] || A.sp[1] != B.sp[1] || A.sp[2] != B.sp[2] || A.nsp != B.nsp)
         return fail(c, POOCH_E_INVALID, "add: shapes differ");

@@ -72,6 +72,7 @@ def test_malformed_graphs_are_rejected():
     assert t == 1
     u = L.pooch_conv(h, 0, 5, k3, one, one, 2)
     assert L.pooch_add(h, t, u) == B.E_INVALID                          # shapes differ
+    assert L.pooch_add(h, t, t) == B.E_INVALID                          # a tensor plus itself
     assert L.pooch_softmax_ce(h, t) == B.E_INVALID                      # logits must be N x classes
     assert L.pooch_finalize(h) == B.E_INVALID                           # no loss node
     assert b"softmax_ce" in L.pooch_last_error(h)

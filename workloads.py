@@ -201,6 +201,62 @@ def late_fork(batch=2, ch=8, size=8, nclasses=3):
     return net
 
 
+def random_net(seed, batch=2, ch=4, size=6, nclasses=3, residual=False):
+    """Test shape: a random directed acyclic graph of shape-preserving layers (3x3 and 1x1 convolutions, batch
+    normalisation, ReLU, 3x3 stride-1 max-pool, adds of two different earlier tensors), every tensor consumed,
+    closed by a global pool, FC and the loss.  Exercises forks, joins and chains of layers whose outputs are no
+    feature maps in orders no configured network has.  residual: also draws whole conv-bn-relu groups and
+    residual joins relu(bn(conv(a)) + b), relu(bn(conv(a)) + bn(conv(b))), the patterns the fused kernels serve."""
+    rng = np.random.default_rng(seed)
+    net = Net()
+    ts = [net.input((batch, ch, size, size))]
+    consumed = set()
+    for _ in range(int(rng.integers(4, 14))):
+        ops = ("conv3", "conv1", "bn", "relu", "add", "pool", "bn", "relu", "add")
+        if residual:
+            ops = ops + ("cbr", "join", "join", "join2")
+        op = ops[int(rng.integers(0, len(ops)))]
+        a = ts[int(rng.integers(max(0, len(ts) - 4), len(ts)))]
+        if op in ("cbr", "join", "join2"):
+            b = ts[int(rng.integers(0, len(ts)))]
+            u = net.bn(net.conv(a, ch, (3, 3), (1, 1), (1, 1)))
+            if op == "cbr":
+                t = net.relu(u)
+            elif op == "join" and b != 0:
+                t = net.relu(net.add(u, b) if rng.integers(0, 2) else net.add(b, u))
+                consumed.add(b)
+            else:
+                t = net.relu(net.add(u, net.bn(net.conv(b, ch, (1, 1), (1, 1), (0, 0)))))
+                consumed.add(b)
+            consumed.add(a)
+            ts.append(t)
+            continue
+        if op == "conv3":
+            t = net.conv(a, ch, (3, 3), (1, 1), (1, 1))
+        elif op == "conv1":
+            t = net.conv(a, ch, (1, 1), (1, 1), (0, 0))
+        elif op == "bn":
+            t = net.bn(a)
+        elif op == "relu":
+            t = net.relu(a)
+        elif op == "pool":
+            t = net.maxpool(a, (3, 3), (1, 1), (1, 1))
+        else:
+            b = ts[int(rng.integers(0, len(ts)))]
+            if b == a:
+                continue
+            t = net.add(a, b)
+            consumed.add(b)
+        consumed.add(a)
+        ts.append(t)
+    t = ts[-1]
+    for u in ts[1:-1]:
+        if u not in consumed:
+            t = net.add(t, u)
+    net.softmax_ce(net.fc(net.gavgpool(t), nclasses))
+    return net
+
+
 def resnet50(batch=64, size=224, nclasses=1000, blocks=(3, 4, 6, 3), width=64):
     """ResNet-50, original form: 7x7/2 stem, 3x3/2 maxpool pad 1, bottleneck 3-4-6-3 with a
     projection shortcut in the first block of each stage, 1000-way FC."""
