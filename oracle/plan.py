@@ -587,15 +587,16 @@ def _walk(G, cls, cap, ahead, info):
 
 def _shared_reader(G, i, gloc):
     """Backward of z = a + b hands dy to both inputs.  When one input u is consumed by this add alone,
-    is produced after the other input t and after every other consumer of t, and its own backward
-    never needs to modify dy, then u's backward has read dy before anything is accumulated into t's
-    gradient: both gradients can be the one dy buffer.  Returns the position of u in the inputs, or None."""
+    is produced after the other input t and after every other consumer of t, does not read t itself
+    (its backward would add to t's gradient while still reading dy), and its own backward never needs
+    to modify dy, then u's backward has read dy before anything is accumulated into t's gradient:
+    both gradients can be the one dy buffer.  Returns the position of u in the inputs, or None."""
     ins = G.inputs[i]
     if len(ins) != 2 or ins[0] == ins[1] or 0 in ins or gloc[ins[0]] is not None or gloc[ins[1]] is not None:
         return None
     for ju in (0, 1):
         u, t = ins[ju], ins[1 - ju]
-        if G.consumers[u] != [i] or G.ops[u] in ("add", "addrelu") or t > u:
+        if G.consumers[u] != [i] or G.ops[u] in ("add", "addrelu") or t > u or t in G.inputs[u]:
             continue
         if any(c != i and c > u for c in G.consumers[t]):
             continue

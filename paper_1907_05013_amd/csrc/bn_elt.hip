@@ -707,7 +707,7 @@ hipError_t bn_fwd_from_tiles(const float *x, const float *gamma, const float *be
 hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const float *beta, const float *mean, const float *istd,
                   float *dx, float *dgamma, float *dbeta, float *ws, int64_t M, int C, bool accumulate, bool relu, hipStream_t s)
 {
-    if (!x || !dy || !gamma || !beta || !mean || !istd || !dx || !dgamma || !dbeta || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
+    if (!x || !dy || !gamma || !beta || !mean || !istd || !dgamma || !dbeta || !ws || !bn_args_ok(M, C)) return hipErrorInvalidValue;
     const bool al = ((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx | (uintptr_t)ws | (uintptr_t)mean | (uintptr_t)istd |
                      (uintptr_t)gamma | (uintptr_t)dgamma | (uintptr_t)dbeta) % 16 == 0;
     Lay2D L = layout2d(M, C, al, MAX_RBLK);
@@ -723,6 +723,7 @@ hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const flo
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    if (!dx) return hipSuccess;   // the input's gradient is not wanted: dgamma and dbeta only, dy stays as it is
     L = layout2d(M, C, al, APPLY_BLOCKS, 4);
     const dim3 grid(L.nblk, L.gy), block(BNT);
     const float inv_m = (float)(1.0 / (double)M);

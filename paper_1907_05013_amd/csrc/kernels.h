@@ -72,7 +72,8 @@ hipError_t bn_add_relu_fwd(const float *x, const float *other, const float *gamm
 // apply only, with saved statistics (used when a BN output is recomputed)
 hipError_t bn_apply(const float *x, const float *gamma, const float *beta, const float *mean, const float *istd,
                     float *y, int64_t M, int C, bool relu, hipStream_t s);
-// dgamma, dbeta and dx (dx may alias dy); accumulate adds into dx instead of overwriting.
+// dgamma, dbeta and dx (dx may alias dy; null: dgamma and dbeta only, dy is not touched); accumulate adds into dx
+// instead of overwriting.
 // relu: dy is the gradient of max(bn(x), 0); the decision bn(x) > 0 is re-derived from x.
 hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const float *beta, const float *mean, const float *istd,
                   float *dx, float *dgamma, float *dbeta, float *ws, int64_t M, int C, bool accumulate, bool relu, hipStream_t s);

@@ -399,6 +399,8 @@ struct Walker {
                 const int u = in2[ju], t = in2[1 - ju];
                 if (G.consumers[u].size() != 1 || G.consumers[u][0] != i) continue;
                 if (G.nodes[u].op == OP_ADD || G.nodes[u].op == OP_ADDRELU || t > u) continue;
+                // u must not read t itself: its backward would add to t's gradient while still reading dy
+                if (std::find(G.inputs[u].begin(), G.inputs[u].end(), t) != G.inputs[u].end()) continue;
                 bool late = false;
                 for (int c : G.consumers[t]) late = late || (c != i && c > u);
                 if (late) continue;

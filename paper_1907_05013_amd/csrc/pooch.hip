@@ -290,7 +290,8 @@ struct Exec {
         }
         case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
-            float *dx = m0 == M_NONE ? D(dy) : D(o0);
+            // no gradient wanted for the input (the network input): dy may be another tensor's gradient too, leave it alone
+            float *dx = m0 == M_NONE ? nullptr : D(o0);
             return pk::bn_bwd(D(need), D(dy), R(P(i, 0).off_val), R(P(i, 1).off_val), R(c->off_mean[i]), R(c->off_istd[i]), dx,
                               R(P(i, 0).off_grad), R(P(i, 1).off_grad), R(c->off_ws_bn), M, (int)nd.C, m0 == M_ACC,
                               nd.op == OP_BNRELU, s);

@@ -41,6 +41,8 @@ def _accesses(G, c):
             off, mode = outs[j]
             if mode == M_NONE:
                 continue
+            # only element-wise backward passes may produce their result in the buffer they read dy from
+            assert off != dy or op in ("relu", "bn", "bnrelu", "add", "addrelu"), ("backward writes into its own dy", c)
             if mode == M_WRITE:
                 acc.append((off, G.gbytes[t], True, ("g", t)))
             elif mode == M_ACC:
