@@ -19,7 +19,7 @@ TEST INFRASTRUCTURE ONLY (slow, obvious, no sharing with the HIP library).  It c
   * mode "refine" (not in the paper): the two steps followed by an iterated local search over
     single class changes, judged by the same simulation.
 
-Where the paper is silent the readings are those listed in DESIGN.md ("Readings").
+Where the paper is silent, the reading taken is stated at the function that needs it.
 """
 from collections import deque
 
