@@ -131,7 +131,11 @@ pooch_status pooch_finalize(pooch_ctx *);
 /* ---- parameters and data -------------------------------------------------------------
  * Parameters in layer order: conv -> W[K,C,k...]; bn -> gamma[C], beta[C]; fc -> W[O,I], b[O]
  * (I flattened in logical C,(D,)H,W order).  set_* copy from host synchronously; get_grad
- * copies the gradient of parameter i (same shape) back after a step. */
+ * copies the gradient of parameter i (same shape) back after a step.
+ * Anything that runs the network (pooch_step, pooch_step_timed, the profiling calls) returns
+ * POOCH_E_STATE until a batch and every parameter have been set (labels index the logits, so
+ * stale memory must never be run); pooch_get_grad and pooch_sgd_update return POOCH_E_STATE
+ * until a step has run. */
 int32_t pooch_num_params(pooch_ctx *);
 pooch_status pooch_param_info(pooch_ctx *, int32_t i, int64_t *numel, int32_t *node);
 pooch_status pooch_set_param(pooch_ctx *, int32_t i, const float *host);

@@ -53,6 +53,10 @@ struct pooch_ctx {
     std::vector<int64_t> off_mean, off_istd;  // per node (BN only), resident offsets
     std::vector<int64_t> off_rmean, off_rvar; // running averages of the same layers
     float bn_decay = 0.9f;
+    // what a step needs before it may touch the device: a batch (the labels index the logits) and every parameter;
+    // and what an update or a read-back of gradients needs: a step that has run
+    bool has_batch = false, has_grads = false;
+    std::vector<char> param_set;
     int64_t off_input = 0, off_labels = 0, off_ws_wgrad = 0, off_ws_bn = 0, off_loss_ps = 0, off_loss = 0;
     int64_t resident_bytes = 0;
     int nclasses = 0;
@@ -368,6 +372,9 @@ pooch_status copy_out_capture(pooch_ctx *c, int i, const float *dev)
 pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd, float *loss_out)
 {
     if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (!c->has_batch) return fail(c, POOCH_E_STATE, "no batch: call pooch_set_batch first");
+    for (char ok : c->param_set)
+        if (!ok) return fail(c, POOCH_E_STATE, "a parameter was never set: call pooch_set_param for every parameter first");
     const size_t swap_bytes = (size_t)S.swap_bytes;
     if (swap_bytes > 0 && (!c->pinned || swap_bytes > c->pinned_bytes)) return fail(c, POOCH_E_BUDGET, "pinned buffer too small");
     pooch_status ps = ensure_events(c, c->sync_events, (size_t)S.n_events, hipEventDisableTiming);
@@ -446,6 +453,7 @@ pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool prof
         }
     }
     for (int s = 0; s < 3; ++s) HIPCHK(hipStreamSynchronize(c->st[s]));
+    c->has_grads = true;
     if (loss_out) HIPCHK(hipMemcpy(loss_out, c->arena + c->off_loss, 4, hipMemcpyDeviceToHost));
     return POOCH_OK;
 }
@@ -813,6 +821,7 @@ pooch_status pooch_finalize(pooch_ctx *c)
             HIPCHK(hipMemcpy(c->arena + c->off_rvar[i], one.data(), one.size() * 4, hipMemcpyHostToDevice));
         }
     }
+    c->param_set.assign(c->params.size(), 0);
     c->finalized = true;
     return POOCH_OK;
 }
@@ -846,6 +855,7 @@ pooch_status pooch_set_param(pooch_ctx *c, int32_t i, const float *host)
     const ParamInfo &p = c->params[i];
     if (p.off_val_t < 0) {
         HIPCHK(hipMemcpy(c->arena + p.off_val, host, (size_t)p.numel * 4, hipMemcpyHostToDevice));
+        c->param_set[i] = 1;
         return POOCH_OK;
     }
     const pk::ConvGeom g = conv_geom(c->G, p.node, c->in_cdev);
@@ -854,6 +864,7 @@ pooch_status pooch_set_param(pooch_ctx *c, int32_t i, const float *host)
     filter_to_device_layouts(host, g.K, Clog, g.C, g.taps(), krc.data(), crk.data());
     HIPCHK(hipMemcpy(c->arena + p.off_val, krc.data(), (size_t)p.dev_numel * 4, hipMemcpyHostToDevice));
     HIPCHK(hipMemcpy(c->arena + p.off_val_t, crk.data(), (size_t)p.dev_numel * 4, hipMemcpyHostToDevice));
+    c->param_set[i] = 1;
     return POOCH_OK;
 }
 
@@ -862,6 +873,7 @@ pooch_status pooch_get_grad(pooch_ctx *c, int32_t i, float *host)
     NEED_FINAL(c);
     if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
     if (i < 0 || i >= (int32_t)c->params.size() || !host) return fail(c, POOCH_E_INVALID, "get_grad: bad argument");
+    if (!c->has_grads) return fail(c, POOCH_E_STATE, "get_grad: no step has run");
     const ParamInfo &p = c->params[i];
     if (p.off_val_t < 0) {
         HIPCHK(hipMemcpy(host, c->arena + p.off_grad, (size_t)p.numel * 4, hipMemcpyDeviceToHost));
@@ -886,6 +898,7 @@ pooch_status pooch_set_batch(pooch_ctx *c, const float *x_host, const int32_t *l
     act_to_device_layout(x_host, in.N, in.C, c->in_cdev, in.sp[0] * in.sp[1] * in.sp[2], tmp.data());
     HIPCHK(hipMemcpy(c->arena + c->off_input, tmp.data(), tmp.size() * 4, hipMemcpyHostToDevice));
     HIPCHK(hipMemcpy(c->arena + c->off_labels, labels_host, (size_t)in.N * 4, hipMemcpyHostToDevice));
+    c->has_batch = true;
     return POOCH_OK;
 }
 
@@ -1071,6 +1084,7 @@ pooch_status pooch_sgd_update(pooch_ctx *c, float lr)
     NEED_FINAL(c);
     if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
     if (!(lr == lr)) return fail(c, POOCH_E_INVALID, "sgd_update: learning rate is NaN");
+    if (!c->has_grads) return fail(c, POOCH_E_STATE, "sgd_update: no step has run");
     hipStream_t s = c->st[S_COMPUTE];
     for (const ParamInfo &p : c->params) {
         float *val = reinterpret_cast<float *>(c->arena + p.off_val);

@@ -299,6 +299,40 @@ def test_random_graphs_vs_oracle_and_random_plans():
         assert ran >= 1, seed
 
 
+def test_nothing_runs_before_batch_and_parameters_are_set():
+    """stale arena memory is never executed (the labels index the logits) nor read back as a gradient"""
+    net = workloads.tiny_cnn()
+    res, peak = plan_sizes(net)
+    pinned = sum(OP.Graph(net, fuse=FUSE).fmap_bytes()) + 256
+    c = B.Context(net, res + 2 * peak, pinned_bytes=pinned)
+    c.set_plan([B.KEEP] * c.n_fmaps)
+    params = workloads.make_params(net, 1)
+    x, t = workloads.make_batch(net, 1)
+    shapes = [s for _, _, s in workloads.param_shapes(net)]
+
+    def refused(call):
+        with pytest.raises(B.PoochError) as e:
+            call()
+        assert e.value.status == B.E_STATE
+    refused(c.step)                       # neither batch nor parameters
+    c.set_batch(x, t)
+    refused(c.step)                       # no parameters
+    refused(lambda: c.profile_step(True))
+    refused(lambda: c.sgd_update(0.1))
+    refused(lambda: c.get_grads(shapes))
+    c.set_params(params[:-1] + [params[-1]])
+    loss = c.step()
+    assert np.isfinite(loss)
+    c.sgd_update(0.1)
+    c.close()
+    c = B.Context(net, res + 2 * peak, pinned_bytes=pinned)
+    c.set_plan([B.KEEP] * c.n_fmaps)
+    c.set_params(params)
+    refused(c.step)                       # parameters but no batch
+    refused(lambda: c.profile(0, 1))
+    c.close()
+
+
 def test_add_whose_inputs_cannot_share_one_gradient_buffer():
     """the skip tensor of the first add has a consumer created after the branch, so the branch's batch
     normalisation (applied inside the add + relu, its own output never written) receives a gradient buffer
