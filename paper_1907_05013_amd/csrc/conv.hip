@@ -78,11 +78,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     // aligned, conflict-free 128-bit reads)
     constexpr int NT = 64 * WGM * WGN;
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    // tile rows are BKT floats, unpadded; the 16-byte piece q of row w sits at piece q ^ ((w >> 1) & 3): the four lanes
-    // that store one row fill its 64 bytes, two rows fill all banks once, and the eight rows a group of lanes reads
-    // at one k offset fall on eight different pieces
-    constexpr int LDT = BKT;
-    static_assert(BKT == 16, "the piece swizzle is for 16-float tile rows");
+    constexpr int LDT = BKT + 4;
     constexpr int KQ = BKT / 4;                      // float4 per tile row
     constexpr int RPP = NT / KQ;                     // rows covered per pass of vector loads
     constexpr int A_V = (BM + RPP - 1) / RPP, B_V = (BN + RPP - 1) / RPP;
@@ -311,16 +307,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 #pragma unroll
             for (int i = 0; i < A_V; ++i)
                 if (vrow + i * RPP < BM)
-                    *reinterpret_cast<f32x4 *>(&As[(vrow + i * RPP) * LDT + (vk ^ ((((vrow + i * RPP) >> 1) & 3) << 2))]) = (LIN || ((amask >> i) & 1u)) ? av[i] : f32x4{0.f, 0.f, 0.f, 0.f};
+                    *reinterpret_cast<f32x4 *>(&As[(vrow + i * RPP) * LDT + vk]) = (LIN || ((amask >> i) & 1u)) ? av[i] : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int i = 0; i < B_V; ++i)
                 if (vrow + i * RPP < BN)
-                    *reinterpret_cast<f32x4 *>(&Bs[(vrow + i * RPP) * LDT + (vk ^ ((((vrow + i * RPP) >> 1) & 3) << 2))]) = (LIN || ((bmask >> i) & 1u)) ? bv[i] : f32x4{0.f, 0.f, 0.f, 0.f};
+                    *reinterpret_cast<f32x4 *>(&Bs[(vrow + i * RPP) * LDT + vk]) = (LIN || ((bmask >> i) & 1u)) ? bv[i] : f32x4{0.f, 0.f, 0.f, 0.f};
         } else {
 #pragma unroll
-            for (int i = 0; i < A_S; ++i) As[(tid / BKT + i * RPS) * LDT + ((tid % BKT) ^ ((((tid / BKT + i * RPS) >> 1) & 3) << 2))] = as[i];
+            for (int i = 0; i < A_S; ++i) As[(tid / BKT + i * RPS) * LDT + (tid % BKT)] = as[i];
 #pragma unroll
-            for (int i = 0; i < B_S; ++i) Bs[(tid / BKT + i * RPS) * LDT + ((tid % BKT) ^ ((((tid / BKT + i * RPS) >> 1) & 3) << 2))] = bs[i];
+            for (int i = 0; i < B_S; ++i) Bs[(tid / BKT + i * RPS) * LDT + (tid % BKT)] = bs[i];
         }
     };
 
@@ -354,19 +350,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             float af[TM][8], bf[TN][8];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const int w = wm * TM * 32 + i * 32 + r, sw = ((w >> 1) & 3) << 2;
-                const float *ap = &As[w * LDT];
-                const f32x4 lo = *reinterpret_cast<const f32x4 *>(ap + ((h * 8) ^ sw));
-                const f32x4 hi = *reinterpret_cast<const f32x4 *>(ap + ((h * 8 + 4) ^ sw));
+                const float *ap = &As[(wm * TM * 32 + i * 32 + r) * LDT + sub * 16 + h * 8];
+                const f32x4 lo = *reinterpret_cast<const f32x4 *>(ap);
+                const f32x4 hi = *reinterpret_cast<const f32x4 *>(ap + 4);
                 af[i][0] = lo.x; af[i][1] = lo.y; af[i][2] = lo.z; af[i][3] = lo.w;
                 af[i][4] = hi.x; af[i][5] = hi.y; af[i][6] = hi.z; af[i][7] = hi.w;
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int w = wn * TN * 32 + j * 32 + r, sw = ((w >> 1) & 3) << 2;
-                const float *bp = &Bs[w * LDT];
-                const f32x4 lo = *reinterpret_cast<const f32x4 *>(bp + ((h * 8) ^ sw));
-                const f32x4 hi = *reinterpret_cast<const f32x4 *>(bp + ((h * 8 + 4) ^ sw));
+                const float *bp = &Bs[(wn * TN * 32 + j * 32 + r) * LDT + sub * 16 + h * 8];
+                const f32x4 lo = *reinterpret_cast<const f32x4 *>(bp);
+                const f32x4 hi = *reinterpret_cast<const f32x4 *>(bp + 4);
                 bf[j][0] = lo.x; bf[j][1] = lo.y; bf[j][2] = lo.z; bf[j][3] = lo.w;
                 bf[j][4] = hi.x; bf[j][5] = hi.y; bf[j][6] = hi.z; bf[j][7] = hi.w;
             }
