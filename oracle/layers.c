@@ -346,24 +346,31 @@ void orc_fc_bwd(const REAL *x, const REAL *w, const REAL *dy,
     }
 }
 
-/* L = -(1/N) sum_n log softmax(z_n)[t_n], log-softmax taken with the row maximum
- * subtracted; dz = (softmax(z) - onehot(t)) / N.  Returns L. */
+/* L = -(1/N) sum_n log softmax(z_n)[t_n];  dz = (softmax(z) - onehot(t)) / N.  Returns L.
+ * With mx the row maximum, -log softmax(z)[t] = (mx - z_t) + log(sum_j exp(z_j - mx)).  One term of that sum is
+ * exp(0) = 1 (the first maximal element's), so the sum is 1 + rest and its logarithm log1p(rest): written this way
+ * the definition keeps full precision for a sample whose labelled class leads by a wide margin (rest ~ 1e-15 would
+ * otherwise be rounded into the 1).  Likewise softmax(z)[t] - 1 = -(sum of the other classes' terms) / (whole sum). */
 double orc_softmax_ce(const REAL *z, const int32_t *t, REAL *dz, i64 N, i64 K)
 {
     double loss = 0.0;
     for (i64 n = 0; n < N; ++n) {
         const REAL *zr = z + n * K;
-        double mx = (double)zr[0];
-        for (i64 j = 1; j < K; ++j) if ((double)zr[j] > mx) mx = (double)zr[j];
-        double se = 0.0;
-        for (i64 j = 0; j < K; ++j) se += exp((double)zr[j] - mx);
-        const double lse = mx + log(se);
-        loss += lse - (double)zr[t[n]];
-        if (dz)
+        i64 am = 0;
+        for (i64 j = 1; j < K; ++j) if ((double)zr[j] > (double)zr[am]) am = j;
+        const double mx = (double)zr[am];
+        double rest = 0.0;                       /* every term but the first maximal element's */
+        for (i64 j = 0; j < K; ++j) if (j != am) rest += exp((double)zr[j] - mx);
+        loss += (mx - (double)zr[t[n]]) + log1p(rest);
+        if (dz) {
+            double others = 0.0;                 /* every term but the labelled class's */
+            for (i64 j = 0; j < K; ++j) if (j != t[n]) others += exp((double)zr[j] - mx);
+            const double all = others + exp((double)zr[t[n]] - mx);
             for (i64 j = 0; j < K; ++j) {
-                const double p = exp((double)zr[j] - lse);
-                dz[n * K + j] = (REAL)((p - (j == t[n] ? 1.0 : 0.0)) / (double)N);
+                const double g = j == t[n] ? -others / all : exp((double)zr[j] - mx) / all;
+                dz[n * K + j] = (REAL)(g / (double)N);
             }
+        }
     }
     return loss / (double)N;
 }

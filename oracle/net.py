@@ -15,6 +15,13 @@ mean <- d mean + (1 - d) batch mean, var <- d var + (1 - d) batch variance m / m
 m values per channel, from mean 0 and variance 1, d = 0.9 -- the convention of the framework
 the paper's implementation sits in (section 5).  Kept in float64 whatever the step's dtype.
 
+Where floating point decides something discrete -- which elements a ReLU lets through, which element of a
+window is the maximum -- two correct fp32 evaluations may decide differently for values within rounding of a tie,
+and the backward pass then differs by that element's whole gradient.  A comparison can therefore hand backward()
+the other side's decisions (`decide_from`): the backward of a ReLU then masks with that side's output instead of
+this forward pass's, and the backward of a max-pool picks its maxima in that side's input.  Everything else,
+the forward pass included, is unchanged.
+
 Test infrastructure only; imports nothing from the HIP library or its binding.
 """
 import numpy as np
@@ -90,9 +97,12 @@ class OracleNet:
         d = self.decay
         self.running[i] = [d * rm + (1.0 - d) * mu, d * rv + (1.0 - d) * var * (m / max(m - 1, 1))]
 
-    def backward(self):
-        """returns (param grads in parameter order, gradient of the loss w.r.t. the input)"""
+    def backward(self, decide_from=None):
+        """returns (param grads in parameter order, gradient of the loss w.r.t. the input).
+        decide_from: {relu layer: an output tensor of it, max-pool layer: an input tensor of it} whose signs /
+        maxima replace this forward pass's own where the layer's backward takes its discrete decision."""
         net, out = self.net, self.out
+        decide_from = decide_from or {}
         g = [None] * len(net)
 
         def acc(i, v):
@@ -118,12 +128,13 @@ class OracleNet:
                 pgrads[i] = [dg, db]
                 acc(layer["x"], dx)
             elif op == "relu":
-                acc(layer["x"], L.relu_bwd(out[i], dy))
+                acc(layer["x"], L.relu_bwd(np.ascontiguousarray(decide_from.get(i, out[i]), self.dtype), dy))
             elif op == "add":
                 acc(layer["a"], dy)
                 acc(layer["b"], dy)
             elif op == "maxpool":
-                acc(layer["x"], L.maxpool_bwd(out[layer["x"]], dy, layer["k"], layer["stride"], layer["pad"]))
+                xin = np.ascontiguousarray(decide_from.get(i, out[layer["x"]]), self.dtype)
+                acc(layer["x"], L.maxpool_bwd(xin, dy, layer["k"], layer["stride"], layer["pad"]))
             elif op == "gavgpool":
                 acc(layer["x"], L.gavgpool_bwd(dy, out[layer["x"]].shape))
             elif op == "fc":
@@ -136,7 +147,7 @@ class OracleNet:
             flat.extend(pgrads[i])
         return flat, g[0]
 
-    def step(self, x, labels):
+    def step(self, x, labels, decide_from=None):
         loss = self.forward(x, labels)
-        grads, dx = self.backward()
+        grads, dx = self.backward(decide_from)
         return loss, grads, dx

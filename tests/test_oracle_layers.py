@@ -207,6 +207,55 @@ def test_softmax_ce_closed_forms(K):
         np.testing.assert_allclose(dz, fd_grad(f, z, 1e-5), atol=1e-8)
 
 
+def _softmax_ce_decimal(z, t):
+    """loss and dz of softmax cross-entropy by the definition -log(exp(z_t) / sum_j exp(z_j)) in 60-digit decimal
+    arithmetic (no max subtraction, no log1p: at this precision the plain definition needs neither)"""
+    import decimal
+    D = decimal.Decimal
+    with decimal.localcontext() as ctx:
+        ctx.prec = 60
+        N, K = z.shape
+        loss = D(0)
+        dz = np.empty((N, K), object)
+        for n in range(N):
+            # shifted by an integer so that exp stays in Decimal's exponent range; exact in decimal
+            shift = D(int(np.floor(float(z[n].max()))))
+            e = [(D(float(v)) - shift).exp() for v in z[n]]
+            tot = sum(e)
+            loss += -(e[t[n]] / tot).ln()
+            for j in range(K):
+                dz[n, j] = (e[j] / tot - (1 if j == t[n] else 0)) / N
+        return float(loss / N), np.array([[float(v) for v in row] for row in dz])
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_softmax_ce_confident_samples(dtype):
+    """a labelled class that leads by a wide margin: loss and gradient are tiny and must not be lost to rounding.
+    Closed form -- one class M above K - 1 equal ones: loss = log1p((K-1) e^-M), dz_t = -(K-1) e^-M / (1 + (K-1) e^-M) / N
+    -- and random logits scaled by 50 against the definition in 60-digit decimal arithmetic."""
+    import math
+    K, N = 1000, 3
+    for M in (10.0, 40.0, 80.0):
+        z = np.full((N, K), -1.5, dtype)
+        t = np.array([0, 7, K - 1], np.int32)
+        z[np.arange(N), t] += dtype(M)
+        loss, dz = L.softmax_ce(z, t)
+        q = (K - 1) * math.exp(-M)
+        assert abs(loss - math.log1p(q)) <= 1e-12 * math.log1p(q), (M, loss, math.log1p(q))
+        want_t = -q / (1 + q) / N
+        got_t = dz[np.arange(N), t].astype(np.float64)
+        assert np.all(np.abs(got_t - want_t) <= 2e-7 * abs(want_t)), (M, got_t, want_t)   # dz is stored in `dtype`
+    rng = np.random.default_rng(3)
+    z = (rng.standard_normal((4, 12)) * 50).astype(dtype)
+    t = np.array([int(np.argmax(z[0])), int(np.argmax(z[1])), 3, int(np.argmin(z[3]))], np.int32)
+    loss, dz = L.softmax_ce(z, t)
+    want_loss, want_dz = _softmax_ce_decimal(z.astype(np.float64), t)
+    assert abs(loss - want_loss) <= 1e-12 * abs(want_loss)
+    tol = 2e-7 if dtype == np.float32 else 1e-12
+    floor = 1e-37 if dtype == np.float32 else 1e-300          # below the storage type's normal range
+    assert np.all(np.abs(dz.astype(np.float64) - want_dz) <= tol * np.abs(want_dz) + floor)
+
+
 def _net_fd(net, seed, nsample=40):
     params = [p.astype(np.float64) for p in workloads.make_params(net, seed, perturb=True)]
     x, t = workloads.make_batch(net, seed)
@@ -297,3 +346,39 @@ def test_bn_running_averages_closed_form():
     o1.forward(xb, tb)
     np.testing.assert_allclose(o1.running[1][0], 0.5 * xb.reshape(3))
     np.testing.assert_allclose(o1.running[1][1], 0.5)
+
+
+def test_backward_with_decisions_handed_in():
+    """OracleNet.backward(decide_from=...): with the forward pass's own tensors nothing changes (same bits); with an
+    all-zero tensor for one ReLU nothing passes it, so every gradient upstream of it is exactly zero and the
+    ones downstream are untouched; a max-pool handed another input routes by that input's maxima."""
+    net = workloads.Net()
+    t = net.input((2, 3, 8, 8))
+    t = net.relu(net.bn(net.conv(t, 4, (3, 3), (1, 1), (1, 1))))      # relu = 3
+    t = net.maxpool(t, (2, 2), (2, 2), (0, 0))                         # maxpool = 4
+    t = net.relu(net.bn(net.conv(t, 5, (3, 3), (1, 1), (1, 1))))      # relu = 7
+    net.softmax_ce(net.fc(net.gavgpool(t), 3))
+    params = workloads.make_params(net, 3, perturb=True)
+    x, lab = workloads.make_batch(net, 3)
+    o = OracleNet(net, params, np.float64)
+    loss, g0, dx0 = o.step(x.astype(np.float64), lab)
+    g1, dx1 = o.backward({3: o.out[3], 7: o.out[7], 4: o.out[3]})
+    assert all(a.tobytes() == b.tobytes() for a, b in zip(g0, g1)) and dx0.tobytes() == dx1.tobytes()
+    g2, dx2 = o.backward({7: np.zeros_like(o.out[7])})
+    names = workloads.param_shapes(net)
+    for (node, _, _), a, b in zip(names, g0, g2):
+        if node < 7:
+            assert not a.any() or not b.any()          # upstream of the blocked ReLU: exactly zero now
+            assert not b.any()
+        else:
+            assert a.tobytes() == b.tobytes()
+    assert not dx2.any()
+    # the max-pool decides from the tensor it is handed: reversing every 2x2 window's contents moves the gradient
+    flipped = np.ascontiguousarray(o.out[3][:, :, ::-1, ::-1])
+    g3, _ = o.backward({4: flipped})
+    dy_pool = np.ones_like(o.out[4])
+    want = L.maxpool_bwd(flipped, dy_pool, (2, 2), (2, 2), (0, 0))
+    own = L.maxpool_bwd(o.out[3], dy_pool, (2, 2), (2, 2), (0, 0))
+    assert not np.array_equal(want, own)
+    assert any(a.tobytes() != b.tobytes() for a, b in zip(g0[:3], g3[:3]))
+    assert all(a.tobytes() == b.tobytes() for a, b in zip(g0[3:], g3[3:]))
