@@ -21,7 +21,7 @@
  *     workspaces, the input batch, every activation and every gradient map live at
  *     offsets inside the arena, so exceeding the budget is impossible by construction.
  *     Running out of room is a PLANNING-time error (POOCH_E_BUDGET), never a mid-step one:
- *     this is the paper's "excluding out-of-memory errors" (section 4.1.1).
+ *     plans that run out of memory are excluded when the plan is made (section 4.1.1).
  *   - A context is not thread-safe; use one per thread.  All streams must have default
  *     priority.
  *   - A context created with arena == NULL is "planning only": graph, profile injection,
@@ -151,6 +151,14 @@ pooch_status pooch_get_param(pooch_ctx *, int32_t i, float *host);
  * for tests, not for timed runs).  host == NULL cancels the capture of that layer.  The
  * buffer must stay valid until cancelled or the context is destroyed. */
 pooch_status pooch_capture_tensor(pooch_ctx *, int32_t id, float *host);
+/* test aid for the error path: the next replay of a command list (pooch_step, pooch_step_timed, a profiling
+ * iteration, pooch_refine_profile) reports POOCH_E_HIP when it reaches command `command_index` (a row of
+ * pooch_get_commands for pooch_step) instead of enqueueing it, once; a negative index cancels.  Nothing faults: the
+ * commands before it run normally.  What every failure inside a step guarantees, injected or real: the call returns
+ * only after everything it had enqueued has finished; gradients count as absent until a later step completes;
+ * parameters, batch, profile and plan are untouched, so the same context may step again (BN running averages of
+ * the layers that ran have moved).  A failed profiling iteration drops the samples gathered so far. */
+pooch_status pooch_inject_failure(pooch_ctx *, int64_t command_index);
 /* gradient of the loss w.r.t. saved BN statistics is internal; the per-channel batch mean
  * and 1/sqrt(var+eps) of BN node `node` (C floats each) can be read back for tests. */
 pooch_status pooch_get_bn_stats(pooch_ctx *, int32_t node, float *mean, float *istd);
@@ -185,7 +193,7 @@ size_t pooch_resident_bytes(pooch_ctx *);
  * set_profile injects a profile (tests, CPU-only planning). */
 pooch_status pooch_profile(pooch_ctx *, int warmup, int iters);
 /* The same, one iteration at a time, for callers whose first training iterations double as the
- * profiling phase (section 4.1.2: "profiling is done during the first several iterations"): each call
+ * profiling phase (section 4.1.2 places the profiling in the first few training iterations): each call
  * runs one all-swap step (forward + backward, gradients valid afterwards); timed != 0 adds its
  * durations to the samples.  pooch_finish_profile turns the samples into the profile (median). */
 pooch_status pooch_profile_step(pooch_ctx *, int timed, float *loss_out);

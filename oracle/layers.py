@@ -30,11 +30,6 @@ def _i(*v):
     return [C.c_int64(int(x)) for x in v]
 
 
-def _sp3(t):
-    """pad a 2-d (h,w) tuple to (1-or-0-filled d, h, w)"""
-    return tuple(t)
-
-
 def _geom(x, k, stride, pad):
     """NC(D)HW array + 2-d or 3-d kernel geometry -> (N,C,D,H,W), k3, s3, p3"""
     nsp = len(k)

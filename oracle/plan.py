@@ -7,8 +7,8 @@ TEST INFRASTRUCTURE ONLY (slow, obvious, no sharing with the HIP library).  It c
   * the static schedule of one step under a classification: swap-out after the last forward
     use, swap-in before the first backward use (section 3.1), discard and recursive
     recomputation (section 3.2), swap-ins moved up as far as memory has room (section 4.3)
-    or started together with the preceding backward computation (section 5.1, "w/o
-    scheduling"), all inside a fixed-size arena with a first-fit allocator,
+    or started together with the preceding backward computation (section 5.1, the variant
+    without scheduling), all inside a fixed-size arena with a first-fit allocator,
   * the timeline simulation over three serial resources -- compute, device-to-host,
     host-to-device -- from profiled durations (section 4.1.2),
   * the two-step heuristic search (section 4.4): L_O / L_I extraction on the all-swap
@@ -771,7 +771,7 @@ class Planner:
                 trial[G.fidx[t]] = KEEP
                 T = self.evaluate(trial)
                 if T is None:
-                    break       # kept "as long as it can fit", in order from the output layer: the scan ends here
+                    break       # section 4.4.2: kept from the output layer while they still fit; the scan ends at the first map that does not
                 cur = trial
                 if T < best_T:
                     best_T, best = T, list(cur)

@@ -62,6 +62,7 @@ SYMBOLS = {
     "pooch_get_grad": (_i32, [_ctx, _i32, C.c_void_p]),
     "pooch_set_batch": (_i32, [_ctx, C.c_void_p, C.c_void_p]),
     "pooch_capture_tensor": (_i32, [_ctx, _i32, C.c_void_p]),
+    "pooch_inject_failure": (_i32, [_ctx, _i64]),
     "pooch_get_bn_stats": (_i32, [_ctx, _i32, C.c_void_p, C.c_void_p]),
     "pooch_set_bn_decay": (_i32, [_ctx, C.c_float]),
     "pooch_get_bn_running": (_i32, [_ctx, _i32, C.c_void_p, C.c_void_p]),
@@ -123,7 +124,18 @@ def _hip_rt():
     global _hip
     if _hip is None:
         import torch  # noqa: F401
-        h = C.CDLL("libamdhip64.so.7")
+        # the copy of the runtime that torch has mapped into this process, by its path: opening it by a
+        # fixed soname could load a second runtime (or none) next to the one that owns the arena
+        path = None
+        with open("/proc/self/maps") as f:
+            for line in f:
+                name = line.rsplit(" ", 1)[-1].strip()
+                if os.path.basename(name).startswith("libamdhip64.so"):
+                    path = name
+                    break
+        if path is None:
+            raise RuntimeError("no HIP runtime (libamdhip64) is mapped into this process: torch did not load one")
+        h = C.CDLL(path)
         h.hipHostMalloc.restype = C.c_int
         h.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), _sz, C.c_uint]
         h.hipHostFree.restype = C.c_int
@@ -307,6 +319,10 @@ class Context:
             assert array.dtype == np.float32 and array.flags.c_contiguous
             self._keep.append(array)
         self._chk(self.L.pooch_capture_tensor(self.h, node, array.ctypes.data if array is not None else None))
+
+    def inject_failure(self, command_index):
+        """test aid: the next replay fails with E_HIP at this command (negative: cancel)"""
+        self._chk(self.L.pooch_inject_failure(self.h, int(command_index)))
 
     def bn_stats(self, node, channels):
         mean = np.empty(channels, np.float32)

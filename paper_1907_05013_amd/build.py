@@ -33,10 +33,17 @@ def build(verbose=False):
     subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB])
     for o in objs:
         os.remove(o)
-    # counter-calibration aid (a plain copy kernel of known size), see csrc/hbm_copy_probe.hip
-    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", os.path.join(CSRC, "hbm_copy_probe.hip"), "-o", PROBE])
     return LIB
 
 
+def build_probe():
+    """the counter-calibration aid (a plain copy kernel of known size, csrc/hbm_copy_probe.hip): not part of the library,
+    built only by `python -m paper_1907_05013_amd.build probe` before a `rocprofv3 --pmc` calibration run"""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", os.path.join(CSRC, "hbm_copy_probe.hip"), "-o", PROBE])
+    return PROBE
+
+
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build_probe() if sys.argv[1:] == ["probe"] else build(verbose=True))

@@ -6,7 +6,7 @@
 //    Swap-out follows the last forward use, swap-in precedes the first backward use (3.1);
 //    a recompute-class map is dropped after its last forward use and regenerated from its
 //    producer's inputs, recursively (3.2).  Swap-ins are issued as early as the arena has
-//    room (4.3) or together with the preceding backward computation ("w/o scheduling", 5.1).
+//    room (4.3) or together with the preceding backward computation (the unscheduled variant measured in section 5.1).
 //    Because the problem is identical every iteration, allocation order is static: the
 //    paper profiles malloc/free order at run time (4.2); here it is decided once, and every
 //    cross-stream hazard is an explicit event wait, so a plan that builds can never run out
@@ -793,7 +793,7 @@ void Planner::step1(const std::vector<uint8_t> &allswap, double T_all, std::vect
             std::vector<uint8_t> trial = cur;
             trial[G.fidx[t]] = CLS_KEEP;
             const double T = evaluate(trial);
-            if (T < 0.0) break;   // "as long as it can fit", in order from the output layer: the scan ends here
+            if (T < 0.0) break;   // section 4.4.2: maps are kept from the output layer while they still fit, so the scan ends at the first that does not
             cur = trial;
             if (T < best_T) {
                 best_T = T;

@@ -89,6 +89,7 @@ struct pooch_ctx {
     std::vector<hipEvent_t> timing_events;  // with timing
     std::vector<float *> capture;           // per node host destination or nullptr
     std::vector<float> host_tmp;
+    int64_t fail_at = -1;                   // test aid (pooch_inject_failure): command of the next replay that fails
     std::string err;
 };
 
@@ -366,10 +367,11 @@ pooch_status copy_out_capture(pooch_ctx *c, int i, const float *dev)
     return POOCH_OK;
 }
 
-// Replays a command list.  tm != nullptr: every forward / re-forward / backward / copy command
+// Enqueues a command list.  tm != nullptr: every forward / re-forward / backward / copy command
 // is bracketed by timing events on its own stream; profile_refwd additionally runs (and
 // times) each layer's re-forward variant right after its forward, on the same buffers.
-pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd, float *loss_out)
+// Returns at the first failure with whatever was enqueued before it still in flight: run_schedule() cleans up.
+pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd)
 {
     if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
     if (!c->has_batch) return fail(c, POOCH_E_STATE, "no batch: call pooch_set_batch first");
@@ -404,6 +406,10 @@ pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool prof
     for (size_t k = 0; k < S.cmds.size(); ++k) {
         const Cmd &cm = S.cmds[k];
         const int stream = cm.kind <= K_BWD ? S_COMPUTE : (cm.kind == K_OUT ? S_D2H : (cm.kind == K_IN ? S_H2D : cm.id));
+        if ((int64_t)k == c->fail_at) {
+            c->fail_at = -1;
+            return fail(c, POOCH_E_HIP, "injected failure at command " + std::to_string(k) + " (pooch_inject_failure)");
+        }
         if (tm && tm->start[k] >= 0) HIPCHK(hipEventRecord(c->timing_events[tm->start[k]], c->st[stream]));
         switch (cm.kind) {
         case K_FWD: case K_REFWD: {
@@ -452,9 +458,29 @@ pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool prof
         default: return fail(c, POOCH_E_INVALID, "unknown command");
         }
     }
-    for (int s = 0; s < 3; ++s) HIPCHK(hipStreamSynchronize(c->st[s]));
-    c->has_grads = true;
+    return POOCH_OK;
+}
+
+// Replays a command list and waits for it.  A failure part-way (a HIP call that returns an error, a command that
+// does not fit its buffers) leaves commands of the first part queued on up to three streams: they are waited for
+// before the error is reported, so that nothing of the failed step is still running when the caller acts on it,
+// and the gradients are marked absent (pooch_get_grad / pooch_sgd_update refuse until a step has completed).
+// What a later step needs is untouched by a partial one -- parameters, the batch and the plan are only read, and a
+// step writes every range of the dynamic region before it reads it -- so the same context can simply step again;
+// BN running averages of the layers that did run have moved.
+pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd, float *loss_out)
+{
+    c->has_grads = false;
+    pooch_status ps = enqueue_schedule(c, S, tm, profile_refwd);
+    hipError_t first = hipSuccess;
+    for (int s = 0; s < 3; ++s) {
+        const hipError_t e = hipStreamSynchronize(c->st[s]);
+        if (first == hipSuccess) first = e;
+    }
+    if (ps != POOCH_OK) return ps;   // the message of the failure itself stays
+    if (first != hipSuccess) return fail(c, POOCH_E_HIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(first));
     if (loss_out) HIPCHK(hipMemcpy(loss_out, c->arena + c->off_loss, 4, hipMemcpyDeviceToHost));
+    c->has_grads = true;
     return POOCH_OK;
 }
 
@@ -912,6 +938,13 @@ pooch_status pooch_capture_tensor(pooch_ctx *c, int32_t id, float *host)
     return POOCH_OK;
 }
 
+pooch_status pooch_inject_failure(pooch_ctx *c, int64_t command_index)
+{
+    if (!c) return POOCH_E_INVALID;
+    c->fail_at = command_index < 0 ? -1 : command_index;
+    return POOCH_OK;
+}
+
 pooch_status pooch_get_bn_stats(pooch_ctx *c, int32_t node, float *mean, float *istd)
 {
     NEED_FINAL(c);
@@ -1025,6 +1058,15 @@ pooch_status profile_one(pooch_ctx *c, bool timed, float *loss_out)
     return POOCH_OK;
 }
 
+// a profiling iteration failed: no half-gathered samples and no profiling schedule are left behind (the profile
+// measured or injected earlier, if any, stays valid)
+void profile_abort(pooch_ctx *c)
+{
+    c->prof_sched_ok = false;
+    c->prof_sched = Schedule();
+    c->smp_f.clear(); c->smp_b.clear(); c->smp_r.clear(); c->smp_o.clear(); c->smp_i.clear();
+}
+
 pooch_status profile_end(pooch_ctx *c)
 {
     const int n = c->G.n();
@@ -1056,7 +1098,10 @@ pooch_status pooch_profile(pooch_ctx *c, int warmup, int iters)
     if (ps != POOCH_OK) return ps;
     for (int it = 0; it < warmup + iters; ++it) {
         ps = profile_one(c, it >= warmup, nullptr);
-        if (ps != POOCH_OK) return ps;
+        if (ps != POOCH_OK) {
+            profile_abort(c);
+            return ps;
+        }
     }
     return profile_end(c);
 }
@@ -1069,7 +1114,9 @@ pooch_status pooch_profile_step(pooch_ctx *c, int timed, float *loss_out)
         const pooch_status ps = profile_begin(c);
         if (ps != POOCH_OK) return ps;
     }
-    return profile_one(c, timed != 0, loss_out);
+    const pooch_status ps = profile_one(c, timed != 0, loss_out);
+    if (ps != POOCH_OK) profile_abort(c);   // the samples gathered so far are dropped with the failed iteration
+    return ps;
 }
 
 pooch_status pooch_finish_profile(pooch_ctx *c)

@@ -305,16 +305,32 @@ __device__ __forceinline__ float block_reduce(float v, float *sh, bool is_max)
     return r;
 }
 
-// one block per sample: lse = max + log sum exp(z - max)
-__device__ __forceinline__ float row_lse(const float *__restrict__ zr, int K, float *sh)
+// Softmax cross-entropy of one sample (one block per sample), evaluated so that no digits cancel when the
+// sample is classified with a large margin.  With mx the row maximum,
+//     -log softmax(z)[t] = (mx - z_t) + log(sum_j exp(z_j - mx)).
+// The sum always holds the maximal element's own term exp(0) = 1, so it is taken as 1 + rest, where
+// rest = sum over the elements below the maximum of exp(z_j - mx) + (number of maximal elements - 1), and the
+// logarithm as log1p(rest): both addends of the loss are non-negative and each is accurate to fp32 rounding,
+// where max + log(sum) - z_t loses everything below 1e-7 * |z_t|.
+struct RowSums {
+    float mx;     // row maximum
+    float rest;   // sum_j exp(z_j - mx) without one maximal element's term
+};
+
+__device__ __forceinline__ RowSums row_sums(const float *__restrict__ zr, int K, float *sh)
 {
     float mx = -INFINITY;
     for (int j = threadIdx.x; j < K; j += blockDim.x) mx = fmaxf(mx, zr[j]);
     mx = block_reduce(mx, sh, true);
-    float se = 0.f;
-    for (int j = threadIdx.x; j < K; j += blockDim.x) se += expf(zr[j] - mx);
-    se = block_reduce(se, sh, false);
-    return mx + logf(se);
+    float below = 0.f, ties = 0.f;   // ties: a count, exact in fp32 (K < 2^24 is checked on the host)
+    for (int j = threadIdx.x; j < K; j += blockDim.x) {
+        const float v = zr[j];
+        if (v < mx) below += expf(v - mx);
+        else ties += 1.f;
+    }
+    below = block_reduce(below, sh, false);
+    ties = block_reduce(ties, sh, false);
+    return RowSums{mx, below + (ties - 1.f)};
 }
 
 __global__ __launch_bounds__(256) void softmax_ce_row_kernel(const float *__restrict__ z, const int32_t *__restrict__ labels,
@@ -323,10 +339,10 @@ __global__ __launch_bounds__(256) void softmax_ce_row_kernel(const float *__rest
     __shared__ float sh[4];
     const int n = blockIdx.x;
     const float *zr = z + (int64_t)n * K;
-    const float lse = row_lse(zr, K, sh);
+    const RowSums rs = row_sums(zr, K, sh);
     if (threadIdx.x == 0) {
         const int t = labels[n];
-        per_sample[n] = (t >= 0 && t < K) ? lse - zr[t] : 0.f;
+        per_sample[n] = (t >= 0 && t < K) ? (rs.mx - zr[t]) + log1pf(rs.rest) : 0.f;
     }
 }
 
@@ -339,6 +355,10 @@ __global__ __launch_bounds__(64) void loss_mean_kernel(const float *__restrict__
     if (threadIdx.x == 0) loss[0] = (float)(s / (double)N);
 }
 
+// dz_j = (softmax(z)_j - [j == t]) / N.  For the labelled class softmax - 1 = -(sum of the other classes' terms) /
+// (sum of all terms): the numerator is summed without the labelled class's own term instead of being formed as a
+// difference from 1, so a confidently classified sample keeps a gradient accurate to rounding (p_t - 1 in fp32 would be 0
+// or a few bits).
 template <bool ACCUM>
 __global__ __launch_bounds__(256) void softmax_ce_bwd_kernel(const float *__restrict__ z, const int32_t *__restrict__ labels,
                                                               float *dz, int K, float inv_n)
@@ -346,10 +366,18 @@ __global__ __launch_bounds__(256) void softmax_ce_bwd_kernel(const float *__rest
     __shared__ float sh[4];
     const int n = blockIdx.x;
     const float *zr = z + (int64_t)n * K;
-    const float lse = row_lse(zr, K, sh);
     const int t = labels[n];
+    float mx = -INFINITY;
+    for (int j = threadIdx.x; j < K; j += blockDim.x) mx = fmaxf(mx, zr[j]);
+    mx = block_reduce(mx, sh, true);
+    float others = 0.f;
+    for (int j = threadIdx.x; j < K; j += blockDim.x)
+        if (j != t) others += expf(zr[j] - mx);
+    others = block_reduce(others, sh, false);
+    const float et = (t >= 0 && t < K) ? expf(zr[t] - mx) : 0.f;
+    const float scale = inv_n / (others + et);
     for (int j = threadIdx.x; j < K; j += blockDim.x) {
-        const float v = (expf(zr[j] - lse) - (j == t ? 1.f : 0.f)) * inv_n;
+        const float v = (j == t ? -others : expf(zr[j] - mx)) * scale;
         float *o = dz + (int64_t)n * K + j;
         *o = ACCUM ? *o + v : v;
     }
@@ -441,7 +469,7 @@ hipError_t bias_grad(const float *dy, float *db, int N, int O, hipStream_t s)
 
 hipError_t softmax_ce_fwd(const float *z, const int32_t *labels, float *per_sample, float *loss, int N, int K, hipStream_t s)
 {
-    if (!z || !labels || !per_sample || !loss || N <= 0 || K <= 0) return hipErrorInvalidValue;
+    if (!z || !labels || !per_sample || !loss || N <= 0 || K <= 0 || K >= (1 << 24)) return hipErrorInvalidValue;
     softmax_ce_row_kernel<<<dim3(N), dim3(256), 0, s>>>(z, labels, per_sample, K);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -451,7 +479,7 @@ hipError_t softmax_ce_fwd(const float *z, const int32_t *labels, float *per_samp
 
 hipError_t softmax_ce_bwd(const float *z, const int32_t *labels, float *dz, int N, int K, bool accumulate, hipStream_t s)
 {
-    if (!z || !labels || !dz || N <= 0 || K <= 0) return hipErrorInvalidValue;
+    if (!z || !labels || !dz || N <= 0 || K <= 0 || K >= (1 << 24)) return hipErrorInvalidValue;
     const float inv_n = 1.f / (float)N;
     if (accumulate) softmax_ce_bwd_kernel<true><<<dim3(N), dim3(256), 0, s>>>(z, labels, dz, K, inv_n);
     else softmax_ce_bwd_kernel<false><<<dim3(N), dim3(256), 0, s>>>(z, labels, dz, K, inv_n);

@@ -1,8 +1,9 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
 and every out-of-core plan against the in-core GPU run, bit for bit.
 
-Tolerance (floating point): per tensor, ||gpu - oracle||_2 <= 1e-3 * ||oracle||_2, and for
-the loss |gpu - oracle| <= 1e-3 * |oracle| -- the bar the benchmark spec fixes for fp32.
+Tolerance (floating point), per tensor: ||gpu - oracle||_2 <= 1e-3 * ||oracle||_2 AND, element by element,
+max |gpu - oracle| <= 1e-3 * rms(oracle) (a norm alone would let one wrong halo row or channel of a large
+tensor through); for the loss |gpu - oracle| <= 1e-3 * |oracle| -- the bar the benchmark spec fixes for fp32.
 The oracle accumulates in double; the kernels accumulate in fp32 (MFMA), so the observed
 error is far below the bar and the tests also print it.  Swapping copies bits and
 recomputation re-executes the same deterministic kernels (sections 3.1, 3.2), so any plan
@@ -16,22 +17,10 @@ import workloads
 from oracle.net import OracleNet
 from oracle import plan as OP
 from paper_1907_05013_amd import binding as B
+from parity_util import RTOL, say, errs, rel, close
 
 pytestmark = pytest.mark.gpu
-RTOL = 1e-3
 BIG = 1 << 44
-
-
-def say(*a):
-    print(*a)
-    sys.stdout.flush()
-
-
-def rel(a, b):
-    a = np.asarray(a, np.float64).ravel()
-    b = np.asarray(b, np.float64).ravel()
-    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
-
 
 FUSE = True     # the library's default; test_unfused_layers_* runs the separate kernels
 
@@ -83,18 +72,13 @@ def check_against_oracle(tag, net, seed, perturb=True, capture=True):
     worst = 0.0
     if capture:
         for i in sorted(go):
-            r = rel(go[i], oo[i])
-            worst = max(worst, r)
-            assert np.isfinite(go[i]).all(), (tag, "layer", i, net[i]["op"], "not finite")
-            assert r <= RTOL, (tag, "forward of layer", i, net[i]["op"], r)
+            worst = max(worst, close((tag, "forward of layer", i, net[i]["op"]), go[i], oo[i]))
     assert abs(gl - ol) <= RTOL * abs(ol), (tag, "loss", gl, ol)
     names = workloads.param_shapes(net)
     for k, (a, b) in enumerate(zip(gg, og)):
-        r = rel(a, b)
-        worst = max(worst, r)
-        assert a.shape == b.shape and np.isfinite(a).all()
-        assert r <= RTOL, (tag, "gradient of parameter", k, names[k], r)
-    say("[ok]", tag, "loss gpu %.7f oracle %.7f worst relative error %.2e" % (gl, ol, worst))
+        assert a.shape == b.shape
+        worst = max(worst, close((tag, "gradient of parameter", k, names[k]), a, b))
+    say("[ok]", tag, "loss gpu %.7f oracle %.7f; worst error (L2 and element-wise) %.2e of a bar of %.0e" % (gl, ol, worst, RTOL))
     return params, x, t, gl, gg
 
 
@@ -260,14 +244,14 @@ def check_ill_conditioned(tag, net, seed):
     _, og64, _ = OracleNet(net, params, np.float64).step(x, t)
     gl, gg, go, _ = gpu_step(net, params, x, t, capture=True)
     for i in sorted(go):
-        assert np.isfinite(go[i]).all() and rel(go[i], oo[i]) <= RTOL, (tag, "forward of layer", i, net[i]["op"], rel(go[i], oo[i]))
+        close((tag, "forward of layer", i, net[i]["op"]), go[i], oo[i])
     assert abs(gl - ol) <= RTOL * abs(ol), (tag, "loss", gl, ol)
     names = workloads.param_shapes(net)
     scale = max(float(np.linalg.norm(b64)) for b64 in og64)
     for k, (a, b, b64) in enumerate(zip(gg, og, og64)):
         assert a.shape == b.shape and np.isfinite(a).all()
         err = float(np.linalg.norm(np.asarray(a, np.float64) - b64))
-        assert rel(a, b) <= RTOL or err <= 1e-5 * scale, (tag, "gradient of parameter", k, names[k], rel(a, b), err, scale)
+        assert max(errs(a, b)) <= RTOL or err <= 1e-5 * scale, (tag, "gradient of parameter", k, names[k], errs(a, b), err, scale)
     return params, x, t, gl, gg
 
 
@@ -330,6 +314,71 @@ def test_nothing_runs_before_batch_and_parameters_are_set():
     c.set_params(params)
     refused(c.step)                       # parameters but no batch
     refused(lambda: c.profile(0, 1))
+    c.close()
+
+
+def test_failed_step_leaves_the_context_usable():
+    """error path: a step that fails part-way (forced from the host: a command of the list reports a failure instead
+    of being enqueued; every kernel that was launched runs to its end) returns only after its queued work has
+    drained, withdraws the gradients, and the same context then steps to the in-core bits; profiling into a pinned
+    buffer that cannot hold the maps is refused (POOCH_E_BUDGET) without disturbing the installed plan; a failed
+    profiling iteration leaves no half-gathered samples behind."""
+    net = reduced_nets()["resnet"]
+    params = workloads.make_params(net, 31, perturb=True)
+    x, t = workloads.make_batch(net, 31)
+    shapes = [s for _, _, s in workloads.param_shapes(net)]
+    loss, grads, _, _ = gpu_step(net, params, x, t)
+    G = OP.Graph(net, fuse=FUSE)
+    res, peak = plan_sizes(net)
+    rng = np.random.default_rng(12)
+    cap = int(peak * 0.7) // 256 * 256
+    while True:
+        cls = [int(v) for v in rng.integers(0, 3, len(G.fmaps))]
+        try:
+            S = OP.build_schedule(G, cls, cap, True)
+        except OP.Budget:
+            continue
+        if S.n_refwd >= 2 and cls.count(B.SWAP) >= 3:
+            break
+    c = B.Context(net, res + cap, pinned_bytes=sum(G.fmap_bytes()) + 256, fuse=FUSE)
+    c.set_params(params)
+    c.set_batch(x, t)
+    c.set_plan(cls, True)
+    rows = c.commands()
+    assert c.step() == loss
+    for k in (3, len(rows) // 2, len(rows) - 2):          # early in forward, around the turn, late in backward
+        c.inject_failure(k)
+        with pytest.raises(B.PoochError) as e:
+            c.step()
+        assert e.value.status == B.E_HIP and "injected" in str(e.value)
+        with pytest.raises(B.PoochError) as e:
+            c.get_grads(shapes)
+        assert e.value.status == B.E_STATE
+        with pytest.raises(B.PoochError) as e:
+            c.sgd_update(0.1)
+        assert e.value.status == B.E_STATE
+        assert_bit_exact("step after a failure at command %d" % k, (loss, grads), (c.step(), c.get_grads(shapes)))
+    # a failed profiling iteration: nothing to finish afterwards, and profiling starts afresh
+    c.profile_step(timed=True)
+    c.inject_failure(10)
+    with pytest.raises(B.PoochError):
+        c.profile_step(timed=True)
+    with pytest.raises(B.PoochError) as e:
+        c.finish_profile()
+    assert e.value.status == B.E_STATE
+    c.profile(0, 1)
+    assert_bit_exact("step after a failed profiling iteration", (loss, grads), (c.step(), c.get_grads(shapes)))
+    c.close()
+    # pinned buffer too small for the all-swap profiling run: refused, the installed in-core plan still runs
+    c = B.Context(net, res + 2 * peak, pinned_bytes=4096, fuse=FUSE)
+    c.set_params(params)
+    c.set_batch(x, t)
+    c.set_plan([B.KEEP] * c.n_fmaps)
+    with pytest.raises(B.BudgetError):
+        c.profile(0, 1)
+    with pytest.raises(B.BudgetError):
+        c.set_plan([B.SWAP] * c.n_fmaps)
+    assert_bit_exact("in-core step after a refused profiling run", (loss, grads), (c.step(), c.get_grads(shapes)))
     c.close()
 
 
@@ -454,6 +503,73 @@ def test_training_loop_profile_then_plan_vs_oracle():
     say("[ok] training loop: losses", ["%.4f" % v for v in l_in], "worst parameter error %.2e" % worst)
 
 
+def test_softmax_ce_confident_samples_vs_oracle():
+    """loss and gradient of samples classified with a wide margin (a trained network's usual state), where
+    max + log(sum) - z_t cancels in fp32: logits = 50 x with random and with correct labels, and the labelled class
+    40 above the rest.  The FC in front is s times the identity, so both sides see the same logits."""
+    for tag, K, N, scale, margin, correct in (("logits x50, random labels", 1000, 8, 50.0, 0.0, False),
+                                              ("logits x50, correct labels", 1000, 8, 50.0, 0.0, True),
+                                              ("labelled class 40 above the rest", 1000, 8, 1.0, 40.0, True),
+                                              ("10 classes, margin 25", 10, 5, 1.0, 25.0, True)):
+        net = workloads.Net()
+        net.softmax_ce(net.fc(net.input((N, K, 1, 1)), K))
+        rng = np.random.default_rng(K + int(margin))
+        x = (rng.standard_normal((N, K, 1, 1)) * (1.0 if scale != 1.0 else 0.5)).astype(np.float32)
+        t = rng.integers(0, K, N).astype(np.int32)
+        if correct:
+            t = x.reshape(N, K).argmax(1).astype(np.int32)
+        x[np.arange(N), t, 0, 0] += np.float32(margin)
+        params = [(np.eye(K) * scale).astype(np.float32), np.zeros(K, np.float32)]
+        say("[case] softmax-CE,", tag)
+        ol, og, _ = oracle_step(net, params, x, t)
+        gl, gg, _, _ = gpu_step(net, params, x, t)
+        assert abs(gl - ol) <= RTOL * abs(ol), (tag, "loss", gl, ol)
+        worst = max(close((tag, "gradient", k), a, b) for k, (a, b) in enumerate(zip(gg, og)))
+        say("[ok] softmax-CE, %s: loss gpu %.9e oracle %.9e (relative difference %.1e), worst gradient error %.2e"
+            % (tag, gl, ol, abs(gl - ol) / abs(ol), worst))
+
+
+def test_static_policy_of_section_5_2_on_config2():
+    """the policy the paper compares against: plan it on configuration 2 in the smallest of a few arenas that
+    admits it, execute it, same bits as the in-core run; classes equal to the plan oracle's"""
+    net, seed = workloads.load("bottleneck")
+    params = workloads.make_params(net, seed)
+    x, t = workloads.make_batch(net, seed)
+    shapes = [s for _, _, s in workloads.param_shapes(net)]
+    loss, grads, _, _ = gpu_step(net, params, x, t)
+    res, peak = plan_sizes(net)
+    G = OP.Graph(net, fuse=FUSE)
+    nf = len(G.fmaps)
+    pinned = sum(G.fmap_bytes()) + 256
+    zero = OP.Profile([0.0] * G.n, [0.0] * G.n, [0.0] * G.n, [0.0] * nf, [0.0] * nf)   # the policy is static
+    for frac in (0.5, 0.6, 0.7, 0.8, 0.9):
+        cap = int(peak * frac) // 256 * 256
+        try:
+            ocls, _ = OP.Planner(G, zero, cap, pinned_cap=pinned).plan("superneurons")
+            break
+        except OP.Budget:
+            # the library must refuse where the oracle does
+            c = B.Context(net, res + cap, pinned_bytes=pinned)
+            with pytest.raises(B.BudgetError):
+                c.plan("superneurons")
+            c.close()
+    else:
+        pytest.fail("the static policy fits no arena below the in-core peak")
+    c = B.Context(net, res + cap, pinned_bytes=pinned)
+    c.set_params(params)
+    c.set_batch(x, t)
+    cls, _ = c.plan("superneurons")
+    assert list(cls) == list(ocls)
+    assert B.SWAP in cls and B.RECOMPUTE in cls and B.KEEP in cls
+    l1 = c.step()
+    st = c.stats()
+    assert st.resident_bytes + st.extent_bytes <= st.arena_bytes and st.n_refwd > 0 and st.swap_out_bytes > 0
+    assert_bit_exact("config2 static policy", (loss, grads), (l1, c.get_grads(shapes)))
+    say("[ok] static policy on config2 at %.0f %% of the in-core peak: keep/swap/recompute %d/%d/%d, %d re-forwards"
+        % (100 * frac, st.n_keep, st.n_swap, st.n_recompute, st.n_refwd))
+    c.close()
+
+
 # ------------------------------------------------------------------ reduced copies of configs 2-5
 
 def reduced_nets():
@@ -494,55 +610,54 @@ def test_reduced_configs_vs_oracle_and_random_plans(name):
 
 # ------------------------------------------------------------------ full-size runs
 
-def decision_aware_check(tag, net, seed, perturb=False):
-    """Whole-net parity where ReLU sign decisions can differ between two correct fp32 runs.
+def decision_aware_check(tag, net, seed, perturb=False, report_own=True):
+    """Whole-net parity at sizes where ReLU sign decisions can differ between two correct fp32 runs.
 
-    A pre-activation within rounding distance of zero may legitimately land on either side;
-    the backward pass then differs by that element's whole gradient, which moves every
-    upstream weight gradient by about 1/sqrt(#positions) of its norm per flipped element
-    (the oracle's own fp32-storage build differs from its fp64 build by up to 1e-2 on
-    ResNet-50 for this reason alone).  So: forward values and the loss are held to 1e-3;
-    every decision that differs must be a near-tie (the oracle's pre-activation lies within
-    5e-3 of the tensor's rms from zero); with no differing
-    decision the gradients are held to 1e-3, otherwise to
-        1e-3 + 4 * e0 + 0.5 * sqrt(sum_l F_l / P_l)
-    with e0 = error of the oracle's fp32 build against its fp64 build on that tensor,
-    F_l the differing decisions of ReLU layer l and P_l its positions (batch x space)."""
+    A pre-activation within rounding distance of zero may legitimately land on either side; the backward pass
+    then differs by that element's whole gradient (the oracle's own fp32-storage build differs from its fp64 build
+    by up to 1e-2 on ResNet-50 for this reason alone).  Where floating point decides something discrete both sides
+    must take the decision in one precision, the kernel's: the oracle's backward pass is handed the GPU's ReLU
+    outputs (which elements pass) and the GPU's max-pool inputs (which element of a window is the maximum), and
+    then every gradient is held to the plain 1e-3 bars, L2 and element-wise, with no further allowance.  Forward
+    tensors and the loss are compared with the oracle's own forward pass at 1e-3, and every decision that differs
+    from the oracle's must be a near-tie: the oracle's pre-activation lies within 5e-3 of the tensor's rms of zero.
+    report_own: also print the error against the oracle's own decisions (one more oracle backward pass)."""
     params = workloads.make_params(net, seed, perturb=perturb)
     x, t = workloads.make_batch(net, seed)
     say("[case]", tag, "input", net[0]["shape"], "layers", len(net), "seed", seed)
     o32 = OracleNet(net, params, np.float32)
-    l32, g32, _ = o32.step(x, t)
-    o64 = OracleNet(net, params, np.float64)
-    l64, g64, _ = o64.step(x, t)
+    l32 = o32.forward(x, t)
+    say("[step]", tag, "oracle forward done")
     gl, gg, go, _ = gpu_step(net, params, x, t, capture=True)
+    say("[step]", tag, "GPU step done")
     assert abs(gl - l32) <= RTOL * abs(l32), (tag, "loss", gl, l32)
-    flips, allowance2, worst_f = 0, 0.0, 0.0
+    flips, worst_f, decide = 0, 0.0, {}
     for i in sorted(go):
-        r = rel(go[i], o32.out[i])
-        worst_f = max(worst_f, r)
-        assert np.isfinite(go[i]).all() and r <= RTOL, (tag, "forward of layer", i, net[i]["op"], r)
+        worst_f = max(worst_f, close((tag, "forward of layer", i, net[i]["op"]), go[i], o32.out[i]))
         if net[i]["op"] == "relu":
+            decide[i] = go[i]
             diff = (go[i] > 0) != (o32.out[i] > 0)
             f = int(diff.sum())
             if f:
-                # valid only as a near-tie: the oracle's pre-activation is within 5e-3 of the
-                # tensor's rms from zero (forward values themselves agree to 1e-3, checked above)
                 pre = o32.out[net[i]["x"]]
                 rms = float(np.sqrt(np.mean(pre.astype(np.float64) ** 2)))
                 assert float(np.abs(pre[diff]).max()) <= 5e-3 * rms, (tag, "layer", i, "decision differs away from a tie")
                 flips += f
-                allowance2 += f / (pre.shape[0] * float(np.prod(pre.shape[2:])))
+    for i, L in enumerate(net):
+        if L["op"] == "maxpool":
+            decide[i] = go[L["x"]]
+    g32, _ = o32.backward(decide)
+    say("[step]", tag, "oracle backward (GPU's decisions) done")
     names = workloads.param_shapes(net)
     worst_g = 0.0
-    for k, (a, b32, b64) in enumerate(zip(gg, g32, g64)):
-        e0 = rel(b32, b64)
-        bar = RTOL if flips == 0 else RTOL + 4 * e0 + 0.5 * np.sqrt(allowance2)
-        r = rel(a, b32)
-        worst_g = max(worst_g, r)
-        assert np.isfinite(a).all() and r <= bar, (tag, "gradient of parameter", k, names[k], r, bar)
-    say("[ok]", tag, "loss gpu %.7f oracle %.7f; worst forward error %.2e; %d differing ReLU decisions; worst gradient error %.2e"
-        % (gl, l32, worst_f, flips, worst_g))
+    for k, (a, b32) in enumerate(zip(gg, g32)):
+        worst_g = max(worst_g, close((tag, "gradient of parameter", k, names[k]), a, b32))
+    own = ""
+    if report_own and flips:
+        g_own, _ = o32.backward()
+        own = "; against the oracle's own decisions the worst gradient error would be %.2e" % max(rel(a, b) for a, b in zip(gg, g_own))
+    say("[ok]", tag, "loss gpu %.7f oracle %.7f; worst forward error %.2e, worst gradient error %.2e (L2 and element-wise, bar %.0e); "
+        "%d ReLU decisions differ from the oracle's, all near-ties%s" % (gl, l32, worst_f, worst_g, RTOL, flips, own))
     return params, x, t, gl, gg
 
 
@@ -595,6 +710,13 @@ def test_resnet50_full_resolution_small_batch():
     the batch extent"""
     net, seed = workloads.load("resnet50_b64", batch=4)
     decision_aware_check("resnet50 224 batch 4", net, seed)
+
+
+def test_config3_resnet50_batch64_vs_oracle():
+    """configuration 3 as given: ResNet-50, 224 x 224, batch 64, in-core, every forward tensor, the loss and all 161
+    gradients against the whole oracle (the batch-64 tile choices differ from batch 4's and batch 640's)"""
+    net, seed = workloads.load("resnet50_b64")
+    decision_aware_check("config3 resnet50 224 batch 64", net, seed, report_own=False)
 
 
 def kinkless_probe(x_shape, cout, k, stride, pad, with_bn):

@@ -12,8 +12,6 @@ The CPU oracle cannot run 14.8 TFLOP with 51 GB of saved maps in a test, so pari
     its filter, channel by channel (the loss does not change when a filter is rescaled, because
     BN divides the scale out); the FC bias gradient sums to zero (softmax rows sum to one).
 ResNet-50 at full resolution against the whole oracle is in test_gpu_parity.py at batch 4."""
-import sys
-
 import numpy as np
 import pytest
 
@@ -21,12 +19,9 @@ import workloads
 from oracle import layers as OL
 from paper_1907_05013_amd import binding as B
 
+from parity_util import say
+
 pytestmark = pytest.mark.gpu
-
-
-def say(*a):
-    print(*a)
-    sys.stdout.flush()
 
 
 def incore_arena(net):
@@ -108,23 +103,40 @@ def test_resnet50_b640_under_16gib_matches_incore_bit_for_bit():
     c = B.Context(net, 16 << 30, pinned_bytes=fm + 4096)
     c.set_params(params)
     c.set_batch(x, t)
-    c.profile(warmup=1, iters=2)
+    c.profile(warmup=1, iters=3)
+
+    def run_and_compare(tag, predicted):
+        loss1 = c.step()
+        st = c.stats()
+        grads1 = c.get_grads(shapes)
+        say("[b640] %s: keep/swap/recompute %d/%d/%d, %d re-forwards, swapped %.1f GB each way, predicted %.0f ms, measured %.0f ms"
+            % (tag, st.n_keep, st.n_swap, st.n_recompute, st.n_refwd, st.swap_out_bytes / 1e9, predicted, st.step_ms))
+        assert st.resident_bytes + st.extent_bytes <= 16 << 30
+        assert st.n_swap + st.n_recompute > 0
+        assert np.float32(loss0).tobytes() == np.float32(loss1).tobytes(), (tag, loss0, loss1)
+        for k, (a, b) in enumerate(zip(grads0, grads1)):
+            assert a.tobytes() == b.tobytes(), (tag, "gradient", k, pshapes[k])
+        # the timeline simulation predicts the measured step (section 4.1.2): best of three steps within 10 %
+        measured = []
+        for _ in range(3):
+            c.step()
+            measured.append(c.stats().step_ms)
+        say("[b640] %s: simulated %.1f ms, measured %s ms" % (tag, predicted, ", ".join("%.1f" % v for v in measured)))
+        assert abs(min(measured) - predicted) <= 0.10 * predicted, (tag, measured, predicted)
+
+    # the paper's two steps (section 4.4)
     cls, predicted = c.plan("pooch", 8)
-    loss1 = c.step()
-    st = c.stats()
-    grads1 = c.get_grads(shapes)
-    say("[b640] keep/swap/recompute %d/%d/%d, %d re-forwards, swapped %.1f GB each way, predicted %.0f ms, measured %.0f ms"
-        % (st.n_keep, st.n_swap, st.n_recompute, st.n_refwd, st.swap_out_bytes / 1e9, predicted, st.step_ms))
-    assert st.resident_bytes + st.extent_bytes <= 16 << 30
-    assert st.n_swap + st.n_recompute > 0
-    assert np.float32(loss0).tobytes() == np.float32(loss1).tobytes(), (loss0, loss1)
-    for k, (a, b) in enumerate(zip(grads0, grads1)):
-        assert a.tobytes() == b.tobytes(), ("gradient", k, pshapes[k])
-    # the timeline simulation predicts the measured step (section 4.1.2); the profile is two timed iterations,
-    # so take the best of a few steps and leave room for the run-to-run spread of such a short profile
-    measured = []
-    for _ in range(3):
-        c.step()
-        measured.append(c.stats().step_ms)
-    assert abs(min(measured) - predicted) <= 0.35 * predicted, (measured, predicted)
+    run_and_compare("two-step plan", predicted)
+    # the plan bench.py times: two steps + local search with its settings (4 bits, 300 restarts), the layers
+    # re-timed under that plan, classified once more
+    c.plan("refine", 4, restarts=300)
+    c.refine_profile(2)
+    cls, predicted = c.plan("refine", 4, restarts=300)
+    run_and_compare("refined plan (bench.py's)", predicted)
+    # the static policy of section 5.2 does not fit this arena at batch 640 (the paper reports the same of its own
+    # implementation of that policy); the refusal leaves the installed plan in place
+    with pytest.raises(B.BudgetError):
+        c.plan("superneurons")
+    assert np.array_equal(c.get_plan(), cls)
+    assert np.float32(c.step()).tobytes() == np.float32(loss0).tobytes()
     c.close()
