@@ -247,6 +247,22 @@ pooch_status pooch_get_commands(pooch_ctx *, int64_t *rows, int64_t max_rows, in
  * all three streams before returning; *loss_out (may be NULL) receives the mean loss. */
 pooch_status pooch_step(pooch_ctx *, float *loss_out);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): pooch_step with the kernels' scratch -- the filter gradients' split-K partial sums, the batch
+ * normalisations' reduction partials and per-tile statistics, the per-sample losses -- taken from an array that is
+ * part of the library's code object (128 MiB = 134 217 728 bytes, held by every GPU the library runs on until the
+ * process ends) instead of from the arena's resident region.  Same kernels, same command list, same bits as
+ * pooch_step; inputs and outputs (arena, pinned buffer, streams, *loss_out) are the caller's as before.  The call
+ * allocates nothing on the device or through the runtime: no hipMalloc / hipFree, no event creation (the plan's events
+ * are made when the plan is installed), no torch call.
+ * POOCH_E_BUDGET, with both sizes in pooch_last_error(), when the network's scratch exceeds the array (ResNet-50
+ * needs 96 MiB at batch 640 and passes, 163 MiB at batch 2048 and does not; pooch_stats.scratch_bytes tells) -- checked first, so a planning-only context can ask;
+ * POOCH_E_STATE without arena or plan; POOCH_E_HIP if the array's address could not be obtained when the context
+ * was created.  All contexts on one GPU share that GPU's one array, which keeps the previous call's contents:
+ * nothing in it has to start at zero (every range is written by the step before it is read), but two such calls
+ * that overlap in time on one GPU -- from two contexts, or two threads -- race; serialise them. */
+pooch_status pooch_step_static_scratch(pooch_ctx *, float *loss_out);
+
 typedef struct pooch_stats {
     double step_ms;            /* wall time of the last step (host clock, enqueue to sync) */
     double predicted_ms;       /* simulated step time of the installed plan (0 without profile) */
@@ -260,6 +276,8 @@ typedef struct pooch_stats {
     int32_t n_commands;        /* length of the replayed command list */
     int32_t n_refwd;           /* forward re-executions per step */
     int32_t reserved;
+    uint64_t scratch_bytes;    /* device scratch the kernels of a step use beyond their inputs and outputs (part of
+                                  resident_bytes; what pooch_step_static_scratch needs of its static array) */
 } pooch_stats;
 pooch_status pooch_get_stats(pooch_ctx *, pooch_stats *);
 

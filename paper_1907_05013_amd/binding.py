@@ -29,7 +29,8 @@ class Stats(C.Structure):
                 ("peak_bytes", C.c_uint64), ("extent_bytes", C.c_uint64),
                 ("resident_bytes", C.c_uint64), ("arena_bytes", C.c_uint64),
                 ("n_keep", C.c_int32), ("n_swap", C.c_int32), ("n_recompute", C.c_int32),
-                ("n_commands", C.c_int32), ("n_refwd", C.c_int32), ("reserved", C.c_int32)]
+                ("n_commands", C.c_int32), ("n_refwd", C.c_int32), ("reserved", C.c_int32),
+                ("scratch_bytes", C.c_uint64)]
 
 
 _ctx = C.c_void_p
@@ -87,6 +88,7 @@ SYMBOLS = {
     "pooch_get_overhead_sets": (_i32, [_ctx, _pu8, _pu8]),
     "pooch_get_commands": (_i32, [_ctx, _pi64, _i64, _pi64]),
     "pooch_step": (_i32, [_ctx, _pf]),
+    "pooch_step_static_scratch": (_i32, [_ctx, _pf]),
     "pooch_get_stats": (_i32, [_ctx, C.POINTER(Stats)]),
     "pooch_step_timed": (_i32, [_ctx, _pf, _pd, _pd, _pd, _pd]),
     "pooch_node_kernel": (C.c_char_p, [_ctx, _i32, C.c_int]),
@@ -422,6 +424,12 @@ class Context:
     def step(self):
         loss = C.c_float()
         self._chk(self.L.pooch_step(self.h, C.byref(loss)))
+        return loss.value
+
+    def step_static_scratch(self):
+        """pooch_step with the kernels' scratch in the library's static device array (allocates nothing)"""
+        loss = C.c_float()
+        self._chk(self.L.pooch_step_static_scratch(self.h, C.byref(loss)))
         return loss.value
 
     def step_timed(self):

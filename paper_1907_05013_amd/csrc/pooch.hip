@@ -16,9 +16,51 @@
 #include <cstdlib>
 #include <chrono>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 using namespace pooch;
+
+// ---- static scratch of pooch_step_static_scratch ------------------------------------------------------------
+// Device memory the kernels of a step use beyond their inputs and outputs -- the filter gradients' split-K
+// partials, the batch normalisations' reduction partials and per-tile statistics, the per-sample losses -- for
+// callers that may not allocate: a file-scope array instead of a range of the arena.  Every GPU the library runs
+// on holds its own copy from the moment the code object is loaded there until the process ends.  In host code the
+// array's name is only a handle: its device address comes from hipGetSymbolAddress, once per device
+// (static_scratch_for), and that address is what kernels and copies are given.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)128 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};   // per device: address of that device's copy of `scratch`
+
+// address of `scratch` on `device`; looked up on first use with that device current
+hipError_t static_scratch_for(int device, void **out)
+{
+    *out = nullptr;
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        int current = -1;
+        hipError_t e = hipGetDevice(&current);
+        if (e != hipSuccess) return e;
+        if (current != device) {
+            e = hipSetDevice(device);
+            if (e != hipSuccess) return e;
+        }
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (current != device) (void)hipSetDevice(current);
+        if (e != hipSuccess) return e;
+        if (!ptr || (uintptr_t)ptr % 256 != 0) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+}  // namespace
 
 namespace {
 
@@ -58,6 +100,8 @@ struct pooch_ctx {
     bool has_batch = false, has_grads = false;
     std::vector<char> param_set;
     int64_t off_input = 0, off_labels = 0, off_ws_wgrad = 0, off_ws_bn = 0, off_loss_ps = 0, off_loss = 0;
+    int64_t ws_wgrad_bytes = 0, ws_bn_bytes = 0, loss_ps_bytes = 0;   // sizes of the three scratch ranges (256-byte rounded)
+    char *static_scratch = nullptr;         // this context's GPU's copy of the static scratch array (compute contexts)
     int64_t resident_bytes = 0;
     int nclasses = 0;
     // device channel count of the network input: a 3-channel input read only by convolutions is
@@ -185,7 +229,16 @@ struct Exec {
     pooch_ctx *c;
     const Schedule &S;
     hipEvent_t mid = nullptr;  // when set, recorded between the filter gradient and the data gradient
-    explicit Exec(pooch_ctx *ctx, const Schedule &s) : c(ctx), S(s) {}
+    // kernel scratch: ranges of the arena's resident region, or of the static scratch array
+    float *ws_wgrad, *ws_bn, *loss_ps;
+    Exec(pooch_ctx *ctx, const Schedule &s, bool static_scratch) : c(ctx), S(s)
+    {
+        char *base = static_scratch ? ctx->static_scratch : ctx->arena + ctx->off_ws_wgrad;
+        // the three ranges lie in this order, back to back, in the arena too (pooch_finalize)
+        ws_wgrad = reinterpret_cast<float *>(base);
+        ws_bn = reinterpret_cast<float *>(base + ctx->ws_wgrad_bytes);
+        loss_ps = reinterpret_cast<float *>(base + ctx->ws_wgrad_bytes + ctx->ws_bn_bytes);
+    }
 
     float *R(int64_t off) const { return reinterpret_cast<float *>(c->arena + off); }  // resident
     float *D(int64_t off) const
@@ -204,7 +257,7 @@ struct Exec {
         switch (nd.op) {
         case OP_CONV:
             return pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i, c->in_cdev), s,
-                                (!refwd && c->stats_to[i] >= 0) ? R(c->off_ws_bn) : nullptr);
+                                (!refwd && c->stats_to[i] >= 0) ? ws_bn : nullptr);
         case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
             const bool relu = nd.op == OP_BNRELU;
@@ -213,19 +266,19 @@ struct Exec {
             if (G.apply_into[i] >= 0) {   // applied inside the add + ReLU that consumes it: statistics only
                 if (refwd) return hipSuccess;   // nothing to recompute: the statistics are saved, there is no output
                 if (c->stats_from[i] >= 0)
-                    return pk::bn_stats_from_tiles(R(c->off_ws_bn), c->stats_tiles[i][0], c->stats_tiles[i][1], M, (int)nd.C,
+                    return pk::bn_stats_from_tiles(ws_bn, c->stats_tiles[i][0], c->stats_tiles[i][1], M, (int)nd.C,
                                                    nd.eps, R(c->off_mean[i]), R(c->off_istd[i]), run, s);
-                return pk::bn_stats(D(in0), R(c->off_mean[i]), R(c->off_istd[i]), R(c->off_ws_bn), M, (int)nd.C, nd.eps, run, s);
+                return pk::bn_stats(D(in0), R(c->off_mean[i]), R(c->off_istd[i]), ws_bn, M, (int)nd.C, nd.eps, run, s);
             }
             if (refwd)
                 return pk::bn_apply(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), R(c->off_mean[i]), R(c->off_istd[i]),
                                     D(out), M, (int)nd.C, relu, s);
             if (c->stats_from[i] >= 0)   // the convolution that has just run left the statistics per row tile
                 return pk::bn_fwd_from_tiles(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), D(out), R(c->off_mean[i]),
-                                             R(c->off_istd[i]), R(c->off_ws_bn), c->stats_tiles[i][0], c->stats_tiles[i][1], M,
+                                             R(c->off_istd[i]), ws_bn, c->stats_tiles[i][0], c->stats_tiles[i][1], M,
                                              (int)nd.C, nd.eps, relu, run, s);
             return pk::bn_fwd(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), D(out), R(c->off_mean[i]), R(c->off_istd[i]),
-                              R(c->off_ws_bn), M, (int)nd.C, nd.eps, relu, run, s);
+                              ws_bn, M, (int)nd.C, nd.eps, relu, run, s);
         }
         case OP_RELU: return pk::relu_fwd(D(in0), D(out), nd.numel(), s);
         case OP_ADD: return pk::add_fwd(D(in0), D(in1), D(out), nd.numel(), s);
@@ -254,7 +307,7 @@ struct Exec {
         }
         case OP_LOSS: {
             const Node &z = G.nodes[nd.in[0]];
-            return pk::softmax_ce_fwd(D(in0), reinterpret_cast<const int32_t *>(c->arena + c->off_labels), R(c->off_loss_ps),
+            return pk::softmax_ce_fwd(D(in0), reinterpret_cast<const int32_t *>(c->arena + c->off_labels), loss_ps,
                                       R(c->off_loss), (int)z.N, (int)z.C, s);
         }
         default: return hipErrorInvalidValue;
@@ -280,7 +333,7 @@ struct Exec {
         switch (nd.op) {
         case OP_CONV: case OP_FC: {
             const pk::ConvGeom g = conv_geom(G, i, c->in_cdev);
-            hipError_t e = pk::conv_wgrad(D(dy), D(need), R(P(i, 0).off_grad), R(c->off_ws_wgrad), g, s);
+            hipError_t e = pk::conv_wgrad(D(dy), D(need), R(P(i, 0).off_grad), ws_wgrad, g, s);
             if (e != hipSuccess) return e;
             if (nd.op == OP_FC) {
                 e = pk::bias_grad(D(dy), R(P(i, 1).off_grad), (int)nd.N, (int)nd.C, s);
@@ -298,7 +351,7 @@ struct Exec {
             // no gradient wanted for the input (the network input): dy may be another tensor's gradient too, leave it alone
             float *dx = m0 == M_NONE ? nullptr : D(o0);
             return pk::bn_bwd(D(need), D(dy), R(P(i, 0).off_val), R(P(i, 1).off_val), R(c->off_mean[i]), R(c->off_istd[i]), dx,
-                              R(P(i, 0).off_grad), R(P(i, 1).off_grad), R(c->off_ws_bn), M, (int)nd.C, m0 == M_ACC,
+                              R(P(i, 0).off_grad), R(P(i, 1).off_grad), ws_bn, M, (int)nd.C, m0 == M_ACC,
                               nd.op == OP_BNRELU, s);
         }
         case OP_ADDRELU: {
@@ -371,7 +424,7 @@ pooch_status copy_out_capture(pooch_ctx *c, int i, const float *dev)
 // is bracketed by timing events on its own stream; profile_refwd additionally runs (and
 // times) each layer's re-forward variant right after its forward, on the same buffers.
 // Returns at the first failure with whatever was enqueued before it still in flight: run_schedule() cleans up.
-pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd)
+pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd, bool static_scratch)
 {
     if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
     if (!c->has_batch) return fail(c, POOCH_E_STATE, "no batch: call pooch_set_batch first");
@@ -379,8 +432,13 @@ pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool 
         if (!ok) return fail(c, POOCH_E_STATE, "a parameter was never set: call pooch_set_param for every parameter first");
     const size_t swap_bytes = (size_t)S.swap_bytes;
     if (swap_bytes > 0 && (!c->pinned || swap_bytes > c->pinned_bytes)) return fail(c, POOCH_E_BUDGET, "pinned buffer too small");
-    pooch_status ps = ensure_events(c, c->sync_events, (size_t)S.n_events, hipEventDisableTiming);
-    if (ps != POOCH_OK) return ps;
+    pooch_status ps = POOCH_OK;
+    if (static_scratch) {   // this path creates nothing: the events were made when the plan was installed
+        if (c->sync_events.size() < (size_t)S.n_events) return fail(c, POOCH_E_STATE, "the plan's events do not exist");
+    } else {
+        ps = ensure_events(c, c->sync_events, (size_t)S.n_events, hipEventDisableTiming);
+        if (ps != POOCH_OK) return ps;
+    }
     const int64_t cap = (int64_t)c->arena_bytes - c->resident_bytes;
     size_t n_te = 0;
     if (tm) {
@@ -400,7 +458,7 @@ pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool 
         ps = ensure_events(c, c->timing_events, n_te, hipEventDefault);
         if (ps != POOCH_OK) return ps;
     }
-    Exec X(c, S);
+    Exec X(c, S, static_scratch);
     const Graph &G = c->G;
     auto in_arena = [&](int64_t off, int64_t bytes) { return off == OFF_INPUT || off == OFF_NONE || (off >= 0 && off + bytes <= cap); };
     for (size_t k = 0; k < S.cmds.size(); ++k) {
@@ -468,10 +526,11 @@ pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool 
 // What a later step needs is untouched by a partial one -- parameters, the batch and the plan are only read, and a
 // step writes every range of the dynamic region before it reads it -- so the same context can simply step again;
 // BN running averages of the layers that did run have moved.
-pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd, float *loss_out)
+pooch_status run_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd, float *loss_out,
+                          bool static_scratch = false)
 {
     c->has_grads = false;
-    pooch_status ps = enqueue_schedule(c, S, tm, profile_refwd);
+    pooch_status ps = enqueue_schedule(c, S, tm, profile_refwd, static_scratch);
     hipError_t first = hipSuccess;
     for (int s = 0; s < 3; ++s) {
         const hipError_t e = hipStreamSynchronize(c->st[s]);
@@ -541,6 +600,10 @@ pooch_status install(pooch_ctx *c, const std::vector<uint8_t> &cls, bool ahead, 
     const int64_t cap = (int64_t)c->arena_bytes - c->resident_bytes;
     const int64_t pinned_cap = c->arena ? (int64_t)c->pinned_bytes : -1;
     if (!build_schedule(c->G, cls, cap, ahead, pinned_cap, S, &why)) return fail(c, POOCH_E_BUDGET, why);
+    if (c->arena) {   // the plan's events exist from here on: a step creates none
+        const pooch_status ps = ensure_events(c, c->sync_events, (size_t)S.n_events, hipEventDisableTiming);
+        if (ps != POOCH_OK) return ps;
+    }
     c->sched = std::move(S);
     c->cls = cls;
     c->ahead = ahead;
@@ -585,6 +648,16 @@ pooch_status pooch_create(void *arena, size_t arena_bytes, void *pinned_host, si
     c->st[0] = static_cast<hipStream_t>(stream_compute);
     c->st[1] = static_cast<hipStream_t>(stream_d2h);
     c->st[2] = static_cast<hipStream_t>(stream_h2d);
+    if (arena) {
+        // the GPU that holds the arena also holds a copy of the static scratch array: its address there, looked up once
+        // per device (pooch_step_static_scratch); a failure is reported by that entry point, not here
+        hipPointerAttribute_t attr;
+        void *ptr = nullptr;
+        if (hipPointerGetAttributes(&attr, arena) == hipSuccess && static_scratch_for(attr.device, &ptr) == hipSuccess)
+            c->static_scratch = static_cast<char *>(ptr);
+        else
+            (void)hipGetLastError();
+    }
     *out = c;
     return POOCH_OK;
 }
@@ -832,9 +905,13 @@ pooch_status pooch_finalize(pooch_ctx *c)
             ws_bn = std::max(ws_bn, pk::bn_tiles_workspace_floats(tiles_m, (int)G.nodes[i].C) * 4);
         }
     }
-    c->off_ws_wgrad = take((int64_t)ws_wgrad);
-    c->off_ws_bn = take((int64_t)ws_bn);
-    c->off_loss_ps = take(G.nodes[0].N * 4);
+    // the kernels' scratch: three ranges back to back (Exec relies on the order)
+    c->ws_wgrad_bytes = round_up((int64_t)ws_wgrad);
+    c->ws_bn_bytes = round_up((int64_t)ws_bn);
+    c->loss_ps_bytes = round_up(G.nodes[0].N * 4);
+    c->off_ws_wgrad = take(c->ws_wgrad_bytes);
+    c->off_ws_bn = take(c->ws_bn_bytes);
+    c->off_loss_ps = take(c->loss_ps_bytes);
     c->off_loss = take(4);
     c->resident_bytes = off;
     if ((size_t)off > c->arena_bytes) return fail(c, POOCH_E_BUDGET, "the resident region alone exceeds the arena");
@@ -1317,6 +1394,22 @@ pooch_status pooch_step(pooch_ctx *c, float *loss_out)
     return ps;
 }
 
+pooch_status pooch_step_static_scratch(pooch_ctx *c, float *loss_out)
+{
+    NEED_FINAL(c);
+    const int64_t need = c->ws_wgrad_bytes + c->ws_bn_bytes + c->loss_ps_bytes;
+    if ((size_t)need > STATIC_SCRATCH_BYTES)
+        return fail(c, POOCH_E_BUDGET, "step_static_scratch: this network's kernels need " + std::to_string(need) +
+                                           " bytes of scratch, the static buffer holds " + std::to_string(STATIC_SCRATCH_BYTES));
+    if (!c->arena) return fail(c, POOCH_E_STATE, "planning-only context (no arena)");
+    if (!c->has_plan) return fail(c, POOCH_E_STATE, "step: no plan installed");
+    if (!c->static_scratch) return fail(c, POOCH_E_HIP, "step_static_scratch: the static scratch array's device address is not available");
+    const auto t0 = std::chrono::steady_clock::now();
+    const pooch_status ps = run_schedule(c, c->sched, nullptr, false, loss_out, true);
+    c->last_step_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    return ps;
+}
+
 pooch_status pooch_get_stats(pooch_ctx *c, pooch_stats *st)
 {
     NEED_FINAL(c);
@@ -1324,6 +1417,7 @@ pooch_status pooch_get_stats(pooch_ctx *c, pooch_stats *st)
     std::memset(st, 0, sizeof(*st));
     st->resident_bytes = (uint64_t)c->resident_bytes;
     st->arena_bytes = (uint64_t)c->arena_bytes;
+    st->scratch_bytes = (uint64_t)(c->ws_wgrad_bytes + c->ws_bn_bytes + c->loss_ps_bytes);
     if (!c->has_plan) return POOCH_OK;
     st->step_ms = c->last_step_ms;
     st->predicted_ms = c->predicted_ms;

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_stats_struct_matches_header_size():
     # 2 doubles + 6 uint64 + 6 int32
-    assert C.sizeof(B.Stats) == 2 * 8 + 6 * 8 + 6 * 4
+    assert C.sizeof(B.Stats) == 2 * 8 + 6 * 8 + 6 * 4 + 8
 
 
 def test_planning_only_context_resnet50_feature_maps():
