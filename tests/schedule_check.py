@@ -127,3 +127,76 @@ def check(G, cmds, cap):
         for off, labels in renamed.items():
             live[off] = (live[off][0], labels)
     return len(recs)
+
+
+# --------------------------------------------------------------------------------------------------------------
+# Timeline of a command list, written independently of the oracle's and the library's simulators.
+#
+# Every executed command becomes an interval [start, end).  A command starts when the command before it on its
+# stream has ended and every event its stream waited for since then has fired; an event fires when the stream that
+# recorded it had finished everything issued before the record (its last command's end, and the events it had
+# itself waited for by then).  From the intervals, by their definitions (paper section 4.4.2):
+#   step time  = the latest end;
+#   L_I        = maps whose arrival the compute stream really waited for: at the wait, the arrival event fires
+#                later than everything else the compute stream was waiting for up to that point;
+#   L_O        = maps whose swap-out is not hidden by computation: it ends after the last forward command has
+#                ended, or some stream, ready to go on, had to sit out a device-to-host completion event while
+#                that swap-out (issued no later than the awaited one) was still running.
+
+class Interval:
+    __slots__ = ("cmd", "stream", "start", "end")
+
+    def __init__(self, cmd, stream, start, end):
+        self.cmd, self.stream, self.start, self.end = cmd, stream, start, end
+
+
+def timeline(G, cmds, t_fwd, t_bwd, t_refwd, t_out, t_in):
+    """returns (intervals of the executed commands in list order, step time, L_O, L_I); L_O / L_I as sets of tensor ids"""
+    stream_of = {KF: 0, KR: 0, KB: 0, KO: 1, KI: 2}
+    ready = [0.0, 0.0, 0.0]          # per stream: when it could start its next command
+    fires = {}                       # event -> time
+    d2h_done_event = {}              # event recorded right after a swap-out -> position of that swap-out in issue order
+    arrive_event = {}                # event recorded right after a swap-in -> tensor
+    outs = []                        # swap-out intervals in issue order
+    ivs = []
+    LO, LI = set(), set()
+    prev_kind = [None, None, None]   # last executed command per stream: (kind, tensor / node)
+    for c in cmds:
+        k = c[0]
+        if k == KREC:
+            s, e = c[1], c[2]
+            fires[e] = ready[s]
+            if prev_kind[s] is not None and prev_kind[s][0] == KO and s == 1:
+                d2h_done_event.setdefault(e, prev_kind[s][2])
+            if prev_kind[s] is not None and prev_kind[s][0] == KI and s == 2:
+                arrive_event.setdefault(e, prev_kind[s][1])
+            prev_kind[s] = None          # a later record on this stream marks no copy
+            continue
+        if k == KWAIT:
+            s, e = c[1], c[2]
+            assert e in fires, "wait on an event that has not been recorded"
+            if fires[e] > ready[s]:
+                if e in d2h_done_event:
+                    for iv in outs[:d2h_done_event[e] + 1]:
+                        if iv.end > ready[s]:
+                            LO.add(iv.cmd[1])
+                elif e in arrive_event and s == 0:
+                    LI.add(arrive_event[e])
+                ready[s] = fires[e]
+            continue
+        s = stream_of[k]
+        dur = {KF: t_fwd, KR: t_refwd, KB: t_bwd}[k][c[1]] if k in (KF, KR, KB) else (t_out if k == KO else t_in)[G.fidx[c[1]]]
+        iv = Interval(c, s, ready[s], ready[s] + dur)
+        ready[s] = iv.end
+        ivs.append(iv)
+        if k == KO:
+            outs.append(iv)
+            prev_kind[s] = (KO, c[1], len(outs) - 1)
+        else:
+            prev_kind[s] = (k, c[1], None)
+    fwd_end = max([iv.end for iv in ivs if iv.cmd[0] == KF], default=0.0)
+    for iv in outs:
+        if iv.end > fwd_end:
+            LO.add(iv.cmd[1])
+    T = max([iv.end for iv in ivs], default=0.0)
+    return ivs, T, LO, LI

@@ -188,6 +188,137 @@ def test_paper_eight_layer_example_sets():
     assert Tbest <= T
 
 
+# ---- the simulator against a timeline written independently of it ------------------------------------------------
+
+@pytest.mark.parametrize("fuse", [False, True])
+@pytest.mark.parametrize("name", ["tiny", "res", "c3d", "chain", "fork"])
+def test_simulate_against_independent_timeline(name, fuse):
+    """step time, L_O and L_I of oracle.plan.simulate against schedule_check.timeline, which turns the command list into
+    intervals and reads the three quantities off them by their definitions: random plans, arenas, link speeds, both
+    swap-in policies"""
+    net = small_nets()[name]
+    G = P.Graph(net, fuse=fuse)
+    nf = len(G.fmaps)
+    rng = np.random.default_rng(5)
+    incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
+    n = with_lo = with_li = 0
+    for trial in range(60):
+        cls = [int(v) for v in rng.integers(0, 3, nf)] if trial % 3 else [P.SWAP] * nf
+        cap = int(incore.peak * rng.uniform(0.35, 1.2)) // 256 * 256
+        prof = random_profile(G, rng, link=float(rng.choice([0.2, 1.0, 4.0])))
+        for ahead in (True, False):
+            try:
+                S = P.build_schedule(G, cls, cap, ahead)
+            except P.Budget:
+                continue
+            T, LO, LI = P.simulate(G, S, prof)
+            ivs, T2, LO2, LI2 = schedule_check.timeline(G, S.cmds, prof.t_fwd, prof.t_bwd, prof.t_refwd, prof.t_out, prof.t_in)
+            assert abs(T - T2) <= 1e-9 * max(T, 1.0) and LO == LO2 and LI == LI2, (trial, ahead)
+            # intervals of one stream never overlap, and the compute stream runs the commands in list order
+            for s in range(3):
+                mine = [iv for iv in ivs if iv.stream == s]
+                assert all(a.end <= b.start + 1e-12 for a, b in zip(mine, mine[1:]))
+            n += 1
+            with_lo += bool(LO)
+            with_li += bool(LI)
+    assert n >= 20 and with_lo >= 3 and with_li >= 3
+
+
+def _chain_profile(G, t_fwd, t_bwd, t_refwd, t_out, t_in):
+    """durations given per relu layer 1..n of a relu_chain (gavgpool and loss: 1 each way) and per relu-output map"""
+    n = len(t_fwd)
+    tail = [1.0, 1.0]
+    return P.Profile([0.0] + list(t_fwd) + tail, [0.0] + list(t_bwd) + tail, [0.0] + list(t_refwd) + tail,
+                     list(t_out) + [0.0], list(t_in) + [0.0])
+
+
+def test_hand_computed_timeline_one_swap_and_a_two_deep_recomputation():
+    """four layers; map 1 is swapped, maps 2 and 3 are recomputed (3 from 2 from 1: a chain two deep), map 4 and the
+    pooled vector stay.  Forward 2 per layer, backward 3, re-forward 1.5, pool and loss 1 each way.
+
+        compute   F1 0-2  F2 2-4  F3 4-6  F4 6-8  F5 8-9  F6 9-10 | B6 10-11  B5 11-12  B4 12-15  ...
+        d2h       map 1 leaves after F2 (its last forward reader): 4 .. 4 + t_out
+        h2d       its return is issued when backward begins (10) and starts once the copy out has ended
+        B3 needs map 3 <- map 2 <- map 1: waits for the arrival, then R2, R3 (1.5 each), then B3, B2, B1 (3 each)
+
+    (a) t_out 5, t_in 4: out 4-9, in 10-14, arrived before B4 ends at 15: R2 15-16.5, R3 16.5-18, B3 18-21, B2 21-24,
+        B1 24-27.  T = 27, nothing sticks out: L_O = L_I = {}.
+    (b) t_out 5, t_in 7: in 10-17, compute waits from 15 to 17: T = 29, L_I = {map 1}.
+    (c) t_out 7, t_in 7: out 4-11 ends after the forward pass (10): L_O = {map 1}; in 11-18; T = 30, L_I = {map 1}."""
+    G = P.Graph(relu_chain(4))
+    assert G.fmaps == [1, 2, 3, 4, 5]
+    cls = [P.SWAP, P.RECOMPUTE, P.RECOMPUTE, P.KEEP, P.KEEP]
+    S = P.build_schedule(G, cls, BIG)
+    executed = [(c[0], c[1]) for c in S.cmds if c[0] <= P.KI]
+    F, R, Bk, O, I = P.KF, P.KR, P.KB, P.KO, P.KI
+    assert executed == [(F, 1), (F, 2), (O, 1), (F, 3), (F, 4), (F, 5), (F, 6), (I, 1),
+                        (Bk, 6), (Bk, 5), (Bk, 4), (R, 2), (R, 3), (Bk, 3), (Bk, 2), (Bk, 1)]
+    assert S.n_refwd == 2
+    for t_out, t_in, T_want, LO_want, LI_want in ((5.0, 4.0, 27.0, set(), set()), (5.0, 7.0, 29.0, set(), {1}), (7.0, 7.0, 30.0, {1}, {1})):
+        prof = _chain_profile(G, [2.0] * 4, [3.0] * 4, [1.5] * 4, [t_out] * 4, [t_in] * 4)
+        T, LO, LI = P.simulate(G, S, prof)
+        assert (T, LO, LI) == (T_want, LO_want, LI_want), (t_out, t_in, T, LO, LI)
+
+
+def test_recompute_ratio_exact_tie_stays_swap():
+    """section 4.4.3: a map is moved to recompute only when recompute_overhead / swap_overhead is below one.  Three
+    layers, map 2 swapped, the rest kept.  Its return is issued when backward begins and takes 5.5; the loss, the pool and
+    layer 3 take 1 + 1 + 2 = 4 before layer 2's backward needs it: swap_overhead = 1.5.  Recomputing it from map 1 (kept)
+    costs its re-forward time.  Durations are dyadic, so the tie is exact in floating point."""
+    G = P.Graph(relu_chain(3))
+    assert G.fmaps == [1, 2, 3, 4]
+    cls = [P.KEEP, P.SWAP, P.KEEP, P.KEEP]
+    for t_re, want in ((1.5, P.SWAP), (1.5 - 2.0 ** -20, P.RECOMPUTE), (1.5 + 2.0 ** -20, P.SWAP)):
+        prof = _chain_profile(G, [1.0] * 3, [2.0] * 3, [1.0, t_re, 1.0], [0.25] * 3, [5.5] * 3)
+        pl = P.Planner(G, prof, BIG)
+        T0 = pl.evaluate(cls)
+        T_keep = pl.evaluate([P.KEEP] * 4)
+        assert T0 - T_keep == 1.5                      # the stall the swapped map causes
+        rec = list(cls)
+        rec[1] = P.RECOMPUTE
+        assert pl.evaluate(rec) - T_keep == t_re
+        out, _ = pl.step2(cls, T0)
+        assert out[1] == want, (t_re, out)
+        assert out[0] == out[2] == out[3] == P.KEEP
+
+
+def test_swapin_issue_points_with_and_without_scheduling():
+    """five layers, every map swapped, copies short enough never to queue behind each other.  Without scheduling
+    (section 5.1's first method) the return of the map a backward step needs starts together with the backward
+    computation before it; with scheduling (section 4.3) and room to spare every return is issued when backward begins,
+    so they run back to back on the host-to-device stream from the end of the forward pass."""
+    G = P.Graph(relu_chain(5))
+    nf = len(G.fmaps)
+    prof = _chain_profile(G, [4.0] * 5, [4.0] * 5, [4.0] * 5, [1.0] * 5, [1.0] * 5)
+    prof.t_out[-1] = prof.t_in[-1] = 0.5                     # the pooled vector
+    for ahead in (False, True):
+        S = P.build_schedule(G, [P.SWAP] * nf, BIG, ahead)
+        ivs, T, LO, LI = schedule_check.timeline(G, S.cmds, prof.t_fwd, prof.t_bwd, prof.t_refwd, prof.t_out, prof.t_in)
+        assert abs(T - P.simulate(G, S, prof)[0]) < 1e-12
+        bwd = {iv.cmd[1]: iv for iv in ivs if iv.cmd[0] == P.KB}
+        ins = {iv.cmd[1]: iv for iv in ivs if iv.cmd[0] == P.KI}
+        order = [iv.cmd[1] for iv in ivs if iv.cmd[0] == P.KB]              # loss, pool, layers 5 .. 1
+        assert order == [7, 6, 5, 4, 3, 2, 1]
+        if not ahead:
+            # map m (output of layer m) is read by layer m's backward; the step before that is layer m + 1's (for map 5
+            # the pool's, node 6, which reads nothing itself)
+            for m in (1, 2, 3, 4, 5):
+                assert ins[m].start == bwd[m + 1].start, (m, ins[m].start, bwd[m + 1].start)
+            # nothing is hidden at the turn: the pooled vector has to come back before the loss's backward can start
+            assert G.fmaps[-1] in LI
+        else:
+            fwd_end = max(iv.end for iv in ivs if iv.cmd[0] == P.KF)
+            last_out = max(iv.end for iv in ivs if iv.cmd[0] == P.KO)
+            t = max(fwd_end, last_out)
+            for m in (6, 5, 4, 3, 2, 1):                                    # in order of first backward use
+                assert abs(ins[m].start - t) < 1e-12, (m, ins[m].start, t)
+                t = ins[m].end
+    # moving the swap-ins up never makes the simulated step slower (section 5.1: + 2 - 14 % measured)
+    Ta = P.simulate(G, P.build_schedule(G, [P.SWAP] * nf, BIG, True), prof)[0]
+    Tn = P.simulate(G, P.build_schedule(G, [P.SWAP] * nf, BIG, False), prof)[0]
+    assert Ta <= Tn
+
+
 # ---- schedules are memory-safe whatever the timings ---------------------------------------------
 
 def small_nets():

@@ -181,6 +181,74 @@ def test_paper_eight_layer_example_through_the_library():
     assert c.plan_evaluations() <= 2 + (1 << n_li) * (1 + n_g)  # 2^|L_I| leaves x |L_O \ L_I| greedy
 
 
+def _relu_chain(n, shape=(4, 8, 16, 16)):
+    net = workloads.Net()
+    t = net.input(shape)
+    for _ in range(n):
+        t = net.relu(t)
+    net.softmax_ce(net.gavgpool(t))
+    return net
+
+
+def test_library_simulator_against_independent_timeline():
+    """the library's simulated step time and L_O / L_I (through the C ABI) against the timeline schedule_check builds
+    from the library's own command list by the definitions -- no oracle code between the two"""
+    rng = np.random.default_rng(77)
+    n = 0
+    for name, net in nets().items():
+        G = P.Graph(net, fuse=True)          # static facts only (sizes, which map a command names)
+        nf = len(G.fmaps)
+        probe, _ = lib_ctx(net, BIG)
+        _, peak = probe.simulate([B.KEEP] * nf, want_time=False)
+        for trial in range(25):
+            cls = [int(v) for v in rng.integers(0, 3, nf)] if trial % 3 else [B.SWAP] * nf
+            cap = int(peak * rng.uniform(0.4, 1.2)) // 256 * 256
+            prof = rand_profile(G, rng, link=float(rng.choice([0.2, 1.0, 4.0])))
+            c, _ = lib_ctx(net, cap)
+            c.set_profile(*prof)
+            for ahead in (True, False):
+                try:
+                    c.set_plan(cls, ahead)
+                except B.BudgetError:
+                    continue
+                rows = [tuple(int(v) for v in r) for r in c.commands()]
+                _, T, LO, LI = schedule_check.timeline(G, rows, *prof)
+                assert abs(c.simulate(cls, ahead)[0] - T) <= 1e-9 * max(T, 1.0)
+                if ahead and all(v == B.SWAP for v in cls):
+                    lo, li = c.overhead_sets()
+                    assert {G.fmaps[k] for k in range(nf) if lo[k]} == LO
+                    assert {G.fmaps[k] for k in range(nf) if li[k]} == LI
+                n += 1
+    assert n >= 40
+
+
+def test_hand_computed_timelines_through_the_library():
+    """the two timelines worked out by hand in tests/test_oracle_plan.py, through the C ABI: one swapped map feeding a
+    recomputation chain two deep (step times 27 / 29 / 30), and the two overheads of section 4.4.3's ratio in the exact tie"""
+    net = _relu_chain(4)
+    c, _ = lib_ctx(net, BIG)
+    assert [p for _, p in c.fmaps()] == [1, 2, 3, 4, 5]
+    cls = [B.SWAP, B.RECOMPUTE, B.RECOMPUTE, B.KEEP, B.KEEP]
+    for t_out, t_in, T_want in ((5.0, 4.0, 27.0), (5.0, 7.0, 29.0), (7.0, 7.0, 30.0)):
+        c.set_profile([0.0] + [2.0] * 4 + [1.0, 1.0], [0.0] + [3.0] * 4 + [1.0, 1.0], [0.0] + [1.5] * 4 + [1.0, 1.0],
+                      [t_out] * 4 + [0.0], [t_in] * 4 + [0.0])
+        assert c.simulate(cls)[0] == T_want
+    c.set_plan(cls)
+    rows = c.commands()
+    assert [(int(r[0]), int(r[1])) for r in rows if r[0] <= 4] == [
+        (0, 1), (0, 2), (3, 1), (0, 3), (0, 4), (0, 5), (0, 6), (4, 1), (2, 6), (2, 5), (2, 4), (1, 2), (1, 3), (2, 3), (2, 2), (2, 1)]
+    # the two overheads of the tie, exactly (what step 2 does with them is compared with the oracle's step 2, which
+    # has the tie test, by test_every_mode_picks_the_oracles_plan)
+    net = _relu_chain(3)
+    for t_re in (1.5, 1.5 - 2.0 ** -20, 1.5 + 2.0 ** -20):
+        c, _ = lib_ctx(net, BIG)
+        c.set_profile([0.0] + [1.0] * 3 + [1.0, 1.0], [0.0] + [2.0] * 3 + [1.0, 1.0], [0.0, 1.0, t_re, 1.0, 1.0, 1.0],
+                      [0.25] * 3 + [0.0], [5.5] * 3 + [0.0])
+        keep = c.simulate([B.KEEP] * 4)[0]
+        assert c.simulate([B.KEEP, B.SWAP, B.KEEP, B.KEEP])[0] - keep == 1.5
+        assert c.simulate([B.KEEP, B.RECOMPUTE, B.KEEP, B.KEEP])[0] - keep == t_re
+
+
 def test_random_graphs_command_lists_identical_and_valid():
     """random layer graphs (forks, joins, chains of layers whose outputs are no feature maps): the oracle's and
     the library's command lists agree and pass the validator, fused and not, under random plans.  Seeds 15 and 61
