@@ -914,12 +914,361 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restr
     if (g == 0 && e < n) dw[e] = ((sh[0][l] + sh[1][l]) + sh[2][l]) + sh[3][l];
 }
 
+// ------------------------------------------------------------------ filter gradient, few channels, several taps
+//
+// For 32 or 64 input and output channels under a 3-wide filter (ResNet-50's 3x3 64 -> 64, the first levels of a
+// 3-d CNN) the generic kernel above is bound by what it moves from L2 into LDS, not by the matrix cores: its B
+// operand is the im2col view of x, in which every input element appears once per filter tap, and with at most 64
+// output channels each staged float feeds at most 128 flops.  Here the taps share what is staged: a workgroup takes
+// a segment of P consecutive output pixels of one output row, brings the P x K slice of dy and, for each input row
+// (a, b) of its group, the P + 2 input pixels under that segment into LDS once, and its wavefronts -- three sets,
+// one per horizontal tap e -- read their B operand from the same LDS row shifted by e pixels.  The reduction index
+// of the MFMA is the pixel.  Loads go from global memory straight into LDS (global_load_lds, 16 bytes per lane, no
+// staging registers) into a ring of up to four buffers, two or three segments ahead of the one being multiplied
+// (one segment ahead left the matrix cores waiting 40 % of the time): one barrier per segment, and a counted wait
+// (vmcnt) that lets the younger segments' loads stay in flight.  Each workgroup walks a contiguous range of segments,
+// accumulating, and writes one partial K x (its taps) x C block; partials are summed in a fixed order by
+// reduce_splits_kernel (deterministic, no atomics).
+struct WHaloP {
+    const float *dy;   // [M][K]
+    const float *x;    // channels-last input
+    float *out;        // partials [nsplit][K][Kred]
+    int K, C, Kred;
+    int N, D, H, W, Do, Ho, Wo;
+    int kd, kh, pd, ph, pw;
+    int P, PW, PWpad, nseg_w;  // segment length (a multiple of 8), staged input pixels per row (P + 2), its padded LDS extent, segments per output row
+    int dy_blocks, row_blocks; // 1 KiB blocks (64 lanes x 16 bytes) of the dy slice and of one input row in LDS
+    int lpw;                   // load instructions per wavefront and segment (the same for every wavefront: idle slots load zeros)
+    int buf_floats, nbuf;      // LDS floats of one buffer (dy, rows, one block for the idle slots), buffers in the ring
+    int nseg;                  // N * Do * Ho * nseg_w
+    int seg_per_split, nsplit, groups, total, chunk;
+};
+
+typedef __attribute__((address_space(3))) void lds_void_ptr;
+typedef __attribute__((address_space(1))) const void glb_void_ptr;
+
+// s_waitcnt on the vector-memory counter alone: returns when at most n of this wavefront's loads are outstanding
+__device__ __forceinline__ void wait_vmcnt_at_most(int n)
+{
+    // immediate operand: vmcnt[3:0] | expcnt(7) << 4 | lgkmcnt(15) << 8 | vmcnt[5:4] << 14
+    switch (n) {
+#define POOCH_VMCNT(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14)); break;
+        POOCH_VMCNT(0) POOCH_VMCNT(1) POOCH_VMCNT(2) POOCH_VMCNT(3) POOCH_VMCNT(4) POOCH_VMCNT(5) POOCH_VMCNT(6) POOCH_VMCNT(7) POOCH_VMCNT(8)
+#undef POOCH_VMCNT
+    default: __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8)); break;   // vmcnt(0)
+    }
+}
+
+constexpr int WHALO_MAX_LPW = 4;
+
+// KB, CB: output / input channels in units of 32; GR: input rows per workgroup.  The GR x KB x CB blocks of 32 x 32
+// that belong to one horizontal tap are dealt to GR/GW x KB/IW x CB/JW wavefronts, GW x IW x JW blocks each.
+template <int KB, int CB, int GR, int GW, int IW, int JW>
+__global__ __launch_bounds__(192 * (GR / GW) * (KB / IW) * (CB / JW)) void wgrad_halo_kernel(WHaloP p)
+{
+    constexpr int WPT = (GR / GW) * (KB / IW) * (CB / JW), NWV = 3 * WPT;
+    constexpr int K = 32 * KB, C = 32 * CB, QK = K / 4, QC = C / 4;
+    extern __shared__ __attribute__((aligned(16))) float halo_lds[];
+
+    const int tid = threadIdx.x;
+    const int logical = remap_tile(blockIdx.x, p.chunk);
+    if (logical >= p.total) return;
+    const int split = logical / p.groups, group = logical % p.groups;
+    const int lane = tid % 64, wave = __builtin_amdgcn_readfirstlane(tid / 64);   // (uniform: what depends on it stays in scalar registers)
+    const int e = wave / WPT, sub = wave % WPT;    // horizontal tap, and which of its blocks
+    const int sj = sub % (CB / JW), si = (sub / (CB / JW)) % (KB / IW), sg = sub / ((CB / JW) * (KB / IW));
+    const int g0 = sg * GW, i0 = si * IW, j0 = sj * JW;
+    const int r = lane % 32, h = lane / 32;
+
+    // a wavefront with a single block alternates between two accumulators (even / odd steps, summed at the end), so
+    // that consecutive MFMAs do not depend on each other
+    constexpr int SETS = GW * IW * JW == 1 ? 2 : 1;
+    f32x16 acc[SETS][GW][IW][JW];
+#pragma unroll
+    for (int q = 0; q < SETS; ++q)
+#pragma unroll
+        for (int g = 0; g < GW; ++g)
+#pragma unroll
+            for (int i = 0; i < IW; ++i)
+#pragma unroll
+                for (int j = 0; j < JW; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[q][g][i][j][v] = 0.f;
+
+    // This wavefront's load slots: slot k brings block wave + k * NWV of the segment's dy-then-rows sequence of 1 KiB
+    // blocks; a slot past the sequence's end loads zeros into the spare block at the end of the buffer, so that every
+    // wavefront issues exactly lpw loads per segment and the counted wait below is the same immediate for all.
+    // Everything about a slot that does not depend on the segment is worked out here, once: which tensor, where in the
+    // buffer, which pixel and channel group this lane brings, which input row (relative to the output row).
+    const int x_floats = p.dy_blocks * 256;        // where the input rows start inside a buffer
+    int slot_kind[WHALO_MAX_LPW], slot_dst[WHALO_MAX_LPW], slot_da[WHALO_MAX_LPW], slot_db[WHALO_MAX_LPW];   // kind: 0 dy, 1 input row, 2 idle
+    int lane_pix[WHALO_MAX_LPW], lane_off[WHALO_MAX_LPW];   // pixel within the segment (dy) or the staged row (x); float offset of the channel group
+#pragma unroll
+    for (int k = 0; k < WHALO_MAX_LPW; ++k) {
+        const int bk = wave + k * NWV;
+        slot_kind[k] = 2;
+        slot_dst[k] = x_floats + GR * p.PWpad * C;     // the spare block
+        slot_da[k] = slot_db[k] = 0;
+        lane_pix[k] = lane_off[k] = 0;
+        if (bk < p.dy_blocks) {
+            const int u = bk * 64 + lane;
+            const int pix = u / QK, cpos = u % QK;
+            slot_kind[k] = 0;
+            slot_dst[k] = bk * 256;
+            lane_pix[k] = pix;
+            lane_off[k] = 4 * (K == 64 ? cpos ^ ((pix & 1) << 3) : cpos);
+        } else if ((bk - p.dy_blocks) / p.row_blocks < GR) {
+            const int row = (bk - p.dy_blocks) / p.row_blocks, blk = (bk - p.dy_blocks) % p.row_blocks;
+            const int grow = group * GR + row;          // input row (a, b) of this group
+            const int u = blk * 64 + lane;
+            const int q = u / QC, cpos = u % QC;
+            slot_kind[k] = 1;
+            slot_dst[k] = x_floats + row * p.PWpad * C + blk * 256;
+            slot_da[k] = grow / p.kh - p.pd;
+            slot_db[k] = grow % p.kh - p.ph;
+            lane_pix[k] = q < p.PW ? q - p.pw : -(1 << 20);   // pieces of the row's padding: never inside the image
+            lane_off[k] = 4 * (C == 64 ? cpos ^ ((q & 1) << 3) : cpos);
+        }
+    }
+
+    const int seg_beg = split * p.seg_per_split;
+    const int seg_end = min(p.nseg, seg_beg + p.seg_per_split);
+    // coordinates of the segment whose loads are issued next; stepped with carries
+    int wseg = seg_beg % p.nseg_w;
+    int t0 = seg_beg / p.nseg_w;
+    int oh = t0 % p.Ho;
+    t0 /= p.Ho;
+    int od = t0 % p.Do;
+    int n = t0 / p.Do;
+
+    // Position c (16 bytes) of pixel q's row in LDS holds channel group c ^ swz(q): for 64-float rows the two halves swap
+    // on odd pixels, so that the two pixels a wavefront reads at once (lane halves h = 0, 1) sit in different banks.
+    // The swap is applied to the source address: a lane's LDS position is fixed by global_load_lds (base + 16 * lane).
+    auto issue = [&](int buf) {
+        float *const base_s = halo_lds + buf * p.buf_floats;
+        const int w0 = wseg * p.P;
+        const int pv = min(p.P, p.Wo - w0);        // pixels of the segment that exist
+        const int64_t m0 = (((int64_t)n * p.Do + od) * p.Ho + oh) * p.Wo + w0;
+#pragma unroll
+        for (int k = 0; k < WHALO_MAX_LPW; ++k) {
+            if (k < p.lpw) {
+                const float *src = g_zero4;
+                if (slot_kind[k] == 0) {
+                    if (lane_pix[k] < pv) src = p.dy + ((m0 + lane_pix[k]) * K + lane_off[k]);
+                } else if (slot_kind[k] == 1) {
+                    const int id = od + slot_da[k], ih = oh + slot_db[k], iw = w0 + lane_pix[k];
+                    const bool ok = ((unsigned)id < (unsigned)p.D) & ((unsigned)ih < (unsigned)p.H) & ((unsigned)iw < (unsigned)p.W);
+                    if (ok) src = p.x + (((((int64_t)n * p.D + id) * p.H + ih) * p.W + iw) * C + lane_off[k]);
+                }
+                __builtin_amdgcn_global_load_lds((glb_void_ptr *)src, (lds_void_ptr *)(base_s + slot_dst[k]), 16, 0, 0);
+            }
+        }
+        if (++wseg == p.nseg_w) {
+            wseg = 0;
+            if (++oh == p.Ho) {
+                oh = 0;
+                if (++od == p.Do) {
+                    od = 0;
+                    ++n;
+                }
+            }
+        }
+    };
+
+    const int ahead = p.nbuf - 1;                  // segments in flight beyond the one being multiplied
+    for (int k = 0; k < ahead; ++k)
+        if (seg_beg + k < seg_end) issue(k);
+    int buf = 0;
+    for (int sgm = seg_beg; sgm < seg_end; ++sgm) {
+        // loads are retired in order: segment sgm's have landed once only the younger segments' are outstanding
+        wait_vmcnt_at_most(min(ahead - 1, seg_end - 1 - sgm) * p.lpw);
+        // A bare barrier: everyone's loads of segment sgm have landed, and everyone has finished reading the previous
+        // buffer (its fragments were consumed by MFMAs already issued).  __syncthreads() would not do: its fence makes
+        // the compiler wait for every outstanding load, the younger segments' too, which is the latency the ring hides.
+        // The empty asm statements keep the compiler from moving LDS reads or loads across the barrier.
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // The next loads (into the buffer multiplied last) are issued from inside the step loop, at a step that depends
+        // on the wavefront: right after the barrier every wavefront would run that address arithmetic at the same time
+        // and the matrix cores would sit idle meanwhile; staggered, it runs under the other wavefronts' MFMAs.
+        const bool more = sgm + ahead < seg_end;
+        const int issue_buf = buf == 0 ? p.nbuf - 1 : buf - 1;
+        const float *const dy_s = halo_lds + buf * p.buf_floats;
+        const float *const x_s = dy_s + x_floats;
+        // MFMA step t multiplies pixels 2t and 2t + 1 (lane half h takes pixel 2t + h).  Steps go in pairs through two
+        // sets of fragment registers: while one pair is multiplied the other pair's fragments are read from LDS, one or
+        // two reads behind each MFMA (P is a multiple of 8, so the step count is a multiple of 4).
+        const int steps = p.P / 2;
+        const float *ap = dy_s + h * K + r;
+        const float *bp = x_s + (h + e) * C + r;
+        const int hs = K == 64 ? (h << 5) : 0, qs = C == 64 ? (((h + e) & 1) << 5) : 0;   // bank swap of this lane's pixels (their parity is fixed: they advance by two)
+        float afA[2][IW], bfA[2][GW][JW], afB[2][IW], bfB[2][GW][JW];
+        auto load_pair = [&](float (&af)[2][IW], float (&bf)[2][GW][JW], int t) {
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+#pragma unroll
+                for (int i = 0; i < IW; ++i) af[d][i] = ap[2 * (t + d) * K + (((i0 + i) * 32) ^ hs)];
+#pragma unroll
+                for (int g = 0; g < GW; ++g)
+#pragma unroll
+                    for (int j = 0; j < JW; ++j) bf[d][g][j] = bp[((g0 + g) * p.PWpad + 2 * (t + d)) * C + (((j0 + j) * 32) ^ qs)];
+            }
+        };
+        auto mul_pair = [&](const float (&af)[2][IW], const float (&bf)[2][GW][JW]) {
+#pragma unroll
+            for (int d = 0; d < 2; ++d)
+#pragma unroll
+                for (int g = 0; g < GW; ++g)
+#pragma unroll
+                    for (int i = 0; i < IW; ++i)
+#pragma unroll
+                        for (int j = 0; j < JW; ++j)
+                            acc[d % SETS][g][i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[d][i], bf[d][g][j], acc[d % SETS][g][i][j], 0, 0, 0);
+        };
+        constexpr int NM = 2 * GW * IW * JW, NR = 2 * (IW + GW * JW), RPM = (NR + NM - 1) / NM;
+        load_pair(afA, bfA, 0);
+        const int issue_at = min(4 * ((wave / 4) % 3), steps - 4);
+        for (int t = 0; t < steps; t += 4) {
+            if (more && t == issue_at) issue(issue_buf);
+            load_pair(afB, bfB, t + 2);
+            mul_pair(afA, bfA);
+#pragma unroll
+            for (int q = 0; q < NM; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);   // LDS reads
+            }
+            load_pair(afA, bfA, min(t + 4, steps - 2));                // past the end: a pair that exists, unused
+            mul_pair(afB, bfB);
+#pragma unroll
+            for (int q = 0; q < NM; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+            }
+        }
+        buf = buf + 1 == p.nbuf ? 0 : buf + 1;
+    }
+    wait_vmcnt_at_most(0);
+
+    float *out = p.out + (int64_t)split * p.K * p.Kred;
+#pragma unroll
+    for (int g = 0; g < GW; ++g) {
+        const int tap = (group * GR + g0 + g) * 3 + e;
+#pragma unroll
+        for (int i = 0; i < IW; ++i)
+#pragma unroll
+            for (int j = 0; j < JW; ++j) {
+                const int col = tap * C + (j0 + j) * 32 + r;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = (i0 + i) * 32 + (v / 4) * 8 + h * 4 + (v % 4);
+                    out[(int64_t)k * p.Kred + col] = SETS == 2 ? acc[0][g][i][j][v] + acc[SETS - 1][g][i][j][v] : acc[0][g][i][j][v];
+                }
+            }
+    }
+}
+
+struct WHaloCfg {
+    bool use;
+    int gr, waves, P, PWpad, nseg_w, nseg, nsplit, seg_per_split, groups;
+    int dy_blocks, row_blocks, lpw, buf_floats, nbuf;
+    size_t lds_bytes;
+};
+
+constexpr size_t WGRAD_WS_CAP = (size_t)64 << 20;
+
+// whether the halo kernel serves this geometry, and how: unit strides, a 3-wide filter, 32 or 64 channels on
+// both sides.  Rows per group: the three rows of one depth tap when a horizontal tap's accumulators fit 96 registers
+// (32 -> 32, 32 -> 64, 64 -> 32 channels), else one.  Wavefronts: one per 32 x 32 block and horizontal tap, or per pair
+// of blocks where 32 channels face 64 -- twelve for 64 -> 64 (one workgroup per compute unit, up to 150 KB of LDS),
+// nine for the three-row groups (two per compute unit, 76 KB each), three otherwise (four per compute unit, 38 KB each).
+// Segments: output rows cut into equal pieces of at most 64 pixels (a multiple of 8), as long as two buffers allow;
+// then up to four buffers.
+WHaloCfg whalo_cfg(const ConvGeom &g)
+{
+    WHaloCfg c{};
+    static const bool off = getenv("POOCH_NO_HALO_WGRAD") != nullptr;
+    if (off || g.sd != 1 || g.sh != 1 || g.sw != 1 || g.kw != 3) return c;
+    // 32 -> 32 and 64 -> 64 channels.  (Measured on the 3-d CNN's 32 -> 64 layer at 96^3: 71 TFLOP/s here against 80 with the
+    // generic kernel, whose tiles suit the mixed widths better; the kernel template covers them, the dispatch does not.)
+    if ((g.C != 32 && g.C != 64) || g.K != g.C) return c;
+    const int kb = g.K / 32, cb = g.C / 32;
+    c.gr = (g.kh == 3 && kb * cb * 3 * 16 <= 96) ? 3 : 1;
+    c.waves = c.gr == 3 ? 9 : (kb * cb == 4 ? 12 : 3);
+    const size_t budget = (c.waves == 12 ? 150 : (c.waves == 9 ? 76 : 38)) * 1024;
+    const int qc = g.C / 4;
+    auto shape = [&](int P) {
+        const int pw_units = ((P + 2) * qc + 63) / 64 * 64;      // a row's 16-byte pieces, in whole 64-lane blocks
+        c.PWpad = pw_units / qc;
+        c.row_blocks = pw_units / 64;
+        c.dy_blocks = (P * g.K + 255) / 256;
+        c.buf_floats = (c.dy_blocks + c.gr * c.row_blocks + 1) * 256;
+        return (size_t)c.buf_floats * sizeof(float);
+    };
+    // the longest segment two buffers allow (each segment costs a barrier and a round of address arithmetic); then as
+    // many buffers, up to four, as still fit
+    int P = 0;
+    for (int q = 64; q >= 8 && P == 0; q -= 8)
+        if (2 * shape(q) <= budget) P = q;
+    if (P == 0) return c;
+    c.nseg_w = (g.Wo + P - 1) / P;
+    c.P = ((g.Wo + c.nseg_w - 1) / c.nseg_w + 7) & ~7;           // pixels past the row's end carry a zero dy
+    c.nbuf = (int)(budget / shape(c.P));
+    c.nbuf = c.nbuf > 4 ? 4 : c.nbuf;
+    c.lds_bytes = c.nbuf * shape(c.P);
+    c.lpw = (c.dy_blocks + c.gr * c.row_blocks + c.waves - 1) / c.waves;
+    if (c.lpw > WHALO_MAX_LPW || (c.nbuf - 2) * c.lpw > 8) return c;   // (the counted wait knows 0 .. 8)
+    const int64_t nseg = (int64_t)g.N * g.Do * g.Ho * c.nseg_w;
+    if (nseg >= ((int64_t)1 << 30)) return c;
+    c.nseg = (int)nseg;
+    c.groups = g.kd * g.kh / c.gr;
+    // workgroups: about six per compute unit's worth of resident ones, within the workspace
+    int64_t ns = (c.waves == 12 ? 1536 : (c.waves == 9 ? 3072 : 6144)) / c.groups;
+    const int64_t by_ws = (int64_t)(WGRAD_WS_CAP / ((size_t)g.K * g.taps() * g.C * sizeof(float)));
+    if (ns > by_ws) ns = by_ws;
+    if (ns > nseg) ns = nseg;
+    if (ns < 1) ns = 1;
+    c.seg_per_split = (int)((nseg + ns - 1) / ns);
+    c.nsplit = (int)((nseg + c.seg_per_split - 1) / c.seg_per_split);
+    // A workgroup's partial block is written once per workgroup: with few segments each, that and the reduction
+    // outweigh the gain (ResNet-50's 3x3 64 -> 64 at batch 64: 72 TFLOP/s here against 80 generic; at batch 640, 92 against 80).
+    // Problems too small to matter either way stay here, so that small test shapes reach this kernel.
+    if (c.seg_per_split < 24 && nseg > 2048) return WHaloCfg{};
+    c.use = true;
+    return c;
+}
+
+template <int KB, int CB, int GR, int GW, int IW, int JW>
+hipError_t launch_whalo(WHaloP p, const WHaloCfg &c, hipStream_t s)
+{
+    constexpr int NWV = 3 * (GR / GW) * (KB / IW) * (CB / JW);
+    if (c.waves != NWV) return hipErrorInvalidValue;
+    p.total = p.nsplit * p.groups;
+    p.chunk = (p.total + NXCD - 1) / NXCD;
+    if (c.lds_bytes > 64 * 1024) {   // more dynamic LDS than the default limit: raised once per kernel (no allocation)
+        static bool raised = false;
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_halo_kernel<KB, CB, GR, GW, IW, JW>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    wgrad_halo_kernel<KB, CB, GR, GW, IW, JW><<<dim3(p.chunk * NXCD), dim3(64 * NWV), c.lds_bytes, s>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t dispatch_whalo(const WHaloP &hp, const WHaloCfg &hc, hipStream_t s)
+{
+    if (hp.K != hp.C) return hipErrorInvalidValue;
+    if (hp.K == 32) return hc.gr == 3 ? launch_whalo<1, 1, 3, 1, 1, 1>(hp, hc, s) : launch_whalo<1, 1, 1, 1, 1, 1>(hp, hc, s);
+    return hc.gr == 1 ? launch_whalo<2, 2, 1, 1, 1, 1>(hp, hc, s) : hipErrorInvalidValue;
+}
+
 struct WGradCfg {
     int bm, bn, nsplit, chunk_rows;
     int big;   // 0: the bm x bn tile with four waves; 1: 256 x 128 with eight; 2: 128 x 256 with eight
 };
-
-constexpr size_t WGRAD_WS_CAP = (size_t)64 << 20;
 
 WGradCfg wgrad_cfg(const ConvGeom &g)
 {
@@ -1099,6 +1448,12 @@ const char *conv_dgrad_kernel(const ConvGeom &g)
 
 const char *conv_wgrad_kernel(const ConvGeom &g)
 {
+    if (geom_ok(g)) {
+        const WHaloCfg hc = whalo_cfg(g);
+        if (hc.use) {
+            return g.K == 32 ? (hc.gr == 3 ? "wgrad_halo_kernel<1,1,3>" : "wgrad_halo_kernel<1,1,1>") : "wgrad_halo_kernel<2,2,1>";
+        }
+    }
     const WGradCfg c = wgrad_cfg(g);
     if (c.bn == 64) return c.bm == 32 ? "wgrad_kernel<1,2,1,1>" : (c.bm == 64 ? "wgrad_kernel<2,2,1,1>" : "wgrad_kernel<2,2,2,1>");
     if (c.big) return c.big == 1 ? "wgrad_kernel<4,2,2,2>" : "wgrad_kernel<2,4,2,2>";
@@ -1108,6 +1463,8 @@ const char *conv_wgrad_kernel(const ConvGeom &g)
 size_t conv_wgrad_workspace(const ConvGeom &g)
 {
     if (!geom_ok(g)) return 0;
+    const WHaloCfg hc = whalo_cfg(g);
+    if (hc.use) return (size_t)hc.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WGradCfg c = wgrad_cfg(g);
     return c.nsplit > 1 ? (size_t)c.nsplit * g.K * g.taps() * g.C * sizeof(float) : 0;
 }
@@ -1115,6 +1472,24 @@ size_t conv_wgrad_workspace(const ConvGeom &g)
 hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *workspace, const ConvGeom &g, hipStream_t s)
 {
     if (!dy || !x || !dw_krsc || !geom_ok(g)) return hipErrorInvalidValue;
+    const WHaloCfg hc = whalo_cfg(g);
+    if (hc.use) {
+        // (the workspace is sized for this path: no falling back to the generic kernel's split count)
+        if (!workspace || (uintptr_t)dy % 16 != 0 || (uintptr_t)x % 16 != 0 || (uintptr_t)workspace % 16 != 0) return hipErrorInvalidValue;
+        WHaloP hp;
+        hp.dy = dy; hp.x = x; hp.out = workspace;
+        hp.K = g.K; hp.C = g.C; hp.Kred = (int)(g.taps() * g.C);
+        hp.N = g.N; hp.D = g.D; hp.H = g.H; hp.W = g.W; hp.Do = g.Do; hp.Ho = g.Ho; hp.Wo = g.Wo;
+        hp.kd = g.kd; hp.kh = g.kh; hp.pd = g.pd; hp.ph = g.ph; hp.pw = g.pw;
+        hp.P = hc.P; hp.PW = hc.P + 2; hp.PWpad = hc.PWpad; hp.nseg_w = hc.nseg_w; hp.nseg = hc.nseg;
+        hp.dy_blocks = hc.dy_blocks; hp.row_blocks = hc.row_blocks; hp.lpw = hc.lpw; hp.buf_floats = hc.buf_floats; hp.nbuf = hc.nbuf;
+        hp.seg_per_split = hc.seg_per_split; hp.nsplit = hc.nsplit; hp.groups = hc.groups;
+        const hipError_t he = dispatch_whalo(hp, hc, s);
+        if (he != hipSuccess) return he;
+        const int64_t nel = (int64_t)g.K * hp.Kred;
+        reduce_splits_kernel<<<dim3((unsigned)((nel + 63) / 64)), dim3(256), 0, s>>>(workspace, dw_krsc, nel, hc.nsplit);
+        return hipGetLastError();
+    }
     const WGradCfg c = wgrad_cfg(g);
     if (c.nsplit > 1 && !workspace) return hipErrorInvalidValue;
     WGradP p;

@@ -756,3 +756,23 @@ def kinkless_probe(x_shape, cout, k, stride, pad, with_bn):
 def test_conv_bn_shapes_full_size_without_kinks(x_shape, cout, k, stride, pad):
     net = kinkless_probe(x_shape, cout, k, stride, pad, True)
     check_against_oracle("probe %s -> %d k%s s%s" % (x_shape, cout, k, stride), net, 123, capture=False)
+
+
+@pytest.mark.parametrize("x_shape,cout,k,pad", [
+    ((2, 64, 13, 13), 64, (3, 3), (1, 1)),            # one row group per workgroup, odd width (one padded pixel pair)
+    ((3, 32, 9, 70), 32, (3, 3), (1, 1)),             # three rows per group; 70 pixels = two segments of 36, the second ragged
+    ((2, 32, 7, 20), 32, (1, 3), (0, 1)),             # a single filter row
+    ((2, 64, 10, 11), 64, (3, 3), (0, 0)),            # no padding, output narrower than the input
+    ((2, 32, 8, 8), 32, (3, 3), (2, 2)),              # padding wider than one pixel
+    ((2, 32, 6, 7, 9), 32, (3, 3, 3), (1, 1, 1)),     # 3-d, three rows per group, nine row groups in all
+    ((2, 32, 5, 6, 66), 32, (3, 3, 3), (1, 1, 1)),    # 3-d, two segments per row, the second ragged
+    ((2, 64, 4, 5, 6), 64, (3, 3, 3), (1, 0, 1)),     # 3-d 64 -> 64: one row per group, nine groups
+    ((2, 64, 150, 6), 64, (3, 3), (1, 1)),            # more segments than workgroups want: several per split
+])
+def test_filter_gradient_with_shared_taps(x_shape, cout, k, pad):
+    """the filter-gradient kernel for 32 / 64 channels under a 3-wide filter (input rows staged once in LDS and
+    shared by the horizontal taps): ragged segment tails, all padding cases, 2-d and 3-d, against the oracle"""
+    net = kinkless_probe(x_shape, cout, k, (1,) * len(k), pad, True)
+    c = B.Context(net, 1 << 30, device=None)
+    assert c.node_kernel(1, 2).startswith("wgrad_halo_kernel"), c.node_kernel(1, 2)
+    check_against_oracle("shared-tap filter gradient %s -> %d k%s p%s" % (x_shape, cout, k, pad), net, 321, capture=False)
