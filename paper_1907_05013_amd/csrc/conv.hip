@@ -47,6 +47,9 @@ struct IGemmP {
     int Ds, Hs, Ws;  // spatial dims of src
     int kd, kh, kw, sd, sh, sw, pd, ph, pw;
     int tiles_n, total_tiles, chunk;
+    // split over the reduction: ksplit > 1 gives workgroup (tile, ks) the slices [ks * kslices, (ks + 1) * kslices) and sends its
+    // result to dst + ks * M * Nout (a stack of partial results that splitk_reduce_kernel sums in a fixed order)
+    int ksplit, kslices;
     // destination rows: identity, or (dst_strided) GEMM row (n,d,h,w) -> row ((n*DD + d*SD)*HD + h*SH)*WD + w*SW
     int dst_strided, DD, HD, WD, SD, SH, SW;
 };
@@ -97,9 +100,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     __shared__ int rowdst[BM];
 
     const int tid = threadIdx.x;
-    const int logical = remap_tile(blockIdx.x, p.chunk);
-    if (logical >= p.total_tiles) return;
+    const int logical_wg = remap_tile(blockIdx.x, p.chunk);
+    if (logical_wg >= p.total_tiles * p.ksplit) return;
+    const int ks = logical_wg / p.total_tiles, logical = logical_wg % p.total_tiles;
     const int m0 = (logical / p.tiles_n) * BM, n0 = (logical % p.tiles_n) * BN;
+    float *const dst = p.dst + (int64_t)ks * p.M * p.Nout;
 
     for (int r = tid; r < BM; r += NT) {
         const int m = m0 + r;
@@ -149,6 +154,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     bool brow[LIN ? B_V : 1];
     int ta = 0, tb = 0, te = 0, tc = 0;              // tap (a, b, e) and channel offset of the slice start
     int pk = vk;                                     // LIN == 2: this thread's position in the reduction
+    const int nk_all = (p.Kred + BKT - 1) / BKT;
+    const int it_beg = ks * p.kslices, it_end = p.ksplit > 1 ? min(nk_all, it_beg + p.kslices) : nk_all;
+    if (LIN == 1 && it_beg > 0) {                    // a later part of the reduction: its first slice's tap
+        const int kfirst = it_beg * BKT;
+        const int tap = kfirst / p.Cs;
+        tc = kfirst - tap * p.Cs;
+        te = tap % p.kw;
+        tb = (tap / p.kw) % p.kh;
+        ta = tap / (p.kw * p.kh);
+    }
     if (LIN == 2) {
         const int tap = vk / p.Cs;
         te = tap % p.kw;
@@ -165,7 +180,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
         for (int i = 0; i < B_V; ++i) {
             const int n = n0 + vrow + i * RPP;
             brow[i] = (vrow + i * RPP < BN) & (n < p.Nout);
-            bptr[i] = p.wgt + (brow[i] ? (int64_t)n * p.Kred + vk : 0);
+            bptr[i] = p.wgt + (brow[i] ? (int64_t)n * p.Kred + vk + (LIN == 1 ? it_beg * BKT : 0) : 0);
         }
     }
     auto load_tiles_tap = [&](bool live) {
@@ -332,11 +347,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     const int wm = wave / WGN, wn = wave % WGN;
     const int r = lane % 32, h = lane / 32;
 
-    const int nk = (p.Kred + BKT - 1) / BKT;
+    const int nk = it_end;
     if (LIN == 2) load_tiles_tap(true);
-    else if (LIN) load_tiles_lin(true);
-    else load_tiles(0);
-    for (int it = 0; it < nk; ++it) {
+    else if (LIN) load_tiles_lin(it_beg < nk);
+    else load_tiles(it_beg * BKT);
+    for (int it = it_beg; it < nk; ++it) {
         store_tiles();
         __syncthreads();
         if (LIN == 2) load_tiles_tap(it + 1 < nk);
@@ -426,7 +441,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
                     okq[q] = m >= 0;
                 }
                 if (m >= 0 && ncol < p.Nout) {
-                    f32x4 *dp = reinterpret_cast<f32x4 *>(p.dst + (int64_t)m * p.Nout + ncol);
+                    f32x4 *dp = reinterpret_cast<f32x4 *>(dst + (int64_t)m * p.Nout + ncol);
                     if (ACCUM) val = __builtin_nontemporal_load(dp) + val;
                     __builtin_nontemporal_store(val, dp);
                 }
@@ -503,7 +518,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     for (int i = 0; i < TM; ++i) {
         const int m = rowdst[wm * TM * 32 + i * 32 + r];
         if (m < 0) continue;
-        float *drow = p.dst + (int64_t)m * p.Nout;
+        float *drow = dst + (int64_t)m * p.Nout;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int cbase = n0 + wn * TN * 32 + j * 32 + 4 * h;
@@ -529,7 +544,8 @@ hipError_t launch_igemm(IGemmP p, bool vec, int lin, bool accum, hipStream_t s, 
     const int tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.Nout + BN - 1) / BN;
     p.total_tiles = tiles_m * p.tiles_n;
-    p.chunk = (p.total_tiles + NXCD - 1) / NXCD;
+    if (p.ksplit < 1) p.ksplit = 1;
+    p.chunk = (p.total_tiles * p.ksplit + NXCD - 1) / NXCD;
     const dim3 grid(p.chunk * NXCD), block(64 * WGM * WGN);
     if (stats_tiles) {   // layout query of the statistics a STATS launch writes: row tiles, rows per tile
         stats_tiles[0] = tiles_m;
@@ -576,11 +592,77 @@ int igemm_linear_mode(int cs, bool dgrad, bool unit_stride, bool accum)
     return 0;
 }
 
-template <bool DGRAD>
-hipError_t dispatch_igemm(const IGemmP &p, bool accum, hipStream_t s, int *stats_tiles = nullptr)
+// Few tiles, long reduction (ResNet-50's last stages at batch 64, the deep levels of a 3-d CNN on one volume): 128 x 128
+// tiles leave compute units idle and quarter-size tiles halve the flops per staged byte.  Such a GEMM keeps the 128 x 128
+// tile and splits its reduction over ksplit workgroups per tile instead; each writes its partial result to a workspace
+// and splitk_reduce_kernel adds the parts in a fixed order (deterministic, no atomics).  The convolution then leaves no
+// batch-normalisation statistics (its tiles never see the finished values); these outputs are small, and the
+// normalisation's own statistics pass over them costs microseconds.
+constexpr size_t IGEMM_WS_CAP = (size_t)64 << 20;
+
+struct SplitK {
+    int ksplit, kslices;
+};
+
+SplitK igemm_splitk(int M, int Nout, int Kred, int lin, bool dst_strided)
 {
+    static const bool off = getenv("POOCH_NO_SPLITK") != nullptr;
+    SplitK k{1, 0};
+    if (off || lin != 1 || dst_strided || Nout <= 64 || Nout % 4 != 0) return k;
+    const int64_t tiles = ((int64_t)(M + 127) / 128) * ((Nout + 127) / 128);
+    const int nk = (Kred + BK - 1) / BK;
+    // (a reduction of 1024: 76 TFLOP/s split against 81 with quarter-size tiles; 2048: 78 against 70; 2304 and more: 89 - 106 against 60 - 92)
+    if (tiles >= 384 || nk < 96) return k;
+    int64_t want = (768 + tiles - 1) / tiles;                   // about three workgroups per compute unit
+    if (want > 8) want = 8;
+    if (want > nk / 16) want = nk / 16;                         // at least 16 slices (256 reduction steps) per part
+    const int64_t by_ws = (int64_t)(IGEMM_WS_CAP / ((size_t)M * Nout * sizeof(float)));
+    if (want > by_ws) want = by_ws;
+    if (want < 2) return k;
+    k.kslices = (int)((nk + want - 1) / want);
+    k.ksplit = (nk + k.kslices - 1) / k.kslices;
+    if (k.ksplit < 2) k = SplitK{1, 0};
+    return k;
+}
+
+// dst[i] (+)= ((part[0][i] + part[1][i]) + part[2][i]) + ...: one float4 per thread
+template <bool ACCUM>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, float *__restrict__ dst, int64_t n4, int ksplit)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    const f32x4 *pp = reinterpret_cast<const f32x4 *>(part);
+    f32x4 v = __builtin_nontemporal_load(pp + i);
+    for (int k = 1; k < ksplit; ++k) v += __builtin_nontemporal_load(pp + (int64_t)k * n4 + i);
+    f32x4 *dp = reinterpret_cast<f32x4 *>(dst) + i;
+    if (ACCUM) v = *dp + v;
+    __builtin_nontemporal_store(v, dp);
+}
+
+template <bool DGRAD>
+hipError_t dispatch_igemm(const IGemmP &p0, bool accum, hipStream_t s, int *stats_tiles = nullptr, float *workspace = nullptr)
+{
+    IGemmP p = p0;
+    p.ksplit = 1;
+    p.kslices = 0;
     const bool vec = (p.Cs % 4 == 0) && ((uintptr_t)p.src % 16 == 0) && ((uintptr_t)p.wgt % 16 == 0);
     const int lin = vec ? igemm_linear_mode(p.Cs, DGRAD, p.sd == 1 && p.sh == 1 && p.sw == 1, accum) : 0;
+    const SplitK sk = igemm_splitk(p.M, p.Nout, p.Kred, lin, p.dst_strided != 0);
+    if (sk.ksplit > 1) {
+        if (stats_tiles || p.stats) return hipErrorInvalidValue;      // no statistics from a split reduction
+        if (!workspace || (uintptr_t)workspace % 16 != 0 || (uintptr_t)p.dst % 16 != 0) return hipErrorInvalidValue;
+        float *const final_dst = p.dst;
+        p.dst = workspace;
+        p.ksplit = sk.ksplit;
+        p.kslices = sk.kslices;
+        const hipError_t e = launch_igemm<2, 2, 2, 2, BK, DGRAD>(p, vec, lin, false, s, nullptr);
+        if (e != hipSuccess) return e;
+        const int64_t n4 = (int64_t)p.M * p.Nout / 4;
+        const dim3 grid((unsigned)((n4 + 255) / 256));
+        if (accum) splitk_reduce_kernel<true><<<grid, dim3(256), 0, s>>>(workspace, final_dst, n4, sk.ksplit);
+        else splitk_reduce_kernel<false><<<grid, dim3(256), 0, s>>>(workspace, final_dst, n4, sk.ksplit);
+        return hipGetLastError();
+    }
     // too few 128x128 tiles to fill 256 compute units three workgroups deep: quarter-size tiles
     if (p.Nout > 64 && ((int64_t)(p.M + 127) / 128) * ((p.Nout + 127) / 128) < 640) return launch_igemm<2, 2, 1, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
     if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
@@ -1351,7 +1433,15 @@ bool conv_fwd_bn_tiles(const float *x, const float *w_krsc, const ConvGeom &g, i
     return true;
 }
 
-hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s, float *bn_tiles)
+size_t conv_fwd_workspace(const ConvGeom &g)
+{
+    if (!geom_ok(g)) return 0;
+    const int lin = g.C % 4 == 0 ? igemm_linear_mode(g.C, false, true, false) : 0;
+    const SplitK sk = igemm_splitk((int)g.rows_out(), g.K, (int)(g.taps() * g.C), lin, false);
+    return sk.ksplit > 1 ? (size_t)sk.ksplit * g.rows_out() * g.K * sizeof(float) : 0;
+}
+
+hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s, float *bn_tiles, float *workspace)
 {
     if (!x || !w_krsc || !y || !geom_ok(g)) return hipErrorInvalidValue;
     IGemmP p = fwd_params(x, w_krsc, y, g);
@@ -1360,7 +1450,7 @@ hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeo
         if ((uintptr_t)bn_tiles % 16 != 0 || !conv_fwd_bn_tiles(x, w_krsc, g, &tm, &rows)) return hipErrorInvalidValue;
         p.stats = bn_tiles;
     }
-    return dispatch_igemm<false>(p, false, s);
+    return dispatch_igemm<false>(p, false, s, nullptr, workspace);
 }
 
 // a strided 1x1 filter without padding touches only every (sd,sh,sw)-th input position: its
@@ -1371,7 +1461,15 @@ bool pointwise_strided(const ConvGeom &g)
     return g.taps() == 1 && g.pd == 0 && g.ph == 0 && g.pw == 0 && (g.sd > 1 || g.sh > 1 || g.sw > 1);
 }
 
-hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g, bool accumulate, hipStream_t s)
+size_t conv_dgrad_workspace(const ConvGeom &g)
+{
+    if (!geom_ok(g) || pointwise_strided(g)) return 0;
+    const int lin = g.K % 4 == 0 ? igemm_linear_mode(g.K, true, g.sd == 1 && g.sh == 1 && g.sw == 1, false) : 0;
+    const SplitK sk = igemm_splitk((int)g.rows_in(), g.C, (int)(g.taps() * g.K), lin, false);
+    return sk.ksplit > 1 ? (size_t)sk.ksplit * g.rows_in() * g.C * sizeof(float) : 0;
+}
+
+hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g, bool accumulate, hipStream_t s, float *workspace)
 {
     if (!dy || !w_crsk || !dx || !geom_ok(g)) return hipErrorInvalidValue;
     IGemmP p;
@@ -1394,13 +1492,15 @@ hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const Con
     p.Dr = g.D; p.Hr = g.H; p.Wr = g.W; p.Ds = g.Do; p.Hs = g.Ho; p.Ws = g.Wo;
     p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
     p.dst_strided = 0; p.DD = p.HD = p.WD = p.SD = p.SH = p.SW = 0;
-    return dispatch_igemm<true>(p, accumulate, s);
+    return dispatch_igemm<true>(p, accumulate, s, nullptr, workspace);
 }
 
 namespace {
 // tag of the igemm instantiation dispatch_igemm() picks: tile shape, load path, direction
-const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgrad)
+const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgrad, int kred = 0)
 {
+    if (cs % 4 == 0 && igemm_splitk((int)rows, nout, kred, igemm_linear_mode(cs, dgrad, unit_stride, false), false).ksplit > 1)
+        return dgrad ? "igemm_kernel<2,2,2,2,vec+lin,dgrad,splitk>" : "igemm_kernel<2,2,2,2,vec+lin,fwd,splitk>";
     static const char *names[4][4][2] = {
         {{"igemm_kernel<4,1,2,1,scalar,fwd>", "igemm_kernel<4,1,2,1,scalar,dgrad>"},
          {"igemm_kernel<4,1,2,1,vec,fwd>", "igemm_kernel<4,1,2,1,vec,dgrad>"},
@@ -1428,7 +1528,7 @@ const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgr
 
 const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
 {
-    const char *plain = igemm_tag(g.rows_out(), g.K, g.C, true, false);
+    const char *plain = igemm_tag(g.rows_out(), g.K, g.C, true, false, (int)(g.taps() * g.C));
     if (!bn_tiles) return plain;
     // the variant that also leaves batch-normalisation statistics is a kernel of its own
     static std::map<std::string, std::string> names;
@@ -1443,7 +1543,7 @@ const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
 const char *conv_dgrad_kernel(const ConvGeom &g)
 {
     if (pointwise_strided(g)) return igemm_tag(g.rows_out(), g.C, g.K, true, false);   // scatter GEMM over the output rows
-    return igemm_tag(g.rows_in(), g.C, g.K, g.sd == 1 && g.sh == 1 && g.sw == 1, true);
+    return igemm_tag(g.rows_in(), g.C, g.K, g.sd == 1 && g.sh == 1 && g.sw == 1, true, (int)(g.taps() * g.K));
 }
 
 const char *conv_wgrad_kernel(const ConvGeom &g)

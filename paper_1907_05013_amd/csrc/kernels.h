@@ -26,12 +26,18 @@ struct ConvGeom {
 // consecutive output rows, the per-channel mean [K] and sum of squared deviations from it [K] of that
 // tile's rows of y -- the batch-normalisation statistics pass, taken while the results are still on chip.
 // Only where conv_fwd_bn_tiles() says so.
-hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s, float *bn_tiles = nullptr);
+// workspace: conv_fwd_workspace(g) bytes (16-byte aligned) when that is not zero -- a GEMM with few tiles and a long
+// reduction is split over the reduction into partial results there, summed in a fixed order; such a launch leaves no bn_tiles.
+hipError_t conv_fwd(const float *x, const float *w_krsc, float *y, const ConvGeom &g, hipStream_t s, float *bn_tiles = nullptr,
+                    float *workspace = nullptr);
+size_t conv_fwd_workspace(const ConvGeom &g);
 // whether conv_fwd can produce bn_tiles for these operands, and their layout: tile t covers output
 // rows [t * rows_per_tile, min(rows_out, (t + 1) * rows_per_tile))
 bool conv_fwd_bn_tiles(const float *x, const float *w_krsc, const ConvGeom &g, int *tiles_m, int *rows_per_tile);
 // dx[N,D,H,W,C] (+)= data gradient; w_crsk is the transposed filter copy
-hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g, bool accumulate, hipStream_t s);
+hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g, bool accumulate, hipStream_t s,
+                      float *workspace = nullptr);
+size_t conv_dgrad_workspace(const ConvGeom &g);   // bytes conv_dgrad needs at `workspace` (0: none)
 // bytes of split-K workspace conv_wgrad needs for this geometry (0 if none)
 size_t conv_wgrad_workspace(const ConvGeom &g);
 // dw_krsc[K,taps,C] = filter gradient, deterministic split-K through `workspace`

@@ -257,7 +257,7 @@ struct Exec {
         switch (nd.op) {
         case OP_CONV:
             return pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i, c->in_cdev), s,
-                                (!refwd && c->stats_to[i] >= 0) ? ws_bn : nullptr);
+                                (!refwd && c->stats_to[i] >= 0) ? ws_bn : nullptr, ws_wgrad);
         case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
             const bool relu = nd.op == OP_BNRELU;
@@ -301,7 +301,7 @@ struct Exec {
             return pk::gavgpool_fwd(D(in0), D(out), (int)x.N, x.sp[0] * x.sp[1] * x.sp[2], (int)x.C, s);
         }
         case OP_FC: {
-            hipError_t e = pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i, c->in_cdev), s);
+            hipError_t e = pk::conv_fwd(D(in0), R(P(i, 0).off_val), D(out), conv_geom(G, i, c->in_cdev), s, nullptr, ws_wgrad);
             if (e != hipSuccess) return e;
             return pk::bias_add(D(out), R(P(i, 1).off_val), (int)nd.N, (int)nd.C, s);
         }
@@ -344,7 +344,7 @@ struct Exec {
                 if (e != hipSuccess) return e;
             }
             if (m0 == M_NONE) return hipSuccess;
-            return pk::conv_dgrad(D(dy), R(P(i, 0).off_val_t), D(o0), g, m0 == M_ACC, s);
+            return pk::conv_dgrad(D(dy), R(P(i, 0).off_val_t), D(o0), g, m0 == M_ACC, s, ws_wgrad);
         }
         case OP_BN: case OP_BNRELU: {
             const int64_t M = nd.numel() / nd.C;
@@ -854,7 +854,9 @@ pooch_status pooch_finalize(pooch_ctx *c)
             ParamInfo p{i, 0, numel, dev_numel, take(dev_numel * 4), take(dev_numel * 4), take(dev_numel * 4)};
             nd.param[0] = (int)c->params.size();
             c->params.push_back(p);
-            ws_wgrad = std::max(ws_wgrad, pk::conv_wgrad_workspace(g));
+            // one workspace serves the filter gradient's split-K partials and the split reductions of small forward /
+            // data-gradient GEMMs: the launches that use it are serialised on the compute stream
+            ws_wgrad = std::max({ws_wgrad, pk::conv_wgrad_workspace(g), pk::conv_fwd_workspace(g), pk::conv_dgrad_workspace(g)});
             if (nd.op == OP_FC) {
                 ParamInfo b{i, 1, nd.C, nd.C, take(nd.C * 4), -1, take(nd.C * 4)};
                 nd.param[1] = (int)c->params.size();
