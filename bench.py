@@ -269,23 +269,37 @@ def main():
         link = ctx.measure_link(min(1 << 30, (arena_bytes - resident) // 2 // 256 * 256), 3)
         log("[bench] host link: D2H %.1f GB/s, H2D %.1f GB/s" % link)
         t0 = time.perf_counter()
-        prof = ctx.profile(warmup=1, iters=2)
+        prof = ctx.profile(warmup=1, iters=3)
         t1 = time.perf_counter()
         if args.dump_profile:
             np.savez(args.dump_profile, t_fwd=prof[0], t_bwd=prof[1], t_refwd=prof[2], t_out=prof[3], t_in=prof[4],
                      arena_bytes=arena_bytes, pinned_bytes=fm_bytes + 4096)
         if args.mode == "refine" and not args.no_paper_mode:
-            # the paper's own classification (section 4.4, two steps), timed the same way
-            tp = time.perf_counter()
-            _, pred_p = ctx.plan("pooch", args.bits)
-            tp = time.perf_counter() - tp
-            sec_p, _, _ = timed_steps(ctx, torch, args.steps, args.warmup)
-            stp = ctx.stats()
-            result_extra["paper_two_step_plan"] = {
-                "images_per_sec": batch / sec_p, "ms_per_step": sec_p * 1e3, "predicted_ms": pred_p, "plan_s": tp,
-                "keep": stp.n_keep, "swap": stp.n_swap, "recompute": stp.n_recompute, "swap_out_GB": stp.swap_out_bytes / 1e9}
-            log("[bench] paper's two-step plan: %.1f ms/step (predicted %.1f), keep/swap/recompute %d/%d/%d" %
-                (sec_p * 1e3, pred_p, stp.n_keep, stp.n_swap, stp.n_recompute))
+            # The paper's own classification (section 4.4, two steps), timed the same way.  The cap on the exponential
+            # part of step 1 is a reading of the paper, and the result is not monotone in it: the plan of each cap in
+            # {2, 4, 6, 8} is simulated and the fastest by simulation is the one installed and timed.  Done twice, the
+            # second time from a fresh profiling pass, to show the run-to-run range of the two-step plan.
+            runs = []
+            for attempt in range(2):
+                if attempt == 1:
+                    ctx.profile(warmup=0, iters=3)
+                tp = time.perf_counter()
+                best = None
+                for bits in (2, 4, 6, 8):
+                    cls_b, pred_b = ctx.plan("pooch", bits)
+                    if best is None or pred_b < best[1]:
+                        best = (bits, pred_b, cls_b)
+                ctx.set_plan(best[2], True)
+                tp = time.perf_counter() - tp
+                sec_p, _, loss_p = timed_steps(ctx, torch, args.steps, args.warmup)
+                stp = ctx.stats()
+                runs.append({"images_per_sec": batch / sec_p, "ms_per_step": sec_p * 1e3, "predicted_ms": best[1],
+                             "max_bits": best[0], "plan_s": tp, "keep": stp.n_keep, "swap": stp.n_swap,
+                             "recompute": stp.n_recompute, "swap_out_GB": stp.swap_out_bytes / 1e9, "loss": loss_p})
+                log("[bench] paper's two-step plan (%d): %.1f ms/step (predicted %.1f, cap %d bits), keep/swap/recompute %d/%d/%d" %
+                    (attempt + 1, sec_p * 1e3, best[1], best[0], stp.n_keep, stp.n_swap, stp.n_recompute))
+            result_extra["paper_two_step_plan"] = dict(runs[0], runs=runs,
+                                                       ms_per_step_range=[min(r["ms_per_step"] for r in runs), max(r["ms_per_step"] for r in runs)])
         if args.ablation:
             table = {}
             for m in ("swapall_nosched", "swapall", "swapopt", "pooch", "superneurons", "refine"):
@@ -344,7 +358,18 @@ def main():
         del ctx
         torch.cuda.empty_cache()
 
+    loss_matches = None
+    if under_budget and incore_sec is not None:
+        # swapping copies bits and recomputation re-executes the same kernels (sections 3.1, 3.2): the step under the
+        # budget must end in the very loss of the in-core step, bit for bit -- checked here for the plan that was timed
+        loss_matches = np.float32(loss).tobytes() == np.float32(loss_in).tobytes()
+        if not loss_matches:
+            sys.exit("bench.py: the loss under the budget (%r) differs from the in-core loss (%r)" % (loss, loss_in))
+        for r in result_extra.get("paper_two_step_plan", {}).get("runs", []):
+            if np.float32(r["loss"]).tobytes() != np.float32(loss_in).tobytes():
+                sys.exit("bench.py: the loss of the two-step plan (%r) differs from the in-core loss (%r)" % (r["loss"], loss_in))
     by_kernel, (cfl, cms), (bnb, bnms), (ewb, ewms) = rep
+    total_flops = sum(2.0 * M * N * K * (3 if net[i].get("x") != 0 else 2) for i, (M, N, K) in conv_geoms(net).items())
     dom = max(by_kernel.items(), key=lambda kv: kv[1][1])
     dom_tflops = dom[1][0] / (dom[1][1] * 1e-3)
     meas = MEASURED_TRAFFIC_KIB.get((args.workload, dom[0]))
@@ -359,17 +384,28 @@ def main():
         "ms_per_step": sec * 1e3,
         "higher_is_better": True,
         "scaling": "weak",
-        "vs_baseline": (batch / sec) / PAPER_B640_IMG_S if (args.workload == "resnet50_b640_16g" and batch == 640 and
-                                                              abs(arena_bytes - 16 * 2 ** 30) < 2 ** 20) else None,
+        # the paper's 195 images/s for this workload were measured on a V100 with PCIe 3 (section 5.2): other hardware,
+        # context only (`paper_context`), not a baseline to divide by
+        "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "batch": batch, "arena_GiB": arena_bytes / 2 ** 30,
                    "feature_maps_GB": fm_bytes / 1e9, "incore_arena_GB": incore_bytes / 1e9,
                    "under_budget": under_budget},
         "loss": loss,
+        "loss_matches_incore": loss_matches,
+        "value_plan": (("beyond the paper: its two steps plus a local search, layers re-timed under the plan (mode refine); "
+                        "the paper's own two-step plan is timed in paper_two_step_plan") if args.mode == "refine" else
+                       "the paper's method, mode %s" % args.mode) if under_budget else "in-core",
+        "paper_context": {"images_per_sec": PAPER_B640_IMG_S, "hardware": "V100 16 GB, PCIe 3 x16", "note": "ResNet-50 batch 640, section 5.2"}
+        if args.workload == "resnet50_b640_16g" else None,
         "roofline": {"bound": "mfma", "kernel": dom[0], "achieved": dom_tflops / 1e12, "peak": PEAK_MFMA_FP32 / 1e12,
                      "unit": "TFLOP/s", "frac": dom_tflops / PEAK_MFMA_FP32, "traffic": traffic,
                      "traffic_unit": "HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated)",
+                     "traffic_source": ("offline: two rocprofv3 --pmc runs of this command, profiles/resnet50_b640_16g_hbm_traffic.txt "
+                                        "(counters cannot be read from inside an unprofiled run)") if traffic is not None else None,
+                     "step_flops": total_flops,
+                     "step_frac_of_mfma_peak": total_flops / sec / PEAK_MFMA_FP32,
                      "algorithmic_bytes_per_launch": dom[1][3] / max(dom[1][2], 1),
                      "algorithmic_flops_per_launch": dom[1][0] / max(dom[1][2], 1),
                      "launches_per_step": dom[1][2], "avg_launch_ms": dom[1][1] / max(dom[1][2], 1)},
