@@ -156,13 +156,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     int pk = vk;                                     // LIN == 2: this thread's position in the reduction
     const int nk_all = (p.Kred + BKT - 1) / BKT;
     const int it_beg = ks * p.kslices, it_end = p.ksplit > 1 ? min(nk_all, it_beg + p.kslices) : nk_all;
-    if (LIN == 1 && it_beg > 0) {                    // a later part of the reduction: its first slice's tap
-        const int kfirst = it_beg * BKT;
-        const int tap = kfirst / p.Cs;
-        tc = kfirst - tap * p.Cs;
+    // LIN == 1 walks the reduction channel slice by channel slice and, inside a slice, tap by tap (the sum's terms are the
+    // same, their order is this path's own): consecutive steps then read the same channels of pixels one tap apart --
+    // what a neighbouring row of the tile read a step earlier -- so the input is fetched into the XCD's L2 about once
+    // instead of once per tap, the taps of one slice being many steps apart otherwise.
+    const int ntaps = p.kd * p.kh * p.kw;
+    int koff = 0;                                    // offset of the step's filter slice inside a filter row: tap * Cs + tc
+    if (LIN == 1 && it_beg > 0) {                    // a later part of the reduction: its first step's slice and tap
+        const int tap = it_beg % ntaps;
+        tc = (it_beg / ntaps) * BKT;
         te = tap % p.kw;
         tb = (tap / p.kw) % p.kh;
         ta = tap / (p.kw * p.kh);
+        koff = tap * p.Cs + tc;
     }
     if (LIN == 2) {
         const int tap = vk / p.Cs;
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
         for (int i = 0; i < B_V; ++i) {
             const int n = n0 + vrow + i * RPP;
             brow[i] = (vrow + i * RPP < BN) & (n < p.Nout);
-            bptr[i] = p.wgt + (brow[i] ? (int64_t)n * p.Kred + vk + (LIN == 1 ? it_beg * BKT : 0) : 0);
+            bptr[i] = p.wgt + (brow[i] ? (int64_t)n * p.Kred + vk : 0);
         }
     }
     auto load_tiles_tap = [&](bool live) {
@@ -227,17 +233,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
 #pragma unroll
         for (int i = 0; i < B_V; ++i) {
             const bool ok = live & brow[i];
-            bv[i] = ldg4(ok ? bptr[i] : g_zero4);
-            bptr[i] += BKT;
+            bv[i] = ldg4(ok ? bptr[i] + koff : g_zero4);
         }
-        tc += BKT;
-        if (tc == p.Cs) {
-            tc = 0;
-            if (++te == p.kw) {
-                te = 0;
-                if (++tb == p.kh) {
-                    tb = 0;
-                    ++ta;
+        // next step: the next tap of this channel slice, or the first tap of the next slice
+        koff += p.Cs;
+        if (++te == p.kw) {
+            te = 0;
+            if (++tb == p.kh) {
+                tb = 0;
+                if (++ta == p.kd) {
+                    ta = 0;
+                    tc += BKT;
+                    koff = tc;
                 }
             }
         }
