@@ -1185,14 +1185,12 @@ __global__ __launch_bounds__(192 * (GR / GW) * (KB / IW) * (CB / JW)) void wgrad
         const int issue_buf = buf == 0 ? p.nbuf - 1 : buf - 1;
         const float *const dy_s = halo_lds + buf * p.buf_floats;
         const float *const x_s = dy_s + x_floats;
-        // MFMA step t multiplies pixels 2t and 2t + 1 (lane half h takes pixel 2t + h).  Steps go in pairs through two
-        // sets of fragment registers: while one pair is multiplied the other pair's fragments are read from LDS, one or
-        // two reads behind each MFMA (P is a multiple of 8, so the step count is a multiple of 4).
+        // MFMA step t multiplies pixels 2t and 2t + 1 (lane half h takes pixel 2t + h)
         const int steps = p.P / 2;
         const float *ap = dy_s + h * K + r;
         const float *bp = x_s + (h + e) * C + r;
         const int hs = K == 64 ? (h << 5) : 0, qs = C == 64 ? (((h + e) & 1) << 5) : 0;   // bank swap of this lane's pixels (their parity is fixed: they advance by two)
-        float afA[2][IW], bfA[2][GW][JW], afB[2][IW], bfB[2][GW][JW];
+        float af0[2][IW], bf0[2][GW][JW], af1[2][IW], bf1[2][GW][JW], af2[2][IW], bf2[2][GW][JW], af3[2][IW], bf3[2][GW][JW];
         auto load_pair = [&](float (&af)[2][IW], float (&bf)[2][GW][JW], int t) {
 #pragma unroll
             for (int d = 0; d < 2; ++d) {
@@ -1215,25 +1213,43 @@ __global__ __launch_bounds__(192 * (GR / GW) * (KB / IW) * (CB / JW)) void wgrad
                         for (int j = 0; j < JW; ++j)
                             acc[d % SETS][g][i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[d][i], bf[d][g][j], acc[d % SETS][g][i][j], 0, 0, 0);
         };
+        // one MFMA, then its share of the LDS reads issued in the same stretch of code
         constexpr int NM = 2 * GW * IW * JW, NR = 2 * (IW + GW * JW), RPM = (NR + NM - 1) / NM;
-        load_pair(afA, bfA, 0);
-        const int issue_at = min(4 * ((wave / 4) % 3), steps - 4);
-        for (int t = 0; t < steps; t += 4) {
-            if (more && t == issue_at) issue(issue_buf);
-            load_pair(afB, bfB, t + 2);
-            mul_pair(afA, bfA);
+        auto interleave = [&]() {
 #pragma unroll
             for (int q = 0; q < NM; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);   // LDS reads
             }
-            load_pair(afA, bfA, min(t + 4, steps - 2));                // past the end: a pair that exists, unused
-            mul_pair(afB, bfB);
-#pragma unroll
-            for (int q = 0; q < NM; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
-            }
+        };
+        // Pairs of steps go round four sets of fragment registers: while pair k is multiplied, pair k + 2 is read from
+        // LDS, so a read has two pairs' MFMAs to arrive in.  Four pairs per trip; P is a multiple of 8, so what is left
+        // after the last whole trip is nothing or two pairs, which are in their registers by then.  Loads past the end
+        // fetch a pair that exists and is not used.
+        const int last = steps - 2;
+        const int issue_at = 8 * ((wave / 4) % 3);     // the three wavefronts of a SIMD take turns
+        load_pair(af0, bf0, 0);
+        load_pair(af1, bf1, 2);
+        int t = 0;
+        for (; t + 8 <= steps; t += 8) {
+            if (more && t == issue_at) issue(issue_buf);
+            load_pair(af2, bf2, min(t + 4, last));
+            mul_pair(af0, bf0);
+            interleave();
+            load_pair(af3, bf3, min(t + 6, last));
+            mul_pair(af1, bf1);
+            interleave();
+            load_pair(af0, bf0, min(t + 8, last));
+            mul_pair(af2, bf2);
+            interleave();
+            load_pair(af1, bf1, min(t + 10, last));
+            mul_pair(af3, bf3);
+            interleave();
+        }
+        if (more && issue_at >= t) issue(issue_buf);   // (a segment shorter than the wavefront's turn)
+        if (t < steps) {
+            mul_pair(af0, bf0);
+            mul_pair(af1, bf1);
         }
         buf = buf + 1 == p.nbuf ? 0 : buf + 1;
     }
@@ -1306,7 +1322,8 @@ WHaloCfg whalo_cfg(const ConvGeom &g)
     c.nbuf = c.nbuf > 4 ? 4 : c.nbuf;
     c.lds_bytes = c.nbuf * shape(c.P);
     c.lpw = (c.dy_blocks + c.gr * c.row_blocks + c.waves - 1) / c.waves;
-    if (c.lpw > WHALO_MAX_LPW || (c.nbuf - 2) * c.lpw > 8) return c;   // (the counted wait knows 0 .. 8)
+    if (c.lpw > WHALO_MAX_LPW) return c;
+    while (c.nbuf > 2 && (c.nbuf - 2) * c.lpw > 8) --c.nbuf;   // (the counted wait knows 0 .. 8)
     const int64_t nseg = (int64_t)g.N * g.Do * g.Ho * c.nseg_w;
     if (nseg >= ((int64_t)1 << 30)) return c;
     c.nseg = (int)nseg;
