@@ -52,6 +52,9 @@ struct IGemmP {
     int ksplit, kslices;
     // destination rows: identity, or (dst_strided) GEMM row (n,d,h,w) -> row ((n*DD + d*SD)*HD + h*SH)*WD + w*SW
     int dst_strided, DD, HD, WD, SD, SH, SW;
+    // bd > 0: the rows of a tile are a brick of bd x 8 x 8 positions (d, h, w) instead of consecutive rows; tiles enumerate the
+    // bricks of (n, d, h, w) with w fastest.  Requires bd * 64 == rows per tile and Dr % bd == Hr % 8 == Wr % 8 == 0.
+    int bd;
 };
 
 // coordinate in the source tensor touched by filter tap `a` for a row whose base is `base`
@@ -107,16 +110,31 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     float *const dst = p.dst + (int64_t)ks * p.M * p.Nout;
 
     for (int r = tid; r < BM; r += NT) {
-        const int m = m0 + r;
+        int m = m0 + r;
         int4 ri = make_int4(-1, 0, 0, 0);
         int rd = -1;
         if (m < p.M) {
-            const int w_ = m % p.Wr;
-            int t = m / p.Wr;
-            const int h_ = t % p.Hr;
-            t /= p.Hr;
-            const int d_ = t % p.Dr;
-            const int n = t / p.Dr;
+            int n, d_, h_, w_;
+            if (p.bd > 0) {
+                // Under a filter with depth, BM consecutive rows (a strip of one or two lines) touch nine times their own
+                // input; a brick touches (bd + 2) * 10 * 10 / (bd * 64) of it (2.3 for bd = 4), whatever the caches hold.
+                int t = m0 / BM;
+                const int nbw = p.Wr / 8, nbh = p.Hr / 8, nbd = p.Dr / p.bd;
+                w_ = (t % nbw) * 8 + r % 8;
+                t /= nbw;
+                h_ = (t % nbh) * 8 + (r / 8) % 8;
+                t /= nbh;
+                d_ = (t % nbd) * p.bd + r / 64;
+                n = t / nbd;
+                m = ((n * p.Dr + d_) * p.Hr + h_) * p.Wr + w_;
+            } else {
+                w_ = m % p.Wr;
+                int t = m / p.Wr;
+                h_ = t % p.Hr;
+                t /= p.Hr;
+                d_ = t % p.Dr;
+                n = t / p.Dr;
+            }
             ri = DGRAD ? make_int4(n, d_ + p.pd, h_ + p.ph, w_ + p.pw)
                        : make_int4(n, d_ * p.sd - p.pd, h_ * p.sh - p.ph, w_ * p.sw - p.pw);
             rd = p.dst_strided ? ((n * p.DD + d_ * p.SD) * p.HD + h_ * p.SH) * p.WD + w_ * p.SW : m;
@@ -553,6 +571,10 @@ hipError_t launch_igemm(IGemmP p, bool vec, int lin, bool accum, hipStream_t s, 
     p.total_tiles = tiles_m * p.tiles_n;
     if (p.ksplit < 1) p.ksplit = 1;
     p.chunk = (p.total_tiles * p.ksplit + NXCD - 1) / NXCD;
+    // volumes under a filter with depth: brick-shaped row tiles (every variant of the kernel addresses row by row)
+    static const bool no_brick = getenv("POOCH_NO_BRICK") != nullptr;
+    p.bd = 0;
+    if (!no_brick && p.kd > 1 && BM % 64 == 0 && p.Dr % (BM / 64) == 0 && p.Hr % 8 == 0 && p.Wr % 8 == 0) p.bd = BM / 64;
     const dim3 grid(p.chunk * NXCD), block(64 * WGM * WGN);
     if (stats_tiles) {   // layout query of the statistics a STATS launch writes: row tiles, rows per tile
         stats_tiles[0] = tiles_m;
@@ -672,7 +694,13 @@ hipError_t dispatch_igemm(const IGemmP &p0, bool accum, hipStream_t s, int *stat
     }
     // too few 128x128 tiles to fill 256 compute units three workgroups deep: quarter-size tiles
     if (p.Nout > 64 && ((int64_t)(p.M + 127) / 128) * ((p.Nout + 127) / 128) < 640) return launch_igemm<2, 2, 1, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
-    if (p.Nout <= 32) return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
+    // 32 output channels: a wave holds two accumulator blocks, so a 16-wide slice is only 16 MFMAs between two barriers; 32-wide
+    // slices where a tap spans whole ones (3 x 3 x 3, 32 -> 32 at 192^3: forward 94 -> 100 TFLOP/s, data gradient 98 -> 108;
+    // the wider tiles gain nothing from it)
+    if (p.Nout <= 32) {
+        if (lin == 1 && p.Cs % 32 == 0) return launch_igemm<4, 1, 2, 1, 32, DGRAD>(p, vec, lin, accum, s, stats_tiles);
+        return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
+    }
     if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
     return launch_igemm<2, 2, 2, 2, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
 }

@@ -76,6 +76,7 @@ struct ParamInfo {
 
 struct Timing {
     std::vector<int> start, stop;      // per command: indices into the timing-event pool, -1 = untimed
+    std::vector<char> own_start;       // the start event is this command's own (else: the stop event of the command before it on its stream)
     std::vector<int> rstart, rstop;    // profile mode: the re-forward run right after a forward
     std::vector<int> mid;              // conv / fc backward: between the filter and the data gradient
 };
@@ -423,6 +424,9 @@ pooch_status copy_out_capture(pooch_ctx *c, int i, const float *dev)
 // Enqueues a command list.  tm != nullptr: every forward / re-forward / backward / copy command
 // is bracketed by timing events on its own stream; profile_refwd additionally runs (and
 // times) each layer's re-forward variant right after its forward, on the same buffers.
+// A command that follows another on its stream with no wait in between starts at that one's stop
+// event instead of recording one of its own (an event between every two kernels cost 2.3 ms per
+// step on ResNet-50, 10 % of the step at batch 64; half of them are left).
 // Returns at the first failure with whatever was enqueued before it still in flight: run_schedule() cleans up.
 pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool profile_refwd, bool static_scratch)
 {
@@ -445,15 +449,30 @@ pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool 
         const size_t nc = S.cmds.size();
         tm->start.assign(nc, -1); tm->stop.assign(nc, -1); tm->rstart.assign(nc, -1); tm->rstop.assign(nc, -1);
         tm->mid.assign(nc, -1);
+        tm->own_start.assign(nc, 0);
+        int last[3] = {-1, -1, -1};     // per stream: the stop event of its latest command, -1 once the stream may have stalled since
         for (size_t k = 0; k < nc; ++k) {
-            const int kind = S.cmds[k].kind;
+            const Cmd &cm = S.cmds[k];
+            const int kind = cm.kind;
+            if (kind == K_WAIT) last[cm.id] = -1;
             if (kind == K_REC || kind == K_WAIT) continue;
-            tm->start[k] = (int)n_te++; tm->stop[k] = (int)n_te++;
-            const Op op = kind <= K_BWD ? c->G.nodes[S.cmds[k].id].op : OP_INPUT;
-            if (kind == K_BWD && (op == OP_CONV || op == OP_FC)) tm->mid[k] = (int)n_te++;
-            if (profile_refwd && kind == K_FWD && op != OP_LOSS) {
-                tm->rstart[k] = (int)n_te++; tm->rstop[k] = (int)n_te++;
+            const int st = kind <= K_BWD ? S_COMPUTE : (kind == K_OUT ? S_D2H : S_H2D);
+            if (last[st] >= 0) {
+                tm->start[k] = last[st];
+            } else {
+                tm->start[k] = (int)n_te++;
+                tm->own_start[k] = 1;
             }
+            const Op op = kind <= K_BWD ? c->G.nodes[cm.id].op : OP_INPUT;
+            if (kind == K_BWD && (op == OP_CONV || op == OP_FC)) tm->mid[k] = (int)n_te++;
+            tm->stop[k] = (int)n_te++;
+            last[st] = tm->stop[k];
+            if (profile_refwd && kind == K_FWD && op != OP_LOSS) {
+                tm->rstart[k] = tm->stop[k];
+                tm->rstop[k] = (int)n_te++;
+                last[st] = tm->rstop[k];
+            }
+            if (kind == K_FWD && c->capture[cm.id] && op != OP_LOSS) last[st] = -1;   // a blocking copy follows
         }
         ps = ensure_events(c, c->timing_events, n_te, hipEventDefault);
         if (ps != POOCH_OK) return ps;
@@ -468,7 +487,7 @@ pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool 
             c->fail_at = -1;
             return fail(c, POOCH_E_HIP, "injected failure at command " + std::to_string(k) + " (pooch_inject_failure)");
         }
-        if (tm && tm->start[k] >= 0) HIPCHK(hipEventRecord(c->timing_events[tm->start[k]], c->st[stream]));
+        if (tm && tm->own_start[k]) HIPCHK(hipEventRecord(c->timing_events[tm->start[k]], c->st[stream]));
         switch (cm.kind) {
         case K_FWD: case K_REFWD: {
             const int i = cm.id;
@@ -476,7 +495,6 @@ pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool 
             HIPCHK(X.forward(i, cm.a[0], cm.a[1], cm.a[2], cm.kind == K_REFWD));
             if (tm && tm->start[k] >= 0) HIPCHK(hipEventRecord(c->timing_events[tm->stop[k]], c->st[stream]));
             if (tm && tm->rstart[k] >= 0) {
-                HIPCHK(hipEventRecord(c->timing_events[tm->rstart[k]], c->st[stream]));
                 HIPCHK(X.forward(i, cm.a[0], cm.a[1], cm.a[2], true));
                 HIPCHK(hipEventRecord(c->timing_events[tm->rstop[k]], c->st[stream]));
             }
