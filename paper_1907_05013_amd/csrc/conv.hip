@@ -194,7 +194,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
         tb = (tap / p.kw) % p.kh;
         ta = tap / (p.kw * p.kh);
     }
-    if (LIN) {
+    // LIN == 3 (one tap, no padding: a plain GEMM whose A rows are pixels): every row that exists is valid at every step, so
+    // the loop keeps one pointer per row and adds BKT to it -- no range checks, no selects.  Rows past the end of either
+    // operand alias the tile's first row: what they produce is never stored.
+    const float *aptr[LIN == 3 ? A_V : 1];
+    if (LIN == 3) {
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) {
+            const int4 ri = ri_reg[i].x >= 0 ? ri_reg[i] : rowinfo[0];
+            aptr[i] = p.src + (((((int64_t)ri.x * p.Ds + ri.y) * p.Hs + ri.z) * p.Ws + ri.w) * p.Cs + vk + (int64_t)it_beg * BKT);
+        }
+#pragma unroll
+        for (int i = 0; i < B_V; ++i) {
+            int n = n0 + vrow + i * RPP;
+            if (vrow + i * RPP >= BN || n >= p.Nout) n = n0;
+            bptr[i] = p.wgt + ((int64_t)n * p.Kred + vk + (int64_t)it_beg * BKT);
+        }
+    } else if (LIN) {
 #pragma unroll
         for (int i = 0; i < A_V; ++i) {
             const int4 ri = ri_reg[i];
@@ -207,6 +223,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
             bptr[i] = p.wgt + (brow[i] ? (int64_t)n * p.Kred + vk : 0);
         }
     }
+    auto load_tiles_gemm = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) {
+            av[i] = ldg4(aptr[i]);
+            aptr[i] += BKT;
+        }
+#pragma unroll
+        for (int i = 0; i < B_V; ++i) {
+            bv[i] = ldg4(bptr[i]);
+            bptr[i] += BKT;
+        }
+    };
     auto load_tiles_tap = [&](bool live) {
         const bool kok = live & (pk < p.Kred);
         const int64_t tapoff = (((int64_t)ta * p.Hs + tb) * p.Ws + te) * p.Cs;
@@ -373,13 +401,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
     const int r = lane % 32, h = lane / 32;
 
     const int nk = it_end;
-    if (LIN == 2) load_tiles_tap(true);
+    if (LIN == 3) {
+        if (it_beg < nk) load_tiles_gemm();
+    } else if (LIN == 2) load_tiles_tap(true);
     else if (LIN) load_tiles_lin(it_beg < nk);
     else load_tiles(it_beg * BKT);
     for (int it = it_beg; it < nk; ++it) {
         store_tiles();
         __syncthreads();
-        if (LIN == 2) load_tiles_tap(it + 1 < nk);
+        if (LIN == 3) {
+            if (it + 1 < nk) load_tiles_gemm();       // uniform branch: nothing is read past the end of a row
+        } else if (LIN == 2) load_tiles_tap(it + 1 < nk);
         else if (LIN) load_tiles_lin(it + 1 < nk);     // past the end: every element is masked off
         else if (VEC) load_tiles((it + 1) * BKT);
         else if (it + 1 < nk) load_tiles((it + 1) * BKT);
@@ -585,6 +617,7 @@ hipError_t launch_igemm(IGemmP p, bool vec, int lin, bool accum, hipStream_t s, 
         if constexpr (!DGRAD) {
             if (!vec || lin == 0 || accum || p.dst_strided || p.Nout % 4 != 0) return hipErrorInvalidValue;
             if (lin == 2) igemm_kernel<WGM, WGN, TM, TN, BKT, true, 2, false, false, true><<<grid, block, 0, s>>>(p);
+            else if (lin == 3) igemm_kernel<WGM, WGN, TM, TN, BKT, true, 3, false, false, true><<<grid, block, 0, s>>>(p);
             else igemm_kernel<WGM, WGN, TM, TN, BKT, true, 1, false, false, true><<<grid, block, 0, s>>>(p);
         } else {
             return hipErrorInvalidValue;
@@ -596,6 +629,9 @@ hipError_t launch_igemm(IGemmP p, bool vec, int lin, bool accum, hipStream_t s, 
         } else {
             return hipErrorInvalidValue;
         }
+    } else if (vec && lin == 3) {
+        if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, true, 3, DGRAD, true><<<grid, block, 0, s>>>(p);
+        else igemm_kernel<WGM, WGN, TM, TN, BKT, true, 3, DGRAD, false><<<grid, block, 0, s>>>(p);
     } else if (vec && lin) {
         if (accum) igemm_kernel<WGM, WGN, TM, TN, BKT, true, 1, DGRAD, true><<<grid, block, 0, s>>>(p);
         else igemm_kernel<WGM, WGN, TM, TN, BKT, true, 1, DGRAD, false><<<grid, block, 0, s>>>(p);
@@ -675,8 +711,10 @@ hipError_t dispatch_igemm(const IGemmP &p0, bool accum, hipStream_t s, int *stat
     p.ksplit = 1;
     p.kslices = 0;
     const bool vec = (p.Cs % 4 == 0) && ((uintptr_t)p.src % 16 == 0) && ((uintptr_t)p.wgt % 16 == 0);
-    const int lin = vec ? igemm_linear_mode(p.Cs, DGRAD, p.sd == 1 && p.sh == 1 && p.sw == 1, accum) : 0;
+    int lin = vec ? igemm_linear_mode(p.Cs, DGRAD, p.sd == 1 && p.sh == 1 && p.sw == 1, accum) : 0;
     const SplitK sk = igemm_splitk(p.M, p.Nout, p.Kred, lin, p.dst_strided != 0);
+    static const bool no_gemm = getenv("POOCH_NO_GEMM_PATH") != nullptr;
+    if (lin == 1 && !no_gemm && p.kd * p.kh * p.kw == 1 && p.pd == 0 && p.ph == 0 && p.pw == 0) lin = 3;   // one tap, no padding
     if (sk.ksplit > 1) {
         if (stats_tiles || p.stats) return hipErrorInvalidValue;      // no statistics from a split reduction
         if (!workspace || (uintptr_t)workspace % 16 != 0 || (uintptr_t)p.dst % 16 != 0) return hipErrorInvalidValue;
