@@ -676,8 +676,8 @@ SplitK igemm_splitk(int M, int Nout, int Kred, int lin, bool dst_strided)
     if (off || lin != 1 || dst_strided || Nout <= 64 || Nout % 4 != 0) return k;
     const int64_t tiles = ((int64_t)(M + 127) / 128) * ((Nout + 127) / 128);
     const int nk = (Kred + BK - 1) / BK;
-    // (a reduction of 1024: 76 TFLOP/s split against 81 with quarter-size tiles; 2048: 78 against 70; 2304 and more: 89 - 106 against 60 - 92)
-    if (tiles >= 384 || nk < 96) return k;
+    // (a reduction of 2048: 81 TFLOP/s split against 85 with quarter-size tiles; 2304 and more: 89 - 106 against 60 - 90)
+    if (tiles >= 384 || nk < 144) return k;
     int64_t want = (768 + tiles - 1) / tiles;                   // about three workgroups per compute unit
     if (want > 8) want = 8;
     if (want > nk / 16) want = nk / 16;                         // at least 16 slices (256 reduction steps) per part
@@ -733,10 +733,11 @@ hipError_t dispatch_igemm(const IGemmP &p0, bool accum, hipStream_t s, int *stat
     // too few 128x128 tiles to fill 256 compute units three workgroups deep: quarter-size tiles
     if (p.Nout > 64 && ((int64_t)(p.M + 127) / 128) * ((p.Nout + 127) / 128) < 640) return launch_igemm<2, 2, 1, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
     // 32 output channels: a wave holds two accumulator blocks, so a 16-wide slice is only 16 MFMAs between two barriers; 32-wide
-    // slices where a tap spans whole ones (3 x 3 x 3, 32 -> 32 at 192^3: forward 94 -> 100 TFLOP/s, data gradient 98 -> 108;
-    // the wider tiles gain nothing from it)
+    // slices where a tap spans whole ones (3 x 3 x 3, 32 -> 32 at 192^3: forward 104 -> 108 TFLOP/s, data gradient 98 -> 108;
+    // the wider tiles lose 3 % under 3 x 3 filters and gain 1 % at most under 1 x 1)
     if (p.Nout <= 32) {
-        if (lin == 1 && p.Cs % 32 == 0) return launch_igemm<4, 1, 2, 1, 32, DGRAD>(p, vec, lin, accum, s, stats_tiles);
+        static const bool narrow = getenv("POOCH_NO_WIDE_SLICE") != nullptr;
+        if (!narrow && lin == 1 && p.Cs % 32 == 0) return launch_igemm<4, 1, 2, 1, 32, DGRAD>(p, vec, lin, accum, s, stats_tiles);
         return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
     }
     if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
