@@ -11,6 +11,7 @@
 
 #include <cstdlib>
 #include <map>
+#include <mutex>
 #include <string>
 
 namespace pk {
@@ -1587,42 +1588,45 @@ hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const Con
 }
 
 namespace {
-// tag of the igemm instantiation dispatch_igemm() picks: tile shape, load path, direction
-const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgrad, int kred = 0)
+// tag of the igemm instantiation dispatch_igemm() picks: tile shape, load path, direction.  one_tap: a single filter tap
+// and no padding (the plain-GEMM path where whole slices per tap apply)
+const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgrad, int kred, bool one_tap)
 {
-    if (cs % 4 == 0 && igemm_splitk((int)rows, nout, kred, igemm_linear_mode(cs, dgrad, unit_stride, false), false).ksplit > 1)
-        return dgrad ? "igemm_kernel<2,2,2,2,vec+lin,dgrad,splitk>" : "igemm_kernel<2,2,2,2,vec+lin,fwd,splitk>";
-    static const char *names[4][4][2] = {
-        {{"igemm_kernel<4,1,2,1,scalar,fwd>", "igemm_kernel<4,1,2,1,scalar,dgrad>"},
-         {"igemm_kernel<4,1,2,1,vec,fwd>", "igemm_kernel<4,1,2,1,vec,dgrad>"},
-         {"igemm_kernel<4,1,2,1,vec+lin,fwd>", "igemm_kernel<4,1,2,1,vec+lin,dgrad>"},
-         {"igemm_kernel<4,1,2,1,vec+tap,fwd>", ""}},
-        {{"igemm_kernel<4,1,2,2,scalar,fwd>", "igemm_kernel<4,1,2,2,scalar,dgrad>"},
-         {"igemm_kernel<4,1,2,2,vec,fwd>", "igemm_kernel<4,1,2,2,vec,dgrad>"},
-         {"igemm_kernel<4,1,2,2,vec+lin,fwd>", "igemm_kernel<4,1,2,2,vec+lin,dgrad>"},
-         {"igemm_kernel<4,1,2,2,vec+tap,fwd>", ""}},
-        {{"igemm_kernel<2,2,2,2,scalar,fwd>", "igemm_kernel<2,2,2,2,scalar,dgrad>"},
-         {"igemm_kernel<2,2,2,2,vec,fwd>", "igemm_kernel<2,2,2,2,vec,dgrad>"},
-         {"igemm_kernel<2,2,2,2,vec+lin,fwd>", "igemm_kernel<2,2,2,2,vec+lin,dgrad>"},
-         {"igemm_kernel<2,2,2,2,vec+tap,fwd>", ""}},
-        {{"igemm_kernel<2,2,1,1,scalar,fwd>", "igemm_kernel<2,2,1,1,scalar,dgrad>"},
-         {"igemm_kernel<2,2,1,1,vec,fwd>", "igemm_kernel<2,2,1,1,vec,dgrad>"},
-         {"igemm_kernel<2,2,1,1,vec+lin,fwd>", "igemm_kernel<2,2,1,1,vec+lin,dgrad>"},
-         {"igemm_kernel<2,2,1,1,vec+tap,fwd>", ""}}};
-    int tile = nout <= 32 ? 0 : (nout <= 64 ? 1 : 2);
-    if (nout > 64 && ((rows + 127) / 128) * ((nout + 127) / 128) < 640) tile = 3;
     const bool vec = cs % 4 == 0;
     const int lin = vec ? igemm_linear_mode(cs, dgrad, unit_stride, false) : 0;
-    return names[tile][lin ? 1 + lin : (vec ? 1 : 0)][dgrad ? 1 : 0];
+    static const bool no_gemm = getenv("POOCH_NO_GEMM_PATH") != nullptr, narrow = getenv("POOCH_NO_WIDE_SLICE") != nullptr;
+    const bool gemm = lin == 1 && one_tap && !no_gemm;
+    std::string name = "igemm_kernel<";
+    if (vec && igemm_splitk((int)rows, nout, kred, lin, false).ksplit > 1) {
+        name += "2,2,2,2,";
+    } else if (nout > 64 && ((rows + 127) / 128) * ((nout + 127) / 128) < 640) {
+        name += "2,2,1,1,";
+    } else {
+        name += nout <= 32 ? "4,1,2,1," : (nout <= 64 ? "4,1,2,2," : "2,2,2,2,");
+    }
+    const bool split = vec && igemm_splitk((int)rows, nout, kred, lin, false).ksplit > 1;
+    const bool wide = !split && nout <= 32 && lin == 1 && !gemm && cs % 32 == 0 && !narrow &&
+                      !(nout > 64 && ((rows + 127) / 128) * ((nout + 127) / 128) < 640);
+    name += !vec ? "scalar" : (lin == 2 ? "vec+tap" : (gemm ? "vec+gemm" : (lin == 1 ? (wide ? "vec+lin32" : "vec+lin") : "vec")));
+    name += dgrad ? ",dgrad" : ",fwd";
+    if (split) name += ",splitk";
+    name += ">";
+    static std::map<std::string, std::string> names;   // (the caller keeps the pointer)
+    static std::mutex mu;
+    std::lock_guard<std::mutex> lock(mu);
+    return names.emplace(name, name).first->second.c_str();
 }
 }  // namespace
 
 const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
 {
-    const char *plain = igemm_tag(g.rows_out(), g.K, g.C, true, false, (int)(g.taps() * g.C));
+    const bool one_tap = g.taps() == 1 && g.pd == 0 && g.ph == 0 && g.pw == 0;
+    const char *plain = igemm_tag(g.rows_out(), g.K, g.C, true, false, (int)(g.taps() * g.C), one_tap);
     if (!bn_tiles) return plain;
     // the variant that also leaves batch-normalisation statistics is a kernel of its own
     static std::map<std::string, std::string> names;
+    static std::mutex mu;
+    std::lock_guard<std::mutex> lock(mu);
     std::string &v = names[plain];
     if (v.empty()) {
         v = plain;
@@ -1633,8 +1637,9 @@ const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
 
 const char *conv_dgrad_kernel(const ConvGeom &g)
 {
-    if (pointwise_strided(g)) return igemm_tag(g.rows_out(), g.C, g.K, true, false);   // scatter GEMM over the output rows
-    return igemm_tag(g.rows_in(), g.C, g.K, g.sd == 1 && g.sh == 1 && g.sw == 1, true, (int)(g.taps() * g.K));
+    if (pointwise_strided(g)) return igemm_tag(g.rows_out(), g.C, g.K, true, false, 0, true);   // scatter GEMM over the output rows (never split)
+    const bool one_tap = g.taps() == 1 && g.pd == 0 && g.ph == 0 && g.pw == 0;
+    return igemm_tag(g.rows_in(), g.C, g.K, g.sd == 1 && g.sh == 1 && g.sw == 1, true, (int)(g.taps() * g.K), one_tap);
 }
 
 const char *conv_wgrad_kernel(const ConvGeom &g)
