@@ -1405,9 +1405,10 @@ WHaloCfg whalo_cfg(const ConvGeom &g)
     c.seg_per_split = (int)((nseg + ns - 1) / ns);
     c.nsplit = (int)((nseg + c.seg_per_split - 1) / c.seg_per_split);
     // A workgroup's partial block is written once per workgroup: with few segments each, that and the reduction
-    // outweigh the gain (ResNet-50's 3x3 64 -> 64 at batch 64: 72 TFLOP/s here against 80 generic; at batch 640, 92 against 80).
-    // Problems too small to matter either way stay here, so that small test shapes reach this kernel.
-    if (c.seg_per_split < 24 && nseg > 2048) return WHaloCfg{};
+    // outweigh the gain (ResNet-50's 3x3 64 -> 64 at batch 64: 72 TFLOP/s here against 80 generic, at batch 32 60 against 70;
+    // at batch 640, 92 against 80).  Problems too small to matter either way (under 2 GFLOP) stay here, so that small test
+    // shapes reach this kernel.
+    if (c.seg_per_split < 24 && 2.0 * (double)g.rows_out() * g.K * (double)(g.taps() * g.C) > 2e9) return WHaloCfg{};
     c.use = true;
     return c;
 }
