@@ -410,7 +410,10 @@ def main():
                      "step_frac_of_mfma_peak": total_flops / sec / PEAK_MFMA_FP32,
                      "algorithmic_bytes_per_launch": dom[1][3] / max(dom[1][2], 1),
                      "algorithmic_flops_per_launch": dom[1][0] / max(dom[1][2], 1),
-                     "launches_per_step": dom[1][2], "avg_launch_ms": dom[1][1] / max(dom[1][2], 1)},
+                     "launches_per_step": dom[1][2], "avg_launch_ms": dom[1][1] / max(dom[1][2], 1),
+                     "avg_launch_covers": ("the kernel, the reduce_splits_kernel that adds its per-split partial sums (about 13 us at "
+                                           "ResNet-50's sizes) and the gap between the two launches: one event pair per filter-gradient command")
+                     if dom[0].startswith("wgrad") else "the kernel and the launch gap before it"},
         "conv_mfma_util": (cfl / (cms * 1e-3)) / PEAK_MFMA_FP32 if cms > 0 else None,
         "conv_TFLOPs": cfl / (cms * 1e-3) / 1e12 if cms > 0 else None,
         "bn_hbm_GBs": bnb / (bnms * 1e-3) / 1e9 if bnms > 0 else None,
