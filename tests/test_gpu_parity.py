@@ -764,6 +764,28 @@ def test_conv_bn_shapes_full_size_without_kinks(x_shape, cout, k, stride, pad):
     check_against_oracle("probe %s -> %d k%s s%s" % (x_shape, cout, k, stride), net, 123, capture=False)
 
 
+@pytest.mark.parametrize("x_shape,c1,c2,wide", [
+    ((2, 16, 8, 16, 24), 32, 32, (True, True)),       # 32 -> 32: 32-wide slices forward and backward, bricks of 4 x 8 x 8
+    ((1, 32, 12, 8, 16), 64, 32, (True, False)),      # 64 -> 32: wide slices forward; the data gradient has 64 columns (16-wide slices)
+    ((2, 16, 6, 8, 8), 136, 16, (False, False)),      # 136 -> 16: quarter-size tiles backward (bricks of 1 x 8 x 8), 16-channel slices
+])
+def test_volume_tiles_bricks_and_wide_slices(x_shape, c1, c2, wide):
+    """two 3 x 3 x 3 convolutions on volumes whose extents are multiples of 8: row tiles are bricks instead of strips of
+    consecutive positions, and 32 output channels take 32-wide reduction slices; no ReLU, so no decision can differ"""
+    net = workloads.Net()
+    t = net.input(x_shape)
+    t = net.bn(net.conv(t, c1, (3, 3, 3), (1, 1, 1), (1, 1, 1)))
+    t = net.bn(net.conv(t, c2, (3, 3, 3), (1, 1, 1), (1, 1, 1)))
+    net.softmax_ce(net.fc(net.gavgpool(t), 10))
+    c = B.Context(net, 1 << 30, device=None)
+    conv2 = [i for i, L in enumerate(net) if L["op"] == "conv"][1]
+    assert ("lin32" in c.node_kernel(conv2, 0)) == wide[0] and ("lin32" in c.node_kernel(conv2, 1)) == wide[1], \
+        (c.node_kernel(conv2, 0), c.node_kernel(conv2, 1))
+    # (the first normalisation's shift moves the second convolution's output by a constant away from the borders, which the
+    # second normalisation removes: a gradient that is nearly zero in exact arithmetic, hence the ill-conditioned check)
+    check_ill_conditioned("volume tiles %s -> %d -> %d" % (x_shape, c1, c2), net, 555)
+
+
 @pytest.mark.parametrize("x_shape,cout,k,pad", [
     ((2, 64, 13, 13), 64, (3, 3), (1, 1)),            # one row group per workgroup, odd width (one padded pixel pair)
     ((3, 32, 9, 70), 32, (3, 3), (1, 1)),             # three rows per group; 70 pixels = two segments of 36, the second ragged
