@@ -24,6 +24,7 @@ namespace {
 constexpr int BK = 16;   // reduction slice per main-loop iteration
 constexpr int LDK = 20;  // LDS row stride (floats) of [row][k] tiles: 16-byte rows, conflict-free b128 reads
 constexpr int NXCD = 8;
+constexpr int NCU = 256;  // compute units of the one GPU this library is written for
 
 // Loads of tensor data name the global address space.  A pointer that comes out of a parameter
 // struct is a generic one to the compiler, and a generic ("flat") load is also counted by the
@@ -1104,6 +1105,9 @@ struct WHaloP {
 typedef __attribute__((address_space(3))) void lds_void_ptr;
 typedef __attribute__((address_space(1))) const void glb_void_ptr;
 
+// most load instructions a wavefront issues per segment (its slots' bookkeeping lives in registers)
+constexpr int WHALO_MAX_LPW = 4;
+
 // s_waitcnt on the vector-memory counter alone: returns when at most n of this wavefront's loads are outstanding
 __device__ __forceinline__ void wait_vmcnt_at_most(int n)
 {
@@ -1116,7 +1120,6 @@ __device__ __forceinline__ void wait_vmcnt_at_most(int n)
     }
 }
 
-constexpr int WHALO_MAX_LPW = 4;
 
 // KB, CB: output / input channels in units of 32; GR: input rows per workgroup.  The GR x KB x CB blocks of 32 x 32
 // that belong to one horizontal tap are dealt to GR/GW x KB/IW x CB/JW wavefronts, GW x IW x JW blocks each.
@@ -1350,25 +1353,15 @@ struct WHaloCfg {
 
 constexpr size_t WGRAD_WS_CAP = (size_t)64 << 20;
 
-// whether the halo kernel serves this geometry, and how: unit strides, a 3-wide filter, 32 or 64 channels on
-// both sides.  Rows per group: the three rows of one depth tap when a horizontal tap's accumulators fit 96 registers
-// (32 -> 32, 32 -> 64, 64 -> 32 channels), else one.  Wavefronts: one per 32 x 32 block and horizontal tap, or per pair
-// of blocks where 32 channels face 64 -- twelve for 64 -> 64 (one workgroup per compute unit, up to 150 KB of LDS),
-// nine for the three-row groups (two per compute unit, 76 KB each), three otherwise (four per compute unit, 38 KB each).
+// One way of running the halo kernel on a geometry: gr input rows per workgroup, `waves` wavefronts, an LDS budget per
+// workgroup, so many workgroups in all.
 // Segments: output rows cut into equal pieces of at most 64 pixels (a multiple of 8), as long as two buffers allow;
-// then up to four buffers.
-WHaloCfg whalo_cfg(const ConvGeom &g)
+// then up to four buffers.  use stays false where the variant cannot serve the geometry.
+WHaloCfg whalo_plan(const ConvGeom &g, int gr, int waves, size_t budget, int64_t workgroups)
 {
     WHaloCfg c{};
-    static const bool off = getenv("POOCH_NO_HALO_WGRAD") != nullptr;
-    if (off || g.sd != 1 || g.sh != 1 || g.sw != 1 || g.kw != 3) return c;
-    // 32 -> 32 and 64 -> 64 channels.  (Measured on the 3-d CNN's 32 -> 64 layer at 96^3: 71 TFLOP/s here against 80 with the
-    // generic kernel, whose tiles suit the mixed widths better; the kernel template covers them, the dispatch does not.)
-    if ((g.C != 32 && g.C != 64) || g.K != g.C) return c;
-    const int kb = g.K / 32, cb = g.C / 32;
-    c.gr = (g.kh == 3 && kb * cb * 3 * 16 <= 96) ? 3 : 1;
-    c.waves = c.gr == 3 ? 9 : (kb * cb == 4 ? 12 : 3);
-    const size_t budget = (c.waves == 12 ? 150 : (c.waves == 9 ? 76 : 38)) * 1024;
+    c.gr = gr;
+    c.waves = waves;
     const int qc = g.C / 4;
     auto shape = [&](int P) {
         const int pw_units = ((P + 2) * qc + 63) / 64 * 64;      // a row's 16-byte pieces, in whole 64-lane blocks
@@ -1396,28 +1389,54 @@ WHaloCfg whalo_cfg(const ConvGeom &g)
     if (nseg >= ((int64_t)1 << 30)) return c;
     c.nseg = (int)nseg;
     c.groups = g.kd * g.kh / c.gr;
-    // workgroups: about six per compute unit's worth of resident ones, within the workspace
-    int64_t ns = (c.waves == 12 ? 1536 : (c.waves == 9 ? 3072 : 6144)) / c.groups;
+    int64_t ns = workgroups / c.groups;
     const int64_t by_ws = (int64_t)(WGRAD_WS_CAP / ((size_t)g.K * g.taps() * g.C * sizeof(float)));
     if (ns > by_ws) ns = by_ws;
     if (ns > nseg) ns = nseg;
     if (ns < 1) ns = 1;
     c.seg_per_split = (int)((nseg + ns - 1) / ns);
     c.nsplit = (int)((nseg + c.seg_per_split - 1) / c.seg_per_split);
-    // A workgroup's partial block is written once per workgroup: with few segments each, that and the reduction
-    // outweigh the gain (ResNet-50's 3x3 64 -> 64 at batch 64: 72 TFLOP/s here against 80 generic, at batch 32 60 against 70;
-    // at batch 640, 92 against 80).  Problems too small to matter either way (under 2 GFLOP) stay here, so that small test
-    // shapes reach this kernel.
-    if (c.seg_per_split < 24 && 2.0 * (double)g.rows_out() * g.K * (double)(g.taps() * g.C) > 2e9) return WHaloCfg{};
+    // A workgroup's partial block is written once per workgroup: with very few segments each, that and the reduction
+    // outweigh the gain (3 x 3 x 3 64 -> 64 at 32^3, three segments per workgroup: 72 TFLOP/s here against 75 generic;
+    // from five on the kernels are level or this one ahead -- ResNet-50's 3 x 3 64 -> 64 at batch 16: 77 both, at batch 64: 96
+    // against 79; 3 x 3 x 3 32 -> 32 at 64^3: 83 against 58).  Problems too small to matter either way (under 2 GFLOP) stay
+    // here, so that small test shapes reach this kernel.
+    if (c.seg_per_split < 4 && 2.0 * (double)g.rows_out() * g.K * (double)(g.taps() * g.C) > 2e9) return c;
     c.use = true;
     return c;
+}
+
+// whether the halo kernel serves this geometry, and how: unit strides, a 3-wide filter, 32 or 64 channels on
+// both sides.  Rows per group: the three rows of one depth tap when a horizontal tap's accumulators fit 96 registers
+// (32 -> 32 channels), else one.  Wavefronts: one per 32 x 32 block and horizontal tap -- nine for the three-row groups
+// (two workgroups per compute unit, 76 KB of LDS each), twelve for 64 -> 64 (one workgroup per compute unit, up to 150 KB),
+// three for a single filter row of 32 -> 32 (four per compute unit, 38 KB each).
+// Workgroups: exactly as many as are resident at once, each walking its share of the segments from start to end.  More,
+// smaller shares cost a ring fill, a partial block written and a ragged last round each; measured stand-alone, warmed up:
+//   3 x 3 64 -> 64, 640 x 56 x 56 (twelve waves): 256 workgroups 105 TFLOP/s, 240: 99, 192: 80, 768: 105, 1536: 92
+//   3 x 3 x 3 32 -> 32 at 192^3 (nine waves):     512 workgroups 94, 480: 89, 384: 71, 1024: 73, 3072: 82
+//   3 x 3 x 3 64 -> 64 at 96^3 (twelve waves):    256 workgroups 98, 1536: 87
+// (One wavefront per horizontal tap holding all four blocks of 64 -> 64 -- one LDS read per MFMA instead of two, three waves
+// per workgroup, four workgroups per compute unit -- reached 99 on the last of these stand-alone and 74 inside a step, where
+// the four workgroups per compute unit it depends on do not come together; it was taken out again.)
+WHaloCfg whalo_cfg(const ConvGeom &g)
+{
+    static const bool off = getenv("POOCH_NO_HALO_WGRAD") != nullptr;
+    if (off || g.sd != 1 || g.sh != 1 || g.sw != 1 || g.kw != 3) return WHaloCfg{};
+    // 32 -> 32 and 64 -> 64 channels.  (Measured on the 3-d CNN's 32 -> 64 layer at 96^3: 71 TFLOP/s here against 80 with the
+    // generic kernel, whose tiles suit the mixed widths better; the kernel template covers them, the dispatch does not.)
+    if ((g.C != 32 && g.C != 64) || g.K != g.C) return WHaloCfg{};
+    WHaloCfg c;
+    if (g.C == 32) c = g.kh == 3 ? whalo_plan(g, 3, 9, 76 * 1024, 2 * NCU) : whalo_plan(g, 1, 3, 38 * 1024, 4 * NCU);
+    else c = whalo_plan(g, 1, 12, 150 * 1024, NCU);
+    return c.use ? c : WHaloCfg{};
 }
 
 template <int KB, int CB, int GR, int GW, int IW, int JW>
 hipError_t launch_whalo(WHaloP p, const WHaloCfg &c, hipStream_t s)
 {
     constexpr int NWV = 3 * (GR / GW) * (KB / IW) * (CB / JW);
-    if (c.waves != NWV) return hipErrorInvalidValue;
+    if (c.waves != NWV || c.lpw > WHALO_MAX_LPW) return hipErrorInvalidValue;
     p.total = p.nsplit * p.groups;
     p.chunk = (p.total + NXCD - 1) / NXCD;
     if (c.lds_bytes > 64 * 1024) {   // more dynamic LDS than the default limit: raised once per kernel (no allocation)
@@ -1457,7 +1476,8 @@ WGradCfg wgrad_cfg(const ConvGeom &g)
     // (up to 32 output channels: 3x3x3 32->32 at 192^3 6.8 ms at 128 against 7.7 ms at 64)
     c.bn = (Kred <= 64 || (c.bm == 64 && g.C % 16 == 0 && g.taps() > 1)) ? 64 : 128;
     const int64_t tiles = ((g.K + c.bm - 1) / c.bm) * ((Kred + c.bn - 1) / c.bn);
-    // enough workgroups to fill 256 compute units several times over, but each split keeps at
+    // about as many workgroups as are resident at once (four per compute unit; measured on ResNet-50's layers at batch 640:
+    // a target of 512 or 768 loses up to 45 %, 1536 and 2048 are level with 1024), but each split keeps at
     // least 256 rows so that its epilogue (a full tile written to the workspace) stays small
     int64_t ns = (1024 + tiles - 1) / tiles;
     const int64_t max_by_rows = (M + 255) / 256;

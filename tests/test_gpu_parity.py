@@ -796,6 +796,8 @@ def test_volume_tiles_bricks_and_wide_slices(x_shape, c1, c2, wide):
     ((2, 32, 5, 6, 66), 32, (3, 3, 3), (1, 1, 1)),    # 3-d, two segments per row, the second ragged
     ((2, 64, 4, 5, 6), 64, (3, 3, 3), (1, 0, 1)),     # 3-d 64 -> 64: one row per group, nine groups
     ((2, 64, 150, 6), 64, (3, 3), (1, 1)),            # more segments than workgroups want: several per split
+    ((2, 64, 6, 64), 64, (3, 3), (1, 1)),             # rows that fill one 64-pixel segment exactly
+    ((3, 64, 5, 96), 64, (3, 3), (0, 1)),             # two segments of 48 pixels per row, no vertical padding
 ])
 def test_filter_gradient_with_shared_taps(x_shape, cout, k, pad):
     """the filter-gradient kernel for 32 / 64 channels under a 3-wide filter (input rows staged once in LDS and
