@@ -188,9 +188,8 @@ class Context:
                 raise RuntimeError("no GPU: a compute context needs one (use device=None for planning only)")
             self.torch = torch
             self.device = torch.device(device)
-            # Blocks that torch's caching allocator still holds from earlier contexts go back to the driver first: an arena
-            # carved out of device memory they had fragmented was seen to run the same step 30 % slower (one strided
-            # scatter 90 times slower), which fits small page-table fragments under it.
+            # blocks that torch's caching allocator still holds from earlier contexts go back to the driver first, so that
+            # an arena close to the device's capacity fits after smaller ones
             torch.cuda.empty_cache()
             self.arena = torch.empty(self.budget_bytes, dtype=torch.uint8, device=self.device)
             assert self.arena.data_ptr() % 256 == 0
