@@ -1408,7 +1408,7 @@ WHaloCfg whalo_plan(const ConvGeom &g, int gr, int waves, size_t budget, int64_t
 
 // whether the halo kernel serves this geometry, and how: unit strides, a 3-wide filter, 32 or 64 channels on
 // both sides.  Rows per group: the three rows of one depth tap when a horizontal tap's accumulators fit 96 registers
-// (32 -> 32 channels), else one.  Wavefronts: one per 32 x 32 block and horizontal tap -- nine for the three-row groups
+// (32 -> 32, 32 -> 64, 64 -> 32 channels), else one.  Wavefronts: one per 32 x 32 block and horizontal tap -- nine for the three-row groups
 // (two workgroups per compute unit, 76 KB of LDS each), twelve for 64 -> 64 (one workgroup per compute unit, up to 150 KB),
 // three for a single filter row of 32 -> 32 (four per compute unit, 38 KB each).
 // Workgroups: exactly as many as are resident at once, each walking its share of the segments from start to end.  More,
@@ -1423,11 +1423,13 @@ WHaloCfg whalo_cfg(const ConvGeom &g)
 {
     static const bool off = getenv("POOCH_NO_HALO_WGRAD") != nullptr;
     if (off || g.sd != 1 || g.sh != 1 || g.sw != 1 || g.kw != 3) return WHaloCfg{};
-    // 32 -> 32 and 64 -> 64 channels.  (Measured on the 3-d CNN's 32 -> 64 layer at 96^3: 71 TFLOP/s here against 80 with the
-    // generic kernel, whose tiles suit the mixed widths better; the kernel template covers them, the dispatch does not.)
-    if ((g.C != 32 && g.C != 64) || g.K != g.C) return WHaloCfg{};
+    // 32 or 64 channels on either side; mixed widths (each wave holds the two blocks of its row and tap) only with three
+    // filter rows per group.  (3 x 3 x 3 32 -> 64 at 96^3: 95 TFLOP/s against 80 with the generic kernel, 64 -> 32: 85 against 60.)
+    if ((g.C != 32 && g.C != 64) || (g.K != 32 && g.K != 64)) return WHaloCfg{};
+    if (g.K != g.C && g.kh != 3) return WHaloCfg{};
     WHaloCfg c;
-    if (g.C == 32) c = g.kh == 3 ? whalo_plan(g, 3, 9, 76 * 1024, 2 * NCU) : whalo_plan(g, 1, 3, 38 * 1024, 4 * NCU);
+    if (g.K != g.C) c = whalo_plan(g, 3, 9, 76 * 1024, 2 * NCU);
+    else if (g.C == 32) c = g.kh == 3 ? whalo_plan(g, 3, 9, 76 * 1024, 2 * NCU) : whalo_plan(g, 1, 3, 38 * 1024, 4 * NCU);
     else c = whalo_plan(g, 1, 12, 150 * 1024, NCU);
     return c.use ? c : WHaloCfg{};
 }
@@ -1454,6 +1456,8 @@ hipError_t launch_whalo(WHaloP p, const WHaloCfg &c, hipStream_t s)
 
 hipError_t dispatch_whalo(const WHaloP &hp, const WHaloCfg &hc, hipStream_t s)
 {
+    if (hp.K == 64 && hp.C == 32) return hc.gr == 3 ? launch_whalo<2, 1, 3, 1, 2, 1>(hp, hc, s) : hipErrorInvalidValue;
+    if (hp.K == 32 && hp.C == 64) return hc.gr == 3 ? launch_whalo<1, 2, 3, 1, 1, 2>(hp, hc, s) : hipErrorInvalidValue;
     if (hp.K != hp.C) return hipErrorInvalidValue;
     if (hp.K == 32) return hc.gr == 3 ? launch_whalo<1, 1, 3, 1, 1, 1>(hp, hc, s) : launch_whalo<1, 1, 1, 1, 1, 1>(hp, hc, s);
     return hc.gr == 1 ? launch_whalo<2, 2, 1, 1, 1, 1>(hp, hc, s) : hipErrorInvalidValue;
@@ -1668,6 +1672,7 @@ const char *conv_wgrad_kernel(const ConvGeom &g)
     if (geom_ok(g)) {
         const WHaloCfg hc = whalo_cfg(g);
         if (hc.use) {
+            if (g.K != g.C) return g.K == 64 ? "wgrad_halo_kernel<2,1,3>" : "wgrad_halo_kernel<1,2,3>";
             return g.K == 32 ? (hc.gr == 3 ? "wgrad_halo_kernel<1,1,3>" : "wgrad_halo_kernel<1,1,1>") : "wgrad_halo_kernel<2,2,1>";
         }
     }

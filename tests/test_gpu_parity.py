@@ -798,9 +798,13 @@ def test_volume_tiles_bricks_and_wide_slices(x_shape, c1, c2, wide):
     ((2, 64, 150, 6), 64, (3, 3), (1, 1)),            # more segments than workgroups want: several per split
     ((2, 64, 6, 64), 64, (3, 3), (1, 1)),             # rows that fill one 64-pixel segment exactly
     ((3, 64, 5, 96), 64, (3, 3), (0, 1)),             # two segments of 48 pixels per row, no vertical padding
+    ((2, 32, 6, 7, 9), 64, (3, 3, 3), (1, 1, 1)),     # mixed widths, 32 -> 64: each wave holds the two output blocks of its row and tap
+    ((2, 64, 5, 6, 66), 32, (3, 3, 3), (1, 1, 1)),    # 64 -> 32, two segments per row, the second ragged
+    ((3, 32, 9, 70), 64, (3, 3), (1, 1)),             # 32 -> 64 in 2-d
+    ((2, 64, 8, 24), 32, (3, 3), (0, 1)),             # 64 -> 32 in 2-d, no vertical padding
 ])
 def test_filter_gradient_with_shared_taps(x_shape, cout, k, pad):
-    """the filter-gradient kernel for 32 / 64 channels under a 3-wide filter (input rows staged once in LDS and
+    """the filter-gradient kernel for 32 / 64 channels (on either side) under a 3-wide filter (input rows staged once in LDS and
     shared by the horizontal taps): ragged segment tails, all padding cases, 2-d and 3-d, against the oracle"""
     net = kinkless_probe(x_shape, cout, k, (1,) * len(k), pad, True)
     c = B.Context(net, 1 << 30, device=None)
