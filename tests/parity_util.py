@@ -6,7 +6,9 @@ import numpy as np
 
 RTOL = 1e-3     # the bar the benchmark spec fixes for fp32, applied per tensor to both measures of errs()
 
-_PROGRESS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "gpu_tests_progress.log")
+# where the progress lines go besides stdout: POOCH_TEST_LOG_DIR, else the output folder next to tests/ that is listed in .gitignore
+_PROGRESS = os.path.join(os.environ.get("POOCH_TEST_LOG_DIR") or
+                         os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out"), "gpu_tests_progress.log")
 
 
 def say(*a):
