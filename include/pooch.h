@@ -76,7 +76,8 @@ enum {
 
 /* ---- context ------------------------------------------------------------------------
  * arena        DEVICE pointer, 256-byte aligned, arena_bytes long (== the budget); may be
- *              NULL for a planning-only context (arena_bytes still sets the budget).
+ *              NULL for a planning-only context (arena_bytes still sets the budget).  The budget
+ *              counts in whole 256-byte units: a tail of arena_bytes % 256 bytes is never used.
  * pinned_host  pinned HOST buffer that receives swapped-out maps; may be NULL/0 when no
  *              plan ever swaps.
  * stream_*     hipStream_t handles passed as void*: compute, device-to-host, host-to-device.

@@ -479,7 +479,7 @@ pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool 
     }
     Exec X(c, S, static_scratch);
     const Graph &G = c->G;
-    auto in_arena = [&](int64_t off, int64_t bytes) { return off == OFF_INPUT || off == OFF_NONE || (off >= 0 && off + bytes <= cap); };
+    auto in_arena = [&](int64_t off, int64_t bytes) { return off == OFF_INPUT || off == OFF_NONE || (off >= 0 && off % ALIGN == 0 && off + bytes <= cap); };
     for (size_t k = 0; k < S.cmds.size(); ++k) {
         const Cmd &cm = S.cmds[k];
         const int stream = cm.kind <= K_BWD ? S_COMPUTE : (cm.kind == K_OUT ? S_D2H : (cm.kind == K_IN ? S_H2D : cm.id));
@@ -492,7 +492,13 @@ pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool 
         case K_FWD: case K_REFWD: {
             const int i = cm.id;
             if (!in_arena(cm.a[0], G.bytes[i])) return fail(c, POOCH_E_INVALID, "command outside the arena");
-            HIPCHK(X.forward(i, cm.a[0], cm.a[1], cm.a[2], cm.kind == K_REFWD));
+            {
+                const hipError_t fe = X.forward(i, cm.a[0], cm.a[1], cm.a[2], cm.kind == K_REFWD);
+                if (fe != hipSuccess)
+                    return fail(c, POOCH_E_HIP, std::string(cm.kind == K_REFWD ? "re-forward" : "forward") + " of node " + std::to_string(i) +
+                                                    " (command " + std::to_string(k) + ", offsets " + std::to_string(cm.a[0]) + " " + std::to_string(cm.a[1]) + " " +
+                                                    std::to_string(cm.a[2]) + "): " + hipGetErrorString(fe));
+            }
             if (tm && tm->start[k] >= 0) HIPCHK(hipEventRecord(c->timing_events[tm->stop[k]], c->st[stream]));
             if (tm && tm->rstart[k] >= 0) {
                 HIPCHK(X.forward(i, cm.a[0], cm.a[1], cm.a[2], true));
@@ -510,8 +516,12 @@ pooch_status enqueue_schedule(pooch_ctx *c, const Schedule &S, Timing *tm, bool 
                 if (cm.a[3 + 2 * j] != M_NONE && !in_arena(cm.a[2 + 2 * j], G.gbytes[G.nodes[i].in[j]]))
                     return fail(c, POOCH_E_INVALID, "command outside the arena");
             X.mid = (tm && tm->mid[k] >= 0) ? c->timing_events[tm->mid[k]] : nullptr;
-            HIPCHK(X.backward(i, cm.a));
-            X.mid = nullptr;
+            {
+                const hipError_t be = X.backward(i, cm.a);
+                X.mid = nullptr;
+                if (be != hipSuccess)
+                    return fail(c, POOCH_E_HIP, "backward of node " + std::to_string(i) + " (command " + std::to_string(k) + "): " + hipGetErrorString(be));
+            }
             if (tm && tm->start[k] >= 0) HIPCHK(hipEventRecord(c->timing_events[tm->stop[k]], c->st[stream]));
             break;
         }
@@ -660,7 +670,9 @@ pooch_status pooch_create(void *arena, size_t arena_bytes, void *pinned_host, si
     pooch_ctx *c = new (std::nothrow) pooch_ctx();
     if (!c) return POOCH_E_INVALID;
     c->arena = static_cast<char *>(arena);
-    c->arena_bytes = arena_bytes;
+    // whole 256-byte units only: ranges carved from the top of the dynamic region start at (capacity - size), which
+    // has to be as aligned as every other offset (a budget of an odd number of bytes gave a convolution an odd address)
+    c->arena_bytes = arena_bytes / ALIGN * ALIGN;
     c->pinned = static_cast<char *>(pinned_host);
     c->pinned_bytes = pinned_bytes;
     c->st[0] = static_cast<hipStream_t>(stream_compute);

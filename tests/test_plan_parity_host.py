@@ -91,6 +91,34 @@ def test_feature_maps_and_command_lists_identical(name, fuse):
     assert ncmp > 20
 
 
+def test_budget_of_an_odd_number_of_bytes_counts_in_whole_units():
+    """ranges carved from the top of the dynamic region sit at (capacity - size): with a budget that is no multiple of
+    256 they would be misaligned; the library uses the whole 256-byte units of the budget and plans as the oracle
+    does for that many"""
+    net = workloads.tiny_cnn()
+    G = P.Graph(net, fuse=True)
+    incore = P.build_schedule(G, [P.KEEP] * len(G.fmaps), BIG, True)
+    cap = int(incore.peak * 0.7) // 256 * 256
+    res = B.Context(net, 1 << 40, device=None).resident_bytes()
+    c = B.Context(net, res + cap + 131, device=None)
+    c.set_profile(*rand_profile(G, np.random.default_rng(5)))
+    rng = np.random.default_rng(11)
+    done = 0
+    for trial in range(30):
+        cls = [int(v) for v in rng.integers(0, 3, len(G.fmaps))]
+        try:
+            S = P.build_schedule(G, cls, cap, True)
+        except P.Budget:
+            continue
+        c.set_plan(cls, True)
+        rows = c.commands()
+        assert np.array_equal(rows, as_rows(S))
+        schedule_check.check(G, [tuple(int(v) for v in r) for r in rows], cap)      # (asserts 256-byte offsets)
+        done += 1
+    assert done >= 5
+    assert c.stats().arena_bytes == res + cap
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_every_mode_picks_the_oracles_plan(seed):
     rng = np.random.default_rng(100 + seed)
