@@ -283,6 +283,9 @@ def test_random_graphs_vs_oracle_and_random_plans():
                 continue
             l1, g1, _, _ = gpu_step(net, params, x, t, cls=cls, sched=True, dyn_bytes=cap)
             assert_bit_exact("random graph %d trial %d" % (seed, trial), (loss, grads), (l1, g1))
+            if ran == 0:    # a budget that is no multiple of 256 bytes: its whole units are used, every offset stays aligned
+                l2, g2, _, _ = gpu_step(net, params, x, t, cls=cls, sched=True, dyn_bytes=cap + 77)
+                assert_bit_exact("random graph %d trial %d, odd budget" % (seed, trial), (loss, grads), (l2, g2))
             ran += 1
             if ran >= 2:
                 break
