@@ -258,8 +258,25 @@ def main():
         arena_bytes = incore_bytes
     else:
         arena_bytes = int(budget * 2 ** 30)
+    arena_bytes = arena_bytes // 256 * 256          # (the library counts the budget in whole 256-byte units)
     under_budget = arena_bytes < incore_bytes
     fm_bytes = sum(b for b, _ in B.Context(net, 1 << 46, device=None).fmaps())
+    if under_budget:
+        # The profiling pass runs every map as swap, and whether that fits is not monotone in the arena (the static
+        # allocator's placement depends on the capacity): a smaller arena is always within the budget, so step down by 1 %
+        # of the in-core arena at a time, ten times at most, until it does, and say which arena was used.
+        asked = arena_bytes
+        for _ in range(11):
+            try:
+                probe = B.Context(net, arena_bytes, device=None)
+                probe.simulate([B.SWAP] * probe.n_fmaps, want_time=False)
+                break
+            except B.BudgetError:
+                arena_bytes = (arena_bytes - incore_bytes // 100) // 256 * 256
+        else:
+            sys.exit("bench.py: the all-swap profiling pass fits neither %.3f GiB nor up to 10 %% of the in-core arena less" % (asked / 2 ** 30))
+        if arena_bytes != asked:
+            log("[bench] the all-swap profiling pass does not fit %.3f GiB; using %.3f GiB of it" % (asked / 2 ** 30, arena_bytes / 2 ** 30))
     log("[bench] %s: batch %d, %d layers, feature maps %.2f GB, in-core arena %.2f GB, arena %.2f GB" %
         (args.workload, batch, len(net), fm_bytes / 1e9, incore_bytes / 1e9, arena_bytes / 1e9))
 
