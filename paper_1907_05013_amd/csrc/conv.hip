@@ -706,6 +706,211 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     __builtin_nontemporal_store(v, dp);
 }
 
+// ---- 3 x 3 x 3, unit stride, padding 1, 32 -> 32 channels: the input brick stays in LDS ---------------------------------
+// The first level of a 3-d CNN on a 192^3 volume: the reduction is only 864 long, so igemm_kernel stages 27 slices
+// per tile through LDS with a barrier after each and runs at about 105 TFLOP/s.  Here a workgroup of four waves owns
+// a brick of 2 x 8 x 8 output positions (128 GEMM rows, one 32 x 32 block per wave).  It loads the 4 x 10 x 10 input
+// positions the brick's 27 taps touch into LDS ONCE (57.6 KB with rows padded to 36 floats: two workgroups per CU),
+// and the tap loop then reads its A operand straight from that copy -- no staging, no barrier, no address arithmetic
+// beyond a constant per tap.  The B operand (one tap's 32 x 32 filter slice, 4 KB) comes from global memory through
+// the caches, a tap ahead, like A.  Lane (r, h) feeds reduction steps (c = t, c = 16 + t) for t = 0..15, so both of
+// its operands are 64 contiguous bytes.
+// The data gradient is the same convolution over dy with the taps mirrored (position tap t' uses filter tap 26 - t')
+// and the transposed filter copy, which has the same [out][tap][in] layout.
+// Measured on 1 x 192^3 x 32 (stand-alone, warm clocks): 124 TFLOP/s against 105 for igemm_kernel; with LDS filled
+// from registers instead of global memory and no stores the same loop runs at 130, so little is left in this design.
+// (Two variants that were not kept: a persistent workgroup that prefetches the next brick into registers during the
+// tap loop -- 109 TFLOP/s, the in-order counter of outstanding loads makes the filter loads wait for the brick's --
+// and a swizzled, unpadded brick that admits three workgroups per CU -- 118.)
+constexpr int C3_BD = 2, C3_BH = 8, C3_BW = 8, C3_C = 32;
+constexpr int C3_HD = C3_BD + 2, C3_HH = C3_BH + 2, C3_HW = C3_BW + 2, C3_NPIX = C3_HD * C3_HH * C3_HW;
+constexpr int C3_LP = 36;   // floats per pixel in LDS: 16-byte aligned, and eight consecutive pixels start in different banks
+
+template <bool DGRAD, bool ACCUM, bool STATS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv3_halo_kernel(IGemmP p)
+{
+    __shared__ __attribute__((aligned(16))) float brick[C3_NPIX * C3_LP];
+    const int tid = threadIdx.x, lane = tid % 64, r = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int D = p.Dr, H = p.Hr, W = p.Wr;
+    const int nbw = W / C3_BW, nbh = H / C3_BH, nbd = D / C3_BD;
+    int t = blockIdx.x;
+    const int w0 = (t % nbw) * C3_BW; t /= nbw;
+    const int h0 = (t % nbh) * C3_BH; t /= nbh;
+    const int d0 = (t % nbd) * C3_BD;
+    const int n = t / nbd;
+    const float *x = p.src + (int64_t)n * D * H * W * C3_C;
+    {
+        // a halo line (pd, ph) is 10 pixels = 1280 contiguous bytes = 80 lanes x 16 bytes; wave w takes lines w, w + 4, ...
+        // (line numbers, validity and addresses are wave-uniform: scalar arithmetic)
+        constexpr int NL = C3_HD * C3_HH / 4;
+        f32x4 v0[NL], v1[NL];
+        const int pw0 = lane / 8, q4 = 4 * (lane % 8);
+        const bool in0 = !(w0 == 0 && pw0 == 0);                          // pixel w0 - 1 + pw0, pw0 = 0..7
+        const bool in1 = lane < 16 && !(w0 + C3_BW == W && pw0 == 1);     // pixels w0 + 7 and w0 + 8
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < NL; ++k) {
+            const int line = wave + 4 * k, pd = line / C3_HH, ph = line % C3_HH;
+            const int id = d0 + pd - 1, ih = h0 + ph - 1;
+            const bool lok = (unsigned)id < (unsigned)D && (unsigned)ih < (unsigned)H;
+            const float *src = x + ((((int64_t)(lok ? id : 0) * H + (lok ? ih : 0)) * W + w0) * C3_C - C3_C);
+            v0[k] = (lok && in0) ? ldg4(src + 4 * lane) : z;
+            v1[k] = (lok && in1) ? ldg4(src + 4 * lane + 256) : z;
+        }
+#pragma unroll
+        for (int k = 0; k < NL; ++k) {
+            const int line = wave + 4 * k;
+            float *dst = brick + (line * C3_HW + pw0) * C3_LP + q4;
+            *reinterpret_cast<f32x4 *>(dst) = v0[k];
+            if (lane < 16) *reinterpret_cast<f32x4 *>(dst + 8 * C3_LP) = v1[k];
+        }
+    }
+    __syncthreads();
+    const int R = wave * 32 + r;                                          // this lane's GEMM row within the brick
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const float *abase = brick + (((R / 64) * C3_HH + (R / 8) % 8) * C3_HW + R % 8) * C3_LP + h * 16;
+    const float *bbase = p.wgt + (r * 27 * C3_C + h * 16);
+    f32x4 a0[4], b0[4], a1[4], b1[4];
+    auto load = [&](f32x4 (&a)[4], f32x4 (&b)[4], int tap) {
+        const int ta = tap / 9, tb = (tap / 3) % 3, te = tap % 3;
+        const float *ap = abase + ((ta * C3_HH + tb) * C3_HW + te) * C3_LP;
+        const float *bp = bbase + (DGRAD ? 26 - tap : tap) * C3_C;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[i] = *reinterpret_cast<const f32x4 *>(ap + 4 * i);
+            b[i] = ldg4(bp + 4 * i);
+        }
+    };
+    auto mul = [&](const f32x4 (&a)[4], const f32x4 (&b)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(b[i][j], a[i][j], acc, 0, 0, 0);
+    };
+    // loads of tap t + 1 are issued before the MFMAs of tap t; the fences keep the compiler from sinking them to their
+    // first use (which it does to save registers, and which leaves every tap waiting for its own loads)
+    load(a0, b0, 0);
+#pragma unroll 1
+    for (int tap = 0; tap < 26; tap += 2) {
+        load(a1, b1, tap + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mul(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        load(a0, b0, tap + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mul(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    mul(a0, b0);
+
+    // Accumulator element v of lane (r, h) is output channel 8 * (v / 4) + 4 * h + v % 4 of row r.  Through LDS (the
+    // brick's space, once every wave is done with it), so that a store covers whole 128-byte rows.
+    __syncthreads();
+    float *cw = brick + wave * 32 * C3_LP;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const f32x4 val = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+        *reinterpret_cast<f32x4 *>(&cw[r * C3_LP + 8 * g + 4 * h]) = val;
+    }
+    __syncthreads();
+    const int orow = lane / 8, ocol = 4 * (lane % 8);
+    f32x4 vq[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = wave * 32 + q * 8 + orow;
+        const int64_t m = (((int64_t)n * D + d0 + row / 64) * H + h0 + (row / 8) % 8) * W + w0 + row % 8;
+        f32x4 val = *reinterpret_cast<const f32x4 *>(&cw[(q * 8 + orow) * C3_LP + ocol]);
+        vq[q] = val;
+        f32x4 *dp = reinterpret_cast<f32x4 *>(p.dst + m * C3_C + ocol);
+        if (ACCUM) val = __builtin_nontemporal_load(dp) + val;
+        __builtin_nontemporal_store(val, dp);
+    }
+    if constexpr (STATS) {
+        // mean and sum of squared deviations (M2) of the brick's 128 rows per channel, like igemm_kernel's: per wave over
+        // its 32 rows (mean first, then M2 about it), the four waves merged in order by the pairwise update of Chan et al.
+        f32x4 sum = (vq[0] + vq[1]) + (vq[2] + vq[3]);
+#pragma unroll
+        for (int mask = 8; mask < 64; mask <<= 1) {
+            sum.x += __shfl_xor(sum.x, mask, 64); sum.y += __shfl_xor(sum.y, mask, 64);
+            sum.z += __shfl_xor(sum.z, mask, 64); sum.w += __shfl_xor(sum.w, mask, 64);
+        }
+        f32x4 rmean = sum / 32.f;
+        f32x4 rm2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 d = vq[q] - rmean;
+            rm2 += d * d;
+        }
+#pragma unroll
+        for (int mask = 8; mask < 64; mask <<= 1) {
+            rm2.x += __shfl_xor(rm2.x, mask, 64); rm2.y += __shfl_xor(rm2.y, mask, 64);
+            rm2.z += __shfl_xor(rm2.z, mask, 64); rm2.w += __shfl_xor(rm2.w, mask, 64);
+        }
+        __syncthreads();                                  // the staging rows have been read
+        float *sm = brick;                                // [wave][mean, M2][32]
+        if (orow == 0) {
+            *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 0) * 32 + ocol]) = rmean;
+            *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 1) * 32 + ocol]) = rm2;
+        }
+        __syncthreads();
+        if (wave == 0 && orow == 0) {
+            float rn = 32.f;
+#pragma unroll
+            for (int w2 = 1; w2 < 4; ++w2) {
+                const f32x4 mb = *reinterpret_cast<const f32x4 *>(&sm[(w2 * 2 + 0) * 32 + ocol]);
+                const f32x4 d2 = *reinterpret_cast<const f32x4 *>(&sm[(w2 * 2 + 1) * 32 + ocol]);
+                const float tot = rn + 32.f;
+                const f32x4 delta = mb - rmean;
+                rmean += delta * (32.f / tot);
+                rm2 += d2 + delta * delta * (rn * 32.f / tot);
+                rn = tot;
+            }
+            const int64_t tm = blockIdx.x;
+            *reinterpret_cast<f32x4 *>(p.stats + (tm * 2 + 0) * C3_C + ocol) = rmean;
+            *reinterpret_cast<f32x4 *>(p.stats + (tm * 2 + 1) * C3_C + ocol) = rm2;
+        }
+    }
+}
+
+// whether conv3_halo_kernel serves this GEMM: the geometry it is written for (small volumes too: its 128-row bricks give a
+// short launch more workgroups than igemm_kernel's 256-row tiles)
+template <bool DGRAD>
+bool conv3_halo_ok(const IGemmP &p, bool vec)
+{
+    static const bool off = getenv("POOCH_NO_CONV3_HALO") != nullptr;
+    if (off || !vec || p.dst_strided) return false;
+    if (p.kd != 3 || p.kh != 3 || p.kw != 3 || p.sd != 1 || p.sh != 1 || p.sw != 1 || p.pd != 1 || p.ph != 1 || p.pw != 1) return false;
+    if (p.Cs != C3_C || p.Nout != C3_C || p.Kred != 27 * C3_C) return false;
+    if (p.Ds != p.Dr || p.Hs != p.Hr || p.Ws != p.Wr) return false;
+    if (p.Dr % C3_BD != 0 || p.Hr % C3_BH != 0 || p.Wr % C3_BW != 0) return false;
+    return p.M >= C3_BD * C3_BH * C3_BW;
+}
+
+template <bool DGRAD>
+hipError_t launch_conv3_halo(const IGemmP &p, bool accum, hipStream_t s, int *stats_tiles)
+{
+    const int bricks = p.M / (C3_BD * C3_BH * C3_BW);
+    if (stats_tiles) {
+        stats_tiles[0] = bricks;
+        stats_tiles[1] = C3_BD * C3_BH * C3_BW;
+        return hipSuccess;
+    }
+    const dim3 grid(bricks), block(256);
+    if constexpr (DGRAD) {
+        if (p.stats) return hipErrorInvalidValue;
+        if (accum) conv3_halo_kernel<true, true, false><<<grid, block, 0, s>>>(p);
+        else conv3_halo_kernel<true, false, false><<<grid, block, 0, s>>>(p);
+    } else {
+        if (accum) return hipErrorInvalidValue;
+        if (p.stats) conv3_halo_kernel<false, false, true><<<grid, block, 0, s>>>(p);
+        else conv3_halo_kernel<false, false, false><<<grid, block, 0, s>>>(p);
+    }
+    return hipGetLastError();
+}
+
 template <bool DGRAD>
 hipError_t dispatch_igemm(const IGemmP &p0, bool accum, hipStream_t s, int *stats_tiles = nullptr, float *workspace = nullptr)
 {
@@ -738,6 +943,7 @@ hipError_t dispatch_igemm(const IGemmP &p0, bool accum, hipStream_t s, int *stat
     // slices where a tap spans whole ones (3 x 3 x 3, 32 -> 32 at 192^3: forward 104 -> 108 TFLOP/s, data gradient 98 -> 108;
     // the wider tiles lose 3 % under 3 x 3 filters and gain 1 % at most under 1 x 1)
     if (p.Nout <= 32) {
+        if (conv3_halo_ok<DGRAD>(p, vec) && !(accum && !DGRAD)) return launch_conv3_halo<DGRAD>(p, accum, s, stats_tiles);
         static const bool narrow = getenv("POOCH_NO_WIDE_SLICE") != nullptr;
         if (!narrow && lin == 1 && p.Cs % 32 == 0) return launch_igemm<4, 1, 2, 1, 32, DGRAD>(p, vec, lin, accum, s, stats_tiles);
         return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
@@ -1535,6 +1741,18 @@ IGemmP fwd_params(const float *x, const float *w_krsc, float *y, const ConvGeom 
     p.dst_strided = 0; p.DD = p.HD = p.WD = p.SD = p.SH = p.SW = 0;
     return p;
 }
+
+// the data gradient as a GEMM over the INPUT positions (not the scatter form of a strided 1 x 1 filter)
+IGemmP dgrad_params(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g)
+{
+    IGemmP p;
+    p.src = dy; p.wgt = w_crsk; p.dst = dx; p.stats = nullptr;
+    p.M = (int)g.rows_in(); p.Nout = g.C; p.Kred = (int)(g.taps() * g.K); p.Cs = g.K;
+    p.Dr = g.D; p.Hr = g.H; p.Wr = g.W; p.Ds = g.Do; p.Hs = g.Ho; p.Ws = g.Wo;
+    p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
+    p.dst_strided = 0; p.DD = p.HD = p.WD = p.SD = p.SH = p.SW = 0;
+    return p;
+}
 }  // namespace
 
 bool conv_fwd_bn_tiles(const float *x, const float *w_krsc, const ConvGeom &g, int *tiles_m, int *rows_per_tile)
@@ -1604,11 +1822,7 @@ hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const Con
         // rows that are not written keep their zeros, so the scatter always adds
         return dispatch_igemm<false>(p, true, s);
     }
-    p.src = dy; p.wgt = w_crsk; p.dst = dx;
-    p.M = (int)g.rows_in(); p.Nout = g.C; p.Kred = (int)(g.taps() * g.K); p.Cs = g.K;
-    p.Dr = g.D; p.Hr = g.H; p.Wr = g.W; p.Ds = g.Do; p.Hs = g.Ho; p.Ws = g.Wo;
-    p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
-    p.dst_strided = 0; p.DD = p.HD = p.WD = p.SD = p.SH = p.SW = 0;
+    p = dgrad_params(dy, w_crsk, dx, g);
     return dispatch_igemm<true>(p, accumulate, s, nullptr, workspace);
 }
 
@@ -1645,6 +1859,7 @@ const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgr
 
 const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
 {
+    if (conv3_halo_ok<false>(fwd_params(nullptr, nullptr, nullptr, g), true)) return bn_tiles ? "conv3_halo_kernel<fwd+bnstats>" : "conv3_halo_kernel<fwd>";
     const bool one_tap = g.taps() == 1 && g.pd == 0 && g.ph == 0 && g.pw == 0;
     const char *plain = igemm_tag(g.rows_out(), g.K, g.C, true, false, (int)(g.taps() * g.C), one_tap);
     if (!bn_tiles) return plain;
@@ -1663,6 +1878,7 @@ const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
 const char *conv_dgrad_kernel(const ConvGeom &g)
 {
     if (pointwise_strided(g)) return igemm_tag(g.rows_out(), g.C, g.K, true, false, 0, true);   // scatter GEMM over the output rows (never split)
+    if (conv3_halo_ok<true>(dgrad_params(nullptr, nullptr, nullptr, g), true)) return "conv3_halo_kernel<dgrad>";
     const bool one_tap = g.taps() == 1 && g.pd == 0 && g.ph == 0 && g.pw == 0;
     return igemm_tag(g.rows_in(), g.C, g.K, g.sd == 1 && g.sh == 1 && g.sw == 1, true, (int)(g.taps() * g.K), one_tap);
 }

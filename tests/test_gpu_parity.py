@@ -767,14 +767,14 @@ def test_conv_bn_shapes_full_size_without_kinks(x_shape, cout, k, stride, pad):
     check_against_oracle("probe %s -> %d k%s s%s" % (x_shape, cout, k, stride), net, 123, capture=False)
 
 
-@pytest.mark.parametrize("x_shape,c1,c2,wide", [
-    ((2, 16, 8, 16, 24), 32, 32, (True, True)),       # 32 -> 32: 32-wide slices forward and backward, bricks of 4 x 8 x 8
-    ((1, 32, 12, 8, 16), 64, 32, (True, False)),      # 64 -> 32: wide slices forward; the data gradient has 64 columns (16-wide slices)
-    ((2, 16, 6, 8, 8), 136, 16, (False, False)),      # 136 -> 16: quarter-size tiles backward (bricks of 1 x 8 x 8), 16-channel slices
+@pytest.mark.parametrize("x_shape,c1,c2,kernels", [
+    ((2, 16, 8, 16, 12), 32, 32, ("lin32", "lin32")),         # 32 -> 32, a width that is no multiple of 8: 32-wide slices forward and backward
+    ((1, 32, 12, 8, 16), 64, 32, ("lin32", "vec+lin,")),      # 64 -> 32: wide slices forward, bricks of 4 x 8 x 8; the data gradient has 64 columns (16-wide slices)
+    ((2, 16, 6, 8, 8), 136, 16, ("<4,1,2,1,vec,fwd", "<2,2,1,1,")),  # 136 -> 16: quarter-size tiles backward (bricks of 1 x 8 x 8), 16-channel slices
 ])
-def test_volume_tiles_bricks_and_wide_slices(x_shape, c1, c2, wide):
-    """two 3 x 3 x 3 convolutions on volumes whose extents are multiples of 8: row tiles are bricks instead of strips of
-    consecutive positions, and 32 output channels take 32-wide reduction slices; no ReLU, so no decision can differ"""
+def test_volume_tiles_bricks_and_wide_slices(x_shape, c1, c2, kernels):
+    """two 3 x 3 x 3 convolutions on volumes: row tiles are bricks instead of strips of consecutive positions where the extents
+    are multiples of 8, and 32 output channels take 32-wide reduction slices; no ReLU, so no decision can differ"""
     net = workloads.Net()
     t = net.input(x_shape)
     t = net.bn(net.conv(t, c1, (3, 3, 3), (1, 1, 1), (1, 1, 1)))
@@ -782,11 +782,42 @@ def test_volume_tiles_bricks_and_wide_slices(x_shape, c1, c2, wide):
     net.softmax_ce(net.fc(net.gavgpool(t), 10))
     c = B.Context(net, 1 << 30, device=None)
     conv2 = [i for i, L in enumerate(net) if L["op"] == "conv"][1]
-    assert ("lin32" in c.node_kernel(conv2, 0)) == wide[0] and ("lin32" in c.node_kernel(conv2, 1)) == wide[1], \
-        (c.node_kernel(conv2, 0), c.node_kernel(conv2, 1))
+    assert kernels[0] in c.node_kernel(conv2, 0) and kernels[1] in c.node_kernel(conv2, 1), (c.node_kernel(conv2, 0), c.node_kernel(conv2, 1))
     # (the first normalisation's shift moves the second convolution's output by a constant away from the borders, which the
     # second normalisation removes: a gradient that is nearly zero in exact arithmetic, hence the ill-conditioned check)
     check_ill_conditioned("volume tiles %s -> %d -> %d" % (x_shape, c1, c2), net, 555)
+
+
+@pytest.mark.parametrize("x_shape,residual", [
+    ((2, 16, 4, 16, 24), False),      # 2 x 2 x 3 bricks per sample; every brick touches a border of the volume somewhere
+    ((3, 8, 2, 8, 8), False),         # one brick per sample: all six borders at once
+    ((1, 32, 6, 24, 32), False),      # 3 x 3 x 4 bricks: some have their whole halo inside the volume
+    ((2, 16, 4, 8, 16), True),        # the convolution's input also feeds an addition: its data gradient is added to what is there
+])
+def test_brick_resident_3x3x3_convolution(x_shape, residual):
+    """3 x 3 x 3, 32 -> 32 channels, unit stride, padding 1 on volumes of whole 2 x 8 x 8 bricks: the kernel that keeps a brick's
+    input (with its halo) in LDS -- forward with the statistics for the normalisation behind it, and the data gradient (mirrored
+    taps), plain and accumulating; against the oracle"""
+    net = workloads.Net()
+    t = net.input(x_shape)
+    t = net.bn(net.conv(t, 32, (3, 3, 3), (1, 1, 1), (1, 1, 1)))
+    u = net.bn(net.conv(t, 32, (3, 3, 3), (1, 1, 1), (1, 1, 1)))
+    if residual:
+        u = net.add(u, t)
+    net.softmax_ce(net.fc(net.gavgpool(u), 10))
+    c = B.Context(net, 1 << 30, device=None)
+    conv2 = [i for i, L in enumerate(net) if L["op"] == "conv"][1]
+    assert c.node_kernel(conv2, 0) == "conv3_halo_kernel<fwd+bnstats>" and c.node_kernel(conv2, 1) == "conv3_halo_kernel<dgrad>", \
+        (c.node_kernel(conv2, 0), c.node_kernel(conv2, 1))
+    check_ill_conditioned("brick-resident 3x3x3 %s%s" % (x_shape, " + residual" if residual else ""), net, 777)
+
+
+def test_brick_resident_3x3x3_convolution_without_normalisation():
+    """the same kernel where no normalisation follows (no statistics epilogue), on a 32-channel input"""
+    net = kinkless_probe((2, 32, 4, 8, 16), 32, (3, 3, 3), (1, 1, 1), (1, 1, 1), False)
+    c = B.Context(net, 1 << 30, device=None)
+    assert c.node_kernel(1, 0) == "conv3_halo_kernel<fwd>", c.node_kernel(1, 0)
+    check_against_oracle("brick-resident 3x3x3, plain", net, 778, capture=True)
 
 
 @pytest.mark.parametrize("x_shape,cout,k,pad", [
