@@ -57,6 +57,8 @@ struct IGemmP {
     // bd > 0: the rows of a tile are a brick of bd x 8 x 8 positions (d, h, w) instead of consecutive rows; tiles enumerate the
     // bricks of (n, d, h, w) with w fastest.  Requires bd * 64 == rows per tile and Dr % bd == Hr % 8 == Wr % 8 == 0.
     int bd;
+    // > 0: only the first `live` of the Cs source channels can be non-zero, in src and in wgt (forward of a padded network input)
+    int live;
 };
 
 // coordinate in the source tensor touched by filter tap `a` for a row whose base is `base`
@@ -726,6 +728,80 @@ constexpr int C3_BD = 2, C3_BH = 8, C3_BW = 8, C3_C = 32;
 constexpr int C3_HD = C3_BD + 2, C3_HH = C3_BH + 2, C3_HW = C3_BW + 2, C3_NPIX = C3_HD * C3_HH * C3_HW;
 constexpr int C3_LP = 36;   // floats per pixel in LDS: 16-byte aligned, and eight consecutive pixels start in different banks
 
+// The results of a 2 x 8 x 8 brick (four waves, one 32 x 32 accumulator block each; wave w holds rows 32 w .. 32 w + 31 of the
+// brick, w fastest) leave through `lds` (4 x 32 x C3_LP floats that no wave reads any more), so that a store covers whole
+// 128-byte rows.  Accumulator element v of lane (r, h) is output channel 8 * (v / 4) + 4 * h + v % 4 of row r.
+// STATS: mean and sum of squared deviations (M2) of the brick's 128 rows per channel, in igemm_kernel's format: per wave over
+// its 32 rows (mean first, then M2 about it), the four waves merged in order by the pairwise update of Chan et al.
+template <bool ACCUM, bool STATS>
+__device__ __forceinline__ void c3_brick_out(const f32x16 &acc, float *lds, const IGemmP &p, int wave, int lane, int n, int d0, int h0, int w0)
+{
+    const int r = lane % 32, h = lane / 32;
+    const int D = p.Dr, H = p.Hr, W = p.Wr;
+    float *cw = lds + wave * 32 * C3_LP;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const f32x4 val = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+        *reinterpret_cast<f32x4 *>(&cw[r * C3_LP + 8 * g + 4 * h]) = val;
+    }
+    __syncthreads();
+    const int orow = lane / 8, ocol = 4 * (lane % 8);
+    f32x4 vq[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = wave * 32 + q * 8 + orow;
+        const int64_t m = (((int64_t)n * D + d0 + row / 64) * H + h0 + (row / 8) % 8) * W + w0 + row % 8;
+        f32x4 val = *reinterpret_cast<const f32x4 *>(&cw[(q * 8 + orow) * C3_LP + ocol]);
+        vq[q] = val;
+        f32x4 *dp = reinterpret_cast<f32x4 *>(p.dst + m * C3_C + ocol);
+        if (ACCUM) val = __builtin_nontemporal_load(dp) + val;
+        __builtin_nontemporal_store(val, dp);
+    }
+    if constexpr (STATS) {
+        f32x4 sum = (vq[0] + vq[1]) + (vq[2] + vq[3]);
+#pragma unroll
+        for (int mask = 8; mask < 64; mask <<= 1) {
+            sum.x += __shfl_xor(sum.x, mask, 64); sum.y += __shfl_xor(sum.y, mask, 64);
+            sum.z += __shfl_xor(sum.z, mask, 64); sum.w += __shfl_xor(sum.w, mask, 64);
+        }
+        f32x4 rmean = sum / 32.f;
+        f32x4 rm2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 d = vq[q] - rmean;
+            rm2 += d * d;
+        }
+#pragma unroll
+        for (int mask = 8; mask < 64; mask <<= 1) {
+            rm2.x += __shfl_xor(rm2.x, mask, 64); rm2.y += __shfl_xor(rm2.y, mask, 64);
+            rm2.z += __shfl_xor(rm2.z, mask, 64); rm2.w += __shfl_xor(rm2.w, mask, 64);
+        }
+        __syncthreads();                                  // the staging rows have been read
+        float *sm = lds;                                  // [wave][mean, M2][32]
+        if (orow == 0) {
+            *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 0) * 32 + ocol]) = rmean;
+            *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 1) * 32 + ocol]) = rm2;
+        }
+        __syncthreads();
+        if (wave == 0 && orow == 0) {
+            float rn = 32.f;
+#pragma unroll
+            for (int w2 = 1; w2 < 4; ++w2) {
+                const f32x4 mb = *reinterpret_cast<const f32x4 *>(&sm[(w2 * 2 + 0) * 32 + ocol]);
+                const f32x4 d2 = *reinterpret_cast<const f32x4 *>(&sm[(w2 * 2 + 1) * 32 + ocol]);
+                const float tot = rn + 32.f;
+                const f32x4 delta = mb - rmean;
+                rmean += delta * (32.f / tot);
+                rm2 += d2 + delta * delta * (rn * 32.f / tot);
+                rn = tot;
+            }
+            const int64_t tm = blockIdx.x;
+            *reinterpret_cast<f32x4 *>(p.stats + (tm * 2 + 0) * C3_C + ocol) = rmean;
+            *reinterpret_cast<f32x4 *>(p.stats + (tm * 2 + 1) * C3_C + ocol) = rm2;
+        }
+    }
+}
+
 template <bool DGRAD, bool ACCUM, bool STATS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv3_halo_kernel(IGemmP p)
 {
@@ -806,87 +882,84 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     mul(a0, b0);
 
-    // Accumulator element v of lane (r, h) is output channel 8 * (v / 4) + 4 * h + v % 4 of row r.  Through LDS (the
-    // brick's space, once every wave is done with it), so that a store covers whole 128-byte rows.
-    __syncthreads();
-    float *cw = brick + wave * 32 * C3_LP;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const f32x4 val = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
-        *reinterpret_cast<f32x4 *>(&cw[r * C3_LP + 8 * g + 4 * h]) = val;
-    }
-    __syncthreads();
-    const int orow = lane / 8, ocol = 4 * (lane % 8);
-    f32x4 vq[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int row = wave * 32 + q * 8 + orow;
-        const int64_t m = (((int64_t)n * D + d0 + row / 64) * H + h0 + (row / 8) % 8) * W + w0 + row % 8;
-        f32x4 val = *reinterpret_cast<const f32x4 *>(&cw[(q * 8 + orow) * C3_LP + ocol]);
-        vq[q] = val;
-        f32x4 *dp = reinterpret_cast<f32x4 *>(p.dst + m * C3_C + ocol);
-        if (ACCUM) val = __builtin_nontemporal_load(dp) + val;
-        __builtin_nontemporal_store(val, dp);
-    }
-    if constexpr (STATS) {
-        // mean and sum of squared deviations (M2) of the brick's 128 rows per channel, like igemm_kernel's: per wave over
-        // its 32 rows (mean first, then M2 about it), the four waves merged in order by the pairwise update of Chan et al.
-        f32x4 sum = (vq[0] + vq[1]) + (vq[2] + vq[3]);
-#pragma unroll
-        for (int mask = 8; mask < 64; mask <<= 1) {
-            sum.x += __shfl_xor(sum.x, mask, 64); sum.y += __shfl_xor(sum.y, mask, 64);
-            sum.z += __shfl_xor(sum.z, mask, 64); sum.w += __shfl_xor(sum.w, mask, 64);
-        }
-        f32x4 rmean = sum / 32.f;
-        f32x4 rm2 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const f32x4 d = vq[q] - rmean;
-            rm2 += d * d;
-        }
-#pragma unroll
-        for (int mask = 8; mask < 64; mask <<= 1) {
-            rm2.x += __shfl_xor(rm2.x, mask, 64); rm2.y += __shfl_xor(rm2.y, mask, 64);
-            rm2.z += __shfl_xor(rm2.z, mask, 64); rm2.w += __shfl_xor(rm2.w, mask, 64);
-        }
-        __syncthreads();                                  // the staging rows have been read
-        float *sm = brick;                                // [wave][mean, M2][32]
-        if (orow == 0) {
-            *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 0) * 32 + ocol]) = rmean;
-            *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 1) * 32 + ocol]) = rm2;
-        }
-        __syncthreads();
-        if (wave == 0 && orow == 0) {
-            float rn = 32.f;
-#pragma unroll
-            for (int w2 = 1; w2 < 4; ++w2) {
-                const f32x4 mb = *reinterpret_cast<const f32x4 *>(&sm[(w2 * 2 + 0) * 32 + ocol]);
-                const f32x4 d2 = *reinterpret_cast<const f32x4 *>(&sm[(w2 * 2 + 1) * 32 + ocol]);
-                const float tot = rn + 32.f;
-                const f32x4 delta = mb - rmean;
-                rmean += delta * (32.f / tot);
-                rm2 += d2 + delta * delta * (rn * 32.f / tot);
-                rn = tot;
-            }
-            const int64_t tm = blockIdx.x;
-            *reinterpret_cast<f32x4 *>(p.stats + (tm * 2 + 0) * C3_C + ocol) = rmean;
-            *reinterpret_cast<f32x4 *>(p.stats + (tm * 2 + 1) * C3_C + ocol) = rm2;
-        }
-    }
+    __syncthreads();                                      // every wave is done with the brick: its space becomes the staging area
+    c3_brick_out<ACCUM, STATS>(acc, brick, p, wave, lane, n, d0, h0, w0);
 }
 
-// whether conv3_halo_kernel serves this GEMM: the geometry it is written for (small volumes too: its 128-row bricks give a
-// short launch more workgroups than igemm_kernel's 256-row tiles)
-template <bool DGRAD>
-bool conv3_halo_ok(const IGemmP &p, bool vec)
+// ---- the same filter shape on a network input with ONE live channel (a volume of intensities), 32 output channels ----------
+// The reduction is 27 values long.  As a GEMM over the stored four channels (three of them zero) it is 108 long and runs
+// igemm_kernel at 19 TFLOP/s: 0.63 ms for 0.9 GB of output on 192^3, a third of the HBM rate.  Here the brick's halo is 400
+// floats in LDS, a lane gathers its pixel's 27 neighbours from there (reduction steps (2 t, 2 t + 1), the 28th weight is
+// zero), the 27 x 32 filter sits in 14 registers per lane, and a brick costs 14 MFMAs per wave: what remains is writing the
+// result (and its statistics), which is the bound.
+template <bool STATS>
+__global__ __launch_bounds__(256) void conv3_c1_kernel(IGemmP p)
 {
-    static const bool off = getenv("POOCH_NO_CONV3_HALO") != nullptr;
-    if (off || !vec || p.dst_strided) return false;
+    __shared__ __attribute__((aligned(16))) float lds[4 * 32 * C3_LP];      // the halo (400 floats), later the staging rows
+    const int tid = threadIdx.x, lane = tid % 64, r = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int D = p.Dr, H = p.Hr, W = p.Wr, CS = p.Cs;
+    const int nbw = W / C3_BW, nbh = H / C3_BH, nbd = D / C3_BD;
+    int t = blockIdx.x;
+    const int w0 = (t % nbw) * C3_BW; t /= nbw;
+    const int h0 = (t % nbh) * C3_BH; t /= nbh;
+    const int d0 = (t % nbd) * C3_BD;
+    const int n = t / nbd;
+    const float *x = p.src + (int64_t)n * D * H * W * CS;
+    for (int u = tid; u < C3_NPIX; u += 256) {
+        const int id = d0 + u / (C3_HH * C3_HW) - 1, ih = h0 + (u / C3_HW) % C3_HH - 1, iw = w0 + u % C3_HW - 1;
+        const bool ok = (unsigned)id < (unsigned)D && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W;
+        lds[u] = ok ? ldg1(x + (((int64_t)id * H + ih) * W + iw) * CS) : 0.f;
+    }
+    float bw[14];
+#pragma unroll
+    for (int k = 0; k < 14; ++k) {
+        const int tap = 2 * k + h;
+        bw[k] = tap < 27 ? ldg1(p.wgt + ((int64_t)r * 27 + tap) * CS) : 0.f;
+    }
+    __syncthreads();
+    const int R = wave * 32 + r;
+    const int pbase = ((R / 64) * C3_HH + (R / 8) % 8) * C3_HW + R % 8;
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    float af[14];
+#pragma unroll
+    for (int k = 0; k < 14; ++k) {
+        // (the 28th step of the h = 1 lanes reads the 27th neighbour again; its weight is zero)
+        const int t0 = 2 * k, t1 = 2 * k + 1 < 27 ? 2 * k + 1 : 26;
+        const int o0 = ((t0 / 9) * C3_HH + (t0 / 3) % 3) * C3_HW + t0 % 3, o1 = ((t1 / 9) * C3_HH + (t1 / 3) % 3) * C3_HW + t1 % 3;
+        af[k] = lds[pbase + (h ? o1 : o0)];
+    }
+#pragma unroll
+    for (int k = 0; k < 14; ++k) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bw[k], af[k], acc, 0, 0, 0);
+    __syncthreads();                                      // the halo has been read: its space becomes the staging area
+    c3_brick_out<false, STATS>(acc, lds, p, wave, lane, n, d0, h0, w0);
+}
+
+// the geometry the brick kernels are written for: 3 x 3 x 3, unit stride, padding 1, output extents = input extents in whole
+// 2 x 8 x 8 bricks, 32 output channels (small volumes too: 128-row bricks give a short launch more workgroups than
+// igemm_kernel's 256-row tiles)
+bool c3_brick_geom(const IGemmP &p)
+{
+    if (p.dst_strided || p.Nout != C3_C) return false;
     if (p.kd != 3 || p.kh != 3 || p.kw != 3 || p.sd != 1 || p.sh != 1 || p.sw != 1 || p.pd != 1 || p.ph != 1 || p.pw != 1) return false;
-    if (p.Cs != C3_C || p.Nout != C3_C || p.Kred != 27 * C3_C) return false;
     if (p.Ds != p.Dr || p.Hs != p.Hr || p.Ws != p.Wr) return false;
     if (p.Dr % C3_BD != 0 || p.Hr % C3_BH != 0 || p.Wr % C3_BW != 0) return false;
     return p.M >= C3_BD * C3_BH * C3_BW;
+}
+
+bool conv3_halo_ok(const IGemmP &p, bool vec)
+{
+    static const bool off = getenv("POOCH_NO_CONV3_HALO") != nullptr;
+    return !off && vec && c3_brick_geom(p) && p.Cs == C3_C && p.Kred == 27 * C3_C;
+}
+
+// forward over a source of which only the first channel is live
+bool conv3_c1_ok(const IGemmP &p)
+{
+    static const bool off = getenv("POOCH_NO_CONV3_C1") != nullptr;
+    return !off && p.live == 1 && c3_brick_geom(p) && p.Kred == 27 * p.Cs;
 }
 
 template <bool DGRAD>
@@ -908,6 +981,19 @@ hipError_t launch_conv3_halo(const IGemmP &p, bool accum, hipStream_t s, int *st
         if (p.stats) conv3_halo_kernel<false, false, true><<<grid, block, 0, s>>>(p);
         else conv3_halo_kernel<false, false, false><<<grid, block, 0, s>>>(p);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_conv3_c1(const IGemmP &p, hipStream_t s, int *stats_tiles)
+{
+    const int bricks = p.M / (C3_BD * C3_BH * C3_BW);
+    if (stats_tiles) {
+        stats_tiles[0] = bricks;
+        stats_tiles[1] = C3_BD * C3_BH * C3_BW;
+        return hipSuccess;
+    }
+    if (p.stats) conv3_c1_kernel<true><<<dim3(bricks), dim3(256), 0, s>>>(p);
+    else conv3_c1_kernel<false><<<dim3(bricks), dim3(256), 0, s>>>(p);
     return hipGetLastError();
 }
 
@@ -943,7 +1029,8 @@ hipError_t dispatch_igemm(const IGemmP &p0, bool accum, hipStream_t s, int *stat
     // slices where a tap spans whole ones (3 x 3 x 3, 32 -> 32 at 192^3: forward 104 -> 108 TFLOP/s, data gradient 98 -> 108;
     // the wider tiles lose 3 % under 3 x 3 filters and gain 1 % at most under 1 x 1)
     if (p.Nout <= 32) {
-        if (conv3_halo_ok<DGRAD>(p, vec) && !(accum && !DGRAD)) return launch_conv3_halo<DGRAD>(p, accum, s, stats_tiles);
+        if (conv3_halo_ok(p, vec) && !(accum && !DGRAD)) return launch_conv3_halo<DGRAD>(p, accum, s, stats_tiles);
+        if (!DGRAD && !accum && conv3_c1_ok(p)) return launch_conv3_c1(p, s, stats_tiles);
         static const bool narrow = getenv("POOCH_NO_WIDE_SLICE") != nullptr;
         if (!narrow && lin == 1 && p.Cs % 32 == 0) return launch_igemm<4, 1, 2, 1, 32, DGRAD>(p, vec, lin, accum, s, stats_tiles);
         return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
@@ -1550,6 +1637,114 @@ __global__ __launch_bounds__(192 * (GR / GW) * (KB / IW) * (CB / JW)) void wgrad
     }
 }
 
+// ---- filter gradient of that first layer: one live input channel, 32 output channels, 3 x 3 x 3 ----------------------------
+// dw[k][tap] = sum over positions of dy[pos][k] * x[pos + tap]: 27 x 32 results from 0.9 GB of dy on a 192^3 volume.  As a
+// GEMM over the four stored channels the generic kernel stages an im2col view (a 108-wide B operand, three quarters of
+// it zeros) and needs 0.93 ms; the work is reading dy once.  Here every WAVE walks bricks of 2 x 8 x 8 positions on its
+// own -- no workgroup barrier until the end: it loads the brick's 128 rows of dy straight into registers (lanes 0 - 31
+// one row, lanes 32 - 63 the next: whole 128-byte rows), keeps the brick's 4 x 10 x 10 input values in its private 1.6 KB
+// of LDS and gathers from there.  One MFMA per pair of positions (the reduction index is the position): A = dy (index =
+// output channel), B = the input value under tap (lane % 32).  The eight waves of a workgroup add their blocks in a
+// fixed order at the end and write one partial [32][27][Cs] (zeros in the dead channels); reduce_splits_kernel adds the
+// partials in a fixed order.
+struct WGradC1P {
+    const float *dy, *x;
+    float *out;              // [nsplit][32][27][Cs]
+    int N, D, H, W, Cs;
+    int bricks, per_wave;    // bricks in all, bricks per wave (wave g of the grid takes [g * per_wave, (g + 1) * per_wave))
+};
+
+__global__ __launch_bounds__(512) void wgrad3_c1_kernel(WGradC1P p)
+{
+    __shared__ __attribute__((aligned(16))) float lds[8 * 1024];     // per wave: the halo (400 floats); at the end: its 32 x 32 block
+    const int tid = threadIdx.x, lane = tid % 64, r = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    float *halo = lds + wave * 1024;
+    const int D = p.D, H = p.H, W = p.W, CS = p.Cs;
+    const int nbw = W / C3_BW, nbh = H / C3_BH, nbd = D / C3_BD;
+    // B operand of lane (r, h) at step s of a line: halo[(line base) + 2 s + h + off], off = the tap's offset in the halo
+    const int tap = r < 27 ? r : 26;                                  // (columns 27 .. 31 of the block are not stored)
+    const int boff = ((tap / 9) * C3_HH + (tap / 3) % 3) * C3_HW + tap % 3 + h;
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const int g = blockIdx.x * 8 + wave;
+    const int b_end = min((g + 1) * p.per_wave, p.bricks);
+    for (int b = g * p.per_wave; b < b_end; ++b) {                    // (wave-uniform bounds)
+        int t = b;
+        const int w0 = (t % nbw) * C3_BW; t /= nbw;
+        const int h0 = (t % nbh) * C3_BH; t /= nbh;
+        const int d0 = (t % nbd) * C3_BD;
+        const int n = t / nbd;
+        // the brick's dy: 16 lines (d, h) of 8 positions = 1 KB each; step s of a line covers positions 2 s and 2 s + 1
+        float a[64];
+#pragma unroll
+        for (int line = 0; line < 16; ++line) {
+            const int64_t m = (((int64_t)n * D + d0 + line / 8) * H + h0 + line % 8) * W + w0;
+            const float *dp = p.dy + m * C3_C + lane;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) a[line * 4 + s] = ldg1(dp + s * 64);
+        }
+        const float *x = p.x + (int64_t)n * D * H * W * CS;
+#pragma unroll
+        for (int k = 0; k < 7; ++k) {
+            const int u = lane + 64 * k;
+            const int id = d0 + u / (C3_HH * C3_HW) - 1, ih = h0 + (u / C3_HW) % C3_HH - 1, iw = w0 + u % C3_HW - 1;
+            const bool ok = u < C3_NPIX && (unsigned)id < (unsigned)D && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W;
+            const float v = ok ? ldg1(x + (((int64_t)id * H + ih) * W + iw) * CS) : 0.f;
+            if (u < C3_NPIX) halo[u] = v;
+        }
+        // (LDS serves a wave's instructions in order: its own reads below see these writes, and the next brick's writes
+        // come after this brick's reads)
+#pragma unroll
+        for (int line = 0; line < 16; ++line) {
+            const float *hp = halo + ((line / 8) * C3_HH + line % 8) * C3_HW + boff;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[line * 4 + s], hp[2 * s], acc, 0, 0, 0);
+        }
+    }
+    // element v of lane (r, h): output channel 8 * (v / 4) + 4 * h + v % 4, tap r
+    __syncthreads();
+    float *mine = lds + wave * 1024;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mine[(8 * (v / 4) + 4 * h + v % 4) * 32 + r] = acc[v];
+    __syncthreads();
+    float *out = p.out + (int64_t)blockIdx.x * 32 * 27 * CS;
+    for (int e = tid; e < 32 * 27 * CS; e += 512) {
+        const int c = e % CS, kt = e / CS, tp = kt % 27, k = kt / 27;
+        float v = 0.f;
+        if (c == 0) {
+            v = lds[k * 32 + tp];
+#pragma unroll
+            for (int w2 = 1; w2 < 8; ++w2) v += lds[w2 * 1024 + k * 32 + tp];
+        }
+        out[e] = v;
+    }
+}
+
+struct WGradC1Cfg {
+    bool use;
+    int nsplit, per_wave, bricks;
+};
+
+WGradC1Cfg wgrad3_c1_cfg(const ConvGeom &g)
+{
+    static const bool off = getenv("POOCH_NO_CONV3_C1") != nullptr;
+    WGradC1Cfg c{false, 0, 0, 0};
+    if (off || g.Clive != 1 || g.K != C3_C || g.kd != 3 || g.kh != 3 || g.kw != 3) return c;
+    if (g.sd != 1 || g.sh != 1 || g.sw != 1 || g.pd != 1 || g.ph != 1 || g.pw != 1) return c;
+    if (g.Do != g.D || g.Ho != g.H || g.Wo != g.W || g.D % C3_BD != 0 || g.H % C3_BH != 0 || g.W % C3_BW != 0) return c;
+    c.bricks = (int)(g.rows_out() / (C3_BD * C3_BH * C3_BW));
+    if (c.bricks < 1) return c;
+    // one workgroup of eight waves per compute unit where there is that much work, at least four bricks per wave
+    c.nsplit = (c.bricks + 31) / 32;
+    if (c.nsplit > NCU) c.nsplit = NCU;
+    c.per_wave = (c.bricks + c.nsplit * 8 - 1) / (c.nsplit * 8);
+    c.nsplit = (c.bricks + c.per_wave * 8 - 1) / (c.per_wave * 8);     // no workgroup without bricks
+    c.use = true;
+    return c;
+}
+
 struct WHaloCfg {
     bool use;
     int gr, waves, P, PWpad, nseg_w, nseg, nsplit, seg_per_split, groups;
@@ -1739,6 +1934,7 @@ IGemmP fwd_params(const float *x, const float *w_krsc, float *y, const ConvGeom 
     p.Dr = g.Do; p.Hr = g.Ho; p.Wr = g.Wo; p.Ds = g.D; p.Hs = g.H; p.Ws = g.W;
     p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
     p.dst_strided = 0; p.DD = p.HD = p.WD = p.SD = p.SH = p.SW = 0;
+    p.live = g.Clive;
     return p;
 }
 
@@ -1746,7 +1942,7 @@ IGemmP fwd_params(const float *x, const float *w_krsc, float *y, const ConvGeom 
 IGemmP dgrad_params(const float *dy, const float *w_crsk, float *dx, const ConvGeom &g)
 {
     IGemmP p;
-    p.src = dy; p.wgt = w_crsk; p.dst = dx; p.stats = nullptr;
+    p.src = dy; p.wgt = w_crsk; p.dst = dx; p.stats = nullptr; p.live = 0;
     p.M = (int)g.rows_in(); p.Nout = g.C; p.Kred = (int)(g.taps() * g.K); p.Cs = g.K;
     p.Dr = g.D; p.Hr = g.H; p.Wr = g.W; p.Ds = g.Do; p.Hs = g.Ho; p.Ws = g.Wo;
     p.kd = g.kd; p.kh = g.kh; p.kw = g.kw; p.sd = g.sd; p.sh = g.sh; p.sw = g.sw; p.pd = g.pd; p.ph = g.ph; p.pw = g.pw;
@@ -1809,6 +2005,7 @@ hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const Con
     if (!dy || !w_crsk || !dx || !geom_ok(g)) return hipErrorInvalidValue;
     IGemmP p;
     p.stats = nullptr;
+    p.live = 0;
     if (pointwise_strided(g)) {
         if (!accumulate) {
             const hipError_t e = fill_zero(dx, g.rows_in() * g.C, s);
@@ -1859,7 +2056,8 @@ const char *igemm_tag(int64_t rows, int nout, int cs, bool unit_stride, bool dgr
 
 const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
 {
-    if (conv3_halo_ok<false>(fwd_params(nullptr, nullptr, nullptr, g), true)) return bn_tiles ? "conv3_halo_kernel<fwd+bnstats>" : "conv3_halo_kernel<fwd>";
+    if (conv3_halo_ok(fwd_params(nullptr, nullptr, nullptr, g), true)) return bn_tiles ? "conv3_halo_kernel<fwd+bnstats>" : "conv3_halo_kernel<fwd>";
+    if (conv3_c1_ok(fwd_params(nullptr, nullptr, nullptr, g))) return bn_tiles ? "conv3_c1_kernel<fwd+bnstats>" : "conv3_c1_kernel<fwd>";
     const bool one_tap = g.taps() == 1 && g.pd == 0 && g.ph == 0 && g.pw == 0;
     const char *plain = igemm_tag(g.rows_out(), g.K, g.C, true, false, (int)(g.taps() * g.C), one_tap);
     if (!bn_tiles) return plain;
@@ -1878,7 +2076,7 @@ const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
 const char *conv_dgrad_kernel(const ConvGeom &g)
 {
     if (pointwise_strided(g)) return igemm_tag(g.rows_out(), g.C, g.K, true, false, 0, true);   // scatter GEMM over the output rows (never split)
-    if (conv3_halo_ok<true>(dgrad_params(nullptr, nullptr, nullptr, g), true)) return "conv3_halo_kernel<dgrad>";
+    if (conv3_halo_ok(dgrad_params(nullptr, nullptr, nullptr, g), true)) return "conv3_halo_kernel<dgrad>";
     const bool one_tap = g.taps() == 1 && g.pd == 0 && g.ph == 0 && g.pw == 0;
     return igemm_tag(g.rows_in(), g.C, g.K, g.sd == 1 && g.sh == 1 && g.sw == 1, true, (int)(g.taps() * g.K), one_tap);
 }
@@ -1886,6 +2084,7 @@ const char *conv_dgrad_kernel(const ConvGeom &g)
 const char *conv_wgrad_kernel(const ConvGeom &g)
 {
     if (geom_ok(g)) {
+        if (wgrad3_c1_cfg(g).use) return "wgrad3_c1_kernel";
         const WHaloCfg hc = whalo_cfg(g);
         if (hc.use) {
             if (g.K != g.C) return g.K == 64 ? "wgrad_halo_kernel<2,1,3>" : "wgrad_halo_kernel<1,2,3>";
@@ -1901,6 +2100,8 @@ const char *conv_wgrad_kernel(const ConvGeom &g)
 size_t conv_wgrad_workspace(const ConvGeom &g)
 {
     if (!geom_ok(g)) return 0;
+    const WGradC1Cfg c1 = wgrad3_c1_cfg(g);
+    if (c1.use) return (size_t)c1.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WHaloCfg hc = whalo_cfg(g);
     if (hc.use) return (size_t)hc.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WGradCfg c = wgrad_cfg(g);
@@ -1910,6 +2111,20 @@ size_t conv_wgrad_workspace(const ConvGeom &g)
 hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *workspace, const ConvGeom &g, hipStream_t s)
 {
     if (!dy || !x || !dw_krsc || !geom_ok(g)) return hipErrorInvalidValue;
+    const WGradC1Cfg c1 = wgrad3_c1_cfg(g);
+    if (c1.use) {
+        if (!workspace) return hipErrorInvalidValue;
+        WGradC1P cp;
+        cp.dy = dy; cp.x = x; cp.out = workspace;
+        cp.N = g.N; cp.D = g.D; cp.H = g.H; cp.W = g.W; cp.Cs = g.C;
+        cp.bricks = c1.bricks; cp.per_wave = c1.per_wave;
+        wgrad3_c1_kernel<<<dim3(c1.nsplit), dim3(512), 0, s>>>(cp);
+        const hipError_t ce = hipGetLastError();
+        if (ce != hipSuccess) return ce;
+        const int64_t nel = (int64_t)g.K * g.taps() * g.C;
+        reduce_splits_kernel<<<dim3((unsigned)((nel + 63) / 64)), dim3(256), 0, s>>>(workspace, dw_krsc, nel, c1.nsplit);
+        return hipGetLastError();
+    }
     const WHaloCfg hc = whalo_cfg(g);
     if (hc.use) {
         // (the workspace is sized for this path: no falling back to the generic kernel's split count)

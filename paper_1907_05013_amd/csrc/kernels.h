@@ -13,6 +13,8 @@ namespace pk {
 
 struct ConvGeom {
     int N, C, D, H, W;     // input, channels-last N,D,H,W,C (D == 1 for 2-d)
+    int Clive = 0;         // > 0: only the first Clive of the C input channels can be non-zero in x and in the filter (a
+                           // network input of one to three channels is stored with zero channels up to four)
     int K;                 // output channels
     int Do, Ho, Wo;        // output spatial size
     int kd, kh, kw, sd, sh, sw, pd, ph, pw;

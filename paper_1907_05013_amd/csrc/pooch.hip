@@ -160,6 +160,7 @@ pk::ConvGeom conv_geom(const Graph &G, int i, int in_cdev)
     const Node &x = G.nodes[nd.in[0]];
     pk::ConvGeom g;
     g.N = (int)x.N; g.C = nd.in[0] == 0 ? in_cdev : (int)x.C; g.D = (int)x.sp[0]; g.H = (int)x.sp[1]; g.W = (int)x.sp[2];
+    g.Clive = nd.in[0] == 0 && in_cdev != (int)x.C ? (int)x.C : 0;
     g.K = (int)nd.C;
     g.Do = (int)nd.sp[0]; g.Ho = (int)nd.sp[1]; g.Wo = (int)nd.sp[2];
     if (nd.op == OP_FC) {

@@ -820,6 +820,24 @@ def test_brick_resident_3x3x3_convolution_without_normalisation():
     check_against_oracle("brick-resident 3x3x3, plain", net, 778, capture=True)
 
 
+@pytest.mark.parametrize("x_shape,with_bn", [
+    ((2, 1, 2, 8, 8), True),          # one brick per sample: all six borders at once
+    ((3, 1, 4, 16, 24), True),        # 2 x 2 x 3 bricks per sample: fewer bricks than waves, most waves idle
+    ((2, 1, 6, 24, 32), False),       # 72 bricks: some have their whole halo inside; no normalisation behind (no statistics)
+    ((2, 1, 8, 32, 64), True),        # 512 bricks: several workgroups, several bricks per wave (two samples: with one, the pooled
+                                      # output of the normalisation is its shift and the filter gradient is zero)
+])
+def test_single_channel_volume_first_layer(x_shape, with_bn):
+    """3 x 3 x 3 into 32 channels on a network input of one channel (stored with three zero channels): the forward kernel that
+    gathers a position's 27 neighbours from an LDS halo, and the filter gradient in which every wave walks bricks on its own;
+    against the oracle"""
+    net = kinkless_probe(x_shape, 32, (3, 3, 3), (1, 1, 1), (1, 1, 1), with_bn)
+    c = B.Context(net, 1 << 30, device=None)
+    assert c.node_kernel(1, 0) == ("conv3_c1_kernel<fwd+bnstats>" if with_bn else "conv3_c1_kernel<fwd>"), c.node_kernel(1, 0)
+    assert c.node_kernel(1, 2) == "wgrad3_c1_kernel", c.node_kernel(1, 2)
+    check_against_oracle("single-channel first layer %s" % (x_shape,), net, 4242, capture=True)
+
+
 @pytest.mark.parametrize("x_shape,cout,k,pad", [
     ((2, 64, 13, 13), 64, (3, 3), (1, 1)),            # one row group per workgroup, odd width (one padded pixel pair)
     ((3, 32, 9, 70), 32, (3, 3), (1, 1)),             # three rows per group; 70 pixels = two segments of 36, the second ragged
