@@ -13,6 +13,7 @@
 #include <map>
 #include <mutex>
 #include <string>
+#include <type_traits>
 
 namespace pk {
 
@@ -1745,6 +1746,171 @@ WGradC1Cfg wgrad3_c1_cfg(const ConvGeom &g)
     return c;
 }
 
+// ---- filter gradient, 3 x 3 x 3, 32 or 64 channels on either side, whole bricks: brick and halo resident in LDS ------------
+// wgrad_halo_kernel walks segments of one output row: a barrier per segment of at most 64 positions, 32 MFMAs per wave between
+// two barriers, and three groups of workgroups (one per depth tap) that each stage dy and the input rows again (6.6 GB moved for
+// 1.8 GB of operands at 192^3, matrix pipe busy 61 %).  Here a workgroup of four waves takes a brick of 2 x 8 x 8 positions:
+// the brick's dy rows (128 x 32) and the 4 x 10 x 10 input positions under its 27 taps go to LDS once (76 KB, two workgroups
+// per CU, which load and multiply in turns as those of conv3_halo_kernel do); wave w multiplies the taps 7 w .. 7 w + 6 (the
+// fourth wave's seventh is a repeat whose result is dropped: uniform code): per line of eight positions four reads of dy (A
+// operand: index = output channel, reduction index = position) and 28 of the input (B operand: index = input channel) for 28
+// MFMAs -- 448 per wave between two barriers.  Workgroups are persistent (exactly as many as are resident), each accumulates
+// over a contiguous range of bricks and writes one partial [32][27][32] straight from its registers; reduce_splits_kernel
+// adds the partials in a fixed order.  With 64 channels on a side the result falls into two or four such 32 x 27 x 32 blocks
+// (kq, cq), each the work of a workgroup of its own that stages only its 32 channels of dy and of the input (so the LDS
+// footprint stays at 76 KB; dy and the input are then read twice, from the L2 for the most part).
+constexpr size_t WGRAD3_BRICK_LDS = (size_t)(C3_NPIX + C3_BD * C3_BH * C3_BW) * C3_LP * sizeof(float);   // 76 KB
+
+struct WGradB3P {
+    const float *dy, *x;
+    float *out;              // [splits][K][27][C]
+    int N, D, H, W;
+    int K, C;                // 32 or 64 each: a workgroup computes one 32 x 27 x 32 block (kq, cq) of the result for its bricks
+    int bricks, per_split;   // split g takes bricks [g * per_split, min(bricks, (g + 1) * per_split)); workgroup = (g, kq, cq)
+};
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void wgrad3_brick_kernel(WGradB3P p)
+{
+    extern __shared__ __attribute__((aligned(16))) float brick_lds[];        // WGRAD3_BRICK_LDS bytes
+    float *xs = brick_lds, *dys = brick_lds + C3_NPIX * C3_LP;
+    const int tid = threadIdx.x, lane = tid % 64, r = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int D = p.D, H = p.H, W = p.W, KT = p.K, CT = p.C;
+    const int nbw = W / C3_BW, nbh = H / C3_BH, nbd = D / C3_BD;
+    const int nsub = (KT / 32) * (CT / 32), sub = blockIdx.x % nsub, split = blockIdx.x / nsub;
+    const int k0 = 32 * (sub / (CT / 32)), c0 = 32 * (sub % (CT / 32));
+    f32x16 acc[7];
+#pragma unroll
+    for (int i = 0; i < 7; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    int toff[7];                                                              // halo offset (in pixels) of this wave's taps
+#pragma unroll
+    for (int i = 0; i < 7; ++i) {
+        const int tap = min(7 * wave + i, 26);
+        toff[i] = ((tap / 9) * C3_HH + (tap / 3) % 3) * C3_HW + tap % 3;
+    }
+    const float *arow = dys + h * C3_LP + r;                                  // + (8 line + 2 s) * C3_LP
+    const float *brow = xs + h * C3_LP + r;                                   // + (line's pixel + tap offset + 2 s) * C3_LP
+    const int b_end = min((split + 1) * p.per_split, p.bricks);
+    for (int b = split * p.per_split; b < b_end; ++b) {
+        int t = b;
+        const int w0 = (t % nbw) * C3_BW; t /= nbw;
+        const int h0 = (t % nbh) * C3_BH; t /= nbh;
+        const int d0 = (t % nbd) * C3_BD;
+        const int n = t / nbd;
+        __syncthreads();                                  // the previous brick has been read
+        {
+            // input halo: line (pd, ph) = 10 pixels x 32 of their channels = 80 lanes x 16 bytes; wave w takes lines w, w + 4, ...
+            // (wave-uniform); dy: 16 lines of 8 positions x 32 of their channels = 64 lanes x 16 bytes, wave w takes lines w, w + 4, ...
+            const float *x = p.x + (int64_t)n * D * H * W * CT + c0;
+            constexpr int NL = C3_HD * C3_HH / 4;
+            f32x4 v0[NL], v1[NL], vd[4];
+            const int pw0 = lane / 8, q4 = 4 * (lane % 8);
+            const int lx = pw0 * CT + q4, ly = pw0 * KT + q4;     // this lane's 16 bytes of a line: pixel pw0, channels q4 .. q4 + 3
+            const bool in0 = !(w0 == 0 && pw0 == 0);
+            const bool in1 = lane < 16 && !(w0 + C3_BW == W && pw0 == 1);
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k = 0; k < NL; ++k) {
+                const int line = wave + 4 * k, pd = line / C3_HH, ph = line % C3_HH;
+                const int id = d0 + pd - 1, ih = h0 + ph - 1;
+                const bool lok = (unsigned)id < (unsigned)D && (unsigned)ih < (unsigned)H;
+                const float *src = x + ((((int64_t)(lok ? id : 0) * H + (lok ? ih : 0)) * W + w0) * CT - CT);
+                v0[k] = (lok && in0) ? ldg4(src + lx) : z;
+                v1[k] = (lok && in1) ? ldg4(src + lx + 8 * CT) : z;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int line = wave + 4 * k;
+                const int64_t m = (((int64_t)n * D + d0 + line / 8) * H + h0 + line % 8) * W + w0;
+                vd[k] = ldg4(p.dy + m * KT + k0 + ly);
+            }
+#pragma unroll
+            for (int k = 0; k < NL; ++k) {
+                const int line = wave + 4 * k;
+                float *dst = xs + (line * C3_HW + pw0) * C3_LP + q4;
+                *reinterpret_cast<f32x4 *>(dst) = v0[k];
+                if (lane < 16) *reinterpret_cast<f32x4 *>(dst + 8 * C3_LP) = v1[k];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int line = wave + 4 * k;
+                *reinterpret_cast<f32x4 *>(dys + (line * 8 + pw0) * C3_LP + q4) = vd[k];
+            }
+        }
+        __syncthreads();
+        // operands of line l + 1 are read before the MFMAs of line l (the fences keep the compiler from sinking the reads)
+        float a0[4], b0[7][4], a1[4], b1[7][4];
+        auto load = [&](float (&a)[4], float (&bb)[7][4], int line) {
+            const float *ap = arow + line * 8 * C3_LP;
+            const float *bp = brow + ((line / 8) * C3_HH + line % 8) * C3_HW * C3_LP;
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) a[s2] = ap[2 * s2 * C3_LP];
+#pragma unroll
+            for (int i = 0; i < 7; ++i)
+#pragma unroll
+                for (int s2 = 0; s2 < 4; ++s2) bb[i][s2] = bp[(toff[i] + 2 * s2) * C3_LP];
+        };
+        auto mul = [&](const float (&a)[4], const float (&bb)[7][4]) {
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2)
+#pragma unroll
+                for (int i = 0; i < 7; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s2], bb[i][s2], acc[i], 0, 0, 0);
+        };
+        load(a0, b0, 0);
+#pragma unroll 1
+        for (int line = 0; line < 14; line += 2) {
+            load(a1, b1, line + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mul(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            load(a0, b0, line + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            mul(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        load(a1, b1, 15);
+        __builtin_amdgcn_sched_barrier(0);
+        mul(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mul(a1, b1);
+    }
+    // element v of lane (r, h): output channel 8 * (v / 4) + 4 * h + v % 4, input channel r
+    float *out = p.out + ((int64_t)split * KT + k0) * 27 * CT + c0;
+#pragma unroll
+    for (int i = 0; i < 7; ++i) {
+        const int tap = 7 * wave + i;
+        if (tap < 27) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) out[((8 * (v / 4) + 4 * h + v % 4) * 27 + tap) * CT + r] = acc[i][v];
+        }
+    }
+}
+
+struct WGradB3Cfg {
+    bool use;
+    int nsplit, per_wg, bricks;
+};
+
+WGradB3Cfg wgrad3_brick_cfg(const ConvGeom &g)
+{
+    static const bool off = getenv("POOCH_NO_WGRAD3_BRICK") != nullptr;
+    WGradB3Cfg c{false, 0, 0, 0};
+    if (off || g.C % 32 != 0 || g.K % 32 != 0 || g.C > 256 || g.K > 256 || g.kd != 3 || g.kh != 3 || g.kw != 3) return c;
+    if (g.sd != 1 || g.sh != 1 || g.sw != 1 || g.pd != 1 || g.ph != 1 || g.pw != 1) return c;
+    if (g.Do != g.D || g.Ho != g.H || g.Wo != g.W || g.D % C3_BD != 0 || g.H % C3_BH != 0 || g.W % C3_BW != 0) return c;
+    c.bricks = (int)(g.rows_out() / (C3_BD * C3_BH * C3_BW));
+    if (c.bricks < 1) return c;
+    const int nsub = (g.K / 32) * (g.C / 32);
+    c.nsplit = 2 * NCU / nsub;                                       // as many workgroups as are resident at once
+    if (c.nsplit > c.bricks) c.nsplit = c.bricks;
+    c.per_wg = (c.bricks + c.nsplit - 1) / c.nsplit;
+    c.nsplit = (c.bricks + c.per_wg - 1) / c.per_wg;                 // none without bricks
+    c.use = true;
+    return c;
+}
+
 struct WHaloCfg {
     bool use;
     int gr, waves, P, PWpad, nseg_w, nseg, nsplit, seg_per_split, groups;
@@ -2085,6 +2251,7 @@ const char *conv_wgrad_kernel(const ConvGeom &g)
 {
     if (geom_ok(g)) {
         if (wgrad3_c1_cfg(g).use) return "wgrad3_c1_kernel";
+        if (wgrad3_brick_cfg(g).use) return "wgrad3_brick_kernel";
         const WHaloCfg hc = whalo_cfg(g);
         if (hc.use) {
             if (g.K != g.C) return g.K == 64 ? "wgrad_halo_kernel<2,1,3>" : "wgrad_halo_kernel<1,2,3>";
@@ -2102,6 +2269,8 @@ size_t conv_wgrad_workspace(const ConvGeom &g)
     if (!geom_ok(g)) return 0;
     const WGradC1Cfg c1 = wgrad3_c1_cfg(g);
     if (c1.use) return (size_t)c1.nsplit * g.K * g.taps() * g.C * sizeof(float);
+    const WGradB3Cfg b3 = wgrad3_brick_cfg(g);
+    if (b3.use) return (size_t)b3.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WHaloCfg hc = whalo_cfg(g);
     if (hc.use) return (size_t)hc.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WGradCfg c = wgrad_cfg(g);
@@ -2123,6 +2292,26 @@ hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *wo
         if (ce != hipSuccess) return ce;
         const int64_t nel = (int64_t)g.K * g.taps() * g.C;
         reduce_splits_kernel<<<dim3((unsigned)((nel + 63) / 64)), dim3(256), 0, s>>>(workspace, dw_krsc, nel, c1.nsplit);
+        return hipGetLastError();
+    }
+    const WGradB3Cfg b3 = wgrad3_brick_cfg(g);
+    if (b3.use) {
+        if (!workspace || (uintptr_t)dy % 16 != 0 || (uintptr_t)x % 16 != 0) return hipErrorInvalidValue;
+        WGradB3P bp;
+        bp.dy = dy; bp.x = x; bp.out = workspace;
+        bp.N = g.N; bp.D = g.D; bp.H = g.H; bp.W = g.W; bp.K = g.K; bp.C = g.C;
+        bp.bricks = b3.bricks; bp.per_split = b3.per_wg;
+        static bool raised = false;     // more dynamic LDS than the default limit: raised once (no allocation)
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad3_brick_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+        wgrad3_brick_kernel<<<dim3(b3.nsplit * (g.K / 32) * (g.C / 32)), dim3(256), WGRAD3_BRICK_LDS, s>>>(bp);
+        const hipError_t be = hipGetLastError();
+        if (be != hipSuccess) return be;
+        const int64_t nel = (int64_t)g.K * g.taps() * g.C;
+        reduce_splits_kernel<<<dim3((unsigned)((nel + 63) / 64)), dim3(256), 0, s>>>(workspace, dw_krsc, nel, b3.nsplit);
         return hipGetLastError();
     }
     const WHaloCfg hc = whalo_cfg(g);

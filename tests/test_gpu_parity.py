@@ -797,7 +797,7 @@ def test_volume_tiles_bricks_and_wide_slices(x_shape, c1, c2, kernels):
 def test_brick_resident_3x3x3_convolution(x_shape, residual):
     """3 x 3 x 3, 32 -> 32 channels, unit stride, padding 1 on volumes of whole 2 x 8 x 8 bricks: the kernel that keeps a brick's
     input (with its halo) in LDS -- forward with the statistics for the normalisation behind it, and the data gradient (mirrored
-    taps), plain and accumulating; against the oracle"""
+    taps), plain and accumulating -- and the filter gradient that keeps the brick's dy rows beside it; against the oracle"""
     net = workloads.Net()
     t = net.input(x_shape)
     t = net.bn(net.conv(t, 32, (3, 3, 3), (1, 1, 1), (1, 1, 1)))
@@ -807,8 +807,8 @@ def test_brick_resident_3x3x3_convolution(x_shape, residual):
     net.softmax_ce(net.fc(net.gavgpool(u), 10))
     c = B.Context(net, 1 << 30, device=None)
     conv2 = [i for i, L in enumerate(net) if L["op"] == "conv"][1]
-    assert c.node_kernel(conv2, 0) == "conv3_halo_kernel<fwd+bnstats>" and c.node_kernel(conv2, 1) == "conv3_halo_kernel<dgrad>", \
-        (c.node_kernel(conv2, 0), c.node_kernel(conv2, 1))
+    names = [c.node_kernel(conv2, k) for k in range(3)]
+    assert names == ["conv3_halo_kernel<fwd+bnstats>", "conv3_halo_kernel<dgrad>", "wgrad3_brick_kernel"], names
     check_ill_conditioned("brick-resident 3x3x3 %s%s" % (x_shape, " + residual" if residual else ""), net, 777)
 
 
@@ -818,6 +818,23 @@ def test_brick_resident_3x3x3_convolution_without_normalisation():
     c = B.Context(net, 1 << 30, device=None)
     assert c.node_kernel(1, 0) == "conv3_halo_kernel<fwd>", c.node_kernel(1, 0)
     check_against_oracle("brick-resident 3x3x3, plain", net, 778, capture=True)
+
+
+@pytest.mark.parametrize("x_shape,cout", [
+    ((2, 32, 4, 8, 16), 64),          # 32 -> 64: two blocks of 32 output channels, a workgroup each
+    ((2, 64, 2, 8, 8), 32),           # 64 -> 32, one brick per sample (all borders at once)
+    ((2, 64, 4, 16, 8), 64),          # 64 -> 64: four blocks
+    ((3, 32, 6, 16, 24), 32),         # 54 bricks: several per workgroup
+    ((2, 96, 2, 8, 16), 128),         # 96 -> 128: twelve blocks, two bricks each
+    ((2, 256, 2, 8, 8), 32),          # 256 -> 32: eight blocks along the input channels
+])
+def test_brick_filter_gradient_all_widths(x_shape, cout):
+    """the 3 x 3 x 3 filter gradient on whole bricks for multiples of 32 channels on either side (the result in blocks of 32 x 27 x 32,
+    each block the work of its own workgroups, which stage only their 32 channels of dy and of the input); against the oracle"""
+    net = kinkless_probe(x_shape, cout, (3, 3, 3), (1, 1, 1), (1, 1, 1), True)
+    c = B.Context(net, 1 << 30, device=None)
+    assert c.node_kernel(1, 2) == "wgrad3_brick_kernel", c.node_kernel(1, 2)
+    check_against_oracle("brick filter gradient %s -> %d" % (x_shape, cout), net, 909, capture=False)
 
 
 @pytest.mark.parametrize("x_shape,with_bn", [
