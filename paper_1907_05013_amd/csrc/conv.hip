@@ -724,7 +724,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 // from registers instead of global memory and no stores the same loop runs at 130, so little is left in this design.
 // (Two variants that were not kept: a persistent workgroup that prefetches the next brick into registers during the
 // tap loop -- 109 TFLOP/s, the in-order counter of outstanding loads makes the filter loads wait for the brick's --
-// and a swizzled, unpadded brick that admits three workgroups per CU -- 118.)
+// and a swizzled, unpadded brick that admits three workgroups per CU -- 118.  Wider layers through the same brick space --
+// source channels in groups of 32, two or four blocks of 32 output channels per wave -- ran at 100 TFLOP/s (64 output
+// channels) and 69 (128) against igemm_kernel's 114 and 108 at 96^3 and 48^3: every wave then loads 8 or 16 KB of filter
+// per tap from the L2, where igemm_kernel stages a slice once per workgroup.)
 constexpr int C3_BD = 2, C3_BH = 8, C3_BW = 8, C3_C = 32;
 constexpr int C3_HD = C3_BD + 2, C3_HH = C3_BH + 2, C3_HW = C3_BW + 2, C3_NPIX = C3_HD * C3_HH * C3_HW;
 constexpr int C3_LP = 36;   // floats per pixel in LDS: 16-byte aligned, and eight consecutive pixels start in different banks
