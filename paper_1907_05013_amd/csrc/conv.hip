@@ -7,6 +7,12 @@
 // 64-lane wavefront owns a TM x TN grid of 32x32 accumulators fed by
 // v_mfma_f32_32x32x2_f32.  No atomics: the filter gradient's long reduction is split over
 // workgroups into a workspace and summed in a fixed order.
+// Beside the general kernels (igemm_kernel: forward and data gradient; wgrad_kernel: filter
+// gradient) there are kernels for the shapes on which those fall short: wgrad_halo_kernel (3-wide
+// filters on 32 or 64 channels: the taps share what is staged), and for 3 x 3 x 3 filters on volumes
+// of whole 2 x 8 x 8 bricks conv3_halo_kernel (32 -> 32 channels), wgrad3_brick_kernel (any multiple
+// of 32 channels) and conv3_c1_kernel / wgrad3_c1_kernel (a network input with one live channel),
+// which keep a brick of the input with its halo in LDS for all 27 taps.
 #include "kernels.h"
 
 #include <cstdlib>
@@ -1893,7 +1899,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
 struct WGradB3Cfg {
     bool use;
-    int nsplit, per_wg, bricks;
+    int nsplit, per_split, bricks;   // splits of the brick range (each split: one workgroup per 32 x 27 x 32 block of the result)
 };
 
 WGradB3Cfg wgrad3_brick_cfg(const ConvGeom &g)
@@ -1908,8 +1914,8 @@ WGradB3Cfg wgrad3_brick_cfg(const ConvGeom &g)
     const int nsub = (g.K / 32) * (g.C / 32);
     c.nsplit = 2 * NCU / nsub;                                       // as many workgroups as are resident at once
     if (c.nsplit > c.bricks) c.nsplit = c.bricks;
-    c.per_wg = (c.bricks + c.nsplit - 1) / c.nsplit;
-    c.nsplit = (c.bricks + c.per_wg - 1) / c.per_wg;                 // none without bricks
+    c.per_split = (c.bricks + c.nsplit - 1) / c.nsplit;
+    c.nsplit = (c.bricks + c.per_split - 1) / c.per_split;           // none without bricks
     c.use = true;
     return c;
 }
@@ -2303,7 +2309,7 @@ hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *wo
         WGradB3P bp;
         bp.dy = dy; bp.x = x; bp.out = workspace;
         bp.N = g.N; bp.D = g.D; bp.H = g.H; bp.W = g.W; bp.K = g.K; bp.C = g.C;
-        bp.bricks = b3.bricks; bp.per_split = b3.per_wg;
+        bp.bricks = b3.bricks; bp.per_split = b3.per_split;
         static bool raised = false;     // more dynamic LDS than the default limit: raised once (no allocation)
         if (!raised) {
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad3_brick_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
