@@ -994,6 +994,186 @@ hipError_t launch_conv3_halo(const IGemmP &p, bool accum, hipStream_t s, int *st
     return hipGetLastError();
 }
 
+// ---- the ResNet stem: 7 x 7, stride 2, padding 3, three live input channels (stored as four), 64 output channels ----------
+// As a GEMM over the stored channels the reduction is 196 long (13 slices of 16) for 147 live values, staged per slice:
+// igemm_kernel runs it at 73 TFLOP/s of live flops (2.07 ms at batch 640).  Here a workgroup takes a tile of 8 x 16 output
+// positions, brings the 21 x 37 input pixels under it into LDS once -- one plane per channel and column parity, so that the
+// 16 positions of a tile row read consecutive floats for any tap (x = 2 ox + tx: parity tx % 2, index ox + tx / 2) -- and a
+// lane gathers its position's 147 values from there: 74 reduction steps, lanes 0 - 31 the values 0 .. 73, lanes 32 - 63 the
+// values 74 .. 146 and a zero.  Wave w holds output channels 32 (w / 2) .. + 31 for the tile's rows 64 (w % 2) .. + 63 (two
+// accumulator blocks), so its share of the filter is 74 registers per lane, loaded once: workgroups are persistent.
+constexpr int S7_TH = 8, S7_TW = 16, S7_PH = 2 * S7_TH + 5, S7_PW = 2 * S7_TW + 5, S7_RS = 24;   // tile, patch, plane row stride
+constexpr int S7_PATCH = 3 * 2 * S7_PH * S7_RS;                                                   // floats
+
+// offset in the patch planes of reduction value k = 3 * tap + c (tap = 7 ty + tx), relative to a position's base
+__host__ __device__ constexpr int s7_off(int k)
+{
+    return k >= 147 ? 0 : (((k % 3) * 2 + ((k / 3) % 7) % 2) * S7_PH + (k / 3) / 7) * S7_RS + ((k / 3) % 7) / 2;
+}
+
+template <bool STATS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void stem7_fwd_kernel(IGemmP p, int tiles, int per_wg)
+{
+    __shared__ __attribute__((aligned(16))) float patch[S7_PATCH];
+    __shared__ __attribute__((aligned(16))) float stage[4 * 32 * C3_LP];
+    __shared__ __attribute__((aligned(16))) float sm[4 * 2 * 32];
+    const int tid = threadIdx.x, lane = tid % 64, r = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int nb = wave / 2, half = wave % 2;
+    const int Ho = p.Hr, Wo = p.Wr, H = p.Hs, W = p.Ws, CS = p.Cs, NO = p.Nout;
+    const int tw = Wo / S7_TW, th = Ho / S7_TH;
+    float bw[74];
+#pragma unroll
+    for (int t = 0; t < 74; ++t) {
+        const int k = 74 * h + t;
+        bw[t] = k < 147 ? ldg1(p.wgt + ((int64_t)(32 * nb + r) * 49 + k / 3) * CS + k % 3) : 0.f;
+    }
+    // rows of this lane: R = 64 half + 32 b + r (b = 0, 1): tile row R / 16, column R % 16; block 1 is two tile rows further down
+    const int R0 = 64 * half + r;
+    const float *abase = patch + (2 * (R0 / S7_TW)) * S7_RS + R0 % S7_TW;
+    const int t_end = min((int)(blockIdx.x + 1) * per_wg, tiles);
+    // the pixels of a tile's patch travel global -> registers while the tile before it is multiplied (four per thread), and
+    // go to the planes between two barriers
+    constexpr int NPF = (S7_PH * S7_PW + 255) / 256;
+    f32x4 pf[NPF];
+    auto fetch = [&](int tile) {
+        int t = tile;
+        const int ox0 = (t % tw) * S7_TW; t /= tw;
+        const int oy0 = (t % th) * S7_TH;
+        const float *x = p.src + (int64_t)(t / th) * H * W * CS;
+#pragma unroll
+        for (int j = 0; j < NPF; ++j) {
+            const int u = tid + 256 * j, py = u / S7_PW, px = u % S7_PW;
+            const int iy = 2 * oy0 - 3 + py, ix = 2 * ox0 - 3 + px;
+            const bool ok = u < S7_PH * S7_PW && (unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W;
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            pf[j] = ok ? ldg4(x + ((int64_t)iy * W + ix) * CS) : z;
+        }
+    };
+    if ((int)blockIdx.x * per_wg < t_end) fetch(blockIdx.x * per_wg);
+    for (int tile = blockIdx.x * per_wg; tile < t_end; ++tile) {
+        int t = tile;
+        const int ox0 = (t % tw) * S7_TW; t /= tw;
+        const int oy0 = (t % th) * S7_TH;
+        const int n = t / th;
+        __syncthreads();                                  // the previous tile's patch has been read
+#pragma unroll
+        for (int j = 0; j < NPF; ++j) {
+            const int u = tid + 256 * j, py = u / S7_PW, px = u % S7_PW;
+            if (u < S7_PH * S7_PW) {
+                float *d = patch + ((px & 1) * S7_PH + py) * S7_RS + (px >> 1);
+                d[0] = pf[j].x;
+                d[2 * S7_PH * S7_RS] = pf[j].y;
+                d[4 * S7_PH * S7_RS] = pf[j].z;
+            }
+        }
+        __syncthreads();
+        fetch(min(tile + 1, t_end - 1));                  // (the last tile again: no branch around the loads)
+        f32x16 acc[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+#pragma unroll
+        for (int t2 = 0; t2 < 74; ++t2) {
+            const int off = h ? s7_off(74 + t2) : s7_off(t2);
+            const float a0 = abase[off], a1 = abase[off + 4 * S7_RS];
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bw[t2], a0, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bw[t2], a1, acc[1], 0, 0, 0);
+        }
+        // element v of lane (r, h): output channel 32 nb + 8 (v / 4) + 4 h + v % 4 of row r of the block.  Through this wave's
+        // staging rows (LDS serves a wave's instructions in order), so that a store covers 128-byte pieces of output rows.
+        float *cw = stage + wave * 32 * C3_LP;
+        const int orow = lane / 8, ocol = 4 * (lane % 8);
+        float rn = 0.f;
+        f32x4 rmean = {0.f, 0.f, 0.f, 0.f}, rm2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 val = {acc[b][4 * g], acc[b][4 * g + 1], acc[b][4 * g + 2], acc[b][4 * g + 3]};
+                *reinterpret_cast<f32x4 *>(&cw[r * C3_LP + 8 * g + 4 * h]) = val;
+            }
+            f32x4 vq[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int R = 64 * half + 32 * b + 8 * q + orow;
+                const int64_t m = ((int64_t)n * Ho + oy0 + R / S7_TW) * Wo + ox0 + R % S7_TW;
+                vq[q] = *reinterpret_cast<const f32x4 *>(&cw[(8 * q + orow) * C3_LP + ocol]);
+                __builtin_nontemporal_store(vq[q], reinterpret_cast<f32x4 *>(p.dst + m * NO + 32 * nb + ocol));
+            }
+            if constexpr (STATS) {
+                f32x4 sum = (vq[0] + vq[1]) + (vq[2] + vq[3]);
+#pragma unroll
+                for (int mask = 8; mask < 64; mask <<= 1) {
+                    sum.x += __shfl_xor(sum.x, mask, 64); sum.y += __shfl_xor(sum.y, mask, 64);
+                    sum.z += __shfl_xor(sum.z, mask, 64); sum.w += __shfl_xor(sum.w, mask, 64);
+                }
+                const f32x4 mb = sum / 32.f;
+                f32x4 d2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 d = vq[q] - mb;
+                    d2 += d * d;
+                }
+#pragma unroll
+                for (int mask = 8; mask < 64; mask <<= 1) {
+                    d2.x += __shfl_xor(d2.x, mask, 64); d2.y += __shfl_xor(d2.y, mask, 64);
+                    d2.z += __shfl_xor(d2.z, mask, 64); d2.w += __shfl_xor(d2.w, mask, 64);
+                }
+                const float tot = rn + 32.f;
+                const f32x4 delta = mb - rmean;
+                rmean += delta * (32.f / tot);
+                rm2 += d2 + delta * delta * (rn * 32.f / tot);
+                rn = tot;
+            }
+        }
+        if constexpr (STATS) {
+            // mean and M2 of the tile's 128 rows per channel (igemm_kernel's format): the two waves of a column block, in order
+            if (orow == 0) {
+                *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 0) * 32 + ocol]) = rmean;
+                *reinterpret_cast<f32x4 *>(&sm[(wave * 2 + 1) * 32 + ocol]) = rm2;
+            }
+            __syncthreads();
+            if (half == 0 && orow == 0) {
+                const f32x4 mb = *reinterpret_cast<const f32x4 *>(&sm[((wave + 1) * 2 + 0) * 32 + ocol]);
+                const f32x4 d2 = *reinterpret_cast<const f32x4 *>(&sm[((wave + 1) * 2 + 1) * 32 + ocol]);
+                const f32x4 delta = mb - rmean;
+                rmean += delta * 0.5f;
+                rm2 += d2 + delta * delta * 32.f;             // 64 * 64 / 128
+                *reinterpret_cast<f32x4 *>(p.stats + ((int64_t)tile * 2 + 0) * NO + 32 * nb + ocol) = rmean;
+                *reinterpret_cast<f32x4 *>(p.stats + ((int64_t)tile * 2 + 1) * NO + 32 * nb + ocol) = rm2;
+            }
+        }
+    }
+}
+
+bool stem7_ok(const IGemmP &p)
+{
+    static const bool off = getenv("POOCH_NO_STEM7") != nullptr;
+    if (off || p.dst_strided || p.live != 3 || p.Cs != 4 || p.Nout != 64 || p.Kred != 49 * 4) return false;
+    if (p.kd != 1 || p.kh != 7 || p.kw != 7 || p.sd != 1 || p.sh != 2 || p.sw != 2 || p.pd != 0 || p.ph != 3 || p.pw != 3) return false;
+    if (p.Dr != 1 || p.Ds != 1 || p.Hs != 2 * p.Hr || p.Ws != 2 * p.Wr) return false;
+    if (p.Hr % S7_TH != 0 || p.Wr % S7_TW != 0) return false;
+    return (uintptr_t)p.src % 16 == 0;
+}
+
+hipError_t launch_stem7(const IGemmP &p, hipStream_t s, int *stats_tiles)
+{
+    const int tiles = p.M / (S7_TH * S7_TW);
+    if (stats_tiles) {
+        stats_tiles[0] = tiles;
+        stats_tiles[1] = S7_TH * S7_TW;
+        return hipSuccess;
+    }
+    const int nwg = tiles < 2 * NCU ? tiles : 2 * NCU;          // persistent (two workgroups fit a compute unit): the filter is loaded once each
+    const int per_wg = (tiles + nwg - 1) / nwg;
+    const dim3 grid((tiles + per_wg - 1) / per_wg), block(256);
+    if (p.stats) stem7_fwd_kernel<true><<<grid, block, 0, s>>>(p, tiles, per_wg);
+    else stem7_fwd_kernel<false><<<grid, block, 0, s>>>(p, tiles, per_wg);
+    return hipGetLastError();
+}
+
 hipError_t launch_conv3_c1(const IGemmP &p, hipStream_t s, int *stats_tiles)
 {
     const int bricks = p.M / (C3_BD * C3_BH * C3_BW);
@@ -1045,6 +1225,7 @@ hipError_t dispatch_igemm(const IGemmP &p0, bool accum, hipStream_t s, int *stat
         if (!narrow && lin == 1 && p.Cs % 32 == 0) return launch_igemm<4, 1, 2, 1, 32, DGRAD>(p, vec, lin, accum, s, stats_tiles);
         return launch_igemm<4, 1, 2, 1, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
     }
+    if (!DGRAD && !accum && stem7_ok(p)) return launch_stem7(p, s, stats_tiles);
     if (p.Nout <= 64) return launch_igemm<4, 1, 2, 2, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
     return launch_igemm<2, 2, 2, 2, BK, DGRAD>(p, vec, lin, accum, s, stats_tiles);
 }
@@ -2233,6 +2414,7 @@ const char *conv_fwd_kernel(const ConvGeom &g, bool bn_tiles)
 {
     if (conv3_halo_ok(fwd_params(nullptr, nullptr, nullptr, g), true)) return bn_tiles ? "conv3_halo_kernel<fwd+bnstats>" : "conv3_halo_kernel<fwd>";
     if (conv3_c1_ok(fwd_params(nullptr, nullptr, nullptr, g))) return bn_tiles ? "conv3_c1_kernel<fwd+bnstats>" : "conv3_c1_kernel<fwd>";
+    if (stem7_ok(fwd_params(nullptr, nullptr, nullptr, g))) return bn_tiles ? "stem7_fwd_kernel<fwd+bnstats>" : "stem7_fwd_kernel<fwd>";
     const bool one_tap = g.taps() == 1 && g.pd == 0 && g.ph == 0 && g.pw == 0;
     const char *plain = igemm_tag(g.rows_out(), g.K, g.C, true, false, (int)(g.taps() * g.C), one_tap);
     if (!bn_tiles) return plain;

@@ -855,6 +855,20 @@ def test_single_channel_volume_first_layer(x_shape, with_bn):
     check_against_oracle("single-channel first layer %s" % (x_shape,), net, 4242, capture=True)
 
 
+@pytest.mark.parametrize("x_shape,with_bn", [
+    ((2, 3, 16, 32), True),           # one tile of 8 x 16 outputs per sample: all four borders at once
+    ((3, 3, 48, 64), True),           # 3 x 2 tiles per sample
+    ((2, 3, 32, 96), False),          # no normalisation behind (no statistics)
+])
+def test_resnet_stem_kernel(x_shape, with_bn):
+    """7 x 7, stride 2, padding 3 on a three-channel input (stored with a zero fourth channel) into 64 channels: the forward
+    kernel that gathers a position's 147 values from channel planes of its tile's input patch in LDS; against the oracle"""
+    net = kinkless_probe(x_shape, 64, (7, 7), (2, 2), (3, 3), with_bn)
+    c = B.Context(net, 1 << 30, device=None)
+    assert c.node_kernel(1, 0) == ("stem7_fwd_kernel<fwd+bnstats>" if with_bn else "stem7_fwd_kernel<fwd>"), c.node_kernel(1, 0)
+    check_against_oracle("stem %s" % (x_shape,), net, 4711, capture=True)
+
+
 @pytest.mark.parametrize("x_shape,cout,k,pad", [
     ((2, 64, 13, 13), 64, (3, 3), (1, 1)),            # one row group per workgroup, odd width (one padded pixel pair)
     ((3, 32, 9, 70), 32, (3, 3), (1, 1)),             # three rows per group; 70 pixels = two segments of 36, the second ragged
