@@ -2101,6 +2101,145 @@ WGradB3Cfg wgrad3_brick_cfg(const ConvGeom &g)
     return c;
 }
 
+// ---- filter gradient of the stem: dw[n][tap][c] = sum over output positions of dy[pos][n] * x[2 pos - 3 + tap][c] -----------
+// The generic kernel stages an im2col view of the four stored channels (a 196-wide B operand for 147 live values) and runs
+// at 60 TFLOP/s of live flops (2.5 ms at batch 640).  Here the tile's input patch sits in LDS as in stem7_fwd_kernel; a
+// wave takes two of the tile's eight rows (16 pairs of positions: the reduction index of the MFMA is the position), reads
+// the pair's dy rows straight from global memory (A operand: index = output channel, two blocks of 32) and gathers the B
+// operand (index = reduction value k = 3 tap + c, five blocks of 32 for 147 values) from the patch at a per-lane offset: ten
+// accumulator blocks per wave, ten MFMAs per pair for two loads and five gathers.  dy for the NEXT tile is loaded into the
+// registers a pair has just been multiplied from.  Persistent workgroups; at the end the four waves' blocks are added in
+// a fixed order through LDS into one partial [64][49][4] per workgroup (zeros in the dead channel), and
+// reduce_splits_kernel adds the partials in a fixed order.
+struct Stem7WP {
+    const float *dy, *x;
+    float *out;              // [workgroups][64][49][4]
+    int N, H, W, Ho, Wo;
+    int tiles, per_wg;
+};
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void stem7_wgrad_kernel(Stem7WP p)
+{
+    __shared__ __attribute__((aligned(16))) float patch[S7_PATCH];
+    __shared__ __attribute__((aligned(16))) float red[4 * 1024];
+    const int tid = threadIdx.x, lane = tid % 64, r = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int Ho = p.Ho, Wo = p.Wo, H = p.H, W = p.W;
+    const int tw = Wo / S7_TW, th = Ho / S7_TH;
+    f32x16 acc[2][5];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 5; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    // B operand of lane (r, h), block jb, pair s: patch[(2 (2 wave + s / 8)) * S7_RS + 2 (s % 8) + h + s7_off(32 jb + r)]
+    const float *bptr[5];
+#pragma unroll
+    for (int jb = 0; jb < 5; ++jb) bptr[jb] = patch + (4 * wave) * S7_RS + h + s7_off(min(32 * jb + r, 147));
+    constexpr int NPF = (S7_PH * S7_PW + 255) / 256;
+    f32x4 pf[NPF];
+    float a0[16], a1[16];                                // dy of the tile's pairs: channels r and 32 + r of position 2 s + h
+    auto fetch = [&](int tile) {
+        int t = tile;
+        const int ox0 = (t % tw) * S7_TW; t /= tw;
+        const int oy0 = (t % th) * S7_TH;
+        const float *x = p.x + (int64_t)(t / th) * H * W * 4;
+#pragma unroll
+        for (int j = 0; j < NPF; ++j) {
+            const int u = tid + 256 * j, py = u / S7_PW, px = u % S7_PW;
+            const int iy = 2 * oy0 - 3 + py, ix = 2 * ox0 - 3 + px;
+            const bool ok = u < S7_PH * S7_PW && (unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W;
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            pf[j] = ok ? ldg4(x + ((int64_t)iy * W + ix) * 4) : z;
+        }
+    };
+    auto dyrow = [&](int tile, int s) -> const float * {
+        int t = tile;
+        const int ox0 = (t % tw) * S7_TW; t /= tw;
+        const int oy0 = (t % th) * S7_TH;
+        const int n = t / th;
+        const int64_t m = ((int64_t)n * Ho + oy0 + 2 * wave + s / 8) * Wo + ox0 + 2 * (s % 8) + h;
+        return p.dy + m * 64 + r;
+    };
+    const int t_beg = blockIdx.x * p.per_wg, t_end = min(t_beg + p.per_wg, p.tiles);
+    if (t_beg < t_end) {
+        fetch(t_beg);
+#pragma unroll
+        for (int s2 = 0; s2 < 16; ++s2) {
+            const float *dp = dyrow(t_beg, s2);
+            a0[s2] = ldg1(dp);
+            a1[s2] = ldg1(dp + 32);
+        }
+    }
+    for (int tile = t_beg; tile < t_end; ++tile) {
+        __syncthreads();                                  // the previous tile's patch has been read
+#pragma unroll
+        for (int j = 0; j < NPF; ++j) {
+            const int u = tid + 256 * j, py = u / S7_PW, px = u % S7_PW;
+            if (u < S7_PH * S7_PW) {
+                float *d = patch + ((px & 1) * S7_PH + py) * S7_RS + (px >> 1);
+                d[0] = pf[j].x;
+                d[2 * S7_PH * S7_RS] = pf[j].y;
+                d[4 * S7_PH * S7_RS] = pf[j].z;
+            }
+        }
+        __syncthreads();
+        const int next = min(tile + 1, t_end - 1);        // (the last tile again: no branch around the loads)
+        fetch(next);
+#pragma unroll
+        for (int s2 = 0; s2 < 16; ++s2) {
+            const int so = (2 * (s2 / 8)) * S7_RS + 2 * (s2 % 8);
+#pragma unroll
+            for (int jb = 0; jb < 5; ++jb) {
+                const float bv = bptr[jb][so];
+                acc[0][jb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[s2], bv, acc[0][jb], 0, 0, 0);
+                acc[1][jb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[s2], bv, acc[1][jb], 0, 0, 0);
+            }
+            const float *dp = dyrow(next, s2);
+            a0[s2] = ldg1(dp);
+            a1[s2] = ldg1(dp + 32);
+        }
+    }
+    // element v of lane (r, h) of block (nb, jb): output channel 32 nb + 8 (v / 4) + 4 h + v % 4, reduction value 32 jb + r
+    float *out = p.out + (int64_t)blockIdx.x * 64 * 49 * 4;
+    for (int e = tid; e < 64 * 49; e += 256) out[4 * e + 3] = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int jb = 0; jb < 5; ++jb) {
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[wave * 1024 + (8 * (v / 4) + 4 * h + v % 4) * 32 + r] = acc[nb][jb][v];
+            __syncthreads();
+            for (int e = tid; e < 1024; e += 256) {
+                const int k = 32 * jb + e % 32, n = 32 * nb + e / 32;
+                if (k < 147) out[(n * 49 + k / 3) * 4 + k % 3] = ((red[e] + red[1024 + e]) + red[2048 + e]) + red[3072 + e];
+            }
+        }
+}
+
+struct Stem7WCfg {
+    bool use;
+    int nsplit, per_wg, tiles;
+};
+
+Stem7WCfg stem7_wgrad_cfg(const ConvGeom &g)
+{
+    static const bool off = getenv("POOCH_NO_STEM7") != nullptr;
+    Stem7WCfg c{false, 0, 0, 0};
+    if (off || g.Clive != 3 || g.C != 4 || g.K != 64 || g.D != 1 || g.kd != 1 || g.kh != 7 || g.kw != 7) return c;
+    if (g.sd != 1 || g.sh != 2 || g.sw != 2 || g.pd != 0 || g.ph != 3 || g.pw != 3) return c;
+    if (g.H != 2 * g.Ho || g.W != 2 * g.Wo || g.Ho % S7_TH != 0 || g.Wo % S7_TW != 0) return c;
+    c.tiles = (int)(g.rows_out() / (S7_TH * S7_TW));
+    if (c.tiles < 1) return c;
+    c.nsplit = c.tiles < 2 * NCU ? c.tiles : 2 * NCU;                // as many workgroups as are resident at once
+    c.per_wg = (c.tiles + c.nsplit - 1) / c.nsplit;
+    c.nsplit = (c.tiles + c.per_wg - 1) / c.per_wg;
+    c.use = true;
+    return c;
+}
+
 struct WHaloCfg {
     bool use;
     int gr, waves, P, PWpad, nseg_w, nseg, nsplit, seg_per_split, groups;
@@ -2442,6 +2581,7 @@ const char *conv_wgrad_kernel(const ConvGeom &g)
 {
     if (geom_ok(g)) {
         if (wgrad3_c1_cfg(g).use) return "wgrad3_c1_kernel";
+        if (stem7_wgrad_cfg(g).use) return "stem7_wgrad_kernel";
         if (wgrad3_brick_cfg(g).use) return "wgrad3_brick_kernel";
         const WHaloCfg hc = whalo_cfg(g);
         if (hc.use) {
@@ -2462,6 +2602,8 @@ size_t conv_wgrad_workspace(const ConvGeom &g)
     if (c1.use) return (size_t)c1.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WGradB3Cfg b3 = wgrad3_brick_cfg(g);
     if (b3.use) return (size_t)b3.nsplit * g.K * g.taps() * g.C * sizeof(float);
+    const Stem7WCfg s7 = stem7_wgrad_cfg(g);
+    if (s7.use) return (size_t)s7.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WHaloCfg hc = whalo_cfg(g);
     if (hc.use) return (size_t)hc.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WGradCfg c = wgrad_cfg(g);
@@ -2483,6 +2625,20 @@ hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *wo
         if (ce != hipSuccess) return ce;
         const int64_t nel = (int64_t)g.K * g.taps() * g.C;
         reduce_splits_kernel<<<dim3((unsigned)((nel + 63) / 64)), dim3(256), 0, s>>>(workspace, dw_krsc, nel, c1.nsplit);
+        return hipGetLastError();
+    }
+    const Stem7WCfg s7 = stem7_wgrad_cfg(g);
+    if (s7.use) {
+        if (!workspace || (uintptr_t)x % 16 != 0) return hipErrorInvalidValue;
+        Stem7WP sp;
+        sp.dy = dy; sp.x = x; sp.out = workspace;
+        sp.N = g.N; sp.H = g.H; sp.W = g.W; sp.Ho = g.Ho; sp.Wo = g.Wo;
+        sp.tiles = s7.tiles; sp.per_wg = s7.per_wg;
+        stem7_wgrad_kernel<<<dim3(s7.nsplit), dim3(256), 0, s>>>(sp);
+        const hipError_t se = hipGetLastError();
+        if (se != hipSuccess) return se;
+        const int64_t nel = (int64_t)g.K * g.taps() * g.C;
+        reduce_splits_kernel<<<dim3((unsigned)((nel + 63) / 64)), dim3(256), 0, s>>>(workspace, dw_krsc, nel, s7.nsplit);
         return hipGetLastError();
     }
     const WGradB3Cfg b3 = wgrad3_brick_cfg(g);

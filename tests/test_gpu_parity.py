@@ -862,10 +862,12 @@ def test_single_channel_volume_first_layer(x_shape, with_bn):
 ])
 def test_resnet_stem_kernel(x_shape, with_bn):
     """7 x 7, stride 2, padding 3 on a three-channel input (stored with a zero fourth channel) into 64 channels: the forward
-    kernel that gathers a position's 147 values from channel planes of its tile's input patch in LDS; against the oracle"""
+    kernel that gathers a position's 147 values from channel planes of its tile's input patch in LDS, and the filter gradient
+    that gathers its B operand from the same planes; against the oracle"""
     net = kinkless_probe(x_shape, 64, (7, 7), (2, 2), (3, 3), with_bn)
     c = B.Context(net, 1 << 30, device=None)
     assert c.node_kernel(1, 0) == ("stem7_fwd_kernel<fwd+bnstats>" if with_bn else "stem7_fwd_kernel<fwd>"), c.node_kernel(1, 0)
+    assert c.node_kernel(1, 2) == "stem7_wgrad_kernel", c.node_kernel(1, 2)
     check_against_oracle("stem %s" % (x_shape,), net, 4711, capture=True)
 
 
