@@ -1094,6 +1094,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 const f32x4 val = {acc[b][4 * g], acc[b][4 * g + 1], acc[b][4 * g + 2], acc[b][4 * g + 3]};
                 *reinterpret_cast<f32x4 *>(&cw[r * C3_LP + 8 * g + 4 * h]) = val;
             }
+            __builtin_amdgcn_wave_barrier();
             f32x4 vq[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -1102,6 +1103,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 vq[q] = *reinterpret_cast<const f32x4 *>(&cw[(8 * q + orow) * C3_LP + ocol]);
                 __builtin_nontemporal_store(vq[q], reinterpret_cast<f32x4 *>(p.dst + m * NO + 32 * nb + ocol));
             }
+            __builtin_amdgcn_wave_barrier();
             if constexpr (STATS) {
                 f32x4 sum = (vq[0] + vq[1]) + (vq[2] + vq[3]);
 #pragma unroll
@@ -1886,13 +1888,16 @@ __global__ __launch_bounds__(512) void wgrad3_c1_kernel(WGradC1P p)
             if (u < C3_NPIX) halo[u] = v;
         }
         // (LDS serves a wave's instructions in order: its own reads below see these writes, and the next brick's writes
-        // come after this brick's reads)
+        // come after this brick's reads; the wave barrier emits no instruction, it only keeps the compiler from moving
+        // LDS accesses across it)
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int line = 0; line < 16; ++line) {
             const float *hp = halo + ((line / 8) * C3_HH + line % 8) * C3_HW + boff;
 #pragma unroll
             for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[line * 4 + s], hp[2 * s], acc, 0, 0, 0);
         }
+        __builtin_amdgcn_wave_barrier();
     }
     // element v of lane (r, h): output channel 8 * (v / 4) + 4 * h + v % 4, tap r
     __syncthreads();
