@@ -12,7 +12,9 @@
 // filters on 32 or 64 channels: the taps share what is staged), and for 3 x 3 x 3 filters on volumes
 // of whole 2 x 8 x 8 bricks conv3_halo_kernel (32 -> 32 channels), wgrad3_brick_kernel (any multiple
 // of 32 channels) and conv3_c1_kernel / wgrad3_c1_kernel (a network input with one live channel),
-// which keep a brick of the input with its halo in LDS for all 27 taps.
+// which keep a brick of the input with its halo in LDS for all 27 taps; wgrad2_brick_kernel does the
+// same for 3 x 3 filters on images of whole 8 x 8 bricks, and stem7_fwd_kernel / stem7_wgrad_kernel
+// serve the 7 x 7 stride-2 first layer of ResNet.
 #include "kernels.h"
 
 #include <cstdlib>
@@ -2245,6 +2247,162 @@ Stem7WCfg stem7_wgrad_cfg(const ConvGeom &g)
     return c;
 }
 
+// ---- filter gradient, 3 x 3 (2-d), multiples of 32 channels, whole 8 x 8 bricks: two images' bricks and halos in LDS -------
+// The same scheme for ResNet-50's 3 x 3 layers at 56 x 56 (64 -> 64: wgrad_halo_kernel 97 TFLOP/s in the step).  Nine taps do not
+// divide over four waves, so here the waves split the POSITIONS: a workgroup takes the 8 x 8 brick at the same place of two
+// consecutive images (128 positions, 16 lines of 8; halo 2 x 10 x 10 pixels; 47 KB of LDS), wave w multiplies the lines
+// 4 w .. 4 w + 3 under all nine taps -- nine accumulator blocks per wave; per line 4 reads of dy and 27 of the input (three
+// halo rows of nine pixels) for 36 MFMAs -- and the four waves' blocks are added in a fixed order through LDS at the end.
+// Persistent workgroups, one partial [K][9][C] per split, blocks of 32 x 9 x 32 as in wgrad3_brick_kernel.
+constexpr int W2_NPIX = 2 * C3_HH * C3_HW;
+
+struct WGradB2P {
+    const float *dy, *x;
+    float *out;              // [splits][K][9][C]
+    int N, H, W;
+    int K, C;
+    int bricks, per_split;   // bricks = (N / 2) * (H / 8) * (W / 8)
+};
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void wgrad2_brick_kernel(WGradB2P p)
+{
+    __shared__ __attribute__((aligned(16))) float lds2[(W2_NPIX + 128) * C3_LP];
+    float *xs = lds2, *dys = lds2 + W2_NPIX * C3_LP;
+    const int tid = threadIdx.x, lane = tid % 64, r = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int H = p.H, W = p.W, KT = p.K, CT = p.C;
+    const int nbw = W / C3_BW, nbh = H / C3_BH;
+    const int nsub = (KT / 32) * (CT / 32), sub = blockIdx.x % nsub, split = blockIdx.x / nsub;
+    const int k0 = 32 * (sub / (CT / 32)), c0 = 32 * (sub % (CT / 32));
+    f32x16 acc[9];
+#pragma unroll
+    for (int i = 0; i < 9; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    const float *arow = dys + h * C3_LP + r;                                  // + (8 line + 2 s) * C3_LP
+    const float *brow = xs + h * C3_LP + r;                                   // + ((image * 10 + row + tb) * 10 + j) * C3_LP
+    const int b_end = min((split + 1) * p.per_split, p.bricks);
+    for (int b = split * p.per_split; b < b_end; ++b) {
+        int t = b;
+        const int w0 = (t % nbw) * C3_BW; t /= nbw;
+        const int h0 = (t % nbh) * C3_BH;
+        const int n0 = 2 * (t / nbh);
+        __syncthreads();                                  // the previous bricks have been read
+        {
+            // input halo: 20 lines (image, ph) of 10 pixels x 32 of their channels = 80 lanes x 16 bytes, wave w takes lines
+            // w, w + 4, ...; dy: 16 lines of 8 positions x 32 of their channels, wave w takes lines w, w + 4, ...
+            constexpr int NL = 2 * C3_HH / 4;
+            f32x4 v0[NL], v1[NL], vd[4];
+            const int pw0 = lane / 8, q4 = 4 * (lane % 8);
+            const int lx = pw0 * CT + q4, ly = pw0 * KT + q4;
+            const bool in0 = !(w0 == 0 && pw0 == 0);
+            const bool in1 = lane < 16 && !(w0 + C3_BW == W && pw0 == 1);
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k = 0; k < NL; ++k) {
+                const int line = wave + 4 * k, img = line / C3_HH, ph = line % C3_HH;
+                const int ih = h0 + ph - 1;
+                const bool lok = (unsigned)ih < (unsigned)H;
+                const float *src = p.x + ((((int64_t)(n0 + img) * H + (lok ? ih : 0)) * W + w0) * CT - CT) + c0;
+                v0[k] = (lok && in0) ? ldg4(src + lx) : z;
+                v1[k] = (lok && in1) ? ldg4(src + lx + 8 * CT) : z;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int line = wave + 4 * k;
+                const int64_t m = (((int64_t)(n0 + line / 8)) * H + h0 + line % 8) * W + w0;
+                vd[k] = ldg4(p.dy + m * KT + k0 + ly);
+            }
+#pragma unroll
+            for (int k = 0; k < NL; ++k) {
+                const int line = wave + 4 * k;
+                float *dst = xs + (line * C3_HW + pw0) * C3_LP + q4;
+                *reinterpret_cast<f32x4 *>(dst) = v0[k];
+                if (lane < 16) *reinterpret_cast<f32x4 *>(dst + 8 * C3_LP) = v1[k];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int line = wave + 4 * k;
+                *reinterpret_cast<f32x4 *>(dys + (line * 8 + pw0) * C3_LP + q4) = vd[k];
+            }
+        }
+        __syncthreads();
+        // this wave's four lines; operands of the next line are read before the MFMAs of the current one
+        float a0[4], b0[3][9], a1[4], b1[3][9];
+        auto load = [&](float (&a)[4], float (&bb)[3][9], int line) {
+            const float *ap = arow + line * 8 * C3_LP;
+            const float *bp = brow + ((line / 8) * C3_HH + line % 8) * C3_HW * C3_LP;
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) a[s2] = ap[2 * s2 * C3_LP];
+#pragma unroll
+            for (int tb = 0; tb < 3; ++tb)
+#pragma unroll
+                for (int j = 0; j < 9; ++j) bb[tb][j] = bp[(tb * C3_HW + j) * C3_LP];
+        };
+        auto mul = [&](const float (&a)[4], const float (&bb)[3][9]) {
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2)
+#pragma unroll
+                for (int tb = 0; tb < 3; ++tb)
+#pragma unroll
+                    for (int te = 0; te < 3; ++te)
+                        acc[tb * 3 + te] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s2], bb[tb][2 * s2 + te], acc[tb * 3 + te], 0, 0, 0);
+        };
+        const int l0 = 4 * wave;
+        load(a0, b0, l0);
+        load(a1, b1, l0 + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mul(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        load(a0, b0, l0 + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mul(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        load(a1, b1, l0 + 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mul(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mul(a1, b1);
+    }
+    // element v of lane (r, h) of block tap: output channel 8 * (v / 4) + 4 * h + v % 4, input channel r; the four waves' blocks
+    // are added in wave order
+    float *out = p.out + ((int64_t)split * KT + k0) * 9 * CT + c0;
+    float *red = lds2;                                    // [4 waves][32][32]
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave * 1024 + (8 * (v / 4) + 4 * h + v % 4) * 32 + r] = acc[tap][v];
+        __syncthreads();
+        for (int e = tid; e < 1024; e += 256)
+            out[((e / 32) * 9 + tap) * CT + e % 32] = ((red[e] + red[1024 + e]) + red[2048 + e]) + red[3072 + e];
+    }
+}
+
+struct WGradB2Cfg {
+    bool use;
+    int nsplit, per_split, bricks;
+};
+
+WGradB2Cfg wgrad2_brick_cfg(const ConvGeom &g)
+{
+    static const bool off = getenv("POOCH_NO_WGRAD2_BRICK") != nullptr;
+    WGradB2Cfg c{false, 0, 0, 0};
+    if (off || g.C % 32 != 0 || g.K % 32 != 0 || g.C > 256 || g.K > 256 || g.D != 1 || g.kd != 1 || g.kh != 3 || g.kw != 3) return c;
+    if (g.sd != 1 || g.sh != 1 || g.sw != 1 || g.pd != 0 || g.ph != 1 || g.pw != 1) return c;
+    if (g.Ho != g.H || g.Wo != g.W || g.N % 2 != 0 || g.H % C3_BH != 0 || g.W % C3_BW != 0) return c;
+    c.bricks = (int)(g.rows_out() / (2 * C3_BH * C3_BW));
+    const int nsub = (g.K / 32) * (g.C / 32);
+    if (c.bricks < 4) return c;
+    c.nsplit = 2 * NCU / nsub;                                       // as many workgroups as are resident at once,
+    if (c.nsplit > c.bricks / 4) c.nsplit = c.bricks / 4;            // four bricks each at least
+    if (c.nsplit < 1) c.nsplit = 1;
+    c.per_split = (c.bricks + c.nsplit - 1) / c.nsplit;
+    c.nsplit = (c.bricks + c.per_split - 1) / c.per_split;
+    c.use = true;
+    return c;
+}
+
 struct WHaloCfg {
     bool use;
     int gr, waves, P, PWpad, nseg_w, nseg, nsplit, seg_per_split, groups;
@@ -2588,6 +2746,7 @@ const char *conv_wgrad_kernel(const ConvGeom &g)
         if (wgrad3_c1_cfg(g).use) return "wgrad3_c1_kernel";
         if (stem7_wgrad_cfg(g).use) return "stem7_wgrad_kernel";
         if (wgrad3_brick_cfg(g).use) return "wgrad3_brick_kernel";
+        if (wgrad2_brick_cfg(g).use) return "wgrad2_brick_kernel";
         const WHaloCfg hc = whalo_cfg(g);
         if (hc.use) {
             if (g.K != g.C) return g.K == 64 ? "wgrad_halo_kernel<2,1,3>" : "wgrad_halo_kernel<1,2,3>";
@@ -2609,6 +2768,8 @@ size_t conv_wgrad_workspace(const ConvGeom &g)
     if (b3.use) return (size_t)b3.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const Stem7WCfg s7 = stem7_wgrad_cfg(g);
     if (s7.use) return (size_t)s7.nsplit * g.K * g.taps() * g.C * sizeof(float);
+    const WGradB2Cfg b2 = wgrad2_brick_cfg(g);
+    if (b2.use) return (size_t)b2.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WHaloCfg hc = whalo_cfg(g);
     if (hc.use) return (size_t)hc.nsplit * g.K * g.taps() * g.C * sizeof(float);
     const WGradCfg c = wgrad_cfg(g);
@@ -2664,6 +2825,20 @@ hipError_t conv_wgrad(const float *dy, const float *x, float *dw_krsc, float *wo
         if (be != hipSuccess) return be;
         const int64_t nel = (int64_t)g.K * g.taps() * g.C;
         reduce_splits_kernel<<<dim3((unsigned)((nel + 63) / 64)), dim3(256), 0, s>>>(workspace, dw_krsc, nel, b3.nsplit);
+        return hipGetLastError();
+    }
+    const WGradB2Cfg b2 = wgrad2_brick_cfg(g);
+    if (b2.use) {
+        if (!workspace || (uintptr_t)dy % 16 != 0 || (uintptr_t)x % 16 != 0) return hipErrorInvalidValue;
+        WGradB2P bp;
+        bp.dy = dy; bp.x = x; bp.out = workspace;
+        bp.N = g.N; bp.H = g.H; bp.W = g.W; bp.K = g.K; bp.C = g.C;
+        bp.bricks = b2.bricks; bp.per_split = b2.per_split;
+        wgrad2_brick_kernel<<<dim3(b2.nsplit * (g.K / 32) * (g.C / 32)), dim3(256), 0, s>>>(bp);
+        const hipError_t be = hipGetLastError();
+        if (be != hipSuccess) return be;
+        const int64_t nel = (int64_t)g.K * g.taps() * g.C;
+        reduce_splits_kernel<<<dim3((unsigned)((nel + 63) / 64)), dim3(256), 0, s>>>(workspace, dw_krsc, nel, b2.nsplit);
         return hipGetLastError();
     }
     const WHaloCfg hc = whalo_cfg(g);

@@ -837,6 +837,21 @@ def test_brick_filter_gradient_all_widths(x_shape, cout):
     check_against_oracle("brick filter gradient %s -> %d" % (x_shape, cout), net, 909, capture=False)
 
 
+@pytest.mark.parametrize("x_shape,cout", [
+    ((4, 32, 16, 24), 32),            # 12 pairs of bricks, three splits; every brick touches a border
+    ((2, 64, 8, 32), 64),             # four blocks of 32 x 9 x 32, one split
+    ((6, 64, 24, 24), 32),            # 64 -> 32; bricks with their whole halo inside
+    ((2, 32, 32, 40), 96),            # 32 -> 96
+])
+def test_brick_filter_gradient_2d(x_shape, cout):
+    """3 x 3 filter gradient on images of whole 8 x 8 bricks and an even batch: the bricks at the same place of two images and
+    their halos in LDS, the four waves split the positions and hold all nine taps; against the oracle"""
+    net = kinkless_probe(x_shape, cout, (3, 3), (1, 1), (1, 1), True)
+    c = B.Context(net, 1 << 30, device=None)
+    assert c.node_kernel(1, 2) == "wgrad2_brick_kernel", c.node_kernel(1, 2)
+    check_against_oracle("2-d brick filter gradient %s -> %d" % (x_shape, cout), net, 2929, capture=False)
+
+
 @pytest.mark.parametrize("x_shape,with_bn", [
     ((2, 1, 2, 8, 8), True),          # one brick per sample: all six borders at once
     ((3, 1, 4, 16, 24), True),        # 2 x 2 x 3 bricks per sample: fewer bricks than waves, most waves idle
