@@ -491,6 +491,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
         f32x4 rmean = {0.f, 0.f, 0.f, 0.f}, rm2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
+            // accumulating: the block's old values are all requested here, before the block goes through LDS, without branches
+            // (rows that do not exist read the zero page).  Left to the compiler, each row's load sat under that row's branch,
+            // right before its store: one memory round trip after the other, NQ per block.
+            f32x4 oldv[ACCUM ? NQ : 1];
+            if constexpr (ACCUM) {
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const int m = rowdst[wm * TM * 32 + i * 32 + q * RPI + orow];
+                    const float *op = (m >= 0 && ncol < p.Nout) ? dst + (int64_t)m * p.Nout + ncol : g_zero4;
+                    oldv[q] = __builtin_nontemporal_load((gvec4_ptr)(op));
+                }
+            }
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -512,7 +524,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(IGemmP p)
                 }
                 if (m >= 0 && ncol < p.Nout) {
                     f32x4 *dp = reinterpret_cast<f32x4 *>(dst + (int64_t)m * p.Nout + ncol);
-                    if (ACCUM) val = __builtin_nontemporal_load(dp) + val;
+                    if constexpr (ACCUM) val = oldv[q] + val;
                     __builtin_nontemporal_store(val, dp);
                 }
             }
