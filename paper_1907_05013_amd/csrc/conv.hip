@@ -763,13 +763,24 @@ __device__ __forceinline__ void c3_brick_out(const f32x16 &acc, float *lds, cons
     const int r = lane % 32, h = lane / 32;
     const int D = p.Dr, H = p.Hr, W = p.Wr;
     float *cw = lds + wave * 32 * C3_LP;
+    const int orow = lane / 8, ocol = 4 * (lane % 8);
+    // accumulating: the old values are requested together before the block goes through LDS (a load placed between the
+    // stores waits for the store before it, one memory round trip per row group)
+    f32x4 oldv[ACCUM ? 4 : 1];
+    if constexpr (ACCUM) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int row = wave * 32 + q * 8 + orow;
+            const int64_t m = (((int64_t)n * D + d0 + row / 64) * H + h0 + (row / 8) % 8) * W + w0 + row % 8;
+            oldv[q] = __builtin_nontemporal_load((gvec4_ptr)(p.dst + m * C3_C + ocol));
+        }
+    }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const f32x4 val = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
         *reinterpret_cast<f32x4 *>(&cw[r * C3_LP + 8 * g + 4 * h]) = val;
     }
     __syncthreads();
-    const int orow = lane / 8, ocol = 4 * (lane % 8);
     f32x4 vq[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -778,7 +789,7 @@ __device__ __forceinline__ void c3_brick_out(const f32x16 &acc, float *lds, cons
         f32x4 val = *reinterpret_cast<const f32x4 *>(&cw[(q * 8 + orow) * C3_LP + ocol]);
         vq[q] = val;
         f32x4 *dp = reinterpret_cast<f32x4 *>(p.dst + m * C3_C + ocol);
-        if (ACCUM) val = __builtin_nontemporal_load(dp) + val;
+        if constexpr (ACCUM) val = oldv[q] + val;
         __builtin_nontemporal_store(val, dp);
     }
     if constexpr (STATS) {
@@ -2686,8 +2697,8 @@ hipError_t conv_dgrad(const float *dy, const float *w_crsk, float *dx, const Con
         p.Dr = g.Do; p.Hr = g.Ho; p.Wr = g.Wo; p.Ds = g.Do; p.Hs = g.Ho; p.Ws = g.Wo;
         p.kd = p.kh = p.kw = 1; p.sd = p.sh = p.sw = 1; p.pd = p.ph = p.pw = 0;
         p.dst_strided = 1; p.DD = g.D; p.HD = g.H; p.WD = g.W; p.SD = g.sd; p.SH = g.sh; p.SW = g.sw;
-        // rows that are not written keep their zeros, so the scatter always adds
-        return dispatch_igemm<false>(p, true, s);
+        // rows that are not written keep their zeros; the scattered rows are stored over them, or added to what is there
+        return dispatch_igemm<false>(p, accumulate, s);
     }
     p = dgrad_params(dy, w_crsk, dx, g);
     return dispatch_igemm<true>(p, accumulate, s, nullptr, workspace);
