@@ -93,8 +93,10 @@ __device__ __forceinline__ int remap_tile(int wg, int chunk) { return (wg % NXCD
 // Four waves of four accumulator blocks: the compiler is asked for four waves per SIMD (128 registers, accumulators included).
 // Left alone it gave the accumulating instantiations 142 and the 256 x 64 tile's 130, which cost them the fourth workgroup
 // of a compute unit (1 x 1 256 -> 64 data gradient at batch 640: 1.00 -> 0.91 ms; 3 x 3 64 -> 64 forward 1.32 -> 1.29).
+// Not asked of the 256 x 64 tile's per-thread-tap and general address paths, which would spill 8 - 14 registers.
 template <int WGM, int WGN, int TM, int TN, int BKT, bool VEC, int LIN, bool DGRAD, bool ACCUM, bool STATS = false>
-__global__ __launch_bounds__(64 * WGM * WGN, (TM * TN == 4 && BKT == 16 && WGM * WGN == 4) ? 4 : 1) void igemm_kernel(IGemmP p)
+__global__ __launch_bounds__(64 * WGM * WGN, (TM * TN == 4 && BKT == 16 && WGM * WGN == 4 && (WGM == 2 || LIN == 1 || LIN == 3)) ? 4 : 1)
+void igemm_kernel(IGemmP p)
 {
     // BKT = reduction slice per main-loop iteration; LDS rows are BKT + 4 floats apart (16-byte
     // aligned, conflict-free 128-bit reads)
