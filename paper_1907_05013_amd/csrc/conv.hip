@@ -707,10 +707,14 @@ SplitK igemm_splitk(int M, int Nout, int Kred, int lin, bool dst_strided)
     const int64_t tiles = ((int64_t)(M + 127) / 128) * ((Nout + 127) / 128);
     const int nk = (Kred + BK - 1) / BK;
     // (a reduction of 2048: 81 TFLOP/s split against 85 with quarter-size tiles; 2304 and more: 89 - 106 against 60 - 90)
-    if (tiles >= 384 || nk < 144) return k;
+    // a handful of tiles (the FC layer: 640 x 1000 x 2048 is 40 tiles, one after the other 128 slices long): split whatever the
+    // length, down to 8 slices per part
+    const bool few = tiles < 64 && nk >= 32 && nk < 144;
+    if (!few && (tiles >= 384 || nk < 144)) return k;
     int64_t want = (768 + tiles - 1) / tiles;                   // about three workgroups per compute unit
-    if (want > 8) want = 8;
-    if (want > nk / 16) want = nk / 16;                         // at least 16 slices (256 reduction steps) per part
+    if (want > (few ? 16 : 8)) want = few ? 16 : 8;
+    const int min_slices = few ? 8 : 16;                        // at least 16 slices (256 reduction steps) per part
+    if (want > nk / min_slices) want = nk / min_slices;
     const int64_t by_ws = (int64_t)(IGEMM_WS_CAP / ((size_t)M * Nout * sizeof(float)));
     if (want > by_ws) want = by_ws;
     if (want < 2) return k;
