@@ -284,19 +284,48 @@ __global__ __launch_bounds__(256) void bn_tiles_group_kernel(const float *__rest
     }
 }
 
-__global__ __launch_bounds__(64) void bn_grad_final_kernel(const float *__restrict__ part, const float *__restrict__ istd,
-                                                            float *__restrict__ dgamma, float *__restrict__ dbeta,
-                                                            int nblk, int C)
+// dbeta and dgamma from the per-row-block partial sums [nblk][2][C].  A block takes 16 channels: its 1024 threads are 64 groups
+// of 16 lanes, group g adds the row blocks g, g + 64, ... of its lane's channel (16 consecutive channels per load: 64 contiguous
+// bytes, where one wavefront per channel read 64 different cache lines per step), in double; the 64 group sums are then added in
+// ascending order by the first group.
+constexpr int GF_CH = 16, GF_GROUPS = 64;
+__global__ __launch_bounds__(GF_CH * GF_GROUPS) void bn_grad_final_kernel(const float *__restrict__ part, const float *__restrict__ istd,
+                                                                         float *__restrict__ dgamma, float *__restrict__ dbeta,
+                                                                         int nblk, int C)
 {
-    const int c = blockIdx.x, lane = threadIdx.x;
+    __shared__ double ra[GF_GROUPS][GF_CH], rb[GF_GROUPS][GF_CH];
+    const int tx = threadIdx.x % GF_CH, g = threadIdx.x / GF_CH;
+    const int c = blockIdx.x * GF_CH + tx;
     double a = 0.0, b = 0.0;
-    for (int k = lane; k < nblk; k += 64) {
-        a += (double)part[((int64_t)k * 2 + 0) * C + c];
-        b += (double)part[((int64_t)k * 2 + 1) * C + c];
+    if (c < C) {
+        // eight row blocks' values requested together, added in ascending order
+        int k = g;
+        for (; k + 7 * GF_GROUPS < nblk; k += 8 * GF_GROUPS) {
+            float va[8], vb[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                va[u] = part[((int64_t)(k + u * GF_GROUPS) * 2 + 0) * C + c];
+                vb[u] = part[((int64_t)(k + u * GF_GROUPS) * 2 + 1) * C + c];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                a += (double)va[u];
+                b += (double)vb[u];
+            }
+        }
+        for (; k < nblk; k += GF_GROUPS) {
+            a += (double)part[((int64_t)k * 2 + 0) * C + c];
+            b += (double)part[((int64_t)k * 2 + 1) * C + c];
+        }
     }
-    a = wave_sum(a);
-    b = wave_sum(b);
-    if (lane == 0) {
+    ra[g][tx] = a;
+    rb[g][tx] = b;
+    __syncthreads();
+    if (g == 0 && c < C) {
+        for (int j = 1; j < GF_GROUPS; ++j) {
+            a += ra[j][tx];
+            b += rb[j][tx];
+        }
         dbeta[c] = (float)a;
         dgamma[c] = (float)(b * (double)istd[c]);
     }
@@ -719,7 +748,7 @@ hipError_t bn_bwd(const float *x, const float *dy, const float *gamma, const flo
 #undef PARTIAL
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        bn_grad_final_kernel<<<dim3(C), dim3(64), 0, s>>>(ws, istd, dgamma, dbeta, L.nblk, C);
+        bn_grad_final_kernel<<<dim3((C + GF_CH - 1) / GF_CH), dim3(GF_CH * GF_GROUPS), 0, s>>>(ws, istd, dgamma, dbeta, L.nblk, C);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
