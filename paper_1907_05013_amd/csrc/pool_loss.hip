@@ -5,6 +5,8 @@
 // deterministic and gives the same summation order as scattering window by window.
 #include "kernels.h"
 
+#include <cstdlib>
+
 namespace pk {
 namespace {
 
@@ -45,11 +47,20 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float *__restric
     y[i] = best;
 }
 
+// Workgroups are dealt to the eight XCDs in turn, and each XCD has an L2 of its own.  Overlapping pool windows make
+// neighbouring workgroups read the same input rows; with `spread` (a grid of 8 * spread workgroups) each XCD takes a
+// contiguous eighth of the index space, so those rows are fetched from memory once instead of once per XCD that meets them.
+__device__ __forceinline__ int64_t pool_block(unsigned spread)
+{
+    return spread ? (int64_t)(blockIdx.x % 8) * spread + blockIdx.x / 8 : (int64_t)blockIdx.x;
+}
+
 // Four channels per thread (C % 4 == 0): the same scan order and the same strict comparison per
 // channel as the scalar kernel, with 16-byte accesses.
-__global__ __launch_bounds__(256) void maxpool_fwd_vec4_kernel(const float *__restrict__ x, float *__restrict__ y, PoolGeom g, int64_t total4)
+__global__ __launch_bounds__(256) void maxpool_fwd_vec4_kernel(const float *__restrict__ x, float *__restrict__ y, PoolGeom g, int64_t total4,
+                                                               unsigned spread)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = pool_block(spread) * blockDim.x + threadIdx.x;
     if (i >= total4) return;
     const int C4 = g.C / 4;
     const int c = (int)(i % C4) * 4;
@@ -117,9 +128,9 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const float *__restric
 // (a..a+1, b..b+1) reach that block; their union is a 5x5 patch, loaded once.
 template <bool ACCUM>
 __global__ __launch_bounds__(256) void maxpool_k3s2p1_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy, float *dx,
-                                                                  PoolGeom g, int HB, int WB, int64_t total)
+                                                                  PoolGeom g, int HB, int WB, int64_t total, unsigned spread)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = pool_block(spread) * blockDim.x + threadIdx.x;
     if (i >= total) return;
     const int C4 = g.C / 4;
     const int c = (int)(i % C4) * 4;
@@ -394,6 +405,13 @@ bool pool_ok(const PoolGeom &g)
 }
 
 inline dim3 blocks_for(int64_t total) { return dim3((unsigned)((total + 255) / 256)); }
+// an eighth of the workgroups of a launch whose index space is split over the XCDs (pool_block); 0: plain order
+inline unsigned pool_spread(int64_t total)
+{
+    static const bool off = getenv("POOCH_NO_POOL_XCD") != nullptr;
+    const int64_t blocks = (total + 255) / 256;
+    return (off || blocks < 64) ? 0u : (unsigned)((blocks + 7) / 8);
+}
 
 }  // namespace
 
@@ -401,10 +419,12 @@ hipError_t maxpool_fwd(const float *x, float *y, const PoolGeom &g, hipStream_t 
 {
     if (!x || !y || !pool_ok(g)) return hipErrorInvalidValue;
     const int64_t total = (int64_t)g.N * g.Do * g.Ho * g.Wo * g.C;
-    if (g.C % 4 == 0 && ((uintptr_t)x | (uintptr_t)y) % 16 == 0)
-        maxpool_fwd_vec4_kernel<<<blocks_for(total / 4), dim3(256), 0, s>>>(x, y, g, total / 4);
-    else
+    if (g.C % 4 == 0 && ((uintptr_t)x | (uintptr_t)y) % 16 == 0) {
+        const unsigned sp = pool_spread(total / 4);
+        maxpool_fwd_vec4_kernel<<<sp ? dim3(8 * sp) : blocks_for(total / 4), dim3(256), 0, s>>>(x, y, g, total / 4, sp);
+    } else {
         maxpool_fwd_kernel<<<blocks_for(total), dim3(256), 0, s>>>(x, y, g, total);
+    }
     return hipGetLastError();
 }
 
@@ -416,8 +436,10 @@ hipError_t maxpool_bwd(const float *x, const float *dy, float *dx, const PoolGeo
         g.C % 4 == 0 && al16) {
         const int HB = (g.H + 1) / 2, WB = (g.W + 1) / 2;
         const int64_t tot = (int64_t)g.N * HB * WB * (g.C / 4);
-        if (accumulate) maxpool_k3s2p1_bwd_kernel<true><<<blocks_for(tot), dim3(256), 0, s>>>(x, dy, dx, g, HB, WB, tot);
-        else maxpool_k3s2p1_bwd_kernel<false><<<blocks_for(tot), dim3(256), 0, s>>>(x, dy, dx, g, HB, WB, tot);
+        const unsigned sp = pool_spread(tot);
+        const dim3 grid = sp ? dim3(8 * sp) : blocks_for(tot);
+        if (accumulate) maxpool_k3s2p1_bwd_kernel<true><<<grid, dim3(256), 0, s>>>(x, dy, dx, g, HB, WB, tot, sp);
+        else maxpool_k3s2p1_bwd_kernel<false><<<grid, dim3(256), 0, s>>>(x, dy, dx, g, HB, WB, tot, sp);
         return hipGetLastError();
     }
     if (g.kd == g.sd && g.kh == g.sh && g.kw == g.sw && g.pd == 0 && g.ph == 0 && g.pw == 0 && g.D % g.sd == 0 && g.H % g.sh == 0 &&
