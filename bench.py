@@ -211,8 +211,8 @@ def cpu_baseline(name, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="resnet50_b640_16g", choices=sorted(WORKLOADS))
     ap.add_argument("--budget-gib", type=float, default=None)
     ap.add_argument("--batch", type=int, default=None,
