@@ -41,6 +41,7 @@ MEASURED_TRAFFIC_KIB = {
     ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+lin,fwd+bnstats>"): (127493.0, 151900.0),
 }
 TRAFFIC_SCALE = (2.0, 1.0)
+MASKS = False   # --relu-masks: one-bit ReLU masks (off by default, as in the library)
 
 WORKLOADS = {
     # name: (config loader name, overrides, default budget in GiB or fraction of in-core peak)
@@ -76,14 +77,14 @@ def elem_counts(net):
 
 def incore_arena(net, B):
     """(smallest arena found that holds the in-core run, its peak of live bytes, resident bytes)"""
-    c = B.Context(net, 1 << 46, device=None)
+    c = B.Context(net, 1 << 46, device=None, masks=MASKS)
     keep = [B.KEEP] * c.n_fmaps
     _, peak = c.simulate(keep, want_time=False)
     res = c.resident_bytes()
     dyn = peak
     while True:
         try:
-            B.Context(net, res + dyn, device=None).simulate(keep, want_time=False)
+            B.Context(net, res + dyn, device=None, masks=MASKS).simulate(keep, want_time=False)
             return int(res + dyn), int(peak), int(res)
         except B.BudgetError:
             dyn = int(dyn * 1.02) // 256 * 256 + 256
@@ -231,7 +232,11 @@ def main():
     ap.add_argument("--no-incore", action="store_true")
     ap.add_argument("--dump-profile", default=None, help="write the measured profile (ms per layer / map) to this .npz file")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--relu-masks", action="store_true",
+                    help="one-bit masks for ReLUs whose output no other layer's backward reads (one feature map less for ResNet-50)")
     args = ap.parse_args()
+    global MASKS
+    MASKS = bool(args.relu_masks)
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
 
@@ -260,7 +265,7 @@ def main():
         arena_bytes = int(budget * 2 ** 30)
     arena_bytes = arena_bytes // 256 * 256          # (the library counts the budget in whole 256-byte units)
     under_budget = arena_bytes < incore_bytes
-    fm_bytes = sum(b for b, _ in B.Context(net, 1 << 46, device=None).fmaps())
+    fm_bytes = sum(b for b, _ in B.Context(net, 1 << 46, device=None, masks=MASKS).fmaps())
     if under_budget:
         # The profiling pass runs every map as swap, and whether that fits is not monotone in the arena (the static
         # allocator's placement depends on the capacity): a smaller arena is always within the budget, so step down by 1 %
@@ -268,7 +273,7 @@ def main():
         asked = arena_bytes
         for _ in range(11):
             try:
-                probe = B.Context(net, arena_bytes, device=None)
+                probe = B.Context(net, arena_bytes, device=None, masks=MASKS)
                 probe.simulate([B.SWAP] * probe.n_fmaps, want_time=False)
                 break
             except B.BudgetError:
@@ -282,7 +287,7 @@ def main():
 
     result_extra = {}
     if under_budget:
-        ctx = B.Context(net, arena_bytes, pinned_bytes=fm_bytes + 4096)
+        ctx = B.Context(net, arena_bytes, pinned_bytes=fm_bytes + 4096, masks=MASKS)
         ctx.set_params(params)
         ctx.set_batch(x, t)
         link = ctx.measure_link(min(1 << 30, (arena_bytes - resident) // 2 // 256 * 256), 3)
@@ -365,7 +370,7 @@ def main():
         torch.cuda.empty_cache()
     incore_sec = None
     if not under_budget or not args.no_incore:
-        ctx = B.Context(net, incore_bytes)
+        ctx = B.Context(net, incore_bytes, masks=MASKS)
         ctx.set_params(params)
         ctx.set_batch(x, t)
         ctx.set_plan([B.KEEP] * ctx.n_fmaps)
@@ -410,7 +415,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "batch": batch, "arena_GiB": arena_bytes / 2 ** 30,
                    "feature_maps_GB": fm_bytes / 1e9, "incore_arena_GB": incore_bytes / 1e9,
-                   "under_budget": under_budget},
+                   "under_budget": under_budget, "relu_masks": MASKS},
         "loss": loss,
         "loss_matches_incore": loss_matches,
         "value_plan": (("beyond the paper: its two steps plus a local search, layers re-timed under the plan (mode refine); "

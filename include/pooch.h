@@ -121,6 +121,15 @@ int32_t pooch_softmax_ce(pooch_ctx *, int32_t logits);
  * pooch_node_fused: id of the relu a layer's output is produced in, -1 if the layer writes its own. */
 pooch_status pooch_set_fusion(pooch_ctx *, int enable);
 int32_t pooch_node_fused(pooch_ctx *, int32_t id);
+/* One-bit ReLU masks (default off; call before pooch_finalize): a relu, or an add + relu, whose output no other
+ * layer's backward reads -- the one in front of a global average pool, say -- keeps one bit per element ("was the
+ * output positive") in the resident region for its own backward, which asks nothing else of the output.  The output
+ * then is no feature map (section 4.1.1 classifies what some backward computation reads): it is freed after its last
+ * forward consumer and never swapped or recomputed for the backward pass.  Results are bit-identical to those
+ * without masks.  Off by default because it takes ResNet-50 from the 105 feature maps of table 3 to 104.
+ * pooch_node_keeps_mask: 1 if layer `id` keeps such a mask, 0 if not. */
+pooch_status pooch_set_relu_masks(pooch_ctx *, int enable);
+int32_t pooch_node_keeps_mask(pooch_ctx *, int32_t id);
 /* A convolution whose result goes directly into a batch normalisation also produces that
  * layer's batch statistics while its results are still on chip, which saves the normalisation
  * one of its three passes over the tensor (section 3.3 counts these layers as pure memory

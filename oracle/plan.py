@@ -60,7 +60,7 @@ class Graph:
     `inputs` / `consumers` carry gradients, `finputs` / `fconsumers` say what a forward kernel reads
     (the addrelu reads the BN's input in place of the BN's output) and decide how long tensors live."""
 
-    def __init__(self, net, fuse=False):
+    def __init__(self, net, fuse=False, masks=False):
         self.net = net
         n = len(net)
         self.n = n
@@ -130,6 +130,15 @@ class Graph:
                 self.needs.append([i])
             else:
                 self.needs.append([])
+        # masks=True: a relu / addrelu whose output no other layer's backward reads keeps one bit per element for its own
+        # backward instead of the output, which then is no feature map
+        self.mask_only = [False] * n
+        if masks:
+            read_by_other = set(t for i in range(n) for t in self.needs[i] if t != i)
+            for i, op in enumerate(self.ops):
+                if op in ("relu", "addrelu") and i not in read_by_other:
+                    self.mask_only[i] = True
+                    self.needs[i] = []
         needed = set()
         for i in range(n):
             needed.update(self.needs[i])

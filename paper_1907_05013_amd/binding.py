@@ -54,6 +54,8 @@ SYMBOLS = {
     "pooch_softmax_ce": (_i32, [_ctx, _i32]),
     "pooch_set_fusion": (_i32, [_ctx, C.c_int]),
     "pooch_node_fused": (_i32, [_ctx, _i32]),
+    "pooch_set_relu_masks": (_i32, [_ctx, C.c_int]),
+    "pooch_node_keeps_mask": (_i32, [_ctx, _i32]),
     "pooch_bn_stats_source": (_i32, [_ctx, _i32]),
     "pooch_refine_profile": (_i32, [_ctx, C.c_int, _pf]),
     "pooch_finalize": (_i32, [_ctx]),
@@ -173,9 +175,10 @@ class Context:
     """One pooch_ctx.  `budget_bytes` is the size of the arena.  With device=None the context
     is planning-only (no GPU touched): graph, profile injection, planning, simulation."""
 
-    def __init__(self, net, budget_bytes, pinned_bytes=0, device="cuda:0", fuse=True):
+    def __init__(self, net, budget_bytes, pinned_bytes=0, device="cuda:0", fuse=True, masks=False):
         self.L = lib()
         self.fuse = bool(fuse)
+        self.masks = bool(masks)
         self.net = net
         self.budget_bytes = int(budget_bytes)
         self._keep = []          # python objects whose memory the library borrows
@@ -253,6 +256,7 @@ class Context:
     def _build(self, net):
         L, h = self.L, self.h
         self._chk(L.pooch_set_fusion(h, 1 if self.fuse else 0))
+        self._chk(L.pooch_set_relu_masks(h, 1 if self.masks else 0))
         for i, layer in enumerate(net):
             op = layer["op"]
             if op == "input":
@@ -286,6 +290,10 @@ class Context:
     def node_fused(self, node):
         """id of the relu this layer is executed in, or -1"""
         return self.L.pooch_node_fused(self.h, node)
+
+    def node_keeps_mask(self, node):
+        """True if this relu / add + relu keeps a one-bit mask for its backward instead of its output"""
+        return self._chk(self.L.pooch_node_keeps_mask(self.h, node)) == 1
 
     def bn_stats_source(self, node):
         """id of the conv whose forward also produces this bn layer's batch statistics, or -1"""

@@ -601,6 +601,82 @@ __global__ __launch_bounds__(256) void addrelu_bwd_kernel(const float *__restric
     }
 }
 
+// ---- one-bit ReLU masks ----
+// Thread i owns elements 4 i .. 4 i + 3 (the thread after the last whole group owns the tail of up to three); its four bits
+// go to position 4 (i % 8) of word i / 8, so bit e % 32 of word e / 32 says whether element e was positive.
+__global__ __launch_bounds__(256) void relu_mask_pack_kernel(const float *__restrict__ y, uint32_t *__restrict__ mask, int64_t n)
+{
+    const int64_t n4 = n / 4;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    uint32_t nib = 0;
+    if (i < n4) {
+        const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(y) + i);
+        nib = (v.x > 0.f ? 1u : 0u) | (v.y > 0.f ? 2u : 0u) | (v.z > 0.f ? 4u : 0u) | (v.w > 0.f ? 8u : 0u);
+    } else if (i == n4) {
+        for (int t = 0; t < (int)(n - n4 * 4); ++t) nib |= (y[n4 * 4 + t] > 0.f ? 1u : 0u) << t;
+    }
+    // the eight threads of a word are eight consecutive lanes of one wavefront (256 threads per block, i % 8 == lane % 8)
+    uint32_t w = nib << (4 * (threadIdx.x & 7));
+    w |= __shfl_xor(w, 1, 64);
+    w |= __shfl_xor(w, 2, 64);
+    w |= __shfl_xor(w, 4, 64);
+    if ((threadIdx.x & 7) == 0 && i * 4 < n) mask[i / 8] = w;
+}
+
+__device__ __forceinline__ uint32_t mask_nibble(const uint32_t *__restrict__ mask, int64_t i)
+{
+    return (mask[i / 8] >> (4 * (int)(i & 7))) & 15u;
+}
+__device__ __forceinline__ bool mask_bit(const uint32_t *__restrict__ mask, int64_t e) { return (mask[e / 32] >> (int)(e & 31)) & 1u; }
+
+// dx (+)= dy where the mask is set
+template <bool ACC>
+__global__ __launch_bounds__(256) void relu_bwd_mask_kernel(const uint32_t *__restrict__ mask, const float *dy, float *dx, int64_t n)
+{
+    const int64_t n4 = n / 4;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) {
+        const uint32_t nib = mask_nibble(mask, i);
+        f32x4 d = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(dy) + i);
+        d.x = (nib & 1u) ? d.x : 0.f; d.y = (nib & 2u) ? d.y : 0.f; d.z = (nib & 4u) ? d.z : 0.f; d.w = (nib & 8u) ? d.w : 0.f;
+        if (ACC) d += __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(dx) + i);
+        __builtin_nontemporal_store(d, reinterpret_cast<f32x4 *>(dx) + i);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) {
+        const int64_t t = n4 * 4 + threadIdx.x;
+        const float d = mask_bit(mask, t) ? dy[t] : 0.f;
+        dx[t] = ACC ? dx[t] + d : d;
+    }
+}
+
+// addrelu_bwd_kernel with the mask in place of y
+template <int MODE1>
+__global__ __launch_bounds__(256) void addrelu_bwd_mask_kernel(const uint32_t *__restrict__ mask, float *dy, float *o1, int64_t n)
+{
+    const int64_t n4 = n / 4;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) {
+        const uint32_t nib = mask_nibble(mask, i);
+        f32x4 d = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(dy) + i);
+        f32x4 e = {0.f, 0.f, 0.f, 0.f};
+        if (MODE1 == 2) e = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(o1) + i);
+        d.x = (nib & 1u) ? d.x : 0.f; d.y = (nib & 2u) ? d.y : 0.f; d.z = (nib & 4u) ? d.z : 0.f; d.w = (nib & 8u) ? d.w : 0.f;
+        __builtin_nontemporal_store(d, reinterpret_cast<f32x4 *>(dy) + i);
+        if (MODE1 == 1) __builtin_nontemporal_store(d, reinterpret_cast<f32x4 *>(o1) + i);
+        if (MODE1 == 2) {
+            e.x += d.x; e.y += d.y; e.z += d.z; e.w += d.w;
+            __builtin_nontemporal_store(e, reinterpret_cast<f32x4 *>(o1) + i);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) {
+        const int64_t t = n4 * 4 + threadIdx.x;
+        const float d = mask_bit(mask, t) ? dy[t] : 0.f;
+        dy[t] = d;
+        if (MODE1 == 1) o1[t] = d;
+        if (MODE1 == 2) o1[t] += d;
+    }
+}
+
 // p -= lr * g
 __global__ __launch_bounds__(256) void sgd_kernel(float *__restrict__ p, const float *__restrict__ g, float lr, int64_t n)
 {
@@ -790,6 +866,37 @@ hipError_t add_relu_bwd(const float *y, float *dy, float *o1, int mode1, int64_t
     if (mode1 == 0) addrelu_bwd_kernel<0><<<grid, block, 0, s>>>(y, dy, o1, n);
     else if (mode1 == 1) addrelu_bwd_kernel<1><<<grid, block, 0, s>>>(y, dy, o1, n);
     else addrelu_bwd_kernel<2><<<grid, block, 0, s>>>(y, dy, o1, n);
+    return hipGetLastError();
+}
+size_t relu_mask_bytes(int64_t n) { return n <= 0 ? 0 : (size_t)((n + 31) / 32) * 4; }
+hipError_t relu_mask_pack(const float *y, uint32_t *mask, int64_t n, hipStream_t s)
+{
+    if (n < 0 || n >= ((int64_t)1 << 40) || !y || !mask) return hipErrorInvalidValue;
+    if (n == 0) return hipSuccess;
+    if (((uintptr_t)y | (uintptr_t)mask) % 16 != 0) return hipErrorInvalidValue;
+    const int64_t threads = (n + 3) / 4;   // one per group of four, the last of them for the tail
+    relu_mask_pack_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s>>>(y, mask, n);
+    return hipGetLastError();
+}
+hipError_t relu_bwd_mask(const uint32_t *mask, const float *dy, float *dx, int64_t n, bool accumulate, hipStream_t s)
+{
+    if (n < 0 || n >= ((int64_t)1 << 40) || !mask || !dy || !dx) return hipErrorInvalidValue;
+    if (n == 0) return hipSuccess;
+    if (((uintptr_t)mask | (uintptr_t)dy | (uintptr_t)dx) % 16 != 0) return hipErrorInvalidValue;
+    const dim3 grid(ew_blocks(n)), block(256);
+    if (accumulate) relu_bwd_mask_kernel<true><<<grid, block, 0, s>>>(mask, dy, dx, n);
+    else relu_bwd_mask_kernel<false><<<grid, block, 0, s>>>(mask, dy, dx, n);
+    return hipGetLastError();
+}
+hipError_t add_relu_bwd_mask(const uint32_t *mask, float *dy, float *o1, int mode1, int64_t n, hipStream_t s)
+{
+    if (n < 0 || n >= ((int64_t)1 << 40) || !mask || !dy || (mode1 != 0 && !o1) || mode1 < 0 || mode1 > 2) return hipErrorInvalidValue;
+    if (n == 0) return hipSuccess;
+    if (((uintptr_t)mask | (uintptr_t)dy | (uintptr_t)o1) % 16 != 0) return hipErrorInvalidValue;
+    const dim3 grid(ew_blocks(n)), block(256);
+    if (mode1 == 0) addrelu_bwd_mask_kernel<0><<<grid, block, 0, s>>>(mask, dy, o1, n);
+    else if (mode1 == 1) addrelu_bwd_mask_kernel<1><<<grid, block, 0, s>>>(mask, dy, o1, n);
+    else addrelu_bwd_mask_kernel<2><<<grid, block, 0, s>>>(mask, dy, o1, n);
     return hipGetLastError();
 }
 hipError_t sgd_update(float *p, const float *g, float lr, int64_t n, hipStream_t s)

@@ -56,6 +56,10 @@ struct Graph {
     std::vector<std::vector<int>> finputs, fconsumers;
     std::vector<int> last_consumer;
     std::vector<std::vector<int>> needs;        // tensors the backward of a node reads
+    // masks: a ReLU (or add + ReLU) whose output no OTHER layer's backward reads keeps one bit per element -- was the
+    // output positive -- for its own backward instead of the output (mask_only[node]); the output then is no feature map
+    bool masks = false;
+    std::vector<char> mask_only;
     std::vector<int> fmaps;                     // tensor id of every feature map, ascending
     std::vector<int> fidx;                      // tensor id -> feature-map index or -1
     int n() const { return (int)nodes.size(); }

@@ -94,6 +94,12 @@ hipError_t add_fwd(const float *a, const float *b, float *z, int64_t n, hipStrea
 hipError_t add_relu_fwd(const float *a, const float *b, float *z, int64_t n, hipStream_t s);
 // m = dy where y > 0 else 0, written over dy; mode1 1: o1 = m, 2: o1 += m, 0: o1 unused
 hipError_t add_relu_bwd(const float *y, float *dy, float *o1, int mode1, int64_t n, hipStream_t s);
+// One bit per element of a ReLU output, "was it positive": bit e % 32 of word e / 32 (relu_mask_bytes(n) bytes, 16-byte aligned).
+// The two backward kernels below take the mask in place of the output (same results: they only ever asked y > 0).
+size_t relu_mask_bytes(int64_t n);
+hipError_t relu_mask_pack(const float *y, uint32_t *mask, int64_t n, hipStream_t s);
+hipError_t relu_bwd_mask(const uint32_t *mask, const float *dy, float *dx, int64_t n, bool accumulate, hipStream_t s);
+hipError_t add_relu_bwd_mask(const uint32_t *mask, float *dy, float *o1, int mode1, int64_t n, hipStream_t s);
 // dst += src
 hipError_t accumulate(float *dst, const float *src, int64_t n, hipStream_t s);
 hipError_t copy(float *dst, const float *src, int64_t n, hipStream_t s);

@@ -590,6 +590,18 @@ std::string Graph::analyze()
         default: break;
         }
     }
+    mask_only.assign(n, 0);
+    if (masks) {
+        std::vector<char> read_by_other(n, 0);
+        for (int i = 0; i < n; ++i)
+            for (int t : needs[i])
+                if (t != i) read_by_other[t] = 1;
+        for (int i = 0; i < n; ++i)
+            if ((nodes[i].op == OP_RELU || nodes[i].op == OP_ADDRELU) && !read_by_other[i]) {
+                mask_only[i] = 1;
+                needs[i].clear();
+            }
+    }
     last_consumer.assign(n, -1);
     for (int t = 0; t < n; ++t) {
         if (t != n - 1 && consumers[t].empty() && nodes[t].op != OP_DEAD) return "a layer output is never consumed";

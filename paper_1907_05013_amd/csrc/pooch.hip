@@ -95,6 +95,7 @@ struct pooch_ctx {
     std::vector<ParamInfo> params;
     std::vector<int64_t> off_mean, off_istd;  // per node (BN only), resident offsets
     std::vector<int64_t> off_rmean, off_rvar; // running averages of the same layers
+    std::vector<int64_t> off_mask;            // per node: resident offset of its one-bit ReLU mask, -1 where it keeps none
     float bn_decay = 0.9f;
     // what a step needs before it may touch the device: a batch (the labels index the logits) and every parameter;
     // and what an update or a read-back of gradients needs: a step that has run
@@ -282,20 +283,26 @@ struct Exec {
             return pk::bn_fwd(D(in0), R(P(i, 0).off_val), R(P(i, 1).off_val), D(out), R(c->off_mean[i]), R(c->off_istd[i]),
                               ws_bn, M, (int)nd.C, nd.eps, relu, run, s);
         }
-        case OP_RELU: return pk::relu_fwd(D(in0), D(out), nd.numel(), s);
+        case OP_RELU: {
+            const hipError_t e = pk::relu_fwd(D(in0), D(out), nd.numel(), s);
+            return e != hipSuccess ? e : keep_mask(i, out, refwd);
+        }
         case OP_ADD: return pk::add_fwd(D(in0), D(in1), D(out), nd.numel(), s);
         case OP_ADDRELU: {
             // inputs whose normalisation is applied here: in0 / in1 then is that layer's input
             const bool ap0 = G.apply_into[nd.in[0]] == i, ap1 = G.apply_into[nd.in[1]] == i;
+            hipError_t e;
             if (ap0 || ap1) {
                 const int b = nd.in[ap0 ? 0 : 1], b2 = nd.in[1];
                 const bool both = ap0 && ap1;
-                return pk::bn_add_relu_fwd(D(ap0 ? in0 : in1), D(ap0 ? in1 : in0), R(P(b, 0).off_val), R(P(b, 1).off_val),
-                                           R(c->off_mean[b]), R(c->off_istd[b]), both ? R(P(b2, 0).off_val) : nullptr,
-                                           both ? R(P(b2, 1).off_val) : nullptr, both ? R(c->off_mean[b2]) : nullptr,
-                                           both ? R(c->off_istd[b2]) : nullptr, D(out), nd.numel() / nd.C, (int)nd.C, s);
+                e = pk::bn_add_relu_fwd(D(ap0 ? in0 : in1), D(ap0 ? in1 : in0), R(P(b, 0).off_val), R(P(b, 1).off_val),
+                                        R(c->off_mean[b]), R(c->off_istd[b]), both ? R(P(b2, 0).off_val) : nullptr,
+                                        both ? R(P(b2, 1).off_val) : nullptr, both ? R(c->off_mean[b2]) : nullptr,
+                                        both ? R(c->off_istd[b2]) : nullptr, D(out), nd.numel() / nd.C, (int)nd.C, s);
+            } else {
+                e = pk::add_relu_fwd(D(in0), D(in1), D(out), nd.numel(), s);
             }
-            return pk::add_relu_fwd(D(in0), D(in1), D(out), nd.numel(), s);
+            return e != hipSuccess ? e : keep_mask(i, out, refwd);
         }
         case OP_MAXPOOL: return pk::maxpool_fwd(D(in0), D(out), pool_geom(G, i), s);
         case OP_GAVGPOOL: {
@@ -314,6 +321,14 @@ struct Exec {
         }
         default: return hipErrorInvalidValue;
         }
+    }
+
+    // a ReLU that keeps one bit per element for its backward packs them from the output it has just written; a re-forward
+    // (the output regenerated as another layer's input) finds the same bits in place already
+    hipError_t keep_mask(int i, int64_t out, bool refwd)
+    {
+        if (c->off_mask[i] < 0 || refwd) return hipSuccess;
+        return pk::relu_mask_pack(D(out), reinterpret_cast<uint32_t *>(c->arena + c->off_mask[i]), c->G.nodes[i].numel(), c->st[S_COMPUTE]);
     }
 
     // one gradient output of an element-wise "pass dy on" (residual add)
@@ -364,8 +379,11 @@ struct Exec {
             int first = -1;
             for (int j = 0; j < 2; ++j)
                 if (first < 0 && (modes[j] == M_WRITE || modes[j] == M_ACC)) first = j;
-            hipError_t e = pk::add_relu_bwd(D(need), D(dy), first < 0 ? nullptr : D(offs[first]),
-                                            first < 0 ? 0 : (modes[first] == M_WRITE ? 1 : 2), nd.numel(), s);
+            float *o1 = first < 0 ? nullptr : D(offs[first]);
+            const int mode1 = first < 0 ? 0 : (modes[first] == M_WRITE ? 1 : 2);
+            hipError_t e = c->off_mask[i] >= 0
+                               ? pk::add_relu_bwd_mask(reinterpret_cast<const uint32_t *>(c->arena + c->off_mask[i]), D(dy), o1, mode1, nd.numel(), s)
+                               : pk::add_relu_bwd(D(need), D(dy), o1, mode1, nd.numel(), s);
             if (e != hipSuccess) return e;
             for (int j = first + 1; first >= 0 && j < 2; ++j)
                 if (modes[j] == M_WRITE || modes[j] == M_ACC) {
@@ -376,6 +394,8 @@ struct Exec {
         }
         case OP_RELU:
             if (m0 == M_NONE) return hipSuccess;
+            if (c->off_mask[i] >= 0)
+                return pk::relu_bwd_mask(reinterpret_cast<const uint32_t *>(c->arena + c->off_mask[i]), D(dy), D(o0), nd.numel(), m0 == M_ACC, s);
             return pk::relu_bwd(D(need), D(dy), D(o0), nd.numel(), m0 == M_ACC, s);
         case OP_ADD: {
             hipError_t e = pass_on(dy, o0, m0, nd.numel());
@@ -835,6 +855,20 @@ pooch_status pooch_set_fusion(pooch_ctx *c, int enable)
     return POOCH_OK;
 }
 
+pooch_status pooch_set_relu_masks(pooch_ctx *c, int enable)
+{
+    GRAPH_OPEN(c);
+    c->G.masks = enable != 0;
+    return POOCH_OK;
+}
+
+int32_t pooch_node_keeps_mask(pooch_ctx *c, int32_t id)
+{
+    if (!c || !c->finalized) return POOCH_E_STATE;
+    if (id < 0 || id >= c->G.n()) return POOCH_E_INVALID;
+    return c->G.mask_only[id] ? 1 : 0;
+}
+
 int32_t pooch_node_fused(pooch_ctx *c, int32_t id)
 {
     if (!c || !c->finalized) return POOCH_E_STATE;
@@ -870,10 +904,12 @@ pooch_status pooch_finalize(pooch_ctx *c)
     c->off_istd.assign(n, -1);
     c->off_rmean.assign(n, -1);
     c->off_rvar.assign(n, -1);
+    c->off_mask.assign(n, -1);
     c->params.clear();
     size_t ws_wgrad = 0, ws_bn = 0;
     for (int i = 0; i < n; ++i) {
         Node &nd = G.nodes[i];
+        if (G.mask_only[i]) c->off_mask[i] = take((int64_t)pk::relu_mask_bytes(nd.numel()));
         if (nd.op == OP_CONV || nd.op == OP_FC) {
             const pk::ConvGeom g = conv_geom(G, i, c->in_cdev);
             // the conv kernels index rows and reduction lengths with 32 bits

@@ -23,11 +23,12 @@ pytestmark = pytest.mark.gpu
 BIG = 1 << 44
 
 FUSE = True     # the library's default; test_unfused_layers_* runs the separate kernels
+MASKS = False   # the library's default; test_one_bit_relu_masks_* switches the masks on
 
 
 def plan_sizes(net):
     """(resident bytes, in-core peak of the dynamic region) from a planning-only context"""
-    c = B.Context(net, 1 << 44, device=None, fuse=FUSE)
+    c = B.Context(net, 1 << 44, device=None, fuse=FUSE, masks=MASKS)
     _, peak = c.simulate([B.KEEP] * c.n_fmaps, want_time=False)
     return c.resident_bytes(), peak
 
@@ -36,9 +37,9 @@ def gpu_step(net, params, x, t, cls=None, sched=True, dyn_bytes=None, capture=Fa
     """one step under an explicit classification (default: all keep); returns loss, grads, outs"""
     res, peak = plan_sizes(net)
     dyn = 2 * peak if dyn_bytes is None else dyn_bytes     # in-core: room to spare
-    G = OP.Graph(net, fuse=FUSE)
+    G = OP.Graph(net, fuse=FUSE, masks=MASKS)
     fbytes = sum(G.fmap_bytes())
-    c = B.Context(net, res + dyn, pinned_bytes=fbytes + 256, fuse=FUSE)
+    c = B.Context(net, res + dyn, pinned_bytes=fbytes + 256, fuse=FUSE, masks=MASKS)
     c.set_params(params)
     c.set_batch(x, t)
     c.set_plan([B.KEEP] * c.n_fmaps if cls is None else cls, sched)
@@ -431,6 +432,48 @@ def test_unfused_layers_vs_oracle_and_fused_run(monkeypatch):
     assert abs(l1 - l0) <= 1e-6 * abs(l0)
     for a, b in zip(g1, g0):
         assert rel(a, b) <= 1e-5
+
+
+@pytest.mark.parametrize("fuse", [True, False])
+def test_one_bit_relu_masks_vs_oracle_and_bit_exact(fuse, monkeypatch):
+    """one-bit ReLU masks switched on (the ReLU in front of the global pool keeps a mask, its output is no feature map):
+    every tensor and gradient against the oracle, bit-identical to the run without masks, and bit-identical again under
+    random swap / recompute plans and tight budgets; fused and separate kernels; an element count that is no multiple of 32"""
+    monkeypatch.setattr(sys.modules[__name__], "FUSE", fuse)
+    nets = dict(reduced_nets())
+    odd = workloads.Net()                                     # 3 x 5 x 7 x 7 = 735 elements under the last ReLU: a ragged mask tail
+    t_ = odd.input((3, 3, 9, 9))
+    t_ = odd.relu(odd.bn(odd.conv(t_, 5, (3, 3), (1, 1), (0, 0))))
+    u_ = odd.bn(odd.conv(t_, 5, (3, 3), (1, 1), (1, 1)))
+    odd.softmax_ce(odd.fc(odd.gavgpool(odd.relu(odd.add(u_, t_))), 4))
+    nets["odd"] = odd
+    ran = 0
+    for name, net in nets.items():
+        monkeypatch.setattr(sys.modules[__name__], "MASKS", False)
+        params = workloads.make_params(net, 77, perturb=True)
+        x, t = workloads.make_batch(net, 77)
+        l0, g0, _, _ = gpu_step(net, params, x, t)
+        monkeypatch.setattr(sys.modules[__name__], "MASKS", True)
+        G = OP.Graph(net, fuse=fuse, masks=True)
+        kept = [i for i in range(G.n) if G.mask_only[i]]
+        if not kept:
+            continue
+        _, _, _, l1, g1 = check_against_oracle("%s with one-bit masks (%d kept), fuse %s" % (name, len(kept), fuse), net, 77)
+        assert_bit_exact((name, "masks on vs off"), (l0, g0), (l1, g1))
+        res, peak = plan_sizes(net)
+        rng = np.random.default_rng(5)
+        nf = len(G.fmaps)
+        for trial in range(4):
+            cls = [int(v) for v in rng.integers(0, 3, nf)]
+            dyn = int(peak * rng.uniform(0.6, 1.1)) // 256 * 256
+            try:
+                OP.build_schedule(G, cls, dyn, True)
+            except OP.Budget:
+                continue
+            l2, g2, _, st = gpu_step(net, params, x, t, cls=cls, dyn_bytes=dyn)
+            assert_bit_exact((name, "masks under plan", trial), (l0, g0), (l2, g2))
+            ran += 1
+    assert ran >= 3
 
 
 def test_training_loop_profile_then_plan_vs_oracle():

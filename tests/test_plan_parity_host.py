@@ -30,10 +30,10 @@ def nets():
     }
 
 
-def lib_ctx(net, dyn_cap, fuse=True):
-    probe = B.Context(net, 1 << 40, device=None, fuse=fuse)
+def lib_ctx(net, dyn_cap, fuse=True, masks=False):
+    probe = B.Context(net, 1 << 40, device=None, fuse=fuse, masks=masks)
     res = probe.resident_bytes()
-    return B.Context(net, res + dyn_cap, device=None, fuse=fuse), res
+    return B.Context(net, res + dyn_cap, device=None, fuse=fuse, masks=masks), res
 
 
 def rand_profile(G, rng, link=1.0):
@@ -275,6 +275,52 @@ def test_hand_computed_timelines_through_the_library():
         keep = c.simulate([B.KEEP] * 4)[0]
         assert c.simulate([B.KEEP, B.SWAP, B.KEEP, B.KEEP])[0] - keep == 1.5
         assert c.simulate([B.KEEP, B.RECOMPUTE, B.KEEP, B.KEEP])[0] - keep == t_re
+
+
+def test_one_bit_relu_masks_shrink_the_feature_map_set_alike():
+    """one-bit ReLU masks (off by default): a relu / add + relu whose output no other layer's backward reads keeps a mask and
+    its output stops being a feature map -- the same nodes in oracle and library, the same command lists under random plans,
+    valid by the independent checker; the configured networks lose exactly the ReLU in front of the global pool"""
+    expect = {"tiny": 0, "res": 1, "bott": 1, "fork": None}      # tiny: that ReLU is fused into a BN + ReLU, which reads the BN's input
+    ncmp = 0
+    cases = [(k, nets()[k]) for k in ("tiny", "res", "bott", "fork")] + [("rand%d" % s, workloads.random_net(s, residual=s >= 80)) for s in (3, 15, 61, 85, 97, 110)]
+    for name, net in cases:
+        rng = np.random.default_rng(77)
+        for fuse in (True, False):
+            G0 = P.Graph(net, fuse=fuse)
+            G = P.Graph(net, fuse=fuse, masks=True)
+            kept = [i for i in range(G.n) if G.mask_only[i]]
+            assert len(G.fmaps) == len(G0.fmaps) - len([i for i in kept if i in G0.fmaps])
+            assert all(G.ops[i] in ("relu", "addrelu") and i not in G.fmaps for i in kept)
+            if fuse and expect.get(name) is not None:
+                assert len(kept) == expect[name], (name, kept)
+            nf = len(G.fmaps)
+            incore = P.build_schedule(G, [P.KEEP] * nf, BIG)
+            c, _ = lib_ctx(net, BIG, fuse, masks=True)
+            assert [(G.bytes[t], t) for t in G.fmaps] == c.fmaps()
+            assert [c.node_keeps_mask(i) for i in range(G.n)] == [bool(v) for v in G.mask_only]
+            c0, _ = lib_ctx(net, BIG, fuse)
+            assert not any(c0.node_keeps_mask(i) for i in range(G.n))
+            # the masks live in the resident region: one bit per element, in 256-byte units
+            extra = sum((int(np.prod(G.shape[i])) + 31) // 32 * 4 for i in kept)
+            assert 0 <= c.resident_bytes() - c0.resident_bytes() - extra < 256 * max(len(kept), 1)
+            for trial in range(6):
+                cls = [int(v) for v in rng.integers(0, 3, nf)] if trial else [P.KEEP] * nf
+                cap = BIG if trial == 0 else int(incore.peak * rng.uniform(0.45, 1.2)) // 256 * 256
+                c, _ = lib_ctx(net, cap, fuse, masks=True)
+                for ahead in (True, False):
+                    try:
+                        S = P.build_schedule(G, cls, cap, ahead)
+                    except P.Budget:
+                        with pytest.raises(B.BudgetError):
+                            c.set_plan(cls, ahead)
+                        continue
+                    c.set_plan(cls, ahead)
+                    rows = c.commands()
+                    assert np.array_equal(rows, as_rows(S)), (name, fuse, trial, ahead)
+                    schedule_check.check(G, S.cmds, cap)
+                    ncmp += 1
+    assert ncmp > 100
 
 
 def test_random_graphs_command_lists_identical_and_valid():
