@@ -36,9 +36,9 @@ PAPER_B640_IMG_S = 195.0    # paper, ResNet50 batch 640 on V100 16 GB + PCIe3 (3
 # FETCH_SIZE reads 0.5 GiB there, WRITE_SIZE 1.0 GiB, so fetch x 2.0, write x 1.0.
 # Source: profiles/resnet50_b640_16g_hbm_traffic.txt.  (workload, kernel) -> (fetch KiB, write KiB)
 MEASURED_TRAFFIC_KIB = {
-    ("resnet50_b640_16g", "wgrad_kernel<4,2,2,2>"): (286701.0, 64042.0),
-    ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+gemm,fwd+bnstats>"): (222514.0, 600327.0),
-    ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+lin,fwd+bnstats>"): (127493.0, 151900.0),
+    ("resnet50_b640_16g", "wgrad_kernel<4,2,2,2>"): (286746.0, 64042.0),
+    ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+gemm,fwd+bnstats>"): (222563.0, 600326.0),
+    ("resnet50_b640_16g", "igemm_kernel<2,2,2,2,vec+lin,fwd+bnstats>"): (127516.0, 151900.0),
 }
 TRAFFIC_SCALE = (2.0, 1.0)
 MASKS = False   # --relu-masks: one-bit ReLU masks (off by default, as in the library)
