@@ -253,11 +253,15 @@ __global__ __launch_bounds__(256) void maxpool_tiled_bwd_kernel(const float *__r
             }
 }
 
-// y[n][c] = (1/S) sum_s x[n][s][c].  One block per (image, 64 channels): four wavefronts take every
-// fourth position each (ascending), and the four partial sums are added in a fixed order.
-__global__ __launch_bounds__(256) void gavgpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int N, int64_t S, int C)
+// y[n][c] = (1/S) sum_s x[n][s][c].  One block per (image, 64 channels): its wavefronts -- sixteen for maps of 256 positions
+// or more, else four -- take every sixteenth (fourth) position each (ascending, four loads in flight), and the partial sums
+// are added in ascending order.
+// (With four wavefronts and one load in flight a single volume's 12^3 x 512 map took 0.17 ms: eight blocks, each a chain
+// of 432 dependent loads.)
+template <int GAP_WAVES>
+__global__ __launch_bounds__(64 * GAP_WAVES) void gavgpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int N, int64_t S, int C)
 {
-    __shared__ float part[4][64];
+    __shared__ float part[GAP_WAVES][64];
     const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
     const int cblocks = (C + 63) / 64;
     const int64_t n = blockIdx.x / cblocks;
@@ -265,11 +269,21 @@ __global__ __launch_bounds__(256) void gavgpool_fwd_kernel(const float *__restri
     float s = 0.f;
     if (c < C) {
         const float *p = x + n * S * C + c;
-        for (int64_t k = w; k < S; k += 4) s += p[k * C];
+        int64_t k = w;
+        for (; k + 3 * GAP_WAVES < S; k += 4 * GAP_WAVES) {
+            const float v0 = p[k * C], v1 = p[(k + GAP_WAVES) * C], v2 = p[(k + 2 * GAP_WAVES) * C], v3 = p[(k + 3 * GAP_WAVES) * C];
+            s += v0; s += v1; s += v2; s += v3;
+        }
+        for (; k < S; k += GAP_WAVES) s += p[k * C];
     }
     part[w][lane] = s;
     __syncthreads();
-    if (w == 0 && c < C) y[n * C + c] = (((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]) / (float)S;
+    if (w == 0 && c < C) {
+        float t = part[0][lane];
+#pragma unroll
+        for (int j = 1; j < GAP_WAVES; ++j) t += part[j][lane];
+        y[n * C + c] = t / (float)S;
+    }
 }
 
 template <bool ACCUM>
@@ -461,7 +475,9 @@ hipError_t maxpool_bwd(const float *x, const float *dy, float *dx, const PoolGeo
 hipError_t gavgpool_fwd(const float *x, float *y, int N, int64_t S, int C, hipStream_t s)
 {
     if (!x || !y || N <= 0 || S <= 0 || C <= 0) return hipErrorInvalidValue;
-    gavgpool_fwd_kernel<<<dim3((unsigned)((int64_t)N * ((C + 63) / 64))), dim3(256), 0, s>>>(x, y, N, S, C);
+    const dim3 grid((unsigned)((int64_t)N * ((C + 63) / 64)));
+    if (S >= 256) gavgpool_fwd_kernel<16><<<grid, dim3(1024), 0, s>>>(x, y, N, S, C);
+    else gavgpool_fwd_kernel<4><<<grid, dim3(256), 0, s>>>(x, y, N, S, C);
     return hipGetLastError();
 }
 
